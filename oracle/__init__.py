@@ -1,0 +1,182 @@
+"""ctypes front end of the CPU oracle (test infrastructure: only tests, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the product never does).
+
+Every function takes and returns numpy arrays of UNPACKED values and forwards to the plain C loops in
+qnn_oracle.c; there is no arithmetic in this file beyond dtype/shape marshalling.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "qnn_oracle.c")
+_SO = os.path.join(_HERE, "libqnn_oracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain C, OpenMP over output rows)."""
+    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O3", "-march=native", "-fopenmp", "-fno-fast-math", "-shared", "-fPIC",
+               "-Wall", "-Wextra", "-o", _SO, _SRC]
+        subprocess.run(cmd, check=True)
+    return _SO
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(_SO)
+    return _lib
+
+
+class OracleRangeError(ArithmeticError):
+    pass
+
+
+def _check(rc: int, what: str):
+    if rc == 1:
+        raise OracleRangeError(f"{what}: a result does not fit int32")
+    if rc != 0:
+        raise RuntimeError(f"{what}: oracle returned {rc}")
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def sign(x: np.ndarray) -> np.ndarray:
+    x = _c(x, np.float32)
+    s = np.empty(x.shape, dtype=np.int8)
+    _check(lib().qo_sign(_p(x), C.c_int64(x.size), _p(s)), "sign")
+    return s
+
+
+def pack_bits(s: np.ndarray) -> np.ndarray:
+    """[rows][K] int8 (+1/-1 or 1/0) -> [rows][ceil(K/32)] uint32, element 32j+t at bit t of word j."""
+    s = _c(s, np.int8)
+    rows, K = s.shape
+    out = np.zeros((rows, (K + 31) // 32), dtype=np.uint32)
+    _check(lib().qo_pack_bits(_p(s), C.c_int64(rows), C.c_int64(K), _p(out)), "pack_bits")
+    return out
+
+
+def split_planes(v: np.ndarray, nbits: int) -> np.ndarray:
+    v = _c(v, np.int32)
+    out = np.empty((nbits,) + v.shape, dtype=np.uint8)
+    _check(lib().qo_split_planes(_p(v), C.c_int64(v.size), C.c_int(nbits), _p(out)), "split_planes")
+    return out
+
+
+def gemm_pm1(a: np.ndarray, w: np.ndarray) -> np.ndarray:
+    a = _c(a, np.int8)
+    w = _c(w, np.int8)
+    M, K = a.shape
+    N, K2 = w.shape
+    assert K == K2
+    out = np.empty((M, N), dtype=np.int32)
+    _check(lib().qo_gemm_pm1(_p(a), _p(w), C.c_int64(M), C.c_int64(N), C.c_int64(K), _p(out)), "gemm_pm1")
+    return out
+
+
+def gemm_int(u: np.ndarray, v: np.ndarray) -> np.ndarray:
+    u = _c(u, np.int32)
+    v = _c(v, np.int32)
+    M, K = u.shape
+    N, K2 = v.shape
+    assert K == K2
+    out = np.empty((M, N), dtype=np.int32)
+    _check(lib().qo_gemm_int(_p(u), _p(v), C.c_int64(M), C.c_int64(N), C.c_int64(K), _p(out)), "gemm_int")
+    return out
+
+
+def gemm_planes(pa, ca, mode_a: int, pw, cw, mode_w: int) -> np.ndarray:
+    pa = _c(pa, np.uint8)
+    pw = _c(pw, np.uint8)
+    ca = _c(ca, np.int32)
+    cw = _c(cw, np.int32)
+    Pa, M, K = pa.shape
+    Pb, N, K2 = pw.shape
+    assert K == K2 and ca.size == Pa and cw.size == Pb
+    out = np.empty((M, N), dtype=np.int32)
+    rc = lib().qo_gemm_planes(_p(pa), C.c_int(Pa), _p(ca), C.c_int(mode_a), _p(pw), C.c_int(Pb), _p(cw),
+                              C.c_int(mode_w), C.c_int64(M), C.c_int64(N), C.c_int64(K), _p(out))
+    _check(rc, "gemm_planes")
+    return out
+
+
+def threshold(Cm: np.ndarray, T: np.ndarray, flip=None) -> np.ndarray:
+    Cm = _c(Cm, np.int32)
+    T = _c(T, np.int32)
+    M, N = Cm.shape
+    assert T.size == N
+    f = None if flip is None else _c(flip, np.uint8)
+    out = np.empty((M, N), dtype=np.int8)
+    _check(lib().qo_threshold(_p(Cm), C.c_int64(M), C.c_int64(N), _p(T), _p(f) if f is not None else None,
+                              _p(out)), "threshold")
+    return out
+
+
+def bn_sign(Cm, gamma, beta, mean, var, eps: float) -> np.ndarray:
+    Cm = _c(Cm, np.int32)
+    M, N = Cm.shape
+    g, b, mu, v = (_c(t, np.float64) for t in (gamma, beta, mean, var))
+    out = np.empty((M, N), dtype=np.int8)
+    _check(lib().qo_bn_sign(_p(Cm), C.c_int64(M), C.c_int64(N), _p(g), _p(b), _p(mu), _p(v), C.c_double(eps),
+                            _p(out)), "bn_sign")
+    return out
+
+
+def mlp(x: np.ndarray, W: list, T: list, flip: list | None = None) -> np.ndarray:
+    """x uint8 [batch][dims[0]]; W[l] int8 +-1 [dims[l+1]][dims[l]]; T[l] int32 [dims[l+1]] for l < L-1."""
+    x = _c(x, np.uint8)
+    L = len(W)
+    Ws = [_c(w, np.int8) for w in W]
+    Ts = [_c(t, np.int32) for t in T]
+    assert len(Ts) == L - 1
+    dims = np.array([x.shape[1]] + [w.shape[0] for w in Ws], dtype=np.int64)
+    for l, w in enumerate(Ws):
+        assert w.shape[1] == dims[l]
+    Wp = (C.c_void_p * L)(*[w.ctypes.data for w in Ws])
+    Tp = (C.c_void_p * max(L - 1, 1))(*[t.ctypes.data for t in Ts])
+    if flip is None:
+        Fp = None
+        Fs = []
+    else:
+        Fs = [_c(f, np.uint8) for f in flip]
+        Fp = (C.c_void_p * max(L - 1, 1))(*[f.ctypes.data for f in Fs])
+    out = np.empty((x.shape[0], int(dims[-1])), dtype=np.int32)
+    rc = lib().qo_mlp(_p(x), C.c_int64(x.shape[0]), C.c_int(L), _p(dims), Wp, Tp, Fp, _p(out))
+    _check(rc, "mlp")
+    return out
+
+
+def conv2d(u: np.ndarray, w: np.ndarray, pad: int, stride: int = 1) -> np.ndarray:
+    """u int [B][H][W][Ci], w int [Co][KH][KW][Ci] -> int32 [B][Ho][Wo][Co], zero padding."""
+    u = _c(u, np.int32)
+    w = _c(w, np.int32)
+    B, H, Wd, Ci = u.shape
+    Co, KH, KW, Ci2 = w.shape
+    assert Ci == Ci2
+    Ho = (H + 2 * pad - KH) // stride + 1
+    Wo = (Wd + 2 * pad - KW) // stride + 1
+    out = np.empty((B, Ho, Wo, Co), dtype=np.int32)
+    rc = lib().qo_conv2d(_p(u), C.c_int64(B), C.c_int64(H), C.c_int64(Wd), C.c_int64(Ci), _p(w), C.c_int64(Co),
+                         C.c_int64(KH), C.c_int64(KW), C.c_int64(pad), C.c_int64(stride), _p(out))
+    _check(rc, "conv2d")
+    return out
+
+
+def num_threads() -> int:
+    return int(lib().qo_num_threads())

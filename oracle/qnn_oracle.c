@@ -1,0 +1,240 @@
+/*
+ * CPU oracle for the run-time path of Quantized Neural Networks (Hubara et al., arXiv 1609.07061).
+ *
+ * THIS IS TEST INFRASTRUCTURE, NOT THE PRODUCT.  It is a plain, slow, obviously-correct statement of what the
+ * GPU library has to compute, written from the paper on UNPACKED arrays: one int8 / uint8 / int32 per value,
+ * ordinary multiply-accumulate, no bit packing in the arithmetic, no popcount, no intrinsics, no blocking.
+ * It shares no code, header, table or helper with the HIP path.  Only tests, the smoke check and the
+ * benchmark's CPU-baseline leg may call it.
+ *
+ * The method is an exact re-encoding of integer arithmetic (Sec. 6: the packed kernel and the ordinary kernel
+ * return identical outputs on -1/+1 inputs), so every function below is the plain definition of its result.
+ * All sums are accumulated in int64 and range-checked against int32; a result that does not fit returns
+ * QO_ERR_RANGE and leaves the output unspecified.
+ *
+ * Parity pins (tests marked "not gpu"): fp32 GEMM on +-1 matrices, the agreement-count identity of Eq. (popc),
+ * brute force over all sign vectors for tiny K, Eq. (FirstLayer) (planes vs integer values), a library
+ * convolution in fp64, the float BatchNorm formula evaluated in double, and hand-written expected bits for
+ * float edge values.  No function here is "parity unpinned".
+ */
+#include <stddef.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define QO_OK 0
+#define QO_ERR_RANGE 1
+#define QO_ERR_ARG 2
+#define QO_ERR_NOMEM 3
+
+static int fits_i32(int64_t v) { return v >= (int64_t)INT32_MIN && v <= (int64_t)INT32_MAX; }
+
+/* Deterministic binarization, Sec. 2.1 Eq. (1): +1 if x >= 0, -1 otherwise.
+ * The comparison is the IEEE one on the value: +0 and -0 both give +1, NaN (which is not >= 0) gives -1,
+ * denormals compare by their true value. */
+int qo_sign(const float *x, int64_t n, int8_t *s) {
+    for (int64_t i = 0; i < n; ++i) {
+        float v = x[i];
+        s[i] = (v >= 0.0f) ? (int8_t)1 : (int8_t)-1;
+    }
+    return QO_OK;
+}
+
+/* Concatenation of 32 binary variables into one 32-bit word (Sec. 6).  The paper fixes neither the value<->bit
+ * encoding nor the bit order; the reading used throughout this build is: +1 <-> bit 1, -1 (or 0) <-> bit 0,
+ * element 32*j + t of a row <-> bit t (least significant first) of word j, tail bits beyond K are 0.
+ * `s` may hold +-1 (sign values) or {0,1} (a bit plane): any value > 0 sets the bit. */
+int qo_pack_bits(const int8_t *s, int64_t rows, int64_t K, uint32_t *words) {
+    int64_t Kw = (K + 31) / 32;
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t j = 0; j < Kw; ++j) {
+            uint32_t w = 0;
+            for (int t = 0; t < 32; ++t) {
+                int64_t k = 32 * j + t;
+                if (k < K && s[r * K + k] > 0) w |= (uint32_t)1 << t;
+            }
+            words[r * Kw + j] = w;
+        }
+    }
+    return QO_OK;
+}
+
+/* Bit planes of an integer code, Sec. 2.6 Eq. (FirstLayer): plane n (n = 1 .. nbits) holds the n-th bit,
+ * n = 1 being the least significant (weight 2^(n-1)) and n = nbits the most significant.  planes[p][i] is
+ * plane n = p + 1 of value i.  For negative v the bits are those of its two's-complement representation. */
+int qo_split_planes(const int32_t *v, int64_t n, int nbits, uint8_t *planes) {
+    if (nbits < 1 || nbits > 31) return QO_ERR_ARG;
+    for (int p = 0; p < nbits; ++p)
+        for (int64_t i = 0; i < n; ++i) planes[(int64_t)p * n + i] = (uint8_t)(((uint32_t)v[i] >> p) & 1u);
+    return QO_OK;
+}
+
+/* Binary matrix product on +-1 values (Alg. 4, hidden and output layers; Sec. 6):
+ * C[m][n] = sum_k a[m][k] * w[n][k], a is M x K, w is N x K (one row per output neuron). */
+int qo_gemm_pm1(const int8_t *a, const int8_t *w, int64_t M, int64_t N, int64_t K, int32_t *C) {
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) acc += (int64_t)a[m * K + k] * (int64_t)w[n * K + k];
+            if (!fits_i32(acc)) bad = 1;
+            C[m * N + n] = (int32_t)acc;
+        }
+    }
+    return bad ? QO_ERR_RANGE : QO_OK;
+}
+
+/* Integer matrix product on the VALUES that bit planes encode (left side of Eq. (FirstLayer), s = x . w):
+ * C[m][n] = sum_k u[m][k] * v[n][k]. */
+int qo_gemm_int(const int32_t *u, const int32_t *v, int64_t M, int64_t N, int64_t K, int32_t *C) {
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) acc += (int64_t)u[m * K + k] * (int64_t)v[n * K + k];
+            if (!fits_i32(acc)) bad = 1;
+            C[m * N + n] = (int32_t)acc;
+        }
+    }
+    return bad ? QO_ERR_RANGE : QO_OK;
+}
+
+/* Value of one plane entry: mode 0 ("bit") reads the stored bit as 0/1, mode 1 ("sign") reads it as -1/+1. */
+static int plane_value(uint8_t bit, int mode) { return mode ? (bit ? 1 : -1) : (bit ? 1 : 0); }
+
+/* Right side of Eq. (FirstLayer) generalised to both operands (Sec. 3: one binary product per pair of planes):
+ * C = sum_i sum_j ca[i] * cw[j] * (A_i . W_j^T), taken plane pair by plane pair with explicit coefficients.
+ * pa is [Pa][M][K], pw is [Pb][N][K], entries 0/1. */
+int qo_gemm_planes(const uint8_t *pa, int Pa, const int32_t *ca, int modeA, const uint8_t *pw, int Pb,
+                   const int32_t *cw, int modeW, int64_t M, int64_t N, int64_t K, int32_t *C) {
+    int bad = 0;
+#pragma omp parallel for schedule(static) reduction(| : bad)
+    for (int64_t m = 0; m < M; ++m) {
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t total = 0;
+            for (int i = 0; i < Pa; ++i) {
+                for (int j = 0; j < Pb; ++j) {
+                    const uint8_t *ar = pa + ((int64_t)i * M + m) * K;
+                    const uint8_t *wr = pw + ((int64_t)j * N + n) * K;
+                    int64_t dot = 0;
+                    for (int64_t k = 0; k < K; ++k) dot += plane_value(ar[k], modeA) * plane_value(wr[k], modeW);
+                    total += (int64_t)ca[i] * (int64_t)cw[j] * dot;
+                }
+            }
+            if (!fits_i32(total)) bad = 1;
+            C[m * N + n] = (int32_t)total;
+        }
+    }
+    return bad ? QO_ERR_RANGE : QO_OK;
+}
+
+/* Sign(BatchNorm(.)) of Alg. 4 once BatchNorm has been folded to an integer threshold per neuron:
+ * out = +1 if (C[m][n] >= T[n]) differs from flip[n], else -1.  flip may be NULL (all zero). */
+int qo_threshold(const int32_t *C, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip, int8_t *out) {
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int ge = C[m * N + n] >= T[n];
+            int f = flip ? (flip[n] != 0) : 0;
+            out[m * N + n] = (ge != f) ? (int8_t)1 : (int8_t)-1;
+        }
+    return QO_OK;
+}
+
+/* Sign(BatchNorm(s)) straight from the float definition, in double: y = gamma * (s - mean) / sqrt(var + eps) + beta,
+ * out = +1 if y >= 0 else -1 (Alg. 4 with the inference-time BatchNorm; Eq. (1)).  Used to pin the threshold fold. */
+int qo_bn_sign(const int32_t *C, int64_t M, int64_t N, const double *gamma, const double *beta, const double *mean,
+               const double *var, double eps, int8_t *out) {
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double sd = __builtin_sqrt(var[n] + eps);
+            double y = gamma[n] * (((double)C[m * N + n] - mean[n]) / sd) + beta[n];
+            out[m * N + n] = (y >= 0.0) ? (int8_t)1 : (int8_t)-1;
+        }
+    return QO_OK;
+}
+
+/* Alg. 4, "Running a BNN with L layers", up to and including the integer output-layer product:
+ *   layer 1   : a_1 = x . W_1 on the 8-bit (in general unsigned integer) inputs, a_1^b = Sign(BN(a_1))
+ *   layers k  : a_k = a_{k-1}^b . W_k,  a_k^b = Sign(BN(a_k))         (k = 2 .. L-1)
+ *   layer L   : logits = a_{L-1}^b . W_L                              (the final float BatchNorm is left out)
+ * W[l] is dims[l+1] x dims[l] in +-1; T[l], flip[l] (l < L-1) are the folded BatchNorm of layer l+1. */
+int qo_mlp(const uint8_t *x, int64_t batch, int n_layers, const int64_t *dims, const int8_t *const *W,
+           const int32_t *const *T, const uint8_t *const *flip, int32_t *logits) {
+    if (n_layers < 1) return QO_ERR_ARG;
+    int rc = QO_OK;
+    int64_t maxd = 0;
+    for (int l = 0; l <= n_layers; ++l)
+        if (dims[l] > maxd) maxd = dims[l];
+    int32_t *sum = (int32_t *)malloc(sizeof(int32_t) * (size_t)batch * (size_t)maxd);
+    int8_t *act = (int8_t *)malloc((size_t)batch * (size_t)maxd);
+    int32_t *x32 = (int32_t *)malloc(sizeof(int32_t) * (size_t)batch * (size_t)dims[0]);
+    int32_t *w32 = (int32_t *)malloc(sizeof(int32_t) * (size_t)dims[1] * (size_t)dims[0]);
+    if (!sum || !act || !x32 || !w32) {
+        rc = QO_ERR_NOMEM;
+        goto done;
+    }
+    for (int64_t i = 0; i < batch * dims[0]; ++i) x32[i] = (int32_t)x[i];
+    for (int64_t i = 0; i < dims[1] * dims[0]; ++i) w32[i] = (int32_t)W[0][i];
+    for (int l = 0; l < n_layers; ++l) {
+        int32_t *dst = (l == n_layers - 1) ? logits : sum;
+        if (l == 0)
+            rc = qo_gemm_int(x32, w32, batch, dims[1], dims[0], dst);
+        else
+            rc = qo_gemm_pm1(act, W[l], batch, dims[l + 1], dims[l], dst);
+        if (rc != QO_OK) goto done;
+        if (l < n_layers - 1) qo_threshold(sum, batch, dims[l + 1], T[l], flip ? flip[l] : NULL, act);
+    }
+done:
+    free(sum);
+    free(act);
+    free(x32);
+    free(w32);
+    return rc;
+}
+
+/* Direct 2-D convolution (cross-correlation, as in every deep-learning framework) with zero padding on integer
+ * values; u is [B][H][W][Ci] (channels last), w is [Co][KH][KW][Ci] (the M_l x M_{l-1} x k x k filter bank of
+ * Sec. 5, channels last), out is [B][Ho][Wo][Co] with Ho = (H + 2*pad - KH) / stride + 1.  Inputs outside the
+ * image contribute exactly 0. */
+int qo_conv2d(const int32_t *u, int64_t B, int64_t H, int64_t Wd, int64_t Ci, const int32_t *w, int64_t Co,
+              int64_t KH, int64_t KW, int64_t pad, int64_t stride, int32_t *out) {
+    if (stride < 1 || H + 2 * pad < KH || Wd + 2 * pad < KW) return QO_ERR_ARG;
+    int64_t Ho = (H + 2 * pad - KH) / stride + 1, Wo = (Wd + 2 * pad - KW) / stride + 1;
+    int bad = 0;
+#pragma omp parallel for collapse(2) schedule(static) reduction(| : bad)
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t y = 0; y < Ho; ++y)
+            for (int64_t xo = 0; xo < Wo; ++xo)
+                for (int64_t co = 0; co < Co; ++co) {
+                    int64_t acc = 0;
+                    for (int64_t ky = 0; ky < KH; ++ky)
+                        for (int64_t kx = 0; kx < KW; ++kx) {
+                            int64_t iy = y * stride + ky - pad, ix = xo * stride + kx - pad;
+                            if (iy < 0 || iy >= H || ix < 0 || ix >= Wd) continue;
+                            const int32_t *up = u + ((b * H + iy) * Wd + ix) * Ci;
+                            const int32_t *wp = w + ((co * KH + ky) * KW + kx) * Ci;
+                            for (int64_t ci = 0; ci < Ci; ++ci) acc += (int64_t)up[ci] * (int64_t)wp[ci];
+                        }
+                    if (!fits_i32(acc)) bad = 1;
+                    out[((b * Ho + y) * Wo + xo) * Co + co] = (int32_t)acc;
+                }
+    return bad ? QO_ERR_RANGE : QO_OK;
+}
+
+/* Number of threads the OpenMP loops above actually use (reported beside the CPU-baseline timing). */
+int qo_num_threads(void) {
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}
