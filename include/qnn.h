@@ -1,0 +1,162 @@
+/*
+ * qnn.h - C ABI of the MI355X (gfx950) library for the run-time path of Quantized Neural Networks
+ * (Hubara, Courbariaux, Soudry, El-Yaniv, Bengio; arXiv 1609.07061).
+ *
+ * The path: sign-binarize and bit-pack values (Sec. 2.1 Eq. (1); Sec. 6 "concatenate groups of 32 binary variables
+ * into 32-bit registers"), multiply packed matrices by counting agreements (Sec. 6 Eq. (popc)), handle multi-bit
+ * inputs / activations / weights as weighted sums of binary products over bit planes (Sec. 2.6 Eq. (FirstLayer);
+ * Sec. 3), and apply Sign(BatchNorm(.)) between layers (Alg. 4) as an integer threshold per neuron.
+ *
+ * Conventions shared by every call
+ * --------------------------------
+ *  - Pointers marked DEVICE are HIP device pointers owned by the caller; the library never allocates, frees or keeps
+ *    them.  Pointers marked HOST are read during the call only.  In-place or overlapping input/output is undefined.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls only enqueue work on `stream`;
+ *    they do not synchronize.
+ *  - Return value: QNN_OK (0), or a positive qnn_status; on error nothing has been enqueued and
+ *    qnn_last_error() (thread-local) describes the problem.  Nothing throws across this boundary.
+ *  - Matrices are row-major.  A is M x K (one row per sample), W is N x K (one row per output neuron),
+ *    C = A . W^T is M x N.  Leading dimensions are in ELEMENTS of the pointed-to type.
+ *  - Packed format (the paper leaves it open; this is the library's definition): element k of a row lives in bit
+ *    (k mod 32), least significant first, of 32-bit word (k div 32); little-endian, so a 64-bit view of two words
+ *    holds 64 consecutive elements.  Bit 1 means +1 (sign planes) or 1 (bit planes); bit 0 means -1 or 0.
+ *    A packed row of K elements occupies ceil(K/32) words and ITS TAIL BITS (positions K .. 32*ceil(K/32)-1) MUST BE
+ *    ZERO.  The packing calls guarantee it; the multiply calls rely on it.
+ *  - Packed buffers must be 4-byte aligned; 16-byte aligned bases with leading dimensions that are multiples of 4
+ *    words enable the wide-load paths (anything else is still computed correctly, only slower).
+ *  - M == 0 or N == 0 is a successful no-op.  K must be >= 1.
+ */
+#ifndef QNN_H
+#define QNN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    QNN_OK = 0,
+    QNN_ERR_NULL = 1,        /* a required pointer is NULL */
+    QNN_ERR_SHAPE = 2,       /* a size, leading dimension, plane count or mode is out of range */
+    QNN_ERR_ALIGN = 3,       /* a pointer is not 4-byte aligned */
+    QNN_ERR_OVERFLOW = 4,    /* (sum |coefA|) * (sum |coefW|) * K does not fit int32 */
+    QNN_ERR_UNSUPPORTED = 5, /* requested variant cannot handle these arguments */
+    QNN_ERR_WORKSPACE = 6,   /* workspace NULL, misaligned (256 B) or too small */
+    QNN_ERR_HIP = 7          /* the HIP runtime reported an error at launch */
+} qnn_status;
+
+/* How the entries of a packed plane are read (Sec. 2.6 uses 0/1 bit planes of the input against -1/+1 weights). */
+typedef enum {
+    QNN_PLANE_BIT = 0, /* stored bit b is the number b        in {0, 1}  */
+    QNN_PLANE_SIGN = 1 /* stored bit b is the number 2b - 1   in {-1, +1} */
+} qnn_plane_mode;
+
+/* Which inner product engine a multiply uses.  Results are identical bit for bit; only the speed differs. */
+typedef enum {
+    QNN_ENGINE_AUTO = 0, /* library's choice for the shape */
+    QNN_ENGINE_VALU = 1, /* 32 connections per xor/and + popcount-accumulate pair (Sec. 6 Eq. (popc)) */
+    QNN_ENGINE_MFMA = 2  /* bits expanded on chip to int8 and contracted on the matrix cores */
+} qnn_engine;
+
+#define QNN_MAX_PLANES 8
+#define QNN_MAX_LAYERS 16
+
+/* S1. Deterministic binarization (Sec. 2.1 Eq. (1): +1 if x >= 0, -1 otherwise) fused with packing (Sec. 6).
+ * x: DEVICE float32 [rows][ldx], the first K of each row used.  out: DEVICE uint32 [rows][ldo_words], the first
+ * ceil(K/32) words of each row written (tail bits zero), the rest untouched.
+ * The comparison is IEEE on the value: +0, -0 -> +1; NaN -> -1; denormals are not flushed.
+ * Requires ldx >= K, ldo_words >= ceil(K/32). */
+int qnn_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo_words,
+                  void *stream);
+
+/* S1b. Bit planes of integer codes (Sec. 2.6: x^n is the n-th bit, n = 1 least significant ... n = nbits most
+ * significant) packed along K.  v: DEVICE uint8 [rows][ldv], one code per byte (two's-complement codes are passed
+ * as their low nbits).  planes: DEVICE uint32, plane p (= the paper's n - 1) of row r starts at
+ * planes + p * plane_stride_words + r * ld_words.  1 <= nbits <= 8. */
+int qnn_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,
+                       int64_t ld_words, int64_t plane_stride_words, void *stream);
+
+/* S2. Binary matrix product of Alg. 4 / Sec. 6 on packed +-1 operands:
+ * C[m][n] = sum_k a[m][k] w[n][k] = K - 2 * popcount(A[m] xor W[n])  (Eq. (popc) counts the agreements).
+ * A: DEVICE uint32 [M][lda_words], W: DEVICE uint32 [N][ldw_words], C: DEVICE int32 [M][ldc]. K < 2^31. */
+int qnn_binary_gemm(const uint32_t *A, int64_t lda_words, const uint32_t *W, int64_t ldw_words, int32_t *C,
+                    int64_t ldc, int64_t M, int64_t N, int64_t K, void *stream);
+
+/* Same product with the engine chosen by the caller (for measurements and tests). */
+int qnn_binary_gemm_ex(const uint32_t *A, int64_t lda_words, const uint32_t *W, int64_t ldw_words, int32_t *C,
+                       int64_t ldc, int64_t M, int64_t N, int64_t K, int engine, void *stream);
+
+/* S2+S4 fused. a^b = Sign(BatchNorm(a . W^T)) of Alg. 4 without materialising the int32 sums:
+ * bit[m][n] = (C[m][n] >= T[n]) xor flip[n], written packed along n (n is the next layer's K):
+ * out: DEVICE uint32 [M][ldo_words], first ceil(N/32) words of each row, tail bits zero.
+ * T: DEVICE int32 [N]; flip: DEVICE uint8 [N] (non-zero = invert) or NULL. */
+int qnn_binary_gemm_sign(const uint32_t *A, int64_t lda_words, const uint32_t *W, int64_t ldw_words,
+                         const int32_t *T, const uint8_t *flip, uint32_t *out, int64_t ldo_words, int64_t M,
+                         int64_t N, int64_t K, int engine, void *stream);
+
+/* S3. Multi-bit product as a weighted sum of binary products (Sec. 2.6 Eq. (FirstLayer), Sec. 3):
+ * C = sum_{i<Pa} sum_{j<Pb} coefA[i] * coefW[j] * (A_i . W_j^T), plane entries read according to modeA / modeW.
+ * A_i = A + i * strideA_words is [M][lda_words]; W_j = W + j * strideW_words is [N][ldw_words].
+ * coefA, coefW: HOST int32 arrays (e.g. 1,2,4,...,128 for 8-bit unsigned inputs; 1,2,4,-8 for 4-bit two's
+ * complement).  1 <= Pa, Pb <= QNN_MAX_PLANES.  QNN_ERR_OVERFLOW if (sum|coefA|)(sum|coefW|) K >= 2^31. */
+int qnn_bitplane_gemm(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
+                      int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
+                      int64_t ldw_words, int64_t strideW_words, int32_t *C, int64_t ldc, int64_t M, int64_t N,
+                      int64_t K, int engine, void *stream);
+
+/* S3+S4 fused: the first layer of Alg. 4 (eight weighted plane products, then Sign(BatchNorm(.))), output packed. */
+int qnn_bitplane_gemm_sign(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
+                           int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
+                           int64_t ldw_words, int64_t strideW_words, const int32_t *T, const uint8_t *flip,
+                           uint32_t *out, int64_t ldo_words, int64_t M, int64_t N, int64_t K, int engine,
+                           void *stream);
+
+/* S4. Sign(BatchNorm(.)) of Alg. 4 on materialised sums, with BatchNorm folded to an integer threshold:
+ * bit[m][n] = (C[m][n] >= T[n]) xor flip[n], packed along n.  C: DEVICE int32 [M][ldc]; T: DEVICE int32 [N];
+ * flip: DEVICE uint8 [N] or NULL; out: DEVICE uint32 [M][ldo_words] (first ceil(N/32) words per row). */
+int qnn_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
+                       uint32_t *out, int64_t ldo_words, void *stream);
+
+/* Host helper: fold inference-time BatchNorm y = gamma (s - mean) / sqrt(var + eps) + beta followed by Eq. (1)
+ * into (T, flip) such that for every integer s:  (y >= 0)  <=>  ((s >= T) xor flip).
+ * gamma > 0: T = ceil(mean - beta sqrt(var+eps) / gamma), flip = 0;  gamma < 0: T = floor(same) + 1, flip = 1;
+ * gamma == 0: T = INT32_MIN, flip = (beta < 0).  Thresholds beyond int32 saturate (the comparison then has a
+ * constant outcome for every representable s).  All arrays HOST, length n; computed in double.  No GPU involved. */
+int qnn_fold_batchnorm(const double *gamma, const double *beta, const double *mean, const double *var, double eps,
+                       int64_t n, int32_t *T, uint8_t *flip);
+
+/* S5. Alg. 4 end to end, up to the integer output-layer sums: in_bits-bit unsigned inputs -> bit planes -> first
+ * layer as weighted plane products -> Sign(BatchNorm) -> binary layers -> int32 logits of the last layer.
+ * x: DEVICE uint8 [batch][ldx].  dims: HOST int64 [n_layers + 1] (dims[0] = input width).
+ * W: HOST array of n_layers DEVICE pointers, W[l] packed +-1 [dims[l+1]][ceil(dims[l]/32)] (dense rows).
+ * T, flip: HOST arrays of n_layers - 1 DEVICE pointers (flip, or any flip[l], may be NULL).
+ * logits: DEVICE int32 [batch][ld_logits].  workspace: DEVICE, 256-byte aligned, at least
+ * qnn_binary_mlp_workspace_bytes(...) bytes, contents undefined before and after.
+ * 2 <= n_layers <= QNN_MAX_LAYERS, 1 <= in_bits <= 8. */
+int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers,
+                           const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
+                           const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,
+                           size_t workspace_bytes, int engine, void *stream);
+size_t qnn_binary_mlp_workspace_bytes(int64_t batch, int in_bits, int n_layers, const int64_t *dims);
+
+/* Binarized convolution (Sec. 5 filter bank M_l x M_{l-1} x k x k; Sec. 3 multi-bit activations) without
+ * materialising patches.  Activations: Pa bit planes, channels-last and packed along channels:
+ * plane i of pixel (b, y, x) is Cw = ceil(Cin/32) words at A + i * strideA_words + ((b*H + y)*Wd + x) * Cw.
+ * Weights: Pb planes, filter co is [KH][KW][Cw] words at W + j * strideW_words + co * KH*KW*Cw.
+ * Output: DEVICE int32 [B][Ho][Wo][Cout] dense, Ho = (H + 2 pad - KH) / stride + 1.
+ * Padding pixels contribute exactly 0, which a bit-mode activation encodes as all-zero bits; a sign-mode activation
+ * cannot encode 0, so modeA == QNN_PLANE_SIGN with pad > 0 is QNN_ERR_UNSUPPORTED. */
+int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
+                        int64_t B, int64_t H, int64_t Wd, int64_t Cin, const uint32_t *W, int Pb,
+                        const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
+                        int pad, int stride_hw, int32_t *out, int engine, void *stream);
+
+const char *qnn_last_error(void);
+const char *qnn_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QNN_H */

@@ -1,0 +1,272 @@
+"""Python binding of libqnn (the C ABI in include/qnn.h): argument marshalling only.
+
+Every function has the name of the C entry point it forwards to, takes torch tensors that live on the GPU (PyTorch is
+used for device memory and streams, nothing else), passes their data pointers plus the current HIP stream, and raises
+QnnError on a non-zero status.  Packed words are carried in torch.int32 tensors (same 32 bits as the uint32 of the ABI).
+There is no CPU fallback: importing this package fails if the built library is missing.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+PLANE_BIT, PLANE_SIGN = 0, 1
+ENGINE_AUTO, ENGINE_VALU, ENGINE_MFMA = 0, 1, 2
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqnn.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first with `python -m paper_1609_07061_amd.build` "
+        "(or __graft_entry__.build()); this package has no fallback path"
+    )
+_lib = C.CDLL(LIB_PATH)
+
+_i64, _int, _vp, _sz = C.c_int64, C.c_int, C.c_void_p, C.c_size_t
+_SIGS = {
+    "qnn_pack_sign": [_vp, _i64, _i64, _i64, _vp, _i64, _vp],
+    "qnn_pack_bitplanes": [_vp, _i64, _i64, _i64, _int, _vp, _i64, _i64, _vp],
+    "qnn_binary_gemm": [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _vp],
+    "qnn_binary_gemm_ex": [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _int, _vp],
+    "qnn_binary_gemm_sign": [_vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp],
+    "qnn_bitplane_gemm": [_vp, _int, _vp, _int, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _vp, _i64, _i64, _i64,
+                          _i64, _int, _vp],
+    "qnn_bitplane_gemm_sign": [_vp, _int, _vp, _int, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _vp, _vp, _vp, _i64,
+                               _i64, _i64, _i64, _int, _vp],
+    "qnn_threshold_sign": [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _vp],
+    "qnn_fold_batchnorm": [_vp, _vp, _vp, _vp, C.c_double, _i64, _vp, _vp],
+    "qnn_binary_mlp_forward": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _int, _vp],
+    "qnn_bitplane_conv2d": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
+                            _int, _int, _int, _vp, _int, _vp],
+}
+for _name, _args in _SIGS.items():
+    _f = getattr(_lib, _name)
+    _f.argtypes = _args
+    _f.restype = C.c_int
+_lib.qnn_binary_mlp_workspace_bytes.argtypes = [_i64, _int, _int, _vp]
+_lib.qnn_binary_mlp_workspace_bytes.restype = _sz
+_lib.qnn_last_error.restype = C.c_char_p
+_lib.qnn_version.restype = C.c_char_p
+
+EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_last_error", "qnn_version"])
+
+
+class QnnError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"qnn status {status}: {message}")
+        self.status = status
+
+
+def _check(status: int):
+    if status != 0:
+        raise QnnError(status, _lib.qnn_last_error().decode())
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dev(t: Optional[torch.Tensor], dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a GPU tensor")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}, got {t.dtype}")
+    return t.data_ptr()
+
+
+def _rows_ld(t: torch.Tensor, name: str):
+    """(rows, cols, leading dimension) of a 2-D tensor whose rows are contiguous."""
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with contiguous rows")
+    ld = t.stride(0) if t.shape[0] > 1 else max(t.shape[1], 1)
+    return t.shape[0], t.shape[1], ld
+
+
+def _planes_ld(t: torch.Tensor, name: str):
+    """(planes, rows, words, ld, plane stride) of a [P][rows][words] tensor."""
+    if t.dim() != 3 or (t.shape[2] > 1 and t.stride(2) != 1):
+        raise ValueError(f"{name} must be [planes][rows][words] with contiguous rows")
+    ld = t.stride(1) if t.shape[1] > 1 else max(t.shape[2], 1)
+    ps = t.stride(0) if t.shape[0] > 1 else 0
+    return t.shape[0], t.shape[1], t.shape[2], ld, ps
+
+
+def _coef(c: Sequence[int]):
+    return (C.c_int32 * len(c))(*[int(v) for v in c])
+
+
+def words_for(K: int) -> int:
+    return (K + 31) // 32
+
+
+def qnn_version() -> str:
+    return _lib.qnn_version().decode()
+
+
+def qnn_pack_sign(x: torch.Tensor, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    rows, K, ldx = _rows_ld(x, "x")
+    if out is None:
+        out = torch.empty((rows, words_for(K)), dtype=torch.int32, device=x.device)
+    _, _, ldo = _rows_ld(out, "out")
+    _check(_lib.qnn_pack_sign(_dev(x, torch.float32, "x"), rows, K, ldx, _dev(out, torch.int32, "out"), ldo, _stream()))
+    return out
+
+
+def qnn_pack_bitplanes(v: torch.Tensor, nbits: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    rows, K, ldv = _rows_ld(v, "v")
+    if out is None:
+        out = torch.empty((nbits, rows, words_for(K)), dtype=torch.int32, device=v.device)
+    P, _, _, ld, ps = _planes_ld(out, "out")
+    if P != nbits:
+        raise ValueError("out must have nbits planes")
+    _check(_lib.qnn_pack_bitplanes(_dev(v, torch.uint8, "v"), rows, K, ldv, nbits, _dev(out, torch.int32, "out"), ld,
+                                   ps, _stream()))
+    return out
+
+
+def qnn_binary_gemm(A: torch.Tensor, W: torch.Tensor, K: int, out: Optional[torch.Tensor] = None,
+                    engine: Optional[int] = None) -> torch.Tensor:
+    M, _, lda = _rows_ld(A, "A")
+    N, _, ldw = _rows_ld(W, "W")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _, _, ldc = _rows_ld(out, "out")
+    a, w, c = _dev(A, torch.int32, "A"), _dev(W, torch.int32, "W"), _dev(out, torch.int32, "out")
+    if engine is None:
+        _check(_lib.qnn_binary_gemm(a, lda, w, ldw, c, ldc, M, N, K, _stream()))
+    else:
+        _check(_lib.qnn_binary_gemm_ex(a, lda, w, ldw, c, ldc, M, N, K, engine, _stream()))
+    return out
+
+
+def qnn_binary_gemm_sign(A: torch.Tensor, W: torch.Tensor, K: int, T: torch.Tensor,
+                         flip: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                         engine: int = ENGINE_AUTO) -> torch.Tensor:
+    M, _, lda = _rows_ld(A, "A")
+    N, _, ldw = _rows_ld(W, "W")
+    if out is None:
+        out = torch.empty((M, words_for(N)), dtype=torch.int32, device=A.device)
+    _, _, ldo = _rows_ld(out, "out")
+    _check(_lib.qnn_binary_gemm_sign(_dev(A, torch.int32, "A"), lda, _dev(W, torch.int32, "W"), ldw,
+                                     _dev(T, torch.int32, "T"), _dev(flip, torch.uint8, "flip"),
+                                     _dev(out, torch.int32, "out"), ldo, M, N, K, engine, _stream()))
+    return out
+
+
+def qnn_bitplane_gemm(A: torch.Tensor, coefA: Sequence[int], modeA: int, W: torch.Tensor, coefW: Sequence[int],
+                      modeW: int, K: int, out: Optional[torch.Tensor] = None, engine: int = ENGINE_AUTO) -> torch.Tensor:
+    Pa, M, _, lda, sa = _planes_ld(A, "A")
+    Pb, N, _, ldw, sw = _planes_ld(W, "W")
+    if len(coefA) != Pa or len(coefW) != Pb:
+        raise ValueError("one coefficient per plane")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.int32, device=A.device)
+    _, _, ldc = _rows_ld(out, "out")
+    _check(_lib.qnn_bitplane_gemm(_dev(A, torch.int32, "A"), Pa, _coef(coefA), modeA, lda, sa,
+                                  _dev(W, torch.int32, "W"), Pb, _coef(coefW), modeW, ldw, sw,
+                                  _dev(out, torch.int32, "out"), ldc, M, N, K, engine, _stream()))
+    return out
+
+
+def qnn_bitplane_gemm_sign(A: torch.Tensor, coefA: Sequence[int], modeA: int, W: torch.Tensor, coefW: Sequence[int],
+                           modeW: int, K: int, T: torch.Tensor, flip: Optional[torch.Tensor] = None,
+                           out: Optional[torch.Tensor] = None, engine: int = ENGINE_AUTO) -> torch.Tensor:
+    Pa, M, _, lda, sa = _planes_ld(A, "A")
+    Pb, N, _, ldw, sw = _planes_ld(W, "W")
+    if len(coefA) != Pa or len(coefW) != Pb:
+        raise ValueError("one coefficient per plane")
+    if out is None:
+        out = torch.empty((M, words_for(N)), dtype=torch.int32, device=A.device)
+    _, _, ldo = _rows_ld(out, "out")
+    _check(_lib.qnn_bitplane_gemm_sign(_dev(A, torch.int32, "A"), Pa, _coef(coefA), modeA, lda, sa,
+                                       _dev(W, torch.int32, "W"), Pb, _coef(coefW), modeW, ldw, sw,
+                                       _dev(T, torch.int32, "T"), _dev(flip, torch.uint8, "flip"),
+                                       _dev(out, torch.int32, "out"), ldo, M, N, K, engine, _stream()))
+    return out
+
+
+def qnn_threshold_sign(Cm: torch.Tensor, T: torch.Tensor, flip: Optional[torch.Tensor] = None,
+                       out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    M, N, ldc = _rows_ld(Cm, "C")
+    if out is None:
+        out = torch.empty((M, words_for(N)), dtype=torch.int32, device=Cm.device)
+    _, _, ldo = _rows_ld(out, "out")
+    _check(_lib.qnn_threshold_sign(_dev(Cm, torch.int32, "C"), ldc, M, N, _dev(T, torch.int32, "T"),
+                                   _dev(flip, torch.uint8, "flip"), _dev(out, torch.int32, "out"), ldo, _stream()))
+    return out
+
+
+def qnn_fold_batchnorm(gamma, beta, mean, var, eps: float):
+    """Host-only helper (numpy float64 arrays in, (int32 T, uint8 flip) numpy arrays out)."""
+    import numpy as np
+
+    g, b, m, v = (np.ascontiguousarray(a, dtype=np.float64) for a in (gamma, beta, mean, var))
+    n = g.size
+    T = np.empty(n, dtype=np.int32)
+    flip = np.empty(n, dtype=np.uint8)
+    _check(_lib.qnn_fold_batchnorm(g.ctypes.data, b.ctypes.data, m.ctypes.data, v.ctypes.data, float(eps), n,
+                                   T.ctypes.data, flip.ctypes.data))
+    return T, flip
+
+
+def qnn_binary_mlp_workspace_bytes(batch: int, in_bits: int, dims: Sequence[int]) -> int:
+    d = (C.c_int64 * len(dims))(*[int(v) for v in dims])
+    return int(_lib.qnn_binary_mlp_workspace_bytes(batch, in_bits, len(dims) - 1, d))
+
+
+def qnn_binary_mlp_forward(x: torch.Tensor, in_bits: int, dims: Sequence[int], W: Sequence[torch.Tensor],
+                           T: Sequence[torch.Tensor], flip: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                           logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                           engine: int = ENGINE_AUTO) -> torch.Tensor:
+    batch, _, ldx = _rows_ld(x, "x")
+    L = len(dims) - 1
+    if len(W) != L or len(T) != L - 1:
+        raise ValueError("need one W per layer and one T per hidden layer")
+    for l, w in enumerate(W):
+        if w.dim() != 2 or not w.is_contiguous() or tuple(w.shape) != (dims[l + 1], words_for(dims[l])):
+            raise ValueError(f"W[{l}] must be dense [{dims[l + 1]}][{words_for(dims[l])}]")
+    if logits is None:
+        logits = torch.empty((batch, dims[-1]), dtype=torch.int32, device=x.device)
+    _, _, ldl = _rows_ld(logits, "logits")
+    need = qnn_binary_mlp_workspace_bytes(batch, in_bits, dims)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+    d = (C.c_int64 * (L + 1))(*[int(v) for v in dims])
+    Wp = (C.c_void_p * L)(*[_dev(w, torch.int32, "W") for w in W])
+    Tp = (C.c_void_p * max(L - 1, 1))(*[_dev(t, torch.int32, "T") for t in T])
+    Fp = None
+    if flip is not None:
+        Fp = (C.c_void_p * max(L - 1, 1))(*[_dev(f, torch.uint8, "flip") for f in flip])
+    _check(_lib.qnn_binary_mlp_forward(_dev(x, torch.uint8, "x"), batch, ldx, in_bits, L, d, Wp, Tp, Fp,
+                                       _dev(logits, torch.int32, "logits"), ldl,
+                                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(), engine, _stream()))
+    return logits
+
+
+def qnn_bitplane_conv2d(A: torch.Tensor, coefA: Sequence[int], modeA: int, Cin: int, W: torch.Tensor,
+                        coefW: Sequence[int], modeW: int, pad: int, stride: int = 1,
+                        out: Optional[torch.Tensor] = None, engine: int = ENGINE_AUTO) -> torch.Tensor:
+    """A: [Pa][B][H][W][Cw] packed planes (dense); W: [Pb][Cout][KH][KW][Cw] packed planes (dense)."""
+    if A.dim() != 5 or W.dim() != 5 or not A.is_contiguous() or not W.is_contiguous():
+        raise ValueError("A must be dense [Pa][B][H][W][Cw] and W dense [Pb][Cout][KH][KW][Cw]")
+    Pa, B, H, Wd, Cw = A.shape
+    Pb, Cout, KH, KW, Cw2 = W.shape
+    if Cw != words_for(Cin) or Cw2 != Cw:
+        raise ValueError("channel words do not match Cin")
+    Ho = (H + 2 * pad - KH) // stride + 1
+    Wo = (Wd + 2 * pad - KW) // stride + 1
+    if out is None:
+        out = torch.empty((B, Ho, Wo, Cout), dtype=torch.int32, device=A.device)
+    if not out.is_contiguous() or tuple(out.shape) != (B, Ho, Wo, Cout):
+        raise ValueError("out must be dense [B][Ho][Wo][Cout]")
+    _check(_lib.qnn_bitplane_conv2d(_dev(A, torch.int32, "A"), Pa, _coef(coefA), modeA, A.stride(0) if Pa > 1 else 0,
+                                    B, H, Wd, Cin, _dev(W, torch.int32, "W"), Pb, _coef(coefW), modeW,
+                                    W.stride(0) if Pb > 1 else 0, Cout, KH, KW, pad, stride,
+                                    _dev(out, torch.int32, "out"), engine, _stream()))
+    return out

@@ -1,0 +1,359 @@
+// Entry points of libqnn: argument validation, engine choice and the multi-launch compositions (Alg. 4 forward).
+// Every step of the path runs in the kernels of this library; nothing here computes on the host except the
+// BatchNorm fold, which is host-only by definition.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "qnn_internal.h"
+
+namespace qnn {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int check_launch(const char *what) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail(QNN_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+    return QNN_OK;
+}
+
+namespace {
+
+bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+int64_t sum_abs(const int32_t *c, int n) {
+    int64_t s = 0;
+    for (int i = 0; i < n; ++i) s += c[i] < 0 ? -(int64_t)c[i] : (int64_t)c[i];
+    return s;
+}
+
+int check_planes(const char *who, int P, const int32_t *coef, int mode) {
+    if (P < 1 || P > QNN_MAX_PLANES) return fail(QNN_ERR_SHAPE, "%s: plane count %d not in 1..%d", who, P, QNN_MAX_PLANES);
+    if (!coef) return fail(QNN_ERR_NULL, "%s: coefficient array is NULL", who);
+    if (mode != QNN_PLANE_BIT && mode != QNN_PLANE_SIGN) return fail(QNN_ERR_SHAPE, "%s: unknown plane mode %d", who, mode);
+    return QNN_OK;
+}
+
+int check_engine(int engine) {
+    if (engine != QNN_ENGINE_AUTO && engine != QNN_ENGINE_VALU && engine != QNN_ENGINE_MFMA)
+        return fail(QNN_ERR_SHAPE, "unknown engine %d", engine);
+    return QNN_OK;
+}
+
+int check_range(const GemmArgs &g) {
+    const int64_t sa = sum_abs(g.pa.coef, g.pa.count), sw = sum_abs(g.pw.coef, g.pw.count);
+    // |C| <= sa * sw * K must stay below 2^31
+    const long double bound = (long double)sa * (long double)sw * (long double)g.K;
+    if (bound >= 2147483648.0L)
+        return fail(QNN_ERR_OVERFLOW, "sum|coefA| * sum|coefW| * K = %.0Lf does not fit int32", bound);
+    return QNN_OK;
+}
+
+int dispatch(const GemmArgs &g, int engine, hipStream_t s) {
+    if (engine == QNN_ENGINE_MFMA) {
+        if (!mfma_supports(g)) return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
+        return launch_gemm_mfma(g, s);
+    }
+    if (engine == QNN_ENGINE_AUTO && mfma_supports(g)) return launch_gemm_mfma(g, s);
+    return launch_gemm_valu(g, s);
+}
+
+// Shared validation + launch of the matrix-shaped products.
+int gemm_common(const char *who, const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda,
+                int64_t strideA, const uint32_t *W, int Pb, const int32_t *coefW, int modeW, int64_t ldw,
+                int64_t strideW, const Epilogue &epi, int64_t M, int64_t N, int64_t K, int engine, void *stream) {
+    if (int rc = check_engine(engine)) return rc;
+    if (M < 0 || N < 0) return fail(QNN_ERR_SHAPE, "%s: negative M or N", who);
+    if (K < 1 || K > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "%s: K = %lld out of range", who, (long long)K);
+    if (int rc = check_planes(who, Pa, coefA, modeA)) return rc;
+    if (int rc = check_planes(who, Pb, coefW, modeW)) return rc;
+    const int64_t Kw = words_for(K);
+    if (lda < Kw || ldw < Kw) return fail(QNN_ERR_SHAPE, "%s: leading dimension below ceil(K/32) = %lld", who, (long long)Kw);
+    if (Pa > 1 && strideA < 0) return fail(QNN_ERR_SHAPE, "%s: negative plane stride", who);
+    if (Pb > 1 && strideW < 0) return fail(QNN_ERR_SHAPE, "%s: negative plane stride", who);
+    if (epi.T) {
+        if (epi.ldo < words_for(N)) return fail(QNN_ERR_SHAPE, "%s: ldo_words below ceil(N/32)", who);
+    } else {
+        if (epi.ldc < N) return fail(QNN_ERR_SHAPE, "%s: ldc below N", who);
+    }
+    if (M == 0 || N == 0) return QNN_OK;
+    if (!A || !W) return fail(QNN_ERR_NULL, "%s: operand pointer is NULL", who);
+    if (epi.T ? !epi.out_bits : !epi.C) return fail(QNN_ERR_NULL, "%s: output pointer is NULL", who);
+    if (!aligned4(A) || !aligned4(W) || !aligned4(epi.C) || !aligned4(epi.out_bits) || !aligned4(epi.T))
+        return fail(QNN_ERR_ALIGN, "%s: pointer not 4-byte aligned", who);
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A.base = A;
+    g.A.ld = lda;
+    g.A.plane_stride = strideA;
+    g.pa.count = Pa;
+    g.pa.mode = modeA;
+    for (int i = 0; i < Pa; ++i) g.pa.coef[i] = coefA[i];
+    g.W = W;
+    g.ldw = ldw;
+    g.strideW = strideW;
+    g.pw.count = Pb;
+    g.pw.mode = modeW;
+    for (int i = 0; i < Pb; ++i) g.pw.coef[i] = coefW[i];
+    g.epi = epi;
+    g.M = M;
+    g.N = N;
+    g.K = K;
+    g.Kw = Kw;
+    if (int rc = check_range(g)) return rc;
+    return dispatch(g, engine, static_cast<hipStream_t>(stream));
+}
+
+const int32_t kOne[1] = {1};
+
+}  // namespace
+}  // namespace qnn
+
+using namespace qnn;
+
+extern "C" {
+
+int qnn_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo_words,
+                  void *stream) {
+    if (rows < 0 || K < 1) return fail(QNN_ERR_SHAPE, "pack_sign: rows = %lld, K = %lld", (long long)rows, (long long)K);
+    if (ldx < K || ldo_words < words_for(K)) return fail(QNN_ERR_SHAPE, "pack_sign: leading dimension too small");
+    if (rows == 0) return QNN_OK;
+    if (!x || !out) return fail(QNN_ERR_NULL, "pack_sign: NULL pointer");
+    if (!aligned4(x) || !aligned4(out)) return fail(QNN_ERR_ALIGN, "pack_sign: pointer not 4-byte aligned");
+    return launch_pack_sign(x, rows, K, ldx, out, ldo_words, static_cast<hipStream_t>(stream));
+}
+
+int qnn_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,
+                       int64_t ld_words, int64_t plane_stride_words, void *stream) {
+    if (rows < 0 || K < 1) return fail(QNN_ERR_SHAPE, "pack_bitplanes: rows = %lld, K = %lld", (long long)rows, (long long)K);
+    if (nbits < 1 || nbits > 8) return fail(QNN_ERR_SHAPE, "pack_bitplanes: nbits = %d not in 1..8", nbits);
+    if (ldv < K || ld_words < words_for(K)) return fail(QNN_ERR_SHAPE, "pack_bitplanes: leading dimension too small");
+    if (nbits > 1 && plane_stride_words < 0) return fail(QNN_ERR_SHAPE, "pack_bitplanes: negative plane stride");
+    if (rows == 0) return QNN_OK;
+    if (!v || !planes) return fail(QNN_ERR_NULL, "pack_bitplanes: NULL pointer");
+    if (!aligned4(planes)) return fail(QNN_ERR_ALIGN, "pack_bitplanes: output not 4-byte aligned");
+    return launch_pack_bitplanes(v, rows, K, ldv, nbits, planes, ld_words, plane_stride_words,
+                                 static_cast<hipStream_t>(stream));
+}
+
+int qnn_binary_gemm_ex(const uint32_t *A, int64_t lda_words, const uint32_t *W, int64_t ldw_words, int32_t *C,
+                       int64_t ldc, int64_t M, int64_t N, int64_t K, int engine, void *stream) {
+    Epilogue e{C, ldc, nullptr, nullptr, nullptr, 0};
+    return gemm_common("binary_gemm", A, 1, kOne, QNN_PLANE_SIGN, lda_words, 0, W, 1, kOne, QNN_PLANE_SIGN, ldw_words,
+                       0, e, M, N, K, engine, stream);
+}
+
+int qnn_binary_gemm(const uint32_t *A, int64_t lda_words, const uint32_t *W, int64_t ldw_words, int32_t *C,
+                    int64_t ldc, int64_t M, int64_t N, int64_t K, void *stream) {
+    return qnn_binary_gemm_ex(A, lda_words, W, ldw_words, C, ldc, M, N, K, QNN_ENGINE_AUTO, stream);
+}
+
+int qnn_binary_gemm_sign(const uint32_t *A, int64_t lda_words, const uint32_t *W, int64_t ldw_words,
+                         const int32_t *T, const uint8_t *flip, uint32_t *out, int64_t ldo_words, int64_t M,
+                         int64_t N, int64_t K, int engine, void *stream) {
+    if (!T && M > 0 && N > 0) return fail(QNN_ERR_NULL, "binary_gemm_sign: threshold pointer is NULL");
+    Epilogue e{nullptr, 0, T, flip, out, ldo_words};
+    return gemm_common("binary_gemm_sign", A, 1, kOne, QNN_PLANE_SIGN, lda_words, 0, W, 1, kOne, QNN_PLANE_SIGN,
+                       ldw_words, 0, e, M, N, K, engine, stream);
+}
+
+int qnn_bitplane_gemm(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
+                      int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
+                      int64_t ldw_words, int64_t strideW_words, int32_t *C, int64_t ldc, int64_t M, int64_t N,
+                      int64_t K, int engine, void *stream) {
+    Epilogue e{C, ldc, nullptr, nullptr, nullptr, 0};
+    return gemm_common("bitplane_gemm", A, Pa, coefA, modeA, lda_words, strideA_words, W, Pb, coefW, modeW, ldw_words,
+                       strideW_words, e, M, N, K, engine, stream);
+}
+
+int qnn_bitplane_gemm_sign(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
+                           int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
+                           int64_t ldw_words, int64_t strideW_words, const int32_t *T, const uint8_t *flip,
+                           uint32_t *out, int64_t ldo_words, int64_t M, int64_t N, int64_t K, int engine,
+                           void *stream) {
+    if (!T && M > 0 && N > 0) return fail(QNN_ERR_NULL, "bitplane_gemm_sign: threshold pointer is NULL");
+    Epilogue e{nullptr, 0, T, flip, out, ldo_words};
+    return gemm_common("bitplane_gemm_sign", A, Pa, coefA, modeA, lda_words, strideA_words, W, Pb, coefW, modeW,
+                       ldw_words, strideW_words, e, M, N, K, engine, stream);
+}
+
+int qnn_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
+                       uint32_t *out, int64_t ldo_words, void *stream) {
+    if (M < 0 || N < 0) return fail(QNN_ERR_SHAPE, "threshold_sign: negative M or N");
+    if (ldc < N || ldo_words < words_for(N)) return fail(QNN_ERR_SHAPE, "threshold_sign: leading dimension too small");
+    if (M == 0 || N == 0) return QNN_OK;
+    if (!C || !T || !out) return fail(QNN_ERR_NULL, "threshold_sign: NULL pointer");
+    if (!aligned4(C) || !aligned4(T) || !aligned4(out)) return fail(QNN_ERR_ALIGN, "threshold_sign: pointer not 4-byte aligned");
+    return launch_threshold_sign(C, ldc, M, N, T, flip, out, ldo_words, static_cast<hipStream_t>(stream));
+}
+
+int qnn_fold_batchnorm(const double *gamma, const double *beta, const double *mean, const double *var, double eps,
+                       int64_t n, int32_t *T, uint8_t *flip) {
+    if (n < 0) return fail(QNN_ERR_SHAPE, "fold_batchnorm: negative n");
+    if (n == 0) return QNN_OK;
+    if (!gamma || !beta || !mean || !var || !T || !flip) return fail(QNN_ERR_NULL, "fold_batchnorm: NULL pointer");
+    for (int64_t i = 0; i < n; ++i) {
+        if (!(var[i] + eps > 0.0)) return fail(QNN_ERR_SHAPE, "fold_batchnorm: var + eps <= 0 at %lld", (long long)i);
+        if (gamma[i] == 0.0 || std::isnan(gamma[i])) {
+            // y = beta for every s: constant sign
+            T[i] = INT32_MIN;
+            flip[i] = (beta[i] >= 0.0) ? 0 : 1;
+            continue;
+        }
+        // y >= 0  <=>  gamma * (s - mean) >= -beta * sd  <=>  s >= tau (gamma > 0)  or  s <= tau (gamma < 0)
+        const double tau = mean[i] - beta[i] * std::sqrt(var[i] + eps) / gamma[i];
+        double t;
+        if (gamma[i] > 0.0) {
+            t = std::ceil(tau);
+            flip[i] = 0;
+        } else {
+            t = std::floor(tau) + 1.0;  // s <= floor(tau)  <=>  not (s >= floor(tau) + 1)
+            flip[i] = 1;
+        }
+        if (std::isnan(t)) return fail(QNN_ERR_SHAPE, "fold_batchnorm: NaN threshold at %lld", (long long)i);
+        // saturate: s >= INT32_MIN is always true; a threshold above INT32_MAX is never reached, and INT32_MAX
+        // itself is unreachable for any sum the multiply calls accept (|C| < 2^31 - 1 is not guaranteed, so keep
+        // exactness by only clamping values strictly outside the int32 range)
+        if (t <= -2147483648.0)
+            T[i] = INT32_MIN;
+        else if (t > 2147483647.0) {
+            // never true: encode as "always true" with the opposite flip
+            T[i] = INT32_MIN;
+            flip[i] = flip[i] ? 0 : 1;
+        } else
+            T[i] = (int32_t)t;
+    }
+    return QNN_OK;
+}
+
+size_t qnn_binary_mlp_workspace_bytes(int64_t batch, int in_bits, int n_layers, const int64_t *dims) {
+    if (batch < 0 || in_bits < 1 || in_bits > 8 || n_layers < 2 || n_layers > QNN_MAX_LAYERS || !dims) return 0;
+    auto round256 = [](size_t b) { return (b + 255) & ~(size_t)255; };
+    // rows padded to a multiple of 4 words so that every buffer takes the wide-load path
+    auto ldw = [](int64_t d) { return (size_t)((words_for(d) + 3) & ~(int64_t)3); };
+    size_t planes = round256((size_t)in_bits * (size_t)batch * ldw(dims[0]) * 4);
+    size_t act = 0;
+    for (int l = 1; l < n_layers; ++l) {
+        size_t b = round256((size_t)batch * ldw(dims[l]) * 4);
+        if (b > act) act = b;
+    }
+    return planes + 2 * act + 256;
+}
+
+int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers,
+                           const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
+                           const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,
+                           size_t workspace_bytes, int engine, void *stream) {
+    if (int rc = check_engine(engine)) return rc;
+    if (batch < 0) return fail(QNN_ERR_SHAPE, "mlp: negative batch");
+    if (in_bits < 1 || in_bits > 8) return fail(QNN_ERR_SHAPE, "mlp: in_bits = %d not in 1..8", in_bits);
+    if (n_layers < 2 || n_layers > QNN_MAX_LAYERS) return fail(QNN_ERR_SHAPE, "mlp: n_layers = %d not in 2..%d", n_layers, QNN_MAX_LAYERS);
+    if (!dims || !W || !T) return fail(QNN_ERR_NULL, "mlp: dims / W / T array is NULL");
+    for (int l = 0; l <= n_layers; ++l)
+        if (dims[l] < 1 || dims[l] > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "mlp: dims[%d] = %lld", l, (long long)dims[l]);
+    if (ldx < dims[0] || ld_logits < dims[n_layers]) return fail(QNN_ERR_SHAPE, "mlp: leading dimension too small");
+    if (batch == 0) return QNN_OK;
+    if (!x || !logits) return fail(QNN_ERR_NULL, "mlp: x or logits is NULL");
+    for (int l = 0; l < n_layers; ++l) {
+        if (!W[l]) return fail(QNN_ERR_NULL, "mlp: W[%d] is NULL", l);
+        if (l < n_layers - 1 && !T[l]) return fail(QNN_ERR_NULL, "mlp: T[%d] is NULL", l);
+    }
+    const size_t need = qnn_binary_mlp_workspace_bytes(batch, in_bits, n_layers, dims);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+        return fail(QNN_ERR_WORKSPACE, "mlp: workspace must be 256-byte aligned and hold %zu bytes", need);
+
+    auto round256 = [](size_t b) { return (b + 255) & ~(size_t)255; };
+    auto ldw = [](int64_t d) { return (int64_t)((words_for(d) + 3) & ~(int64_t)3); };
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    uint32_t *planes = reinterpret_cast<uint32_t *>(ws);
+    const int64_t ld0 = ldw(dims[0]);
+    const int64_t plane_stride = batch * ld0;
+    size_t off = round256((size_t)in_bits * (size_t)plane_stride * 4);
+    size_t act_bytes = 0;
+    for (int l = 1; l < n_layers; ++l) {
+        size_t b = round256((size_t)batch * (size_t)ldw(dims[l]) * 4);
+        if (b > act_bytes) act_bytes = b;
+    }
+    uint32_t *act[2] = {reinterpret_cast<uint32_t *>(ws + off), reinterpret_cast<uint32_t *>(ws + off + act_bytes)};
+
+    // Alg. 4, step 1: bit planes of the input, then sum_n 2^(n-1) (x^n . W_1) followed by Sign(BatchNorm)
+    if (int rc = qnn_pack_bitplanes(x, batch, dims[0], ldx, in_bits, planes, ld0, plane_stride, stream)) return rc;
+    int32_t coef[QNN_MAX_PLANES];
+    for (int p = 0; p < in_bits; ++p) coef[p] = 1 << p;
+    if (int rc = qnn_bitplane_gemm_sign(planes, in_bits, coef, QNN_PLANE_BIT, ld0, plane_stride, W[0], 1, kOne,
+                                        QNN_PLANE_SIGN, words_for(dims[0]), 0, T[0], flip ? flip[0] : nullptr, act[0],
+                                        ldw(dims[1]), batch, dims[1], dims[0], engine, stream))
+        return rc;
+    // step 2: hidden layers, product + threshold fused
+    int cur = 0;
+    for (int l = 1; l < n_layers - 1; ++l) {
+        if (int rc = qnn_binary_gemm_sign(act[cur], ldw(dims[l]), W[l], words_for(dims[l]), T[l],
+                                          flip ? flip[l] : nullptr, act[cur ^ 1], ldw(dims[l + 1]), batch,
+                                          dims[l + 1], dims[l], engine, stream))
+            return rc;
+        cur ^= 1;
+    }
+    // step 3: output layer, integer sums
+    const int L = n_layers - 1;
+    return qnn_binary_gemm_ex(act[cur], ldw(dims[L]), W[L], words_for(dims[L]), logits, ld_logits, batch, dims[L + 1],
+                              dims[L], engine, stream);
+}
+
+int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
+                        int64_t B, int64_t H, int64_t Wd, int64_t Cin, const uint32_t *W, int Pb,
+                        const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
+                        int pad, int stride_hw, int32_t *out, int engine, void *stream) {
+    if (int rc = check_engine(engine)) return rc;
+    if (B < 0 || Cout < 0) return fail(QNN_ERR_SHAPE, "conv2d: negative batch or Cout");
+    if (H < 1 || Wd < 1 || Cin < 1 || KH < 1 || KW < 1 || pad < 0 || stride_hw < 1)
+        return fail(QNN_ERR_SHAPE, "conv2d: bad geometry");
+    if (H > 32767 || Wd > 32767 || KH > 255 || KW > 255 || Cin > (1 << 24))
+        return fail(QNN_ERR_SHAPE, "conv2d: geometry beyond supported range");
+    if (H + 2 * (int64_t)pad < KH || Wd + 2 * (int64_t)pad < KW) return fail(QNN_ERR_SHAPE, "conv2d: kernel larger than padded image");
+    if (int rc = check_planes("conv2d", Pa, coefA, modeA)) return rc;
+    if (int rc = check_planes("conv2d", Pb, coefW, modeW)) return rc;
+    if (modeA == QNN_PLANE_SIGN && pad > 0)
+        return fail(QNN_ERR_UNSUPPORTED, "conv2d: zero padding cannot be encoded in a sign-mode activation plane");
+    if (B == 0 || Cout == 0) return QNN_OK;
+    if (!A || !W || !out) return fail(QNN_ERR_NULL, "conv2d: NULL pointer");
+    if (!aligned4(A) || !aligned4(W) || !aligned4(out)) return fail(QNN_ERR_ALIGN, "conv2d: pointer not 4-byte aligned");
+    const int64_t Ho = (H + 2 * pad - KH) / stride_hw + 1, Wo = (Wd + 2 * pad - KW) / stride_hw + 1;
+    const int64_t Cw = words_for(Cin);
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A.base = A;
+    g.A.plane_stride = strideA_words;
+    g.A.rows_are_pixels = 1;
+    g.A.H = (int)H, g.A.Wd = (int)Wd, g.A.Ho = (int)Ho, g.A.Wo = (int)Wo, g.A.Cw = (int)Cw;
+    g.A.KH = KH, g.A.KW = KW, g.A.pad = pad, g.A.stride = stride_hw;
+    g.pa.count = Pa, g.pa.mode = modeA;
+    for (int i = 0; i < Pa; ++i) g.pa.coef[i] = coefA[i];
+    g.W = W;
+    g.Kw = (int64_t)KH * KW * Cw;
+    g.ldw = g.Kw;
+    g.strideW = strideW_words;
+    g.pw.count = Pb, g.pw.mode = modeW;
+    for (int i = 0; i < Pb; ++i) g.pw.coef[i] = coefW[i];
+    g.epi = Epilogue{out, Cout, nullptr, nullptr, nullptr, 0};
+    g.M = B * Ho * Wo;
+    g.N = Cout;
+    g.K = (int64_t)KH * KW * Cin;  // true number of connections per output (channel tail bits are zero)
+    if (g.Kw > 0x7FFFFFFFLL / 32) return fail(QNN_ERR_SHAPE, "conv2d: patch too long");
+    if (int rc = check_range(g)) return rc;
+    return dispatch(g, engine, static_cast<hipStream_t>(stream));
+}
+
+const char *qnn_last_error(void) { return g_err; }
+
+const char *qnn_version(void) { return "libqnn 0.1 (gfx950)"; }
+
+}  // extern "C"

@@ -1,0 +1,73 @@
+// Internal declarations shared by the translation units of libqnn (not part of the public ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "qnn.h"
+
+namespace qnn {
+
+// Records the message returned by qnn_last_error() for the calling thread and passes `code` through.
+int fail(int code, const char *fmt, ...);
+// Checks hipGetLastError() after a launch; QNN_OK or QNN_ERR_HIP.
+int check_launch(const char *what);
+
+static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline int64_t words_for(int64_t K) { return (K + 31) / 32; }
+
+// How the rows of the left operand are found in memory.  rows_are_pixels == 0: row m, word j is at
+// base + m * ld + j (a plain packed matrix).  rows_are_pixels == 1: row m is output pixel (b, y, x) of a
+// convolution over a channels-last packed image and word j = tap * Cw + c addresses channel word c of input pixel
+// (y * stride + ky - pad, x * stride + kx - pad); taps that fall outside the image read as zero words.
+struct LeftAddr {
+    const uint32_t *base;
+    int64_t ld;            // words between consecutive rows (matrix) -- unused for pixels
+    int64_t plane_stride;  // words between consecutive planes
+    int rows_are_pixels;
+    int H, Wd, Ho, Wo, Cw, KH, KW, pad, stride;
+};
+
+// One multi-plane operand description passed by value to the kernels.
+struct Planes {
+    int count;
+    int mode;  // qnn_plane_mode
+    int32_t coef[QNN_MAX_PLANES];
+};
+
+// What the multiply writes.  T == nullptr: int32 sums to C (leading dimension ldc).
+// T != nullptr: bit = (sum >= T[n]) xor flip[n], packed along n into out_bits (leading dimension ldo words).
+struct Epilogue {
+    int32_t *C;
+    int64_t ldc;
+    const int32_t *T;
+    const uint8_t *flip;
+    uint32_t *out_bits;
+    int64_t ldo;
+};
+
+struct GemmArgs {
+    LeftAddr A;
+    Planes pa;
+    const uint32_t *W;
+    int64_t ldw;
+    int64_t strideW;
+    Planes pw;
+    Epilogue epi;
+    int64_t M, N, K;  // K = true number of elements per row (not words)
+    int64_t Kw;       // words per row = ceil(K/32) (for pixels: KH*KW*Cw)
+};
+
+// Engines.  Both return QNN_OK / QNN_ERR_*; `mfma_supports` says whether the matrix-core engine can take the job.
+int launch_gemm_valu(const GemmArgs &g, hipStream_t s);
+bool mfma_supports(const GemmArgs &g);
+int launch_gemm_mfma(const GemmArgs &g, hipStream_t s);
+
+int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo, hipStream_t s);
+int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,
+                          int64_t ld, int64_t plane_stride, hipStream_t s);
+int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
+                          uint32_t *out, int64_t ldo, hipStream_t s);
+
+}  // namespace qnn

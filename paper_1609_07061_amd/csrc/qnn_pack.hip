@@ -1,0 +1,154 @@
+// Bandwidth-bound kernels of the path: sign-binarize + pack (Sec. 2.1 Eq. (1), Sec. 6), bit-plane split + pack
+// (Sec. 2.6 Eq. (FirstLayer)), and threshold + pack (Alg. 4, Sign(BatchNorm(.)) with BatchNorm folded to an integer
+// threshold).  All three turn one predicate per element into packed words with a wavefront ballot: lane l of a
+// 64-wide wave owns element 64*c + l of the wave's chunk, so one ballot yields two finished 32-bit words.
+#include "qnn_internal.h"
+
+namespace qnn {
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+// Eq. (1) on the bit pattern of a float: x >= 0 holds for +-0 and for positive non-NaN values (including +inf).
+// Done on integers so that neither the denormal mode nor fast-math can change the outcome.
+__device__ __forceinline__ bool sign_is_plus(uint32_t bits) {
+    uint32_t mag = bits & 0x7FFFFFFFu;
+    return mag == 0u || ((bits >> 31) == 0u && mag <= 0x7F800000u);
+}
+
+// One wave turns kUnroll*64 consecutive elements of one row into 2*kUnroll words.
+template <int kUnroll>
+__global__ __launch_bounds__(kBlock) void pack_sign_kernel(const uint32_t *__restrict__ x, int64_t rows, int64_t K,
+                                                           int64_t ldx, uint32_t *__restrict__ out, int64_t ldo,
+                                                           int64_t chunks_per_row, int64_t total_chunks) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t Kw = (K + 31) / 32;
+    for (int64_t chunk = wave0; chunk < total_chunks; chunk += wave_stride) {
+        const int64_t r = chunk / chunks_per_row;
+        const int64_t k0 = (chunk - r * chunks_per_row) * (kUnroll * kWave);
+        const uint32_t *row = x + r * ldx;
+        uint32_t v[kUnroll];
+#pragma unroll
+        for (int c = 0; c < kUnroll; ++c) {
+            int64_t k = k0 + c * kWave + lane;
+            v[c] = (k < K) ? __builtin_nontemporal_load(row + k) : 0x80000001u;  // any "minus" pattern: bit 0
+        }
+        uint32_t mine = 0;
+#pragma unroll
+        for (int c = 0; c < kUnroll; ++c) {
+            unsigned long long m = __ballot(sign_is_plus(v[c]));
+            if (lane == 2 * c) mine = (uint32_t)m;
+            if (lane == 2 * c + 1) mine = (uint32_t)(m >> 32);
+        }
+        const int64_t w = k0 / 32 + lane;
+        if (lane < 2 * kUnroll && w < Kw) out[r * ldo + w] = mine;
+    }
+}
+
+// Bit planes: lane l owns code 64*c + l; for every plane one ballot of bit p.
+template <int kUnroll>
+__global__ __launch_bounds__(kBlock) void pack_bitplanes_kernel(const uint8_t *__restrict__ v, int64_t rows, int64_t K,
+                                                                int64_t ldv, int nbits, uint32_t *__restrict__ planes,
+                                                                int64_t ld, int64_t plane_stride,
+                                                                int64_t chunks_per_row, int64_t total_chunks) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t Kw = (K + 31) / 32;
+    for (int64_t chunk = wave0; chunk < total_chunks; chunk += wave_stride) {
+        const int64_t r = chunk / chunks_per_row;
+        const int64_t k0 = (chunk - r * chunks_per_row) * (kUnroll * kWave);
+        const uint8_t *row = v + r * ldv;
+        uint32_t code[kUnroll];
+#pragma unroll
+        for (int c = 0; c < kUnroll; ++c) {
+            int64_t k = k0 + c * kWave + lane;
+            code[c] = (k < K) ? (uint32_t)row[k] : 0u;
+        }
+        const int64_t w = k0 / 32 + lane;
+        for (int p = 0; p < nbits; ++p) {
+            uint32_t mine = 0;
+#pragma unroll
+            for (int c = 0; c < kUnroll; ++c) {
+                unsigned long long m = __ballot((code[c] >> p) & 1u);
+                if (lane == 2 * c) mine = (uint32_t)m;
+                if (lane == 2 * c + 1) mine = (uint32_t)(m >> 32);
+            }
+            if (lane < 2 * kUnroll && w < Kw) planes[p * plane_stride + r * ld + w] = mine;
+        }
+    }
+}
+
+// Threshold: one wave owns 64 consecutive neurons (their T and flip stay in registers) and walks down kRows rows.
+constexpr int kThreshRows = 16;
+__global__ __launch_bounds__(kBlock) void threshold_sign_kernel(const int32_t *__restrict__ C, int64_t ldc, int64_t M,
+                                                                int64_t N, const int32_t *__restrict__ T,
+                                                                const uint8_t *__restrict__ flip,
+                                                                uint32_t *__restrict__ out, int64_t ldo) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t n = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * kWave + lane;
+    const int64_t n_wave0 = n - lane;
+    if (n_wave0 >= N) return;  // wave-uniform
+    const bool live = n < N;
+    const int32_t t = live ? T[n] : 0;
+    const bool f = (live && flip) ? (flip[n] != 0) : false;
+    const int64_t Nw = (N + 31) / 32;
+    const int64_t w = n_wave0 / 32 + lane;
+    for (int64_t m0 = (int64_t)blockIdx.y * kThreshRows; m0 < M; m0 += (int64_t)gridDim.y * kThreshRows) {
+#pragma unroll 4
+        for (int i = 0; i < kThreshRows; ++i) {
+            const int64_t m = m0 + i;
+            if (m >= M) break;
+            int32_t c = live ? __builtin_nontemporal_load(C + m * ldc + n) : 0;
+            unsigned long long mask = __ballot(live && ((c >= t) != f));
+            uint32_t mine = (lane == 0) ? (uint32_t)mask : (uint32_t)(mask >> 32);
+            if (lane < 2 && w < Nw) out[m * ldo + w] = mine;
+        }
+    }
+}
+
+int grid_for(int64_t total_chunks) {
+    int64_t blocks = ceil_div(total_chunks, kWavesPerBlock);
+    const int64_t cap = 256 * 32;  // 256 CUs, plenty of resident waves each; the kernels stride over the rest
+    return (int)(blocks < cap ? blocks : cap);
+}
+
+}  // namespace
+
+int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo, hipStream_t s) {
+    constexpr int kUnroll = 8;  // 512 elements (2 KiB of floats) in flight per wave
+    const int64_t cpr = ceil_div(K, (int64_t)kUnroll * kWave);
+    const int64_t total = rows * cpr;
+    hipLaunchKernelGGL(pack_sign_kernel<kUnroll>, dim3(grid_for(total)), dim3(kBlock), 0, s,
+                       reinterpret_cast<const uint32_t *>(x), rows, K, ldx, out, ldo, cpr, total);
+    return check_launch("pack_sign");
+}
+
+int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,
+                          int64_t ld, int64_t plane_stride, hipStream_t s) {
+    constexpr int kUnroll = 4;
+    const int64_t cpr = ceil_div(K, (int64_t)kUnroll * kWave);
+    const int64_t total = rows * cpr;
+    hipLaunchKernelGGL(pack_bitplanes_kernel<kUnroll>, dim3(grid_for(total)), dim3(kBlock), 0, s, v, rows, K, ldv,
+                       nbits, planes, ld, plane_stride, cpr, total);
+    return check_launch("pack_bitplanes");
+}
+
+int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
+                          uint32_t *out, int64_t ldo, hipStream_t s) {
+    const int64_t gx = ceil_div(N, (int64_t)kBlock);
+    int64_t gy = ceil_div(M, (int64_t)kThreshRows);
+    if (gy > 32768) gy = 32768;  // the kernel strides over the remaining row groups
+    if (gx > 0x7FFFFFFF) return fail(QNN_ERR_SHAPE, "threshold_sign: N too large");
+    hipLaunchKernelGGL(threshold_sign_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), 0, s, C, ldc, M, N, T,
+                       flip, out, ldo);
+    return check_launch("threshold_sign");
+}
+
+}  // namespace qnn

@@ -1,0 +1,283 @@
+"""Parity of the HIP path against the CPU oracle, call by call through the C ABI, element by element, bit exact.
+Inputs are seeded and synthetic; expected values come only from the oracle on unpacked arrays."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import qnn_inputs as qi
+from qnn_testlib import dev, host, host_u32, np_pack_bits, np_pack_pm1, np_unpack_bits
+
+pytestmark = pytest.mark.gpu
+
+q = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    global q
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_1609_07061_amd as mod
+
+    q = mod
+    yield
+    torch.cuda.synchronize()
+
+
+ENGINES = [1, 2, 0]  # VALU, MFMA, AUTO
+
+
+def _engine_or_skip(fn, *a, engine, **kw):
+    try:
+        return fn(*a, engine=engine, **kw)
+    except Exception as e:  # QnnError with status 5 = engine cannot take the job
+        if getattr(e, "status", None) == 5 and engine == 2:
+            pytest.skip("matrix-core engine does not take this shape")
+        raise
+
+
+# ------------------------------------------------------------------ S1 pack_sign
+@pytest.mark.parametrize("rows,K", [(1, 1), (3, 31), (5, 32), (7, 33), (2, 63), (4, 64), (3, 65), (9, 1000), (17, 513),
+                                    (128, 1024), (1024, 1024), (33, 4099)])
+def test_pack_sign(seed, rows, K):
+    x = qi.with_special_floats(qi.normal_f32(seed, 10, (rows, K)), seed, 12)
+    want = oracle.pack_bits(oracle.sign(x))
+    got = host_u32(q.qnn_pack_sign(dev(x)))
+    assert np.array_equal(got, want)
+
+
+def test_pack_sign_strided_leaves_padding_untouched(seed):
+    rows, K, ldx, ldo = 6, 70, 96, 5
+    buf = qi.normal_f32(seed, 13, (rows, ldx))
+    x = dev(buf)[:, :K]
+    out = torch.full((rows, ldo), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    q.qnn_pack_sign(x, out=out[:, :3])
+    got = host_u32(out)
+    assert np.array_equal(got[:, :3], oracle.pack_bits(oracle.sign(buf[:, :K])))
+    assert (got[:, 3:] == 0x5A5A5A5A).all()
+
+
+def test_pack_sign_every_edge_value_in_every_lane():
+    sp = qi.special_floats()
+    x = np.stack([np.roll(np.resize(sp, 128), i) for i in range(64)])
+    assert np.array_equal(host_u32(q.qnn_pack_sign(dev(x))), oracle.pack_bits(oracle.sign(x)))
+
+
+# ------------------------------------------------------------------ S1b pack_bitplanes
+@pytest.mark.parametrize("rows,K,nbits", [(1, 1, 1), (3, 33, 2), (5, 64, 4), (4, 257, 8), (10, 784, 8), (7, 2048, 4),
+                                          (6, 255, 3)])
+def test_pack_bitplanes(seed, rows, K, nbits):
+    v = qi.uniform_int(seed, 14, (rows, K), 0, (1 << nbits) - 1)
+    planes = oracle.split_planes(v, nbits)  # [nbits][rows][K] of 0/1
+    want = np.stack([oracle.pack_bits(planes[p].astype(np.int8)) for p in range(nbits)])
+    got = host_u32(q.qnn_pack_bitplanes(dev(v.astype(np.uint8)), nbits))
+    assert np.array_equal(got, want)
+
+
+def test_pack_bitplanes_twos_complement_codes(seed):
+    v = qi.uniform_int(seed, 15, (5, 100), -8, 7)
+    planes = oracle.split_planes(v, 4)
+    want = np.stack([oracle.pack_bits(planes[p].astype(np.int8)) for p in range(4)])
+    codes = (v & 0xF).astype(np.uint8)
+    assert np.array_equal(host_u32(q.qnn_pack_bitplanes(dev(codes), 4)), want)
+
+
+# ------------------------------------------------------------------ S4 threshold_sign
+@pytest.mark.parametrize("M,N", [(1, 1), (3, 31), (5, 64), (17, 65), (40, 4096), (33, 1000)])
+@pytest.mark.parametrize("with_flip", [False, True])
+def test_threshold_sign(seed, M, N, with_flip):
+    Cm = qi.uniform_int(seed, 16, (M, N), -70, 70)
+    T = qi.uniform_int(seed, 17, (N,), -64, 64)
+    T[0] = -(2**31)
+    flip = qi.bernoulli_bits(seed, 18, (N,)) if with_flip else None
+    want = oracle.pack_bits(oracle.threshold(Cm, T, flip))
+    got = host_u32(q.qnn_threshold_sign(dev(Cm), dev(T), dev(flip) if with_flip else None))
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------------ S2 binary_gemm
+SHAPES = [(1, 1, 1), (3, 5, 31), (17, 3, 32), (64, 17, 33), (130, 64, 63), (5, 130, 64), (64, 64, 65),
+          (17, 130, 784), (130, 17, 1000), (128, 1024, 1024), (257, 300, 4096), (300, 10, 4096)]
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_binary_gemm(seed, M, N, K, engine):
+    a = qi.pm1(seed, 20, (M, K))
+    w = qi.pm1(seed, 21, (N, K))
+    want = oracle.gemm_pm1(a, w)
+    got = _engine_or_skip(q.qnn_binary_gemm, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+def test_binary_gemm_strided_operands_and_output(seed, engine):
+    M, N, K = 70, 90, 200  # 7 words per row, held in rows of 9 / 12 words; C rows of 100
+    a = qi.pm1(seed, 22, (M, K))
+    w = qi.pm1(seed, 23, (N, K))
+    A = dev(np_pack_pm1(a, 9))[:, :7]
+    W = dev(np_pack_pm1(w, 12))[:, :7]
+    out = torch.full((M, 100), -77, dtype=torch.int32, device="cuda")
+    _engine_or_skip(q.qnn_binary_gemm, A, W, K, out=out[:, :N], engine=engine)
+    got = host(out)
+    assert np.array_equal(got[:, :N], oracle.gemm_pm1(a, w))
+    assert (got[:, N:] == -77).all()
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+def test_binary_gemm_from_packed_floats(seed, engine):
+    """Config 1 end to end: fp32 N(0,1) -> sign + pack on the GPU -> product."""
+    xa = qi.normal_f32(seed, 10, (128, 1024))
+    xw = qi.normal_f32(seed, 11, (1024, 1024))
+    want = oracle.gemm_pm1(oracle.sign(xa), oracle.sign(xw))
+    A = q.qnn_pack_sign(dev(xa))
+    W = q.qnn_pack_sign(dev(xw))
+    got = _engine_or_skip(q.qnn_binary_gemm, A, W, 1024, engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (17, 33, 65), (130, 100, 784), (64, 4096, 4096), (200, 1000, 96)])
+@pytest.mark.parametrize("with_flip", [False, True])
+def test_binary_gemm_sign(seed, M, N, K, with_flip, engine):
+    a = qi.pm1(seed, 24, (M, K))
+    w = qi.pm1(seed, 25, (N, K))
+    T = qi.uniform_int(seed, 26, (N,), -8, 8)  # ties C == T are frequent
+    flip = qi.bernoulli_bits(seed, 27, (N,)) if with_flip else None
+    want = oracle.pack_bits(oracle.threshold(oracle.gemm_pm1(a, w), T, flip))
+    got = _engine_or_skip(q.qnn_binary_gemm_sign, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T),
+                          dev(flip) if with_flip else None, engine=engine)
+    assert np.array_equal(host_u32(got), want)
+
+
+# ------------------------------------------------------------------ S3 bitplane_gemm
+def _planes_of(v, nbits):
+    """integer codes -> ([nbits][rows][K] 0/1 planes from the oracle, packed uint32 planes for the GPU)"""
+    p = oracle.split_planes(v, nbits)
+    return p, np_pack_bits(p)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (9, 11, 100), (70, 130, 784), (130, 70, 33), (256, 512, 800)])
+def test_bitplane_u8_times_sign(seed, M, N, K, engine):
+    x = qi.uniform_int(seed, 30, (M, K), 0, 255)
+    w = qi.pm1(seed, 31, (N, K))
+    want = oracle.gemm_int(x, w.astype(np.int32))
+    _, xp = _planes_of(x, 8)
+    got = _engine_or_skip(q.qnn_bitplane_gemm, dev(xp), [1 << p for p in range(8)], q.PLANE_BIT,
+                          dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, K, engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("M,N,K", [(5, 7, 70), (64, 64, 2048), (150, 200, 257)])
+def test_bitplane_int4_times_int4(seed, M, N, K, engine):
+    a = qi.uniform_int(seed, 32, (M, K), -8, 7)
+    w = qi.uniform_int(seed, 33, (N, K), -8, 7)
+    want = oracle.gemm_int(a, w)
+    coef = [1, 2, 4, -8]
+    _, ap = _planes_of(a, 4)
+    _, wp = _planes_of(w, 4)
+    got = _engine_or_skip(q.qnn_bitplane_gemm, dev(ap), coef, q.PLANE_BIT, dev(wp), coef, q.PLANE_BIT, K,
+                          engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("modeA,modeW", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_bitplane_every_mode_pair_against_plane_oracle(seed, modeA, modeW, engine):
+    M, N, K, Pa, Pb = 37, 45, 333, 3, 2
+    pa = qi.bernoulli_bits(seed, 34, (Pa, M, K))
+    pw = qi.bernoulli_bits(seed, 35, (Pb, N, K))
+    ca, cw = [1, -2, 5], [3, -4]
+    want = oracle.gemm_planes(pa, ca, modeA, pw, cw, modeW)
+    got = _engine_or_skip(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, modeA, dev(np_pack_bits(pw)), cw, modeW, K,
+                          engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+def test_bitplane_large_coefficients_fall_back_correctly(seed, engine):
+    M, N, K = 20, 24, 90
+    pa = qi.bernoulli_bits(seed, 36, (2, M, K))
+    pw = qi.bernoulli_bits(seed, 37, (2, N, K))
+    ca, cw = [1000, -3], [7, 300]
+    want = oracle.gemm_planes(pa, ca, 0, pw, cw, 1)
+    got = _engine_or_skip(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, 0, dev(np_pack_bits(pw)), cw, 1, K,
+                          engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+def test_bitplane_gemm_sign_first_layer(seed, engine):
+    M, N, K = 100, 200, 784
+    x = qi.uniform_int(seed, 38, (M, K), 0, 255)
+    w = qi.pm1(seed, 39, (N, K))
+    T = qi.uniform_int(seed, 40, (N,), -3000, 3000)
+    flip = qi.bernoulli_bits(seed, 41, (N,))
+    want = oracle.pack_bits(oracle.threshold(oracle.gemm_int(x, w.astype(np.int32)), T, flip))
+    _, xp = _planes_of(x, 8)
+    got = _engine_or_skip(q.qnn_bitplane_gemm_sign, dev(xp), [1 << p for p in range(8)], q.PLANE_BIT,
+                          dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, K, dev(T), dev(flip), engine=engine)
+    assert np.array_equal(host_u32(got), want)
+
+
+# ------------------------------------------------------------------ S5 MLP (Alg. 4)
+def _mlp_case(seed, batch, dims, stream0, t_hidden=64):
+    L = len(dims) - 1
+    x = qi.uniform_int(seed, stream0, (batch, dims[0]), 0, 255, dtype=np.uint8)
+    W = [qi.pm1(seed, stream0 + 1 + l, (dims[l + 1], dims[l])) for l in range(L)]
+    T = [qi.uniform_int(seed, stream0 + 5 + l, (dims[l + 1],), -t_hidden, t_hidden) for l in range(L - 1)]
+    return x, W, T
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("batch,dims", [(1, [1, 1, 1]), (37, [50, 70, 33, 10]), (300, [784, 256, 192, 128, 10])])
+def test_mlp_forward_small(seed, batch, dims, engine):
+    x, W, T = _mlp_case(seed, batch, dims, 50)
+    flip = [qi.bernoulli_bits(seed, 60 + l, (dims[l + 1],)) for l in range(len(dims) - 2)]
+    want = oracle.mlp(x, W, T, flip)
+    got = _engine_or_skip(q.qnn_binary_mlp_forward, dev(x), 8, dims, [dev(np_pack_pm1(w)) for w in W],
+                          [dev(t) for t in T], [dev(f) for f in flip], engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+# ------------------------------------------------------------------ convolution
+def _conv_case(seed, B, H, Wd, Cin, Cout, KH, abits, stream0):
+    u = qi.uniform_int(seed, stream0, (B, H, Wd, Cin), 0, (1 << abits) - 1)
+    w = qi.pm1(seed, stream0 + 1, (Cout, KH, KH, Cin))
+    up = np_pack_bits(oracle.split_planes(u, abits))  # [abits][B][H][W][Cw]
+    wp = np_pack_pm1(w)[None]  # [1][Cout][KH][KW][Cw]
+    return u, w, up, wp
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("B,H,Wd,Cin,Cout,KH,pad,stride", [(2, 5, 6, 7, 4, 3, 1, 1), (3, 13, 13, 96, 40, 3, 1, 1),
+                                                           (2, 8, 7, 40, 33, 5, 2, 2), (1, 4, 4, 64, 8, 1, 0, 1),
+                                                           (4, 13, 13, 384, 256, 3, 1, 1)])
+def test_conv2d(seed, B, H, Wd, Cin, Cout, KH, pad, stride, engine):
+    u, w, up, wp = _conv_case(seed, B, H, Wd, Cin, Cout, KH, 2, 70)
+    want = oracle.conv2d(u, w.astype(np.int32), pad, stride)
+    got = _engine_or_skip(q.qnn_bitplane_conv2d, dev(up), [1, 2], q.PLANE_BIT, Cin, dev(wp), [1], q.PLANE_SIGN, pad,
+                          stride, engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+def test_conv2d_sign_activations_without_padding(seed, engine):
+    B, H, Wd, Cin, Cout = 2, 6, 7, 50, 12
+    a = qi.pm1(seed, 72, (B, H, Wd, Cin))
+    w = qi.pm1(seed, 73, (Cout, 3, 3, Cin))
+    want = oracle.conv2d(a.astype(np.int32), w.astype(np.int32), 0, 1)
+    got = _engine_or_skip(q.qnn_bitplane_conv2d, dev(np_pack_pm1(a)[None]), [1], q.PLANE_SIGN, Cin,
+                          dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, 0, 1, engine=engine)
+    assert np.array_equal(host(got), want)
+
+
+# ------------------------------------------------------------------ degenerate sizes
+def test_empty_inputs_are_no_ops():
+    e = torch.empty((0, 4), dtype=torch.int32, device="cuda")
+    w = torch.zeros((8, 4), dtype=torch.int32, device="cuda")
+    assert q.qnn_binary_gemm(e, w, 128).shape == (0, 8)
+    assert q.qnn_binary_gemm(w, e, 128).shape == (8, 0)
+    assert q.qnn_pack_sign(torch.empty((0, 5), dtype=torch.float32, device="cuda")).shape == (0, 1)
