@@ -153,6 +153,10 @@ int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int mod
                         const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
                         int pad, int stride_hw, int32_t *out, int engine, void *stream);
 
+/* Engine (QNN_ENGINE_VALU or QNN_ENGINE_MFMA) that the calling thread's last successful multiply call used; 0 before
+ * any.  For reports: results never depend on it. */
+int qnn_last_engine(void);
+
 const char *qnn_last_error(void);
 const char *qnn_version(void);
 

@@ -49,10 +49,11 @@ for _name, _args in _SIGS.items():
     _f.restype = C.c_int
 _lib.qnn_binary_mlp_workspace_bytes.argtypes = [_i64, _int, _int, _vp]
 _lib.qnn_binary_mlp_workspace_bytes.restype = _sz
+_lib.qnn_last_engine.restype = C.c_int
 _lib.qnn_last_error.restype = C.c_char_p
 _lib.qnn_version.restype = C.c_char_p
 
-EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_last_error", "qnn_version"])
+EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_last_engine", "qnn_last_error", "qnn_version"])
 
 
 class QnnError(RuntimeError):
@@ -103,6 +104,10 @@ def _coef(c: Sequence[int]):
 
 def words_for(K: int) -> int:
     return (K + 31) // 32
+
+
+def qnn_last_engine() -> int:
+    return int(_lib.qnn_last_engine())
 
 
 def qnn_version() -> str:

@@ -11,6 +11,7 @@
 namespace qnn {
 
 static thread_local char g_err[512] = "";
+static thread_local int g_last_engine = 0;
 
 int fail(int code, const char *fmt, ...) {
     va_list ap;
@@ -59,12 +60,12 @@ int check_range(const GemmArgs &g) {
 }
 
 int dispatch(const GemmArgs &g, int engine, hipStream_t s) {
-    if (engine == QNN_ENGINE_MFMA) {
-        if (!mfma_supports(g)) return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
-        return launch_gemm_mfma(g, s);
-    }
-    if (engine == QNN_ENGINE_AUTO && mfma_supports(g)) return launch_gemm_mfma(g, s);
-    return launch_gemm_valu(g, s);
+    if (engine == QNN_ENGINE_MFMA && !mfma_supports(g))
+        return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
+    const bool mfma = engine == QNN_ENGINE_MFMA || (engine == QNN_ENGINE_AUTO && mfma_supports(g) && mfma_preferred(g));
+    const int rc = mfma ? launch_gemm_mfma(g, s) : launch_gemm_valu(g, s);
+    if (rc == QNN_OK) g_last_engine = mfma ? QNN_ENGINE_MFMA : QNN_ENGINE_VALU;
+    return rc;
 }
 
 // Shared validation + launch of the matrix-shaped products.
@@ -351,6 +352,8 @@ int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int mod
     if (int rc = check_range(g)) return rc;
     return dispatch(g, engine, static_cast<hipStream_t>(stream));
 }
+
+int qnn_last_engine(void) { return g_last_engine; }
 
 const char *qnn_last_error(void) { return g_err; }
 

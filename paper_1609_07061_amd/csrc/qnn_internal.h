@@ -62,6 +62,7 @@ struct GemmArgs {
 // Engines.  Both return QNN_OK / QNN_ERR_*; `mfma_supports` says whether the matrix-core engine can take the job.
 int launch_gemm_valu(const GemmArgs &g, hipStream_t s);
 bool mfma_supports(const GemmArgs &g);
+bool mfma_preferred(const GemmArgs &g);  // whether AUTO should pick it for this shape
 int launch_gemm_mfma(const GemmArgs &g, hipStream_t s);
 
 int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo, hipStream_t s);
