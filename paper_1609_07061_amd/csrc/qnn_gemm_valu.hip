@@ -52,23 +52,6 @@ __device__ __forceinline__ uint32_t load_left_word(const LeftAddr &A, const uint
     return plane[row.offset + ((int64_t)iy * A.Wd + ix) * A.Cw + c];
 }
 
-// Tile index with consecutive ids of one XCD (ids congruent mod 8 share an L2) laid on neighbouring tiles, and tiles
-// walked in bands of 8 tile-rows so that the W panels a band needs stay cached.
-__device__ __forceinline__ void tile_of_block(uint32_t bid, uint32_t total, uint32_t tiles_m, uint32_t tiles_n,
-                                              uint32_t &tm, uint32_t &tn) {
-    const uint32_t xcd = bid & 7u, slot = bid >> 3;
-    const uint32_t q = total >> 3, r = total & 7u;
-    const uint32_t id = xcd * q + (xcd < r ? xcd : r) + slot;
-    constexpr uint32_t kBand = 8;
-    const uint32_t per_band = kBand * tiles_n;
-    const uint32_t band = id / per_band;
-    const uint32_t first_m = band * kBand;
-    const uint32_t band_rows = (tiles_m - first_m < kBand) ? (tiles_m - first_m) : kBand;
-    const uint32_t in_band = id - band * per_band;
-    tm = first_m + in_band % band_rows;
-    tn = in_band / band_rows;
-}
-
 template <int TM, int TN, bool kXor, bool kPopA, bool kPopW, bool kPixels, bool kSign>
 __global__ __launch_bounds__(kThreads) void gemm_valu_kernel(const GemmArgs g, uint32_t tiles_m, uint32_t tiles_n) {
     constexpr int BM = 16 * TM, BN = 16 * TN;
