@@ -15,8 +15,10 @@
 //     rank-one correction built from per-row sums, which are popcounts of the same raw words:
 //       C = aA aW (S - npad xA0 xW0) + aA bW RA[m] + bA aW RW[n] + K bA bW.
 //   * A wave owns a 128 x 128 tile (4 x 4 blocks of 32 x 32, 256 accumulator registers), a workgroup 2 x 2 waves.
-// The epilogue writes int32 sums, or compares with the folded BatchNorm threshold and re-packs with a ballot
-// (Alg. 4: a^b = Sign(BatchNorm(a))).
+// The epilogue writes int32 sums (16 bytes per lane and store), or compares with the folded BatchNorm threshold and
+// re-packs the bits along n (Alg. 4: a^b = Sign(BatchNorm(a))).
+#include <type_traits>
+
 #include "qnn_internal.h"
 
 namespace qnn {
@@ -38,14 +40,14 @@ struct Code {
     uint32_t inv[QNN_MAX_PLANES];  // 0 or 0xFFFFFFFF
     int32_t d[QNN_MAX_PLANES];     // signed weight of the raw bit in x8 (for the row sums)
     uint32_t bias;                 // 0 or 0x80808080
-    int vec;                       // rows start at multiples of the load width: vector loads allowed
 };
 
 struct MfmaConst {
     Code a, w;
     uint32_t alpha, cRA, cRW, c0;  // C = alpha * S + cRA * RA[m] + cRW * RW[n] + c0   (mod 2^32)
     int needRA, needRW;
-    uint32_t msteps;  // macro steps of 2 * WPL words
+    int alpha_shift;  // alpha == 1 << alpha_shift, or -1 if alpha is not a positive power of two
+    uint32_t msteps;  // macro steps of 2 * WPL words, rounded up to an even count
 };
 
 template <int P>
@@ -71,133 +73,184 @@ __device__ __forceinline__ v4i expand4(const uint32_t (&w)[P], const Code &c, in
     return out;
 }
 
-// WPL packed words of one row starting at word `j0` (zero beyond Kw).
-template <int WPL>
-__device__ __forceinline__ void load_words(const uint32_t *row, uint32_t j0, uint32_t Kw, bool vec, uint32_t (&out)[WPL]) {
-    if (vec && j0 + WPL <= Kw) {
-        if constexpr (WPL == 4) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(row + j0);
+// WPL packed words of one row starting at word `j0`.  Branch-free, so that the loads of a whole step form one
+// straight-line block whose latency the matrix-core work of the previous step covers: an out-of-range request reads
+// word 0 of the row (always valid memory) instead.
+// Chunked mode (kChunk: rows start at multiples of WPL words and Kw is a multiple of WPL, or WPL == 1): a chunk is
+// either completely inside the row or completely outside, the data is returned as loaded and `mask` (all ones / zero)
+// says whether it counts; the consumer applies it, so nothing here depends on the loaded data.  Otherwise words are
+// loaded one by one and zeroed here.
+template <int WPL, bool kChunk>
+__device__ __forceinline__ void load_words(const uint32_t *row, uint32_t j0, uint32_t Kw, bool live, uint32_t (&out)[WPL],
+                                           uint32_t &mask) {
+    if constexpr (kChunk) {
+        const bool ok = live && j0 < Kw;
+        mask = ok ? 0xFFFFFFFFu : 0u;
+        const uint32_t *p = row + (ok ? j0 : 0u);
+        if constexpr (WPL == 8) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(p);
+            const uint4 u = *reinterpret_cast<const uint4 *>(p + 4);
+            out[0] = v.x, out[1] = v.y, out[2] = v.z, out[3] = v.w;
+            out[4] = u.x, out[5] = u.y, out[6] = u.z, out[7] = u.w;
+        } else if constexpr (WPL == 4) {
+            const uint4 v = *reinterpret_cast<const uint4 *>(p);
             out[0] = v.x, out[1] = v.y, out[2] = v.z, out[3] = v.w;
         } else if constexpr (WPL == 2) {
-            const uint2 v = *reinterpret_cast<const uint2 *>(row + j0);
+            const uint2 v = *reinterpret_cast<const uint2 *>(p);
             out[0] = v.x, out[1] = v.y;
         } else {
-            out[0] = row[j0];
+            out[0] = *p;
         }
     } else {
+        mask = 0xFFFFFFFFu;
 #pragma unroll
-        for (int i = 0; i < WPL; ++i) out[i] = (j0 + i < Kw) ? row[j0 + i] : 0u;
+        for (int i = 0; i < WPL; ++i) {
+            const bool ok = live && j0 + i < Kw;
+            const uint32_t v = row[ok ? j0 + i : 0u];
+            out[i] = ok ? v : 0u;
+        }
     }
 }
 
-// Same for a row that is an output pixel of a convolution: word j = tap * Cw + c.
-template <int WPL>
+// Same for a row that is an output pixel of a convolution: word j = tap * Cw + c; taps outside the image are zero.
+// Chunked mode additionally has Cw a multiple of WPL, so a chunk never straddles two taps.
+template <int WPL, bool kChunk>
 __device__ __forceinline__ void load_pixel_words(const LeftAddr &A, const uint32_t *image, int yo, int xo, uint32_t j0,
-                                                 uint32_t Kw, bool vec, uint32_t (&out)[WPL]) {
+                                                 uint32_t Kw, uint32_t (&out)[WPL], uint32_t &mask) {
     const uint32_t Cw = (uint32_t)A.Cw;
-    const uint32_t tap = j0 / Cw, c = j0 - tap * Cw;
-    if (c + WPL <= Cw && j0 + WPL <= Kw) {  // one tap
+    if constexpr (kChunk) {
+        const uint32_t tap = j0 / Cw, c = j0 - tap * Cw;
         const uint32_t ky = tap / (uint32_t)A.KW, kx = tap - ky * (uint32_t)A.KW;
         const int iy = yo * A.stride + (int)ky - A.pad, ix = xo * A.stride + (int)kx - A.pad;
-        if (iy < 0 || iy >= A.H || ix < 0 || ix >= A.Wd) {
+        const bool in = j0 < Kw && iy >= 0 && iy < A.H && ix >= 0 && ix < A.Wd;
+        const int64_t pix = in ? ((int64_t)iy * A.Wd + ix) : 0;
+        load_words<WPL, true>(image + pix * Cw, c, Cw, in, out, mask);
+    } else {
+        mask = 0xFFFFFFFFu;
 #pragma unroll
-            for (int i = 0; i < WPL; ++i) out[i] = 0u;
-        } else {
-            load_words<WPL>(image + ((int64_t)iy * A.Wd + ix) * Cw, c, Cw, vec, out);
-        }
-        return;
-    }
-#pragma unroll
-    for (int i = 0; i < WPL; ++i) {
-        const uint32_t j = j0 + i;
-        uint32_t v = 0u;
-        if (j < Kw) {
+        for (int i = 0; i < WPL; ++i) {
+            const uint32_t j = j0 + i;
             const uint32_t t = j / Cw, cc = j - t * Cw;
             const uint32_t ky = t / (uint32_t)A.KW, kx = t - ky * (uint32_t)A.KW;
             const int iy = yo * A.stride + (int)ky - A.pad, ix = xo * A.stride + (int)kx - A.pad;
-            if (iy >= 0 && iy < A.H && ix >= 0 && ix < A.Wd) v = image[((int64_t)iy * A.Wd + ix) * Cw + cc];
+            const bool in = j < Kw && iy >= 0 && iy < A.H && ix >= 0 && ix < A.Wd;
+            const uint32_t v = image[in ? (((int64_t)iy * A.Wd + ix) * Cw + cc) : 0];
+            out[i] = in ? v : 0u;
         }
-        out[i] = v;
     }
 }
 
-template <int PA, int PW, int WPL, bool kPixels, bool kSign>
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+// The weights feed the row side of the matrix core (accumulator registers 4q .. 4q+3 of a lane are then four
+// consecutive n of one m, i.e. 16 contiguous bytes of C) and the activations the column side (lane = m).
+template <int PA, int PW, int WPL, bool kVec, bool kPixels, bool kSign>
 __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                 uint32_t tiles_n) {
-    uint32_t tile_m, tile_n;
-    tile_of_block(blockIdx.x, tiles_m * tiles_n, tiles_m, tiles_n, tile_m, tile_n);
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    constexpr bool kChunk = kVec || WPL == 1;
+    __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in a scalar register
     const int r = lane & 31, kg = lane >> 5;
-    const int64_t m_wave = (int64_t)tile_m * BM + (wave >> 1) * WTILE;
-    const int64_t n_wave = (int64_t)tile_n * BN + (wave & 1) * WTILE;
     const uint32_t Kw = (uint32_t)g.Kw;
+    const uint32_t total_tiles = tiles_m * tiles_n;
+    const int64_t Nw = (g.N + 31) / 32;
 
-    // the operand rows this lane feeds (clamped: rows past the edge are computed but never stored)
-    int64_t a_off[WB];
-    int a_yo[WB], a_xo[WB];
-    const uint32_t *w_row[WB];
+    // Where this lane's operand rows live for one tile (rows past the edge are clamped: computed, never stored).
+    struct Tile {
+        int64_t m_wave, n_wave;  // wave-uniform
+        int64_t a_off[WB];
+        int a_yo[WB], a_xo[WB];
+        const uint32_t *w_row[WB];
+    };
+    auto locate = [&](uint32_t vb, Tile &t) {
+        uint32_t tile_m, tile_n;
+        tile_of_block(vb, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
+        t.m_wave = (int64_t)tile_m * BM + (wave >> 1) * WTILE;
+        t.n_wave = (int64_t)tile_n * BN + (wave & 1) * WTILE;
 #pragma unroll
-    for (int b = 0; b < WB; ++b) {
-        int64_t m = m_wave + b * 32 + r;
-        if (m > g.M - 1) m = g.M - 1;
-        if (kPixels) {
-            const int64_t per_image = (int64_t)g.A.Ho * g.A.Wo;
-            const int64_t img = m / per_image;
-            const int rem = (int)(m - img * per_image);
-            a_yo[b] = rem / g.A.Wo;
-            a_xo[b] = rem - a_yo[b] * g.A.Wo;
-            a_off[b] = img * g.A.H * g.A.Wd * g.A.Cw;
-        } else {
-            a_off[b] = m * g.A.ld;
-            a_yo[b] = a_xo[b] = 0;
+        for (int b = 0; b < WB; ++b) {
+            int64_t m = t.m_wave + b * 32 + r;
+            if (m > g.M - 1) m = g.M - 1;
+            if (kPixels) {
+                const int64_t per_image = (int64_t)g.A.Ho * g.A.Wo;
+                const int64_t img = m / per_image;
+                const int rem = (int)(m - img * per_image);
+                t.a_yo[b] = rem / g.A.Wo;
+                t.a_xo[b] = rem - t.a_yo[b] * g.A.Wo;
+                t.a_off[b] = img * g.A.H * g.A.Wd * g.A.Cw;
+            } else {
+                t.a_off[b] = m * g.A.ld;
+                t.a_yo[b] = t.a_xo[b] = 0;
+            }
+            int64_t n = t.n_wave + b * 32 + r;
+            if (n > g.N - 1) n = g.N - 1;
+            t.w_row[b] = g.W + n * g.ldw;
         }
-        int64_t n = n_wave + b * 32 + r;
-        if (n > g.N - 1) n = g.N - 1;
-        w_row[b] = g.W + n * g.ldw;
-    }
+    };
 
-    v16i acc[WB][WB];
-#pragma unroll
-    for (int i = 0; i < WB; ++i)
-#pragma unroll
-        for (int j = 0; j < WB; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
-    int32_t ra[WB], rw[WB];
-#pragma unroll
-    for (int b = 0; b < WB; ++b) ra[b] = rw[b] = 0;
-
-    uint32_t curA[WB][PA][WPL], curW[WB][PW][WPL], nxtA[WB][PA][WPL], nxtW[WB][PW][WPL];
-
-    auto fetch = [&](uint32_t s, uint32_t (&dA)[WB][PA][WPL], uint32_t (&dW)[WB][PW][WPL]) {
+    struct Step {
+        uint32_t A[WB][PA][WPL], W[WB][PW][WPL];
+        uint32_t maskA[WB], maskW;  // chunked loads: all ones if the chunk lies inside the row / image
+    };
+    auto fetch = [&](const Tile &t, uint32_t s, Step &d) {
         const uint32_t j0 = s * (2 * WPL) + kg * WPL;
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
             for (int p = 0; p < PA; ++p) {
-                const uint32_t *plane = g.A.base + (int64_t)p * g.A.plane_stride + a_off[b];
+                const uint32_t *plane = g.A.base + (int64_t)p * g.A.plane_stride + t.a_off[b];
                 if (kPixels)
-                    load_pixel_words<WPL>(g.A, plane, a_yo[b], a_xo[b], j0, Kw, mc.a.vec != 0, dA[b][p]);
+                    load_pixel_words<WPL, kChunk>(g.A, plane, t.a_yo[b], t.a_xo[b], j0, Kw, d.A[b][p], d.maskA[b]);
                 else
-                    load_words<WPL>(plane, j0, Kw, mc.a.vec != 0, dA[b][p]);
+                    load_words<WPL, kChunk>(plane, j0, Kw, true, d.A[b][p], d.maskA[b]);
             }
 #pragma unroll
             for (int p = 0; p < PW; ++p)
-                load_words<WPL>(w_row[b] + (int64_t)p * g.strideW, j0, Kw, mc.w.vec != 0, dW[b][p]);
+                load_words<WPL, kChunk>(t.w_row[b] + (int64_t)p * g.strideW, j0, Kw, true, d.W[b][p], d.maskW);
         }
     };
 
-    fetch(0, curA, curW);
-    for (uint32_t s = 0; s < mc.msteps; ++s) {
-        if (s + 1 < mc.msteps) fetch(s + 1, nxtA, nxtW);
-        // row sums of the raw codes (popcounts of the words just used)
+    v16i acc[WB][WB];  // [n block][m block]
+    int32_t ra[WB], rw[WB];
+    auto clear = [&]() {
+#pragma unroll
+        for (int i = 0; i < WB; ++i) {
+            ra[i] = rw[i] = 0;
+#pragma unroll
+            for (int j = 0; j < WB; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+        }
+    };
+
+    auto compute = [&](const Step &c) {
+        // the masks are applied here, at the point of use, so that the loads stay in flight until now
+        uint32_t cA[WB][PA][WPL], cW[WB][PW][WPL];
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+#pragma unroll
+            for (int p = 0; p < PA; ++p)
+#pragma unroll
+                for (int t = 0; t < WPL; ++t) cA[b][p][t] = kChunk ? (c.A[b][p][t] & c.maskA[b]) : c.A[b][p][t];
+#pragma unroll
+            for (int p = 0; p < PW; ++p)
+#pragma unroll
+                for (int t = 0; t < WPL; ++t) cW[b][p][t] = kChunk ? (c.W[b][p][t] & c.maskW) : c.W[b][p][t];
+        }
+        // row sums of the raw codes (popcounts of the words in use)
         if (mc.needRA) {
 #pragma unroll
             for (int b = 0; b < WB; ++b)
 #pragma unroll
                 for (int p = 0; p < PA; ++p)
 #pragma unroll
-                    for (int t = 0; t < WPL; ++t) ra[b] += mc.a.d[p] * (int32_t)__builtin_popcount(curA[b][p][t]);
+                    for (int t = 0; t < WPL; ++t) {
+                        if (PA == 1)
+                            ra[b] += (int32_t)__builtin_popcount(cA[b][p][t]);
+                        else
+                            ra[b] += mc.a.d[p] * (int32_t)__builtin_popcount(cA[b][p][t]);
+                    }
         }
         if (mc.needRW) {
 #pragma unroll
@@ -205,7 +258,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
 #pragma unroll
                 for (int p = 0; p < PW; ++p)
 #pragma unroll
-                    for (int t = 0; t < WPL; ++t) rw[b] += mc.w.d[p] * (int32_t)__builtin_popcount(curW[b][p][t]);
+                    for (int t = 0; t < WPL; ++t) {
+                        if (PW == 1)
+                            rw[b] += (int32_t)__builtin_popcount(cW[b][p][t]);
+                        else
+                            rw[b] += mc.w.d[p] * (int32_t)__builtin_popcount(cW[b][p][t]);
+                    }
         }
 #pragma unroll
         for (int t = 0; t < WPL; ++t) {
@@ -213,9 +271,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
 #pragma unroll
             for (int b = 0; b < WB; ++b) {
 #pragma unroll
-                for (int p = 0; p < PA; ++p) wa[b][p] = (PA == 1) ? curA[b][p][t] : (curA[b][p][t] ^ mc.a.inv[p]);
+                for (int p = 0; p < PA; ++p) wa[b][p] = (PA == 1) ? cA[b][p][t] : (cA[b][p][t] ^ mc.a.inv[p]);
 #pragma unroll
-                for (int p = 0; p < PW; ++p) ww[b][p] = (PW == 1) ? curW[b][p][t] : (curW[b][p][t] ^ mc.w.inv[p]);
+                for (int p = 0; p < PW; ++p) ww[b][p] = (PW == 1) ? cW[b][p][t] : (cW[b][p][t] ^ mc.w.inv[p]);
             }
 #pragma unroll
             for (int half = 0; half < 2; ++half) {
@@ -229,68 +287,158 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                 for (int i = 0; i < WB; ++i)
 #pragma unroll
                     for (int j = 0; j < WB; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fw[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
             }
         }
+    };
+
+    // Accumulator register v of block [bi][bj] is C[m][n] with
+    //   m = m_wave + 32 bj + (lane mod 32),   n = n_wave + 32 bi + 8 (v / 4) + 4 (lane / 32) + v mod 4.
+    // kFast: the wave tile lies completely inside C and C allows 16-byte stores, so nothing needs a bounds check.
+    auto epilogue = [&](const int64_t m_wave, const int64_t n_wave, auto scale, auto fast_tag) {
+        constexpr bool kFast = decltype(fast_tag)::value;
+        // both k-groups of a row hold partial row sums; the weight-row sums are needed per accumulator register
+        // (n varies with the register), so they go through a small per-wave LDS table and come back as broadcasts
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
-#pragma unroll
-            for (int p = 0; p < PA; ++p)
-#pragma unroll
-                for (int t = 0; t < WPL; ++t) curA[b][p][t] = nxtA[b][p][t];
-#pragma unroll
-            for (int p = 0; p < PW; ++p)
-#pragma unroll
-                for (int t = 0; t < WPL; ++t) curW[b][p][t] = nxtW[b][p][t];
+            ra[b] += __shfl_xor(ra[b], 32);
+            rw[b] += __shfl_xor(rw[b], 32);
         }
-    }
-
-    // both k-groups of a row hold partial row sums
+        if (mc.needRW) {
+            if (kg == 0) {
 #pragma unroll
-    for (int b = 0; b < WB; ++b) {
-        ra[b] += __shfl_xor(ra[b], 32);
-        rw[b] += __shfl_xor(rw[b], 32);
-    }
-
-    const int64_t Nw = (g.N + 31) / 32;
-#pragma unroll
-    for (int bi = 0; bi < WB; ++bi) {
-        // accumulator register v of a 32 x 32 block: column = lane mod 32, row = 8 (v / 4) + 4 (lane / 32) + v mod 4
-        uint32_t rterm[16];
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int rowl = 8 * (v >> 2) + 4 * kg + (v & 3);
-            rterm[v] = mc.cRA * (uint32_t)__shfl(ra[bi], rowl) + mc.c0;
+                for (int b = 0; b < WB; ++b) rw_table[wave][b * 32 + r] = mc.cRW * (uint32_t)rw[b];
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's own LDS writes have landed
+            __builtin_amdgcn_wave_barrier();
         }
+        int64_t m_of[WB];
+        uint32_t mterm[WB];
 #pragma unroll
         for (int bj = 0; bj < WB; ++bj) {
-            const int64_t n = n_wave + bj * 32 + r;
-            const bool n_live = n < g.N;
-            const uint32_t cterm = mc.cRW * (uint32_t)rw[bj];
-            if (!kSign) {
+            m_of[bj] = m_wave + bj * 32 + r;
+            mterm[bj] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
+        }
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int64_t m = m_wave + bi * 32 + 8 * (v >> 2) + 4 * kg + (v & 3);
-                    const uint32_t val = mc.alpha * (uint32_t)acc[bi][bj][v] + rterm[v] + cterm;
-                    if (n_live && m < g.M) __builtin_nontemporal_store((int32_t)val, g.epi.C + m * g.epi.ldc + n);
+        for (int bi = 0; bi < WB; ++bi) {
+            const int64_t n_blk = n_wave + bi * 32;
+            uint32_t nterm[16];  // the part that depends on n only
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint4 t4 = make_uint4(0u, 0u, 0u, 0u);
+                if (mc.needRW) t4 = *reinterpret_cast<const uint4 *>(&rw_table[wave][bi * 32 + 8 * q + 4 * kg]);
+                nterm[4 * q] = t4.x, nterm[4 * q + 1] = t4.y, nterm[4 * q + 2] = t4.z, nterm[4 * q + 3] = t4.w;
+            }
+            if constexpr (!kSign) {
+#pragma unroll
+                for (int bj = 0; bj < WB; ++bj) {
+                    int32_t *row = g.epi.C + m_of[bj] * g.epi.ldc + n_blk + 4 * kg;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        i32x4 val;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            val[i] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + i]) + nterm[4 * q + i] + mterm[bj]);
+                        if constexpr (kFast) {
+                            *reinterpret_cast<i32x4 *>(row + 8 * q) = val;
+                        } else if (m_of[bj] < g.M) {
+                            const int64_t n0 = n_blk + 8 * q + 4 * kg;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (n0 + i < g.N) row[8 * q + i] = val[i];
+                        }
+                    }
                 }
             } else {
-                const int32_t T = n_live ? g.epi.T[n] : 0;
-                const bool fl = (n_live && g.epi.flip) ? (g.epi.flip[n] != 0) : false;
-                uint32_t mine = 0;
+                int32_t T[16];
+                uint32_t flips = 0;
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
-                    const uint32_t val = mc.alpha * (uint32_t)acc[bi][bj][v] + rterm[v] + cterm;
-                    const unsigned long long mask = __ballot(n_live && (((int32_t)val >= T) != fl));
-                    const int row0 = 8 * (v >> 2) + (v & 3);  // row of the low half (k-group 0 lanes)
-                    if (lane == row0) mine = (uint32_t)mask;
-                    if (lane == row0 + 4) mine = (uint32_t)(mask >> 32);
+                    const int64_t n = n_blk + 8 * (v >> 2) + 4 * kg + (v & 3);
+                    const bool live = kFast || n < g.N;
+                    T[v] = live ? g.epi.T[n] : 0;
+                    if (g.epi.flip && live && g.epi.flip[n] != 0) flips |= 1u << v;
                 }
-                const int64_t m = m_wave + bi * 32 + lane;
-                const int64_t word = (n_wave + bj * 32) >> 5;
-                if (lane < 32 && m < g.M && word < Nw) g.epi.out_bits[m * g.epi.ldo + word] = mine;
+                const int64_t word = n_blk >> 5;
+#pragma unroll
+                for (int bj = 0; bj < WB; ++bj) {
+                    uint32_t bits = 0;
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int64_t n = n_blk + 8 * (v >> 2) + 4 * kg + (v & 3);
+                        const int32_t val = (int32_t)(scale((uint32_t)acc[bi][bj][v]) + nterm[v] + mterm[bj]);
+                        const bool ge = val >= T[v];
+                        const bool b = (kFast || n < g.N) && (ge != (((flips >> v) & 1u) != 0));
+                        bits |= (b ? 1u : 0u) << (8 * (v >> 2) + (v & 3));
+                    }
+                    bits <<= 4 * kg;
+                    bits |= (uint32_t)__shfl_xor((int)bits, 32);
+                    if (kg == 0 && (kFast || (m_of[bj] < g.M && word < Nw)))
+                        g.epi.out_bits[m_of[bj] * g.epi.ldo + word] = bits;
+                }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
+    };
+    auto finish = [&](const int64_t m_wave, const int64_t n_wave) {
+        const bool interior = m_wave + WTILE <= g.M && n_wave + WTILE <= g.N;
+        const bool wide = kSign || ((g.epi.ldc % 4 == 0) && (reinterpret_cast<uintptr_t>(g.epi.C) % 16 == 0));
+        const bool fast = interior && wide;
+        if (mc.alpha_shift >= 0) {
+            const int sh = mc.alpha_shift;
+            auto scale = [sh](uint32_t x) { return x << sh; };
+            if (fast)
+                epilogue(m_wave, n_wave, scale, std::true_type{});
+            else
+                epilogue(m_wave, n_wave, scale, std::false_type{});
+        } else {
+            const uint32_t al = mc.alpha;
+            auto scale = [al](uint32_t x) { return x * al; };
+            if (fast)
+                epilogue(m_wave, n_wave, scale, std::true_type{});
+            else
+                epilogue(m_wave, n_wave, scale, std::false_type{});
+        }
+    };
+
+    // Persistent workgroups.  Per tile: two steps per trip, ping-pong between two register buffers; the loads of the
+    // next tile's first step are issued before this tile's stores, so they are older than the stores in the memory
+    // queue and the stores drain while the next tile is already being computed.  msteps is even; steps past the end of
+    // K read zero words, which the epilogue constants account for.  The scheduling fences keep each batch of loads in
+    // front of the matrix-core block that hides its latency.
+    Step buf0, buf1;
+    Tile cur;
+    uint32_t vb = blockIdx.x;
+    locate(vb, cur);
+    fetch(cur, 0, buf0);
+    while (true) {
+        clear();
+        for (uint32_t s = 0; s + 2 < mc.msteps; s += 2) {
+            fetch(cur, s + 1, buf1);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(buf0);
+            __builtin_amdgcn_sched_barrier(0);
+            fetch(cur, s + 2, buf0);
+            __builtin_amdgcn_sched_barrier(0);
+            compute(buf1);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        fetch(cur, mc.msteps - 1, buf1);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(buf0);
+        __builtin_amdgcn_sched_barrier(0);
+        // the operand rows of this tile are not needed any more: move on to the next tile's
+        const int64_t m_done = cur.m_wave, n_done = cur.n_wave;
+        const uint32_t vb_next = vb + gridDim.x;
+        const bool more = vb_next < total_tiles;
+        locate(more ? vb_next : vb, cur);  // without a next tile the loads are repeated and ignored
+        fetch(cur, 0, buf0);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(buf1);
+        __builtin_amdgcn_sched_barrier(0);
+        finish(m_done, n_done);
+        if (!more) break;
+        vb = vb_next;
     }
 }
 
@@ -348,11 +496,11 @@ typedef void (*KernelFn)(const GemmArgs, const MfmaConst, uint32_t, uint32_t);
 struct Variant {
     int PA, PW, WPL;
     bool pixels, sign;
-    KernelFn fn;
+    KernelFn fn_vec, fn_any;  // rows aligned to the load width (vector loads) / any layout (word loads)
 };
 
 #define QNN_VARIANT(PA, PW, WPL, PIX, SGN) \
-    { PA, PW, WPL, PIX, SGN, gemm_mfma_kernel<PA, PW, WPL, PIX, SGN> }
+    { PA, PW, WPL, PIX, SGN, gemm_mfma_kernel<PA, PW, WPL, true, PIX, SGN>, gemm_mfma_kernel<PA, PW, WPL, (WPL == 1), PIX, SGN> }
 const Variant kVariants[] = {
     QNN_VARIANT(1, 1, 4, false, false), QNN_VARIANT(1, 1, 4, false, true),  QNN_VARIANT(8, 1, 1, false, false),
     QNN_VARIANT(8, 1, 1, false, true),  QNN_VARIANT(4, 4, 1, false, false), QNN_VARIANT(2, 1, 2, false, false),
@@ -368,13 +516,13 @@ const Variant *find_variant(const GemmArgs &g) {
     return nullptr;
 }
 
-bool prepare(const GemmArgs &g, const Variant *&var, MfmaConst &mc) {
+bool prepare(const GemmArgs &g, const Variant *&var, MfmaConst &mc, bool &vec) {
     var = find_variant(g);
     if (!var) return false;
     int64_t aA, bA, xA0, aW, bW, xW0;
     if (!make_code(g.pa, mc.a, aA, bA, xA0) || !make_code(g.pw, mc.w, aW, bW, xW0)) return false;
     const int64_t step_words = 2 * var->WPL;
-    const int64_t msteps = ceil_div(g.Kw, step_words);
+    const int64_t msteps = 2 * ceil_div(g.Kw, 2 * step_words);
     const int64_t Kproc = msteps * step_words * 32;
     if (Kproc >= 131072) return false;  // |S| <= Kproc * 2^14 must stay below 2^31
     const int64_t npad = Kproc - g.K;
@@ -387,16 +535,20 @@ bool prepare(const GemmArgs &g, const Variant *&var, MfmaConst &mc) {
     mc.needRW = mc.cRW != 0;
     // the row sums are over the true K: RA = sum_p d_p pop_p - K * off; fold the constant part into c0
     mc.c0 += (uint32_t)(aA * bW * (g.K * xA0)) + (uint32_t)(bA * aW * (g.K * xW0));
-    auto vec_ok = [&](const uint32_t *base, int64_t ld, int64_t pstride, int planes, bool pix, int Cw) {
-        const int wpl = var->WPL;
-        if (wpl == 1) return 1;
-        if (reinterpret_cast<uintptr_t>(base) % (4 * wpl)) return 0;
-        if (planes > 1 && pstride % wpl) return 0;
-        if (pix) return (Cw % wpl) == 0 ? 1 : 0;
-        return (ld % wpl) == 0 ? 1 : 0;
+    mc.alpha_shift = -1;
+    for (int sh = 0; sh < 31; ++sh)
+        if (aA * aW == ((int64_t)1 << sh)) mc.alpha_shift = sh;
+    // vector loads need every row (of every plane) to start at a multiple of the load width and to be made of whole
+    // chunks, so that a chunk is either all inside or all outside the row
+    const int wpl = var->WPL;
+    auto aligned = [&](const uint32_t *base, int64_t ld, int64_t pstride, int planes) {
+        if (reinterpret_cast<uintptr_t>(base) % (4 * wpl)) return false;
+        if (planes > 1 && pstride % wpl) return false;
+        return ld % wpl == 0;
     };
-    mc.a.vec = vec_ok(g.A.base, g.A.ld, g.A.plane_stride, g.pa.count, g.A.rows_are_pixels != 0, g.A.Cw);
-    mc.w.vec = vec_ok(g.W, g.ldw, g.strideW, g.pw.count, false, 0);
+    const bool pix = g.A.rows_are_pixels != 0;
+    vec = wpl > 1 && aligned(g.A.base, pix ? g.A.Cw : g.A.ld, g.A.plane_stride, g.pa.count) &&
+          aligned(g.W, g.ldw, g.strideW, g.pw.count) && (pix ? g.A.Cw % wpl == 0 : true) && g.Kw % wpl == 0;
     return true;
 }
 
@@ -405,7 +557,8 @@ bool prepare(const GemmArgs &g, const Variant *&var, MfmaConst &mc) {
 bool mfma_supports(const GemmArgs &g) {
     const Variant *v;
     MfmaConst mc;
-    return prepare(g, v, mc);
+    bool vec;
+    return prepare(g, v, mc, vec);
 }
 
 bool mfma_preferred(const GemmArgs &g) {
@@ -416,10 +569,22 @@ bool mfma_preferred(const GemmArgs &g) {
 int launch_gemm_mfma(const GemmArgs &g, hipStream_t s) {
     const Variant *v;
     MfmaConst mc;
-    if (!prepare(g, v, mc)) return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
+    bool vec;
+    if (!prepare(g, v, mc, vec)) return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
     const int64_t tiles_m = ceil_div(g.M, BM), tiles_n = ceil_div(g.N, BN);
     if (tiles_m * tiles_n > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "gemm: too many tiles");
-    hipLaunchKernelGGL(v->fn, dim3((unsigned)(tiles_m * tiles_n)), dim3(kThreads), 0, s, g, mc, (uint32_t)tiles_m,
+    // one persistent workgroup per compute unit (each takes 512 registers per lane, so one fits)
+    static thread_local int cus = 0;
+    if (cus == 0) {
+        int dev = 0, n = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+            n = 256;
+        cus = n;
+    }
+    const int64_t total = tiles_m * tiles_n;
+    const unsigned grid = (unsigned)(total < cus ? total : cus);
+    hipLaunchKernelGGL(vec ? v->fn_vec : v->fn_any, dim3(grid), dim3(kThreads), 0, s, g, mc, (uint32_t)tiles_m,
                        (uint32_t)tiles_n);
     return check_launch("gemm_mfma");
 }
