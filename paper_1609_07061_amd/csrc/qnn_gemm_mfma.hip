@@ -18,6 +18,7 @@
 // The epilogue writes int32 sums (16 bytes per lane and store), or compares with the folded BatchNorm threshold and
 // re-packs the bits along n (Alg. 4: a^b = Sign(BatchNorm(a))).
 #include <type_traits>
+#include <utility>
 
 #include "qnn_internal.h"
 
@@ -142,13 +143,42 @@ __device__ __forceinline__ void load_pixel_words(const LeftAddr &A, const uint32
 
 typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
 
+#ifdef QNN_MFMA_TRACE
+// Developer build only: wave 0 of every workgroup stamps the shader clock at a few points of each tile.
+__device__ unsigned long long *g_trace = nullptr;
+#define QNN_STAMP(slot)                                                                              \
+    do {                                                                                             \
+        if (g_trace && threadIdx.x == 0 && trace_tile < 8)                                           \
+            g_trace[(blockIdx.x * 8 + trace_tile) * 8 + (slot)] = __builtin_readcyclecounter();      \
+    } while (0)
+#else
+#define QNN_STAMP(slot) \
+    do {                \
+    } while (0)
+#endif
+
+// Scheduling pattern of one phase: after each of its 16 MFMAs, the next share of kTotal vector-ALU instructions.
+template <int kTotal, int... I>
+__device__ __forceinline__ void interleave_groups(std::integer_sequence<int, I...>) {
+    constexpr int n = (int)sizeof...(I);
+    ((__builtin_amdgcn_sched_group_barrier(0x008, 1, 0),
+      __builtin_amdgcn_sched_group_barrier(0x002, kTotal / n + (I < kTotal % n ? 1 : 0), 0)),
+     ...);
+}
+
 // The weights feed the row side of the matrix core (accumulator registers 4q .. 4q+3 of a lane are then four
 // consecutive n of one m, i.e. 16 contiguous bytes of C) and the activations the column side (lane = m).
 template <int PA, int PW, int WPL, bool kVec, bool kPixels, bool kSign>
 __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                 uint32_t tiles_n) {
     constexpr bool kChunk = kVec || WPL == 1;
+#ifdef QNN_MFMA_TRACE
+    uint32_t trace_tile = 0;
+#endif
     __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
+    // per wave: 32 rows x 64 columns of a wave tile (rows padded by 4 ints to spread the banks), see epilogue_rows
+    constexpr int kRowPitch = 64 + 4;
+    __shared__ __attribute__((aligned(16))) int32_t c_rows[kSign ? 1 : kThreads / 64][kSign ? 1 : 32][kSign ? 4 : kRowPitch];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in a scalar register
     const int r = lane & 31, kg = lane >> 5;
@@ -224,81 +254,104 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         }
     };
 
-    auto compute = [&](const Step &c) {
-        // the masks are applied here, at the point of use, so that the loads stay in flight until now
-        uint32_t cA[WB][PA][WPL], cW[WB][PW][WPL];
+    // One phase = the 16 matrix-core instructions of one (word t, half) pair.  The operand bytes of a phase are expanded
+    // while the matrix cores work on the previous phase (an MFMA occupies its pipe for 32 cycles but the wave can
+    // issue independent vector-ALU work meanwhile, provided that work sits BETWEEN the MFMAs in program order), so the
+    // compute of a step takes the operands of its first phase ready-made and leaves those of the following step's
+    // first phase behind.
+    struct Frags {
+        v4i a[WB], w[WB];
+    };
+    struct Words {
+        uint32_t a[WB][PA], w[WB][PW];
+    };
+    // words of slot t of a step, masks applied here, at the point of use, so that the loads stay in flight until now
+    auto prep = [&](const Step &c, int t, Words &o) {
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
-            for (int p = 0; p < PA; ++p)
+            for (int p = 0; p < PA; ++p) o.a[b][p] = kChunk ? (c.A[b][p][t] & c.maskA[b]) : c.A[b][p][t];
 #pragma unroll
-                for (int t = 0; t < WPL; ++t) cA[b][p][t] = kChunk ? (c.A[b][p][t] & c.maskA[b]) : c.A[b][p][t];
-#pragma unroll
-            for (int p = 0; p < PW; ++p)
-#pragma unroll
-                for (int t = 0; t < WPL; ++t) cW[b][p][t] = kChunk ? (c.W[b][p][t] & c.maskW) : c.W[b][p][t];
+            for (int p = 0; p < PW; ++p) o.w[b][p] = kChunk ? (c.W[b][p][t] & c.maskW) : c.W[b][p][t];
         }
-        // row sums of the raw codes (popcounts of the words in use)
-        if (mc.needRA) {
+    };
+    // row sums of the raw codes: popcounts of the words a phase consumes
+    auto count = [&](const Words &o) {
+        // unconditional (a zero coefficient discards the sums that are not needed): a branch here would split the
+        // straight-line block in which the vector-ALU work is spread between the matrix-core instructions
 #pragma unroll
-            for (int b = 0; b < WB; ++b)
+        for (int b = 0; b < WB; ++b) {
 #pragma unroll
-                for (int p = 0; p < PA; ++p)
-#pragma unroll
-                    for (int t = 0; t < WPL; ++t) {
-                        if (PA == 1)
-                            ra[b] += (int32_t)__builtin_popcount(cA[b][p][t]);
-                        else
-                            ra[b] += mc.a.d[p] * (int32_t)__builtin_popcount(cA[b][p][t]);
-                    }
-        }
-        if (mc.needRW) {
-#pragma unroll
-            for (int b = 0; b < WB; ++b)
-#pragma unroll
-                for (int p = 0; p < PW; ++p)
-#pragma unroll
-                    for (int t = 0; t < WPL; ++t) {
-                        if (PW == 1)
-                            rw[b] += (int32_t)__builtin_popcount(cW[b][p][t]);
-                        else
-                            rw[b] += mc.w.d[p] * (int32_t)__builtin_popcount(cW[b][p][t]);
-                    }
-        }
-#pragma unroll
-        for (int t = 0; t < WPL; ++t) {
-            uint32_t wa[WB][PA], ww[WB][PW];
-#pragma unroll
-            for (int b = 0; b < WB; ++b) {
-#pragma unroll
-                for (int p = 0; p < PA; ++p) wa[b][p] = (PA == 1) ? cA[b][p][t] : (cA[b][p][t] ^ mc.a.inv[p]);
-#pragma unroll
-                for (int p = 0; p < PW; ++p) ww[b][p] = (PW == 1) ? cW[b][p][t] : (cW[b][p][t] ^ mc.w.inv[p]);
+            for (int p = 0; p < PA; ++p) {
+                if (PA == 1)
+                    ra[b] += (int32_t)__builtin_popcount(o.a[b][p]);
+                else
+                    ra[b] += mc.a.d[p] * (int32_t)__builtin_popcount(o.a[b][p]);
             }
 #pragma unroll
-            for (int half = 0; half < 2; ++half) {
-                v4i fa[WB], fw[WB];
-#pragma unroll
-                for (int b = 0; b < WB; ++b) {
-                    fa[b] = expand4<PA>(wa[b], mc.a, half * 4);
-                    fw[b] = expand4<PW>(ww[b], mc.w, half * 4);
-                }
-#pragma unroll
-                for (int i = 0; i < WB; ++i)
-#pragma unroll
-                    for (int j = 0; j < WB; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fw[i], fa[j], acc[i][j], 0, 0, 0);
+            for (int p = 0; p < PW; ++p) {
+                if (PW == 1)
+                    rw[b] += (int32_t)__builtin_popcount(o.w[b][p]);
+                else
+                    rw[b] += mc.w.d[p] * (int32_t)__builtin_popcount(o.w[b][p]);
             }
         }
     };
+    auto expand = [&](const Words &o, int half, Frags &f) {
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+            uint32_t xa[PA], xw[PW];
+#pragma unroll
+            for (int p = 0; p < PA; ++p) xa[p] = (PA == 1) ? o.a[b][p] : (o.a[b][p] ^ mc.a.inv[p]);
+#pragma unroll
+            for (int p = 0; p < PW; ++p) xw[p] = (PW == 1) ? o.w[b][p] : (o.w[b][p] ^ mc.w.inv[p]);
+            f.a[b] = expand4<PA>(xa, mc.a, half * 4);
+            f.w[b] = expand4<PW>(xw, mc.w, half * 4);
+        }
+    };
+    auto multiply = [&](const Frags &f) {
+#pragma unroll
+        for (int i = 0; i < WB; ++i)
+#pragma unroll
+            for (int j = 0; j < WB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w[i], f.a[j], acc[i][j], 0, 0, 0);
+    };
+    // Vector-ALU instructions of the next phase, spread evenly over the gaps after the 16 MFMAs of this one.
+    // (Estimated counts: expansion 2 ops per register and plane, popcounts, masks; a group takes what is there.)
+    constexpr auto expand_ops = [](int P, int half) { return P == 1 ? (half ? 8 : 7) : 9 * P + 4; };
+    constexpr auto count_ops = [](int P) { return P == 1 ? 1 : 2 * P; };
+    constexpr int kOpsPhase0 = WB * (expand_ops(PA, 1) + expand_ops(PW, 1) + count_ops(PA) + count_ops(PW));
+    constexpr int kOpsPhase1 = WB * (expand_ops(PA, 0) + expand_ops(PW, 0) + (kChunk ? PA + PW : 0));
+    auto interleave = [&](auto total_tag) {
+        interleave_groups<decltype(total_tag)::value>(std::make_integer_sequence<int, WB * WB>{});
+    };
+    // All phases of step `c`; `f` / `cur` enter holding the operands / words of its phase (0, 0) and leave holding
+    // those of phase (0, 0) of step `n`.
+    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur) {
+#pragma unroll
+        for (int t = 0; t < WPL; ++t) {
+            // phase (t, 0): multiply, meanwhile count the words in use and expand their second half
+            Frags g;
+            count(cur);
+            expand(cur, 1, g);
+            multiply(f);
+            interleave(std::integral_constant<int, kOpsPhase0>{});
+            __builtin_amdgcn_sched_barrier(0);
+            // phase (t, 1): multiply, meanwhile fetch and expand the first half of the following slot
+            if (t + 1 < WPL)
+                prep(c, t + 1, cur);
+            else
+                prep(n, 0, cur);
+            expand(cur, 0, f);
+            multiply(g);
+            interleave(std::integral_constant<int, kOpsPhase1>{});
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
 
-    // Accumulator register v of block [bi][bj] is C[m][n] with
-    //   m = m_wave + 32 bj + (lane mod 32),   n = n_wave + 32 bi + 8 (v / 4) + 4 (lane / 32) + v mod 4.
-    // kFast: the wave tile lies completely inside C and C allows 16-byte stores, so nothing needs a bounds check.
-    auto epilogue = [&](const int64_t m_wave, const int64_t n_wave, auto scale, auto fast_tag) {
-        constexpr bool kFast = decltype(fast_tag)::value;
-        // both k-groups of a row hold partial row sums; the weight-row sums are needed per accumulator register
-        // (n varies with the register), so they go through a small per-wave LDS table and come back as broadcasts
+    // both k-groups of a row hold partial row sums; the weight-row sums are needed per accumulator register (n varies
+    // with the register), so they go through a small per-wave LDS table and come back as broadcasts
+    auto row_sums = [&]() {
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
             ra[b] += __shfl_xor(ra[b], 32);
@@ -312,6 +365,14 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's own LDS writes have landed
             __builtin_amdgcn_wave_barrier();
         }
+    };
+
+    // Accumulator register v of block [bi][bj] is C[m][n] with
+    //   m = m_wave + 32 bj + (lane mod 32),   n = n_wave + 32 bi + 8 (v / 4) + 4 (lane / 32) + v mod 4.
+    // kFast: the wave tile lies completely inside C and C allows 16-byte stores, so nothing needs a bounds check.
+    auto epilogue = [&](const int64_t m_wave, const int64_t n_wave, auto scale, auto fast_tag) {
+        constexpr bool kFast = decltype(fast_tag)::value;
+        row_sums();
         int64_t m_of[WB];
         uint32_t mterm[WB];
 #pragma unroll
@@ -319,6 +380,19 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             m_of[bj] = m_wave + bj * 32 + r;
             mterm[bj] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
         }
+        int32_t T_next[16];
+        uint32_t flips_next = 0;
+        auto load_thresholds = [&](const int64_t n_first, int32_t (&T)[16], uint32_t &flips) {
+            flips = 0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int64_t n = n_first + 8 * (v >> 2) + 4 * kg + (v & 3);
+                const bool live = kFast || n < g.N;
+                T[v] = live ? g.epi.T[n] : 0;
+                if (g.epi.flip && live && g.epi.flip[n] != 0) flips |= 1u << v;
+            }
+        };
+        if constexpr (kSign) load_thresholds(n_wave, T_next, flips_next);
 #pragma unroll
         for (int bi = 0; bi < WB; ++bi) {
             const int64_t n_blk = n_wave + bi * 32;
@@ -350,15 +424,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                     }
                 }
             } else {
+                // thresholds of this block of n were requested one block ahead (their latency hides behind the
+                // previous block's compares); request the next block's now
                 int32_t T[16];
-                uint32_t flips = 0;
+                uint32_t flips = flips_next;
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int64_t n = n_blk + 8 * (v >> 2) + 4 * kg + (v & 3);
-                    const bool live = kFast || n < g.N;
-                    T[v] = live ? g.epi.T[n] : 0;
-                    if (g.epi.flip && live && g.epi.flip[n] != 0) flips |= 1u << v;
-                }
+                for (int v = 0; v < 16; ++v) T[v] = T_next[v];
+                if (bi + 1 < WB) load_thresholds(n_blk + 32, T_next, flips_next);
                 const int64_t word = n_blk >> 5;
 #pragma unroll
                 for (int bj = 0; bj < WB; ++bj) {
@@ -380,6 +452,50 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             __builtin_amdgcn_sched_barrier(0);
         }
     };
+    // int32 output of a wave tile that lies completely inside C: the accumulators of 32 rows (m) x 64 columns (n) at a
+    // time are transposed through LDS so that every store instruction writes four complete 256-byte row segments
+    // (straight from the accumulator layout an instruction would touch 32 rows with 32 bytes each).  The eight LDS
+    // reads of a pass are issued together and only then the eight stores, so that LDS latency is paid once per pass.
+    auto epilogue_rows = [&](const int64_t m_wave, const int64_t n_wave, auto scale) {
+        if constexpr (!kSign) {
+            row_sums();
+            const int out_row = lane >> 4, out_col = (lane & 15) * 4;
+#pragma unroll
+            for (int bj = 0; bj < WB; ++bj) {
+                const uint32_t mterm = mc.cRA * (uint32_t)ra[bj] + mc.c0;
+#pragma unroll
+                for (int pr = 0; pr < WB / 2; ++pr) {
+#pragma unroll
+                    for (int b2 = 0; b2 < 2; ++b2)
+#pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            const int bi = 2 * pr + b2;
+                            const int col = b2 * 32 + 8 * q + 4 * kg;
+                            uint4 t4 = make_uint4(0u, 0u, 0u, 0u);
+                            if (mc.needRW) t4 = *reinterpret_cast<const uint4 *>(&rw_table[wave][pr * 64 + col]);
+                            i32x4 val;
+                            val[0] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + 0]) + t4.x + mterm);
+                            val[1] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + 1]) + t4.y + mterm);
+                            val[2] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + 2]) + t4.z + mterm);
+                            val[3] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + 3]) + t4.w + mterm);
+                            *reinterpret_cast<i32x4 *>(&c_rows[wave][r][col]) = val;
+                        }
+                    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
+                    __builtin_amdgcn_wave_barrier();
+                    i32x4 v[8];
+#pragma unroll
+                    for (int it = 0; it < 8; ++it)
+                        v[it] = *reinterpret_cast<const i32x4 *>(&c_rows[wave][4 * it + out_row][out_col]);
+                    __builtin_amdgcn_sched_barrier(0);
+                    int32_t *dst = g.epi.C + (m_wave + bj * 32 + out_row) * g.epi.ldc + n_wave + pr * 64 + out_col;
+#pragma unroll
+                    for (int it = 0; it < 8; ++it)
+                        __builtin_nontemporal_store(v[it], reinterpret_cast<i32x4 *>(dst + (int64_t)(4 * it) * g.epi.ldc));
+                    __builtin_amdgcn_wave_barrier();
+                }
+            }
+        }
+    };
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) {
         const bool interior = m_wave + WTILE <= g.M && n_wave + WTILE <= g.N;
         const bool wide = kSign || ((g.epi.ldc % 4 == 0) && (reinterpret_cast<uintptr_t>(g.epi.C) % 16 == 0));
@@ -387,14 +503,18 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         if (mc.alpha_shift >= 0) {
             const int sh = mc.alpha_shift;
             auto scale = [sh](uint32_t x) { return x << sh; };
-            if (fast)
+            if (fast && !kSign)
+                epilogue_rows(m_wave, n_wave, scale);
+            else if (fast)
                 epilogue(m_wave, n_wave, scale, std::true_type{});
             else
                 epilogue(m_wave, n_wave, scale, std::false_type{});
         } else {
             const uint32_t al = mc.alpha;
             auto scale = [al](uint32_t x) { return x * al; };
-            if (fast)
+            if (fast && !kSign)
+                epilogue_rows(m_wave, n_wave, scale);
+            else if (fast)
                 epilogue(m_wave, n_wave, scale, std::true_type{});
             else
                 epilogue(m_wave, n_wave, scale, std::false_type{});
@@ -402,31 +522,39 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     };
 
     // Persistent workgroups.  Per tile: two steps per trip, ping-pong between two register buffers; the loads of the
-    // next tile's first step are issued before this tile's stores, so they are older than the stores in the memory
-    // queue and the stores drain while the next tile is already being computed.  msteps is even; steps past the end of
+    // next tile's first step are issued (and its first operands expanded) before this tile's stores, so they are older
+    // than the stores in the memory queue and the stores drain while the next tile is already being computed.  msteps is even; steps past the end of
     // K read zero words, which the epilogue constants account for.  The scheduling fences keep each batch of loads in
     // front of the matrix-core block that hides its latency.
     Step buf0, buf1;
     Tile cur;
+    Frags frags;
+    Words words;
     uint32_t vb = blockIdx.x;
     locate(vb, cur);
     fetch(cur, 0, buf0);
+    prep(buf0, 0, words);
+    expand(words, 0, frags);
+#ifdef QNN_MFMA_TRACE
+    if (g_trace && threadIdx.x == 0) g_trace[(blockIdx.x * 8 + 7) * 8 + 7] = __builtin_amdgcn_s_memrealtime();
+#endif
     while (true) {
+        QNN_STAMP(0);
         clear();
+        QNN_STAMP(1);
         for (uint32_t s = 0; s + 2 < mc.msteps; s += 2) {
             fetch(cur, s + 1, buf1);
             __builtin_amdgcn_sched_barrier(0);
-            compute(buf0);
-            __builtin_amdgcn_sched_barrier(0);
+            compute(buf0, buf1, frags, words);
             fetch(cur, s + 2, buf0);
             __builtin_amdgcn_sched_barrier(0);
-            compute(buf1);
-            __builtin_amdgcn_sched_barrier(0);
+            compute(buf1, buf0, frags, words);
         }
+        QNN_STAMP(2);
         fetch(cur, mc.msteps - 1, buf1);
         __builtin_amdgcn_sched_barrier(0);
-        compute(buf0);
-        __builtin_amdgcn_sched_barrier(0);
+        compute(buf0, buf1, frags, words);
+        QNN_STAMP(3);
         // the operand rows of this tile are not needed any more: move on to the next tile's
         const int64_t m_done = cur.m_wave, n_done = cur.n_wave;
         const uint32_t vb_next = vb + gridDim.x;
@@ -434,9 +562,15 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         locate(more ? vb_next : vb, cur);  // without a next tile the loads are repeated and ignored
         fetch(cur, 0, buf0);
         __builtin_amdgcn_sched_barrier(0);
-        compute(buf1);
-        __builtin_amdgcn_sched_barrier(0);
+        compute(buf1, buf0, frags, words);
+        QNN_STAMP(4);
         finish(m_done, n_done);
+        QNN_STAMP(5);
+#ifdef QNN_MFMA_TRACE
+        if (g_trace && threadIdx.x == 0 && trace_tile < 8)
+            g_trace[(blockIdx.x * 8 + trace_tile) * 8 + 6] = __builtin_amdgcn_s_memrealtime();
+        ++trace_tile;
+#endif
         if (!more) break;
         vb = vb_next;
     }
@@ -588,5 +722,11 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s) {
                        (uint32_t)tiles_n);
     return check_launch("gemm_mfma");
 }
+
+#ifdef QNN_MFMA_TRACE
+extern "C" int qnn_debug_set_trace(unsigned long long *buf) {
+    return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_trace), &buf, sizeof(buf));
+}
+#endif
 
 }  // namespace qnn

@@ -73,7 +73,10 @@ __device__ __forceinline__ void tile_of_block(uint32_t bid, uint32_t total, uint
     const uint32_t band_rows = (tiles_m - first_m < kBand) ? (tiles_m - first_m) : kBand;
     const uint32_t in_band = id - band * per_band;
     tm = first_m + in_band % band_rows;
-    tn = in_band / band_rows;
+    // Tiles that run at the same time sit at the same position of different bands.  Rotating the columns band by band
+    // keeps them in different column ranges of C, so that their stores (and W reads) go to different memory channels
+    // even when the row pitch of C is a power of two.
+    tn = (in_band / band_rows + band * 4u) % tiles_n;
 }
 
 // Engines.  Both return QNN_OK / QNN_ERR_*; `mfma_supports` says whether the matrix-core engine can take the job.
