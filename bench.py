@@ -59,6 +59,9 @@ def main():
     ap.add_argument("--only", default="", help="comma list of c1,c2,c3,c4,c5 (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--traffic-probe", action="store_true",
+                    help="also run a plain 256 MiB device copy (known size) so that rocprofv3 --pmc FETCH_SIZE / "
+                         "WRITE_SIZE readings of the GEMM can be scaled by what the same counter reads for the copy")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (every configuration is measured whole on one MI355X); "
@@ -111,6 +114,13 @@ def main():
             roof["traffic"] = json.load(open(tpath)).get(roof["kernel"] + "@c3")
         except Exception:
             pass
+
+    if args.traffic_probe:
+        D3 = torch.empty_like(C3)
+        for _ in range(3):
+            D3.copy_(C3)  # 268 435 456 bytes read + the same written per call
+        torch.cuda.synchronize()
+        del D3
 
     # ---------------------------------------------------------------- C3 with sign+pack from fp32 included
     if "c3" in only:
