@@ -25,6 +25,7 @@ import numpy as np  # noqa: E402
 
 VALU_PEAK_TOPS = 256 * 64 * 32 * 2.4e9 / 1e12  # 256 CUs x 64 lanes/clk x (32 MAC per xor+bcnt pair = 32 ops/lane/clk) x 2.4 GHz
 MFMA_I8_PEAK_TOPS = 5000.0                     # dense int8 matrix-core peak, 2 ops per MAC
+MFMA_FP4_PEAK_TOPS = 10100.0                   # dense FP4 matrix-core peak
 HBM_PEAK_GBS = 8000.0
 
 
@@ -55,7 +56,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--engine", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--engine", default="auto", choices=["auto", "valu", "mfma", "fp4"])
     ap.add_argument("--only", default="", help="comma list of c1,c2,c3,c4,c5 (default: all)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
@@ -76,7 +77,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    engine = {"auto": q.ENGINE_AUTO, "valu": q.ENGINE_VALU, "mfma": q.ENGINE_MFMA}[args.engine]
+    engine = {"auto": q.ENGINE_AUTO, "valu": q.ENGINE_VALU, "mfma": q.ENGINE_MFMA, "fp4": q.ENGINE_MFMA_FP4}[args.engine]
     only = set(filter(None, args.only.split(","))) or {"c1", "c2", "c3", "c4", "c5"}
     seed = qi.SEED_BASE
     steps, warmup = args.steps, args.warmup
@@ -99,13 +100,20 @@ def main():
 
     rows = np.array([0, 4095, 8191])
     assert np.array_equal(C3[rows].cpu().numpy(), oracle.gemm_pm1(a3[rows], w3)), "C3 output differs from the oracle"
-    used_mfma = q.qnn_last_engine() == q.ENGINE_MFMA
-    if used_mfma:
+    used = q.qnn_last_engine()
+    used_name = {q.ENGINE_VALU: "valu", q.ENGINE_MFMA: "mfma", q.ENGINE_MFMA_FP4: "fp4"}[used]
+    if used == q.ENGINE_MFMA_FP4:
+        roof = {"bound": "mfma", "achieved": tops3, "peak": MFMA_FP4_PEAK_TOPS, "unit": "TOP/s",
+                "frac": tops3 / MFMA_FP4_PEAK_TOPS, "traffic": None, "kernel": "gemm_mfma_kernel<fp4>",
+                "peak_dtype": "fp4 (E2M1) dense MFMA, fp32 accumulate"}
+    elif used == q.ENGINE_MFMA:
         roof = {"bound": "mfma", "achieved": tops3, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
-                "frac": tops3 / MFMA_I8_PEAK_TOPS, "traffic": None, "kernel": "gemm_mfma_kernel"}
+                "frac": tops3 / MFMA_I8_PEAK_TOPS, "traffic": None, "kernel": "gemm_mfma_kernel",
+                "peak_dtype": "int8 dense MFMA, int32 accumulate"}
     else:
         roof = {"bound": "alu", "achieved": tops3, "peak": VALU_PEAK_TOPS, "unit": "TOP/s",
-                "frac": tops3 / VALU_PEAK_TOPS, "traffic": None, "kernel": "gemm_valu_kernel"}
+                "frac": tops3 / VALU_PEAK_TOPS, "traffic": None, "kernel": "gemm_valu_kernel",
+                "peak_dtype": "integer vector ALU: one xor and one popcount-accumulate per 32 MACs"}
     roof["frac_of_int8_mfma_peak"] = tops3 / MFMA_I8_PEAK_TOPS
     roof["frac_of_valu_xor_popcount_peak"] = tops3 / VALU_PEAK_TOPS
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
@@ -222,7 +230,7 @@ def main():
         "dtype": "u32 bit-packed +-1 operands, int32 accumulate",
         "data": "synthetic (seeded Bernoulli(0.5) +-1 operands; stands in for the paper's 8192^3 benchmark matrices)",
         "config": {"workload": "C3: 8192x8192x8192 binary GEMM on packed +-1 operands, int32 output",
-                   "engine": "mfma" if used_mfma else "valu", "M": n, "N": n, "K": n},
+                   "engine": used_name, "M": n, "N": n, "K": n},
         "mlp_forward_samples_per_s": extra.get("c2_mlp_forward", {}).get("samples_per_s"),
         "roofline": roof,
         "cpu_baseline": cpu,

@@ -57,7 +57,9 @@ typedef enum {
 typedef enum {
     QNN_ENGINE_AUTO = 0, /* library's choice for the shape */
     QNN_ENGINE_VALU = 1, /* 32 connections per xor/and + popcount-accumulate pair (Sec. 6 Eq. (popc)) */
-    QNN_ENGINE_MFMA = 2  /* bits expanded on chip to int8 and contracted on the matrix cores */
+    QNN_ENGINE_MFMA = 2, /* bits expanded on chip to int8 and contracted on the matrix cores */
+    QNN_ENGINE_MFMA_FP4 = 3 /* single-plane operands expanded to FP4 zeros and ones, contracted on the matrix cores with
+                               fp32 accumulation (exact: the sums are integers far below 2^24) */
 } qnn_engine;
 
 #define QNN_MAX_PLANES 8
@@ -153,7 +155,7 @@ int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int mod
                         const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
                         int pad, int stride_hw, int32_t *out, int engine, void *stream);
 
-/* Engine (QNN_ENGINE_VALU or QNN_ENGINE_MFMA) that the calling thread's last successful multiply call used; 0 before
+/* Engine (QNN_ENGINE_VALU, QNN_ENGINE_MFMA or QNN_ENGINE_MFMA_FP4) that the calling thread's last successful multiply call used; 0 before
  * any.  For reports: results never depend on it. */
 int qnn_last_engine(void);
 

@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 import torch
 
 PLANE_BIT, PLANE_SIGN = 0, 1
-ENGINE_AUTO, ENGINE_VALU, ENGINE_MFMA = 0, 1, 2
+ENGINE_AUTO, ENGINE_VALU, ENGINE_MFMA, ENGINE_MFMA_FP4 = 0, 1, 2, 3
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqnn.so")

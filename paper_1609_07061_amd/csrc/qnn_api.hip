@@ -45,7 +45,8 @@ int check_planes(const char *who, int P, const int32_t *coef, int mode) {
 }
 
 int check_engine(int engine) {
-    if (engine != QNN_ENGINE_AUTO && engine != QNN_ENGINE_VALU && engine != QNN_ENGINE_MFMA)
+    if (engine != QNN_ENGINE_AUTO && engine != QNN_ENGINE_VALU && engine != QNN_ENGINE_MFMA &&
+        engine != QNN_ENGINE_MFMA_FP4)
         return fail(QNN_ERR_SHAPE, "unknown engine %d", engine);
     return QNN_OK;
 }
@@ -60,11 +61,21 @@ int check_range(const GemmArgs &g) {
 }
 
 int dispatch(const GemmArgs &g, int engine, hipStream_t s) {
+    int chosen = engine;
+    if (engine == QNN_ENGINE_MFMA_FP4 && !mfma_supports(g, true))
+        return fail(QNN_ERR_UNSUPPORTED, "FP4 matrix-core engine takes single-plane operands of supported shapes only");
     if (engine == QNN_ENGINE_MFMA && !mfma_supports(g))
         return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
-    const bool mfma = engine == QNN_ENGINE_MFMA || (engine == QNN_ENGINE_AUTO && mfma_supports(g) && mfma_preferred(g));
-    const int rc = mfma ? launch_gemm_mfma(g, s) : launch_gemm_valu(g, s);
-    if (rc == QNN_OK) g_last_engine = mfma ? QNN_ENGINE_MFMA : QNN_ENGINE_VALU;
+    if (engine == QNN_ENGINE_AUTO) {
+        if (mfma_preferred(g) && mfma_supports(g, true))
+            chosen = QNN_ENGINE_MFMA_FP4;
+        else if (mfma_preferred(g) && mfma_supports(g))
+            chosen = QNN_ENGINE_MFMA;
+        else
+            chosen = QNN_ENGINE_VALU;
+    }
+    const int rc = chosen == QNN_ENGINE_VALU ? launch_gemm_valu(g, s) : launch_gemm_mfma(g, s, chosen == QNN_ENGINE_MFMA_FP4);
+    if (rc == QNN_OK) g_last_engine = chosen;
     return rc;
 }
 

@@ -28,6 +28,8 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef int v8i __attribute__((ext_vector_type(8)));
+typedef float v16f __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
 constexpr int WB = 4;           // 32 x 32 blocks per wave tile side
@@ -71,6 +73,20 @@ __device__ __forceinline__ v4i expand4(const uint32_t (&w)[P], const Code &c, in
         }
         out[jj] = (int)u;
     }
+    return out;
+}
+
+// Single 0/1 plane -> FP4 (E2M1) operands of v_mfma_f32_32x32x64_f8f6f4: nibble 0b0010 is 1.0, so register j holds
+// bits j, j+4, ..., j+28 of the word as eight nibbles worth 0.0 or 1.0 (seven VALU ops per 32 connections).  Products
+// and fp32 sums of zeros and ones are exact far beyond any K the engine accepts.  The upper four registers of the
+// builtin's operand type are not read for this format.
+__device__ __forceinline__ v8i expand_fp4(uint32_t w) {
+    v8i out;
+    out[0] = (int)((w << 1) & 0x22222222u);
+    out[1] = (int)(w & 0x22222222u);
+    out[2] = (int)((w >> 1) & 0x22222222u);
+    out[3] = (int)((w >> 2) & 0x22222222u);
+    out[4] = out[5] = out[6] = out[7] = 0;
     return out;
 }
 
@@ -168,7 +184,7 @@ __device__ __forceinline__ void interleave_groups(std::integer_sequence<int, I..
 
 // The weights feed the row side of the matrix core (accumulator registers 4q .. 4q+3 of a lane are then four
 // consecutive n of one m, i.e. 16 contiguous bytes of C) and the activations the column side (lane = m).
-template <int PA, int PW, int WPL, bool kVec, bool kPixels, bool kSign>
+template <int PA, int PW, int WPL, bool kVec, bool kPixels, bool kSign, bool kFp4 = false>
 __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                 uint32_t tiles_n) {
     constexpr bool kChunk = kVec || WPL == 1;
@@ -241,7 +257,15 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         }
     };
 
-    v16i acc[WB][WB];  // [n block][m block]
+    static_assert(!kFp4 || (PA == 1 && PW == 1), "the FP4 path takes one plane per operand");
+    using Acc = std::conditional_t<kFp4, v16f, v16i>;
+    Acc acc[WB][WB];  // [n block][m block]
+    auto sum_of = [&](const Acc &a, int v) -> uint32_t {  // the integer S of one accumulator register
+        if constexpr (kFp4)
+            return (uint32_t)(int32_t)a[v];
+        else
+            return (uint32_t)a[v];
+    };
     int32_t ra[WB], rw[WB];
     auto clear = [&]() {
 #pragma unroll
@@ -250,7 +274,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
 #pragma unroll
             for (int j = 0; j < WB; ++j)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0;  // (0.0f on the FP4 path)
         }
     };
 
@@ -259,8 +283,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     // issue independent vector-ALU work meanwhile, provided that work sits BETWEEN the MFMAs in program order), so the
     // compute of a step takes the operands of its first phase ready-made and leaves those of the following step's
     // first phase behind.
+    using Operand = std::conditional_t<kFp4, v8i, v4i>;
     struct Frags {
-        v4i a[WB], w[WB];
+        Operand a[WB], w[WB];
     };
     struct Words {
         uint32_t a[WB][PA], w[WB][PW];
@@ -305,8 +330,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             for (int p = 0; p < PA; ++p) xa[p] = (PA == 1) ? o.a[b][p] : (o.a[b][p] ^ mc.a.inv[p]);
 #pragma unroll
             for (int p = 0; p < PW; ++p) xw[p] = (PW == 1) ? o.w[b][p] : (o.w[b][p] ^ mc.w.inv[p]);
-            f.a[b] = expand4<PA>(xa, mc.a, half * 4);
-            f.w[b] = expand4<PW>(xw, mc.w, half * 4);
+            if constexpr (kFp4) {
+                f.a[b] = expand_fp4(xa[0]);
+                f.w[b] = expand_fp4(xw[0]);
+            } else {
+                f.a[b] = expand4<PA>(xa, mc.a, half * 4);
+                f.w[b] = expand4<PW>(xw, mc.w, half * 4);
+            }
         }
     };
     auto multiply = [&](const Frags &f) {
@@ -314,7 +344,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         for (int i = 0; i < WB; ++i)
 #pragma unroll
             for (int j = 0; j < WB; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w[i], f.a[j], acc[i][j], 0, 0, 0);
+                if constexpr (kFp4)
+                    acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.w[i], f.a[j], acc[i][j], 4, 4, 0, 0, 0, 0);
+                else
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(f.w[i], f.a[j], acc[i][j], 0, 0, 0);
     };
     // Vector-ALU instructions of the next phase, spread evenly over the gaps after the 16 MFMAs of this one.
     // (Estimated counts: expansion 2 ops per register and plane, popcounts, masks; a group takes what is there.)
@@ -327,25 +360,43 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     };
     // All phases of step `c`; `f` / `cur` enter holding the operands / words of its phase (0, 0) and leave holding
     // those of phase (0, 0) of step `n`.
+    constexpr int kOpsPhaseFp4 = WB * (7 + 7 + 2 + (kChunk ? 2 : 0));
     auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur) {
 #pragma unroll
         for (int t = 0; t < WPL; ++t) {
-            // phase (t, 0): multiply, meanwhile count the words in use and expand their second half
-            Frags g;
-            count(cur);
-            expand(cur, 1, g);
-            multiply(f);
-            interleave(std::integral_constant<int, kOpsPhase0>{});
-            __builtin_amdgcn_sched_barrier(0);
-            // phase (t, 1): multiply, meanwhile fetch and expand the first half of the following slot
-            if (t + 1 < WPL)
-                prep(c, t + 1, cur);
-            else
-                prep(n, 0, cur);
-            expand(cur, 0, f);
-            multiply(g);
-            interleave(std::integral_constant<int, kOpsPhase1>{});
-            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (kFp4) {
+                // one phase per word: a 32x32x64 FP4 instruction consumes all 32 bits a lane holds
+                Frags g;
+                Words nxt;
+                count(cur);
+                if (t + 1 < WPL)
+                    prep(c, t + 1, nxt);
+                else
+                    prep(n, 0, nxt);
+                expand(nxt, 0, g);
+                multiply(f);
+                interleave(std::integral_constant<int, kOpsPhaseFp4>{});
+                __builtin_amdgcn_sched_barrier(0);
+                f = g;
+                cur = nxt;
+            } else {
+                // phase (t, 0): multiply, meanwhile count the words in use and expand their second half
+                Frags g;
+                count(cur);
+                expand(cur, 1, g);
+                multiply(f);
+                interleave(std::integral_constant<int, kOpsPhase0>{});
+                __builtin_amdgcn_sched_barrier(0);
+                // phase (t, 1): multiply, meanwhile fetch and expand the first half of the following slot
+                if (t + 1 < WPL)
+                    prep(c, t + 1, cur);
+                else
+                    prep(n, 0, cur);
+                expand(cur, 0, f);
+                multiply(g);
+                interleave(std::integral_constant<int, kOpsPhase1>{});
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
     };
 
@@ -412,7 +463,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                         i32x4 val;
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            val[i] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + i]) + nterm[4 * q + i] + mterm[bj]);
+                            val[i] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + i)) + nterm[4 * q + i] + mterm[bj]);
                         if constexpr (kFast) {
                             *reinterpret_cast<i32x4 *>(row + 8 * q) = val;
                         } else if (m_of[bj] < g.M) {
@@ -438,7 +489,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
 #pragma unroll
                     for (int v = 0; v < 16; ++v) {
                         const int64_t n = n_blk + 8 * (v >> 2) + 4 * kg + (v & 3);
-                        const int32_t val = (int32_t)(scale((uint32_t)acc[bi][bj][v]) + nterm[v] + mterm[bj]);
+                        const int32_t val = (int32_t)(scale(sum_of(acc[bi][bj], v)) + nterm[v] + mterm[bj]);
                         const bool ge = val >= T[v];
                         const bool b = (kFast || n < g.N) && (ge != (((flips >> v) & 1u) != 0));
                         bits |= (b ? 1u : 0u) << (8 * (v >> 2) + (v & 3));
@@ -474,10 +525,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                             uint4 t4 = make_uint4(0u, 0u, 0u, 0u);
                             if (mc.needRW) t4 = *reinterpret_cast<const uint4 *>(&rw_table[wave][pr * 64 + col]);
                             i32x4 val;
-                            val[0] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + 0]) + t4.x + mterm);
-                            val[1] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + 1]) + t4.y + mterm);
-                            val[2] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + 2]) + t4.z + mterm);
-                            val[3] = (int32_t)(scale((uint32_t)acc[bi][bj][4 * q + 3]) + t4.w + mterm);
+                            val[0] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + 0)) + t4.x + mterm);
+                            val[1] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + 1)) + t4.y + mterm);
+                            val[2] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + 2)) + t4.z + mterm);
+                            val[3] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + 3)) + t4.w + mterm);
                             *reinterpret_cast<i32x4 *>(&c_rows[wave][r][col]) = val;
                         }
                     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
@@ -631,17 +682,27 @@ struct Variant {
     int PA, PW, WPL;
     bool pixels, sign;
     KernelFn fn_vec, fn_any;  // rows aligned to the load width (vector loads) / any layout (word loads)
+    KernelFn fp4_vec, fp4_any;  // the same on the FP4 matrix-core path (single 0/1 or +-1 planes only), else null
 };
 
-#define QNN_VARIANT(PA, PW, WPL, PIX, SGN) \
-    { PA, PW, WPL, PIX, SGN, gemm_mfma_kernel<PA, PW, WPL, true, PIX, SGN>, gemm_mfma_kernel<PA, PW, WPL, (WPL == 1), PIX, SGN> }
+#define QNN_VARIANT(PA, PW, WPL, PIX, SGN)                                                                        \
+    {                                                                                                             \
+        PA, PW, WPL, PIX, SGN, gemm_mfma_kernel<PA, PW, WPL, true, PIX, SGN>,                                     \
+            gemm_mfma_kernel<PA, PW, WPL, (WPL == 1), PIX, SGN>, nullptr, nullptr                                 \
+    }
+#define QNN_VARIANT_FP4(WPL, PIX, SGN)                                                                            \
+    {                                                                                                             \
+        1, 1, WPL, PIX, SGN, gemm_mfma_kernel<1, 1, WPL, true, PIX, SGN>, gemm_mfma_kernel<1, 1, WPL, false, PIX, SGN>, \
+            gemm_mfma_kernel<1, 1, WPL, true, PIX, SGN, true>, gemm_mfma_kernel<1, 1, WPL, false, PIX, SGN, true>  \
+    }
 const Variant kVariants[] = {
-    QNN_VARIANT(1, 1, 4, false, false), QNN_VARIANT(1, 1, 4, false, true),  QNN_VARIANT(8, 1, 1, false, false),
+    QNN_VARIANT_FP4(4, false, false), QNN_VARIANT_FP4(4, false, true),  QNN_VARIANT(8, 1, 1, false, false),
     QNN_VARIANT(8, 1, 1, false, true),  QNN_VARIANT(4, 4, 1, false, false), QNN_VARIANT(2, 1, 2, false, false),
     QNN_VARIANT(4, 1, 1, false, false), QNN_VARIANT(2, 2, 2, false, false), QNN_VARIANT(1, 1, 4, true, false),
     QNN_VARIANT(2, 1, 2, true, false),
 };
 #undef QNN_VARIANT
+#undef QNN_VARIANT_FP4
 
 const Variant *find_variant(const GemmArgs &g) {
     const bool pixels = g.A.rows_are_pixels != 0, sign = g.epi.T != nullptr;
@@ -650,9 +711,10 @@ const Variant *find_variant(const GemmArgs &g) {
     return nullptr;
 }
 
-bool prepare(const GemmArgs &g, const Variant *&var, MfmaConst &mc, bool &vec) {
+bool prepare(const GemmArgs &g, bool fp4, const Variant *&var, MfmaConst &mc, bool &vec) {
     var = find_variant(g);
     if (!var) return false;
+    if (fp4 && !var->fp4_vec) return false;
     int64_t aA, bA, xA0, aW, bW, xW0;
     if (!make_code(g.pa, mc.a, aA, bA, xA0) || !make_code(g.pw, mc.w, aW, bW, xW0)) return false;
     const int64_t step_words = 2 * var->WPL;
@@ -688,11 +750,11 @@ bool prepare(const GemmArgs &g, const Variant *&var, MfmaConst &mc, bool &vec) {
 
 }  // namespace
 
-bool mfma_supports(const GemmArgs &g) {
+bool mfma_supports(const GemmArgs &g, bool fp4) {
     const Variant *v;
     MfmaConst mc;
     bool vec;
-    return prepare(g, v, mc, vec);
+    return prepare(g, fp4, v, mc, vec);
 }
 
 bool mfma_preferred(const GemmArgs &g) {
@@ -700,11 +762,11 @@ bool mfma_preferred(const GemmArgs &g) {
     return ceil_div(g.M, BM) * ceil_div(g.N, BN) >= 32 && g.K >= 256;
 }
 
-int launch_gemm_mfma(const GemmArgs &g, hipStream_t s) {
+int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
     const Variant *v;
     MfmaConst mc;
     bool vec;
-    if (!prepare(g, v, mc, vec)) return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
+    if (!prepare(g, fp4, v, mc, vec)) return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
     const int64_t tiles_m = ceil_div(g.M, BM), tiles_n = ceil_div(g.N, BN);
     if (tiles_m * tiles_n > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "gemm: too many tiles");
     // one persistent workgroup per compute unit (each takes 512 registers per lane, so one fits)
@@ -718,7 +780,7 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s) {
     }
     const int64_t total = tiles_m * tiles_n;
     const unsigned grid = (unsigned)(total < cus ? total : cus);
-    hipLaunchKernelGGL(vec ? v->fn_vec : v->fn_any, dim3(grid), dim3(kThreads), 0, s, g, mc, (uint32_t)tiles_m,
+    hipLaunchKernelGGL(fp4 ? (vec ? v->fp4_vec : v->fp4_any) : (vec ? v->fn_vec : v->fn_any), dim3(grid), dim3(kThreads), 0, s, g, mc, (uint32_t)tiles_m,
                        (uint32_t)tiles_n);
     return check_launch("gemm_mfma");
 }

@@ -81,9 +81,9 @@ __device__ __forceinline__ void tile_of_block(uint32_t bid, uint32_t total, uint
 
 // Engines.  Both return QNN_OK / QNN_ERR_*; `mfma_supports` says whether the matrix-core engine can take the job.
 int launch_gemm_valu(const GemmArgs &g, hipStream_t s);
-bool mfma_supports(const GemmArgs &g);
+bool mfma_supports(const GemmArgs &g, bool fp4 = false);  // fp4: on the FP4 (E2M1) matrix-core path
 bool mfma_preferred(const GemmArgs &g);  // whether AUTO should pick it for this shape
-int launch_gemm_mfma(const GemmArgs &g, hipStream_t s);
+int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4 = false);
 
 int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo, hipStream_t s);
 int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,

@@ -24,14 +24,14 @@ def _lib():
     torch.cuda.synchronize()
 
 
-ENGINES = [1, 2, 0]  # VALU, MFMA, AUTO
+ENGINES = [1, 2, 3, 0]  # VALU, int8 MFMA, FP4 MFMA, AUTO
 
 
 def _engine_or_skip(fn, *a, engine, **kw):
     try:
         return fn(*a, engine=engine, **kw)
     except Exception as e:  # QnnError with status 5 = engine cannot take the job
-        if getattr(e, "status", None) == 5 and engine == 2:
+        if getattr(e, "status", None) == 5 and engine in (2, 3):
             pytest.skip("matrix-core engine does not take this shape")
         raise
 
