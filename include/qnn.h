@@ -131,6 +131,9 @@ int qnn_fold_batchnorm(const double *gamma, const double *beta, const double *me
 
 /* S5. Alg. 4 end to end, up to the integer output-layer sums: in_bits-bit unsigned inputs -> bit planes -> first
  * layer as weighted plane products -> Sign(BatchNorm) -> binary layers -> int32 logits of the last layer.
+ * (With 8-bit inputs in 16-byte aligned rows the first layer may be evaluated as x . W_1 straight from the codes,
+ * which Eq. (FirstLayer) states to be the same sum; the planes are then not materialised.  Only the low in_bits bits
+ * of a code count.)
  * x: DEVICE uint8 [batch][ldx].  dims: HOST int64 [n_layers + 1] (dims[0] = input width).
  * W: HOST array of n_layers DEVICE pointers, W[l] packed +-1 [dims[l+1]][ceil(dims[l]/32)] (dense rows).
  * T, flip: HOST arrays of n_layers - 1 DEVICE pointers (flip, or any flip[l], may be NULL).

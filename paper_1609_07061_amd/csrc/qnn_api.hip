@@ -297,14 +297,39 @@ int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_
     }
     uint32_t *act[2] = {reinterpret_cast<uint32_t *>(ws + off), reinterpret_cast<uint32_t *>(ws + off + act_bytes)};
 
-    // Alg. 4, step 1: bit planes of the input, then sum_n 2^(n-1) (x^n . W_1) followed by Sign(BatchNorm)
-    if (int rc = qnn_pack_bitplanes(x, batch, dims[0], ldx, in_bits, planes, ld0, plane_stride, stream)) return rc;
+    // Alg. 4, step 1: s = sum_n 2^(n-1) (x^n . W_1), followed by Sign(BatchNorm).  By Eq. (FirstLayer) that sum IS
+    // x . W_1 on the 8-bit codes, and the matrix-core engine can take the codes as they are (x - 128 is an int8
+    // operand): no planes are materialised then.  Otherwise: planes, then the weighted plane products.
     int32_t coef[QNN_MAX_PLANES];
     for (int p = 0; p < in_bits; ++p) coef[p] = 1 << p;
-    if (int rc = qnn_bitplane_gemm_sign(planes, in_bits, coef, QNN_PLANE_BIT, ld0, plane_stride, W[0], 1, kOne,
-                                        QNN_PLANE_SIGN, words_for(dims[0]), 0, T[0], flip ? flip[0] : nullptr, act[0],
-                                        ldw(dims[1]), batch, dims[1], dims[0], engine, stream))
-        return rc;
+    bool first_done = false;
+    if (in_bits == 8 && (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA)) {
+        GemmArgs g;
+        std::memset(&g, 0, sizeof(g));
+        g.A.base = reinterpret_cast<const uint32_t *>(x);
+        g.A.ld = ldx;
+        g.A.rows_are_bytes = 1;
+        g.pa.count = 8, g.pa.mode = QNN_PLANE_BIT;
+        for (int p = 0; p < 8; ++p) g.pa.coef[p] = coef[p];
+        g.W = W[0];
+        g.ldw = words_for(dims[0]);
+        g.pw.count = 1, g.pw.mode = QNN_PLANE_SIGN, g.pw.coef[0] = 1;
+        g.epi = Epilogue{nullptr, 0, T[0], flip ? flip[0] : nullptr, act[0], ldw(dims[1])};
+        g.M = batch, g.N = dims[1], g.K = dims[0], g.Kw = words_for(dims[0]);
+        if (int rc = check_range(g)) return rc;
+        if (mfma_supports(g) && (engine == QNN_ENGINE_MFMA || mfma_preferred(g))) {
+            if (!aligned4(W[0]) || !aligned4(T[0])) return fail(QNN_ERR_ALIGN, "mlp: pointer not 4-byte aligned");
+            if (int rc = launch_gemm_mfma(g, static_cast<hipStream_t>(stream))) return rc;
+            first_done = true;
+        }
+    }
+    if (!first_done) {
+        if (int rc = qnn_pack_bitplanes(x, batch, dims[0], ldx, in_bits, planes, ld0, plane_stride, stream)) return rc;
+        if (int rc = qnn_bitplane_gemm_sign(planes, in_bits, coef, QNN_PLANE_BIT, ld0, plane_stride, W[0], 1, kOne,
+                                            QNN_PLANE_SIGN, words_for(dims[0]), 0, T[0], flip ? flip[0] : nullptr,
+                                            act[0], ldw(dims[1]), batch, dims[1], dims[0], engine, stream))
+            return rc;
+    }
     // step 2: hidden layers, product + threshold fused
     int cur = 0;
     for (int l = 1; l < n_layers - 1; ++l) {

@@ -17,6 +17,7 @@
 //   * A wave owns a 128 x 128 tile (4 x 4 blocks of 32 x 32, 256 accumulator registers), a workgroup 2 x 2 waves.
 // The epilogue writes int32 sums (16 bytes per lane and store), or compares with the folded BatchNorm threshold and
 // re-packs the bits along n (Alg. 4: a^b = Sign(BatchNorm(a))).
+#include <cstring>
 #include <type_traits>
 #include <utility>
 
@@ -184,10 +185,14 @@ __device__ __forceinline__ void interleave_groups(std::integer_sequence<int, I..
 
 // The weights feed the row side of the matrix core (accumulator registers 4q .. 4q+3 of a lane are then four
 // consecutive n of one m, i.e. 16 contiguous bytes of C) and the activations the column side (lane = m).
-template <int PA, int PW, int WPL, bool kVec, bool kPixels, bool kSign, bool kFp4 = false>
+// kBytesA: the left operand is not planes but one uint8 code per element (the 8-bit inputs of Alg. 4's first layer):
+// 16 consecutive bytes of a row, minus 128, ARE an int8 matrix-core operand, so nothing is expanded on that side; the
+// weights' bits are then spread in consecutive (not strided) order to match.
+template <int PA, int PW, int WPL, bool kVec, bool kPixels, bool kSign, bool kFp4 = false, bool kBytesA = false>
 __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                 uint32_t tiles_n) {
     constexpr bool kChunk = kVec || WPL == 1;
+    static_assert(!kBytesA || (PA == 1 && PW == 1 && WPL == 1 && !kPixels && !kFp4), "byte operand: one weight plane");
 #ifdef QNN_MFMA_TRACE
     uint32_t trace_tile = 0;
 #endif
@@ -238,13 +243,27 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     struct Step {
         uint32_t A[WB][PA][WPL], W[WB][PW][WPL];
         uint32_t maskA[WB], maskW;  // chunked loads: all ones if the chunk lies inside the row / image
+        uint32_t Ab[kBytesA ? WB : 1][8];  // byte operand: the 32 codes of this lane's chunk, as 8 dwords
+        uint32_t maskAb[2];                // ... and whether each 16-byte half lies inside the row
     };
     auto fetch = [&](const Tile &t, uint32_t s, Step &d) {
         const uint32_t j0 = s * (2 * WPL) + kg * WPL;
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
+            if constexpr (kBytesA) {
+                // chunk j0 of the row = bytes 32 j0 .. 32 j0 + 31 (K and the row pitch are multiples of 16)
+                const uint8_t *rowb = reinterpret_cast<const uint8_t *>(g.A.base) + t.a_off[b];
 #pragma unroll
-            for (int p = 0; p < PA; ++p) {
+                for (int h = 0; h < 2; ++h) {
+                    const uint32_t off = 32u * j0 + 16u * h;
+                    const bool ok = off < (uint32_t)g.K;
+                    d.maskAb[h] = ok ? 0xFFFFFFFFu : 0u;
+                    const uint4 v = *reinterpret_cast<const uint4 *>(rowb + (ok ? off : 0u));
+                    d.Ab[b][4 * h + 0] = v.x, d.Ab[b][4 * h + 1] = v.y, d.Ab[b][4 * h + 2] = v.z, d.Ab[b][4 * h + 3] = v.w;
+                }
+            }
+#pragma unroll
+            for (int p = 0; p < (kBytesA ? 0 : PA); ++p) {
                 const uint32_t *plane = g.A.base + (int64_t)p * g.A.plane_stride + t.a_off[b];
                 if (kPixels)
                     load_pixel_words<WPL, kChunk>(g.A, plane, t.a_yo[b], t.a_xo[b], j0, Kw, d.A[b][p], d.maskA[b]);
@@ -289,13 +308,19 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     };
     struct Words {
         uint32_t a[WB][PA], w[WB][PW];
+        uint32_t ab[kBytesA ? WB : 1][8];  // byte operand: x - 128 as int8, zero beyond K
     };
     // words of slot t of a step, masks applied here, at the point of use, so that the loads stay in flight until now
     auto prep = [&](const Step &c, int t, Words &o) {
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
-            for (int p = 0; p < PA; ++p) o.a[b][p] = kChunk ? (c.A[b][p][t] & c.maskA[b]) : c.A[b][p][t];
+            for (int p = 0; p < PA; ++p)
+                o.a[b][p] = kBytesA ? 0u : (kChunk ? (c.A[b][p][t] & c.maskA[b]) : c.A[b][p][t]);
+            if constexpr (kBytesA) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) o.ab[b][i] = (c.Ab[b][i] ^ 0x80808080u) & c.maskAb[i >> 2];
+            }
 #pragma unroll
             for (int p = 0; p < PW; ++p) o.w[b][p] = kChunk ? (c.W[b][p][t] & c.maskW) : c.W[b][p][t];
         }
@@ -306,8 +331,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         // straight-line block in which the vector-ALU work is spread between the matrix-core instructions
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
+            if constexpr (kBytesA) {
 #pragma unroll
-            for (int p = 0; p < PA; ++p) {
+                for (int i = 0; i < 8; ++i) ra[b] = __builtin_amdgcn_sdot4((int)o.ab[b][i], 0x01010101, ra[b], false);
+            }
+#pragma unroll
+            for (int p = 0; p < (kBytesA ? 0 : PA); ++p) {
                 if (PA == 1)
                     ra[b] += (int32_t)__builtin_popcount(o.a[b][p]);
                 else
@@ -330,7 +359,16 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             for (int p = 0; p < PA; ++p) xa[p] = (PA == 1) ? o.a[b][p] : (o.a[b][p] ^ mc.a.inv[p]);
 #pragma unroll
             for (int p = 0; p < PW; ++p) xw[p] = (PW == 1) ? o.w[b][p] : (o.w[b][p] ^ mc.w.inv[p]);
-            if constexpr (kFp4) {
+            if constexpr (kBytesA) {
+#pragma unroll
+                for (int jj = 0; jj < 4; ++jj) {
+                    f.a[b][jj] = (int)o.ab[b][4 * half + jj];
+                    // bits 16 half + 4 jj .. + 3 of the word, one per byte: t * (1 + 2^7 + 2^14 + 2^21) puts bit i of the
+                    // 4-bit t at position 8 i (all 16 partial products land on distinct bit positions)
+                    const uint32_t t4 = (xw[0] >> (16 * half + 4 * jj)) & 0xFu;
+                    f.w[b][jj] = (int)(__umul24(t4, 0x00204081u) & 0x01010101u);
+                }
+            } else if constexpr (kFp4) {
                 f.a[b] = expand_fp4(xa[0]);
                 f.w[b] = expand_fp4(xw[0]);
             } else {
@@ -353,8 +391,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     // (Estimated counts: expansion 2 ops per register and plane, popcounts, masks; a group takes what is there.)
     constexpr auto expand_ops = [](int P, int half) { return P == 1 ? (half ? 8 : 7) : 9 * P + 4; };
     constexpr auto count_ops = [](int P) { return P == 1 ? 1 : 2 * P; };
-    constexpr int kOpsPhase0 = WB * (expand_ops(PA, 1) + expand_ops(PW, 1) + count_ops(PA) + count_ops(PW));
-    constexpr int kOpsPhase1 = WB * (expand_ops(PA, 0) + expand_ops(PW, 0) + (kChunk ? PA + PW : 0));
+    constexpr int kOpsPhase0 = kBytesA ? WB * (12 + 8 + 1)
+                                       : WB * (expand_ops(PA, 1) + expand_ops(PW, 1) + count_ops(PA) + count_ops(PW));
+    constexpr int kOpsPhase1 = kBytesA ? WB * (12 + 16 + 1)
+                                       : WB * (expand_ops(PA, 0) + expand_ops(PW, 0) + (kChunk ? PA + PW : 0));
     auto interleave = [&](auto total_tag) {
         interleave_groups<decltype(total_tag)::value>(std::make_integer_sequence<int, WB * WB>{});
     };
@@ -684,6 +724,9 @@ struct Variant {
     KernelFn fn_vec, fn_any;  // rows aligned to the load width (vector loads) / any layout (word loads)
     KernelFn fp4_vec, fp4_any;  // the same on the FP4 matrix-core path (single 0/1 or +-1 planes only), else null
 };
+// left operand given as uint8 codes, one weight plane: [0] int32 output, [1] thresholded output
+const KernelFn kByteKernels[2] = {gemm_mfma_kernel<1, 1, 1, true, false, false, false, true>,
+                                  gemm_mfma_kernel<1, 1, 1, true, false, true, false, true>};
 
 #define QNN_VARIANT(PA, PW, WPL, PIX, SGN)                                                                        \
     {                                                                                                             \
@@ -712,11 +755,22 @@ const Variant *find_variant(const GemmArgs &g) {
 }
 
 bool prepare(const GemmArgs &g, bool fp4, const Variant *&var, MfmaConst &mc, bool &vec) {
-    var = find_variant(g);
-    if (!var) return false;
-    if (fp4 && !var->fp4_vec) return false;
+    static const Variant kBytes = {0, 1, 1, false, false, nullptr, nullptr, nullptr, nullptr};
+    const bool bytes = g.A.rows_are_bytes != 0;
     int64_t aA, bA, xA0, aW, bW, xW0;
-    if (!make_code(g.pa, mc.a, aA, bA, xA0) || !make_code(g.pw, mc.w, aW, bW, xW0)) return false;
+    if (bytes) {
+        // x8 = code - 128 (zero beyond K), true value = x8 + 128; rows of 16-byte aligned chunks only
+        if (fp4 || g.pw.count != 1 || g.K % 16 || g.A.ld % 16 || reinterpret_cast<uintptr_t>(g.A.base) % 16) return false;
+        var = &kBytes;
+        std::memset(&mc.a, 0, sizeof(mc.a));
+        aA = 1, bA = 128, xA0 = 0;
+        if (!make_code(g.pw, mc.w, aW, bW, xW0)) return false;
+    } else {
+        var = find_variant(g);
+        if (!var) return false;
+        if (fp4 && !var->fp4_vec) return false;
+        if (!make_code(g.pa, mc.a, aA, bA, xA0) || !make_code(g.pw, mc.w, aW, bW, xW0)) return false;
+    }
     const int64_t step_words = 2 * var->WPL;
     const int64_t msteps = 2 * ceil_div(g.Kw, 2 * step_words);
     const int64_t Kproc = msteps * step_words * 32;
@@ -743,7 +797,7 @@ bool prepare(const GemmArgs &g, bool fp4, const Variant *&var, MfmaConst &mc, bo
         return ld % wpl == 0;
     };
     const bool pix = g.A.rows_are_pixels != 0;
-    vec = wpl > 1 && aligned(g.A.base, pix ? g.A.Cw : g.A.ld, g.A.plane_stride, g.pa.count) &&
+    vec = !bytes && wpl > 1 && aligned(g.A.base, pix ? g.A.Cw : g.A.ld, g.A.plane_stride, g.pa.count) &&
           aligned(g.W, g.ldw, g.strideW, g.pw.count) && (pix ? g.A.Cw % wpl == 0 : true) && g.Kw % wpl == 0;
     return true;
 }
@@ -780,7 +834,10 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
     }
     const int64_t total = tiles_m * tiles_n;
     const unsigned grid = (unsigned)(total < cus ? total : cus);
-    hipLaunchKernelGGL(fp4 ? (vec ? v->fp4_vec : v->fp4_any) : (vec ? v->fn_vec : v->fn_any), dim3(grid), dim3(kThreads), 0, s, g, mc, (uint32_t)tiles_m,
+    const KernelFn fn = g.A.rows_are_bytes ? kByteKernels[g.epi.T ? 1 : 0]
+                        : fp4              ? (vec ? v->fp4_vec : v->fp4_any)
+                                           : (vec ? v->fn_vec : v->fn_any);
+    hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, g, mc, (uint32_t)tiles_m,
                        (uint32_t)tiles_n);
     return check_launch("gemm_mfma");
 }

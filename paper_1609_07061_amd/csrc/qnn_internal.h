@@ -26,6 +26,7 @@ struct LeftAddr {
     int64_t ld;            // words between consecutive rows (matrix) -- unused for pixels
     int64_t plane_stride;  // words between consecutive planes
     int rows_are_pixels;
+    int rows_are_bytes;  // matrix-core engine only: base points at uint8 codes, one per element, ld = row pitch in bytes
     int H, Wd, Ho, Wo, Cw, KH, KW, pad, stride;
 };
 

@@ -242,6 +242,24 @@ def test_mlp_forward_small(seed, batch, dims, engine):
     assert np.array_equal(host(got), want)
 
 
+@pytest.mark.parametrize("engine", [0, 2])
+@pytest.mark.parametrize("batch,dims,ldx", [(1100, [784, 2048, 64, 10], 800), (520, [1008, 4096, 10], 1008),
+                                            (1030, [16, 2048, 10], 16), (1100, [784, 2048, 64, 10], 788)])
+def test_mlp_forward_first_layer_from_codes(seed, batch, dims, ldx, engine):
+    """Large enough for the matrix-core engine: the first layer reads the 8-bit codes directly when rows are 16-byte
+    aligned (ldx a multiple of 16) and falls back to bit planes otherwise; both must give the oracle's logits."""
+    x, W, T = _mlp_case(seed, batch, dims, 80, t_hidden=40)
+    T[0] = qi.uniform_int(seed, 89, (dims[1],), -3000, 3000)
+    flip = [qi.bernoulli_bits(seed, 90 + l, (dims[l + 1],)) for l in range(len(dims) - 2)]
+    want = oracle.mlp(x, W, T, flip)
+    xb = np.zeros((batch, ldx), dtype=np.uint8)
+    xb[:, : dims[0]] = x
+    xd = dev(xb)[:, : dims[0]]
+    got = _engine_or_skip(q.qnn_binary_mlp_forward, xd, 8, dims, [dev(np_pack_pm1(w)) for w in W],
+                          [dev(t) for t in T], [dev(f) for f in flip], engine=engine)
+    assert np.array_equal(host(got), want)
+
+
 # ------------------------------------------------------------------ convolution
 def _conv_case(seed, B, H, Wd, Cin, Cout, KH, abits, stream0):
     u = qi.uniform_int(seed, stream0, (B, H, Wd, Cin), 0, (1 << abits) - 1)
