@@ -174,6 +174,10 @@ __device__ unsigned long long *g_trace = nullptr;
     } while (0)
 #endif
 
+// The integer S held by one accumulator element (exact on the FP4 path: the fp32 sums are small integers).
+__device__ __forceinline__ uint32_t acc_to_sum(int x) { return (uint32_t)x; }
+__device__ __forceinline__ uint32_t acc_to_sum(float x) { return (uint32_t)(int32_t)x; }
+
 // Scheduling pattern of one phase: after each of its 16 MFMAs, the next share of kTotal vector-ALU instructions.
 template <int kTotal, int... I>
 __device__ __forceinline__ void interleave_groups(std::integer_sequence<int, I...>) {
@@ -279,12 +283,6 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     static_assert(!kFp4 || (PA == 1 && PW == 1), "the FP4 path takes one plane per operand");
     using Acc = std::conditional_t<kFp4, v16f, v16i>;
     Acc acc[WB][WB];  // [n block][m block]
-    auto sum_of = [&](const Acc &a, int v) -> uint32_t {  // the integer S of one accumulator register
-        if constexpr (kFp4)
-            return (uint32_t)(int32_t)a[v];
-        else
-            return (uint32_t)a[v];
-    };
     int32_t ra[WB], rw[WB];
     auto clear = [&]() {
 #pragma unroll
@@ -471,19 +469,29 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             m_of[bj] = m_wave + bj * 32 + r;
             mterm[bj] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
         }
+        // Thresholds and flip flags of one block of 32 n as this lane sees them (register v <-> n = 8 (v / 4) + 4 kg +
+        // v mod 4).  All loads of a block are issued back to back, from clamped (always valid) addresses and without
+        // any data-dependent branch, and are consumed one block later.
         int32_t T_next[16];
-        uint32_t flips_next = 0;
-        auto load_thresholds = [&](const int64_t n_first, int32_t (&T)[16], uint32_t &flips) {
-            flips = 0;
+        uint32_t F_next[16];
+        auto load_thresholds = [&](const int64_t n_first, int32_t (&T)[16], uint32_t (&F)[16]) {
+            int64_t idx[16];
 #pragma unroll
             for (int v = 0; v < 16; ++v) {
                 const int64_t n = n_first + 8 * (v >> 2) + 4 * kg + (v & 3);
-                const bool live = kFast || n < g.N;
-                T[v] = live ? g.epi.T[n] : 0;
-                if (g.epi.flip && live && g.epi.flip[n] != 0) flips |= 1u << v;
+                idx[v] = (kFast || n < g.N) ? n : g.N - 1;
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) T[v] = g.epi.T[idx[v]];
+            if (g.epi.flip) {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) F[v] = g.epi.flip[idx[v]];
+            } else {
+#pragma unroll
+                for (int v = 0; v < 16; ++v) F[v] = 0u;
             }
         };
-        if constexpr (kSign) load_thresholds(n_wave, T_next, flips_next);
+        if constexpr (kSign) load_thresholds(n_wave, T_next, F_next);
 #pragma unroll
         for (int bi = 0; bi < WB; ++bi) {
             const int64_t n_blk = n_wave + bi * 32;
@@ -503,7 +511,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                         i32x4 val;
 #pragma unroll
                         for (int i = 0; i < 4; ++i)
-                            val[i] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + i)) + nterm[4 * q + i] + mterm[bj]);
+                            val[i] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + i])) + nterm[4 * q + i] + mterm[bj]);
                         if constexpr (kFast) {
                             *reinterpret_cast<i32x4 *>(row + 8 * q) = val;
                         } else if (m_of[bj] < g.M) {
@@ -517,23 +525,39 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             } else {
                 // thresholds of this block of n were requested one block ahead (their latency hides behind the
                 // previous block's compares); request the next block's now
-                int32_t T[16];
-                uint32_t flips = flips_next;
+                // e[v] = T - 1 - (part of C that depends on n only): C >= T  <=>  e[v] - (rest of C) < 0.  All terms
+                // are below 2^30 in magnitude (the host checks the bound of C, thresholds are clamped to it, which
+                // does not change any comparison), so the differences cannot wrap.
+                int32_t e[16];
+                uint32_t flips = 0, live_bits = 0;  // at the bit positions 8 (v / 4) + v mod 4 of the partial word
 #pragma unroll
-                for (int v = 0; v < 16; ++v) T[v] = T_next[v];
-                if (bi + 1 < WB) load_thresholds(n_blk + 32, T_next, flips_next);
+                for (int v = 0; v < 16; ++v) {
+                    const int32_t Tc = T_next[v] < -(1 << 30) ? -(1 << 30) : (T_next[v] > (1 << 30) ? (1 << 30) : T_next[v]);
+                    e[v] = Tc - 1 - (int32_t)nterm[v];
+                    const uint32_t pos = 1u << (8 * (v >> 2) + (v & 3));
+                    if (F_next[v] != 0) flips |= pos;
+                    if (kFast || n_blk + 8 * (v >> 2) + 4 * kg + (v & 3) < g.N) live_bits |= pos;
+                }
+                if (bi + 1 < WB) load_thresholds(n_blk + 32, T_next, F_next);
                 const int64_t word = n_blk >> 5;
 #pragma unroll
                 for (int bj = 0; bj < WB; ++bj) {
+                    // four bits per group of consecutive n, most significant first: the sign bit of e[v] - (rest of
+                    // C) is appended with one funnel shift; flips and the n tail are applied to the whole word
                     uint32_t bits = 0;
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int64_t n = n_blk + 8 * (v >> 2) + 4 * kg + (v & 3);
-                        const int32_t val = (int32_t)(scale(sum_of(acc[bi][bj], v)) + nterm[v] + mterm[bj]);
-                        const bool ge = val >= T[v];
-                        const bool b = (kFast || n < g.N) && (ge != (((flips >> v) & 1u) != 0));
-                        bits |= (b ? 1u : 0u) << (8 * (v >> 2) + (v & 3));
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t nib = 0;
+#pragma unroll
+                        for (int i = 3; i >= 0; --i) {
+                            const int v = 4 * q + i;
+                            const uint32_t rest = scale(acc_to_sum(acc[bi][bj][v])) + mterm[bj];
+                            const uint32_t x = (uint32_t)e[v] - rest;
+                            nib = __builtin_amdgcn_alignbit(nib, x, 31);  // (nib << 1) | (x >> 31)
+                        }
+                        bits |= nib << (8 * q);
                     }
+                    bits = (bits ^ flips) & live_bits;
                     bits <<= 4 * kg;
                     bits |= (uint32_t)__shfl_xor((int)bits, 32);
                     if (kg == 0 && (kFast || (m_of[bj] < g.M && word < Nw)))
@@ -565,10 +589,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                             uint4 t4 = make_uint4(0u, 0u, 0u, 0u);
                             if (mc.needRW) t4 = *reinterpret_cast<const uint4 *>(&rw_table[wave][pr * 64 + col]);
                             i32x4 val;
-                            val[0] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + 0)) + t4.x + mterm);
-                            val[1] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + 1)) + t4.y + mterm);
-                            val[2] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + 2)) + t4.z + mterm);
-                            val[3] = (int32_t)(scale(sum_of(acc[bi][bj], 4 * q + 3)) + t4.w + mterm);
+                            val[0] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 0])) + t4.x + mterm);
+                            val[1] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 1])) + t4.y + mterm);
+                            val[2] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 2])) + t4.z + mterm);
+                            val[3] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 3])) + t4.w + mterm);
                             *reinterpret_cast<i32x4 *>(&c_rows[wave][r][col]) = val;
                         }
                     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
@@ -770,6 +794,14 @@ bool prepare(const GemmArgs &g, bool fp4, const Variant *&var, MfmaConst &mc, bo
         if (!var) return false;
         if (fp4 && !var->fp4_vec) return false;
         if (!make_code(g.pa, mc.a, aA, bA, xA0) || !make_code(g.pw, mc.w, aW, bW, xW0)) return false;
+    }
+    if (g.epi.T) {
+        // the threshold epilogue compares through differences, which must not wrap: |C| < 2^30
+        long double bound = (long double)g.K;
+        long double sa = 0, sw = 0;
+        for (int p = 0; p < g.pa.count; ++p) sa += g.pa.coef[p] < 0 ? -(long double)g.pa.coef[p] : g.pa.coef[p];
+        for (int p = 0; p < g.pw.count; ++p) sw += g.pw.coef[p] < 0 ? -(long double)g.pw.coef[p] : g.pw.coef[p];
+        if (bound * sa * sw >= 1073741824.0L) return false;
     }
     const int64_t step_words = 2 * var->WPL;
     const int64_t msteps = 2 * ceil_div(g.Kw, 2 * step_words);
