@@ -150,6 +150,39 @@ def test_binary_gemm_sign(seed, M, N, K, with_flip, engine):
     assert np.array_equal(host_u32(got), want)
 
 
+@pytest.mark.parametrize("engine", ENGINES)
+def test_binary_gemm_sign_extreme_thresholds(seed, engine):
+    """Thresholds far outside the range of C (including both int32 ends) must act as always / never."""
+    M, N, K = 70, 96, 160
+    a = qi.pm1(seed, 28, (M, K))
+    w = qi.pm1(seed, 29, (N, K))
+    T = qi.uniform_int(seed, 26, (N,), -8, 8)
+    T[0::7] = -(2**31)
+    T[1::7] = 2**31 - 1
+    T[2::7] = -(2**30) - 5
+    T[3::7] = 2**30 + 5
+    T[4::7] = K      # reachable only by an exact match of all K signs
+    T[5::7] = K + 1  # never reached
+    flip = qi.bernoulli_bits(seed, 27, (N,))
+    want = oracle.pack_bits(oracle.threshold(oracle.gemm_pm1(a, w), T, flip))
+    got = _engine_or_skip(q.qnn_binary_gemm_sign, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T), dev(flip),
+                          engine=engine)
+    assert np.array_equal(host_u32(got), want)
+
+
+@pytest.mark.parametrize("engine", [2, 3])
+@pytest.mark.parametrize("K", [65536, 130000])
+def test_binary_gemm_long_k_on_matrix_cores(seed, engine, K):
+    """Largest K the matrix-core engine accepts (sums stay exact in int32 / fp32); a != w and a == w rows."""
+    M, N = 40, 33
+    a = qi.pm1(seed, 30, (M, K))
+    w = qi.pm1(seed, 31, (N, K))
+    w[0] = a[0]
+    w[1] = -a[1]
+    got = _engine_or_skip(q.qnn_binary_gemm, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, engine=engine)
+    assert np.array_equal(host(got), oracle.gemm_pm1(a, w))
+
+
 # ------------------------------------------------------------------ S3 bitplane_gemm
 def _planes_of(v, nbits):
     """integer codes -> ([nbits][rows][K] 0/1 planes from the oracle, packed uint32 planes for the GPU)"""
