@@ -93,3 +93,28 @@ def test_config5_lstm_gates_int4(seed):
     wp = np_pack_bits(oracle.split_planes(w, 4))
     got = host(q.qnn_bitplane_gemm(dev(ap), coef, q.PLANE_BIT, dev(wp), coef, q.PLANE_BIT, K))
     assert np.array_equal(got, oracle.gemm_int(a, w))
+
+
+@pytest.mark.parametrize("engine", [0, 2, 3])
+@pytest.mark.parametrize("M,N,ldc", [(4200, 4200, 4200), (4200, 4197, 4197), (4104, 4360, 4400)])
+def test_large_ragged_gemm_parked_and_edge_tiles(seed, M, N, ldc, engine):
+    """More tiles than compute units, K = 8192 and ragged edges: interior tiles take the parked-output path (when the
+    row pitch allows 16-byte stores), edge tiles the bounds-checked one, in the same launch."""
+    K = 8192
+    a = qi.pm1(seed, 60, (M, K))
+    w = qi.pm1(seed, 61, (N, K))
+    out = torch.full((M, ldc), -7, dtype=torch.int32, device="cuda")
+    q.qnn_binary_gemm(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, out=out[:, :N], engine=engine)
+    got = host(out)
+    assert (got[:, N:] == -7).all()
+    got = got[:, :N]
+    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, 4095, 4096, M - 1],
+                                     (qi.raw_u64(seed, 62, 24) % np.uint64(M)).astype(np.int64)]))
+    cols = np.unique(np.concatenate([[0, 127, 128, 255, 256, 4095, 4096, N - 1],
+                                     (qi.raw_u64(seed, 63, 24) % np.uint64(N)).astype(np.int64)]))
+    assert np.array_equal(got[rows], oracle.gemm_pm1(a[rows], w))
+    assert np.array_equal(got[:, cols], oracle.gemm_pm1(a, w[cols]))
+    wsum = w.astype(np.int64).sum(axis=0)
+    asum = a.astype(np.int64).sum(axis=0)
+    assert np.array_equal(got.astype(np.int64).sum(axis=1), a.astype(np.int64) @ wsum)
+    assert np.array_equal(got.astype(np.int64).sum(axis=0), w.astype(np.int64) @ asum)
