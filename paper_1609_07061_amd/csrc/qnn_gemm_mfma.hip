@@ -1,22 +1,29 @@
 // Matrix-core engine of the binary / bit-plane matrix product.
 //
-// The product of Sec. 6 / Sec. 2.6 / Sec. 3 is a dense contraction, so on CDNA4 it can run on the int8 matrix cores
-// (v_mfma_i32_32x32x32_i8) instead of spending one xor and one popcount per 32 connections on the vector ALU:
+// The product of Sec. 6 / Sec. 2.6 / Sec. 3 is a dense contraction, so on CDNA4 it runs on the matrix cores instead of
+// spending one xor and one popcount per 32 connections on the vector ALU.  One kernel template, three operand paths:
+//   FP4   v_mfma_f32_32x32x64_f8f6f4   single plane x single plane: bits become E2M1 zeros and ones (exact fp32 sums)
+//   int8  v_mfma_i32_32x32x32_i8       multi-bit codes: the planes of an operand are OR-ed into one int8 per element
+//   int8, byte operand                 the left operand is given as uint8 codes (first layer of Alg. 4), no expansion
+// Common design:
 //   * Every lane keeps the raw packed words of "its" operand row (lane l: row l mod 32 of a 32-row block, k-group
 //     l div 32) in registers, straight from global memory (the packed operands are so small that L1/L2 serve the
-//     re-reads; no LDS, no barriers).
-//   * A packed word becomes int8 MFMA operands with two VALU ops per 4 bytes: (w >> j) & 0x01010101 picks bits
-//     j, j+8, j+16, j+24.  The order of k inside a dot product is irrelevant as long as both operands use the same
-//     one, and they do, so no bit gather is needed.  With several planes the bytes of the planes are OR-ed at their
-//     power-of-two positions, giving the integer code itself; one pass of the matrix core then replaces Pa*Pb binary
-//     passes.
-//   * Bytes are the raw codes u (optionally minus 128); the true operand values are an affine function of them
-//     (t = alpha * x + beta, e.g. 2b - 1 for a +-1 plane), so the true product follows from the int8 product S with a
+//     re-reads; no LDS, no barriers in the main loop), two buffers ping-pong, loads issued a full step ahead.
+//   * A packed word becomes MFMA operands with shifts and masks: (w >> j) & 0x01010101 picks bits j, j+8, j+16, j+24
+//     into four bytes (FP4: & 0x22222222 picks eight nibbles).  The order of k inside a dot product is irrelevant as
+//     long as both operands use the same one, and they do, so no bit gather is needed.  With several planes the bytes
+//     are OR-ed at their power-of-two positions, giving the integer code itself; one pass of the matrix core then
+//     replaces Pa*Pb binary passes.
+//   * Operands hold raw codes x (optionally minus 128); the true operand values are an affine function of them
+//     (t = alpha * x + beta, e.g. 2b - 1 for a +-1 plane), so the true product follows from the raw product S with a
 //     rank-one correction built from per-row sums, which are popcounts of the same raw words:
 //       C = aA aW (S - npad xA0 xW0) + aA bW RA[m] + bA aW RW[n] + K bA bW.
-//   * A wave owns a 128 x 128 tile (4 x 4 blocks of 32 x 32, 256 accumulator registers), a workgroup 2 x 2 waves.
-// The epilogue writes int32 sums (16 bytes per lane and store), or compares with the folded BatchNorm threshold and
-// re-packs the bits along n (Alg. 4: a^b = Sign(BatchNorm(a))).
+//   * The vector-ALU work of the next 16 MFMAs is placed between the current ones (scheduling groups).
+//   * A wave owns a 128 x 128 tile (4 x 4 blocks of 32 x 32, 256 accumulator registers), a workgroup 2 x 2 waves,
+//     one persistent workgroup per compute unit.
+// Epilogues: int32 sums (row-contiguous 16-byte stores through an LDS transpose, or parked in LDS and written out
+// under the next tile's MFMAs), or the comparison with the folded BatchNorm threshold, re-packed along n
+// (Alg. 4: a^b = Sign(BatchNorm(a))).
 #include <cstring>
 #include <type_traits>
 #include <utility>
