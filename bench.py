@@ -121,7 +121,10 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            roof["traffic"] = json.load(open(tpath)).get(roof["kernel"] + "@c3")
+            t = json.load(open(tpath)).get(roof["kernel"] + "@c3")
+            if t:
+                roof["traffic"] = t["fetch_bytes"] + t["write_bytes"]  # HBM bytes per launch, measured (profiles/)
+                roof["traffic_detail"] = t
         except Exception:
             pass
 
@@ -234,7 +237,9 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u32 bit-packed +-1 operands, int32 accumulate",
+        "dtype": {"fp4": "bit-packed +-1 operands expanded on chip to fp4 (E2M1), fp32 accumulate (exact), int32 out",
+                  "mfma": "bit-packed +-1 operands expanded on chip to int8, int32 accumulate",
+                  "valu": "u32 bit-packed +-1 operands, xor + popcount, int32 accumulate"}[used_name],
         "data": "synthetic (seeded Bernoulli(0.5) +-1 operands; stands in for the paper's 8192^3 benchmark matrices)",
         "config": {"workload": "C3: 8192x8192x8192 binary GEMM on packed +-1 operands, int32 output",
                    "engine": used_name, "M": n, "N": n, "K": n},

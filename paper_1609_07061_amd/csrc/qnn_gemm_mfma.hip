@@ -21,9 +21,8 @@
 //   * The vector-ALU work of the next 16 MFMAs is placed between the current ones (scheduling groups).
 //   * A wave owns a 128 x 128 tile (4 x 4 blocks of 32 x 32, 256 accumulator registers), a workgroup 2 x 2 waves,
 //     one persistent workgroup per compute unit.
-// Epilogues: int32 sums (row-contiguous 16-byte stores through an LDS transpose, or parked in LDS and written out
-// under the next tile's MFMAs), or the comparison with the folded BatchNorm threshold, re-packed along n
-// (Alg. 4: a^b = Sign(BatchNorm(a))).
+// Epilogues: int32 sums (row-contiguous 16-byte stores through an LDS transpose), or the comparison with the folded
+// BatchNorm threshold, re-packed along n (Alg. 4: a^b = Sign(BatchNorm(a))).
 #include <cstring>
 #include <type_traits>
 #include <utility>
@@ -210,12 +209,7 @@ __device__ __forceinline__ void interleave_groups(std::integer_sequence<int, I..
 // kBytesA: the left operand is not planes but one uint8 code per element (the 8-bit inputs of Alg. 4's first layer):
 // 16 consecutive bytes of a row, minus 128, ARE an int8 matrix-core operand, so nothing is expanded on that side; the
 // weights' bits are then spread in consecutive (not strided) order to match.
-// kPark (int32 output that fits int16, at least 32 steps per tile): a finished interior tile is not stored at once but
-// parked in LDS as int16 and written out four rows at a time between the steps of the NEXT tile.  Otherwise all
-// compute units reach their store phase together, HBM needs about 10 us to absorb the 64 MiB burst, and the matrix
-// cores idle meanwhile; parked, the stores trickle out underneath the matrix-core work.
-template <int PA, int PW, int WPL, bool kVec, bool kPixels, bool kSign, bool kFp4 = false, bool kBytesA = false,
-          bool kPark = false>
+template <int PA, int PW, int WPL, bool kVec, bool kPixels, bool kSign, bool kFp4 = false, bool kBytesA = false>
 __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                 uint32_t tiles_n) {
     constexpr bool kChunk = kVec || WPL == 1;
@@ -224,18 +218,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     uint32_t trace_tile = 0;
 #endif
     __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
-    // One LDS tile per wave, used in two ways that never overlap in time:
-    //  - c_rows: 32 rows x 64 int32 columns of a wave tile (rows padded by 4 ints to spread the banks), see epilogue_rows
-    //  - parked (kPark): a whole wave tile, 128 rows of 128 int16 (rows padded by 8), see park / drain_one
+    // per wave: 32 rows x 64 columns of a wave tile (rows padded by 4 ints to spread the banks), see epilogue_rows
     constexpr int kRowPitch = 64 + 4;
-    constexpr int kParkPitch = WTILE + 8;
-    constexpr int kTileBytes = kSign ? 16 : (kPark ? WTILE * kParkPitch * 2 : 32 * kRowPitch * 4);
-    __shared__ __attribute__((aligned(16))) unsigned char lds_tile[kThreads / 64][kTileBytes];
-    static_assert(!kPark || (!kSign && !kPixels && !kBytesA), "parking is for plain int32 outputs");
+    __shared__ __attribute__((aligned(16))) int32_t c_rows[kSign ? 1 : kThreads / 64][kSign ? 1 : 32][kSign ? 4 : kRowPitch];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in a scalar register
-    auto c_rows = [&](int row) __attribute__((always_inline)) { return reinterpret_cast<int32_t *>(lds_tile[wave]) + row * kRowPitch; };
-    auto parked = [&](int row) __attribute__((always_inline)) { return reinterpret_cast<int16_t *>(lds_tile[wave]) + row * kParkPitch; };
     const int r = lane & 31, kg = lane >> 5;
     const uint32_t Kw = (uint32_t)g.Kw;
     const uint32_t total_tiles = tiles_m * tiles_n;
@@ -426,97 +413,16 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     auto interleave = [&](auto total_tag) __attribute__((always_inline)) {
         interleave_groups<decltype(total_tag)::value>(std::make_integer_sequence<int, WB * WB>{});
     };
-    // ---- parked tile (kPark) ----
-    // LDS holds the raw sums S of a finished wave tile as uint16 (they are non-negative and below 2^15), a table of the
-    // row terms of C (one per m) and, in rw_table, the column terms (one per n).  drain_one writes four rows of 128
-    // columns: lane L owns row 4 g + L / 16, columns 4 (L mod 16) .. + 3 and the same + 64.  It is issued inside the
-    // first phase of a step, so its LDS latency and vector-ALU work hide under the matrix-core instructions like the
-    // operand expansion does, and nothing of it stays in registers between steps.
-    __shared__ __attribute__((aligned(16))) uint32_t park_mtab[kPark ? kThreads / 64 : 1][kPark ? WTILE : 4];
-    int64_t park_m = 0, park_n = 0;  // wave tile origin of the parked tile (wave-uniform)
-    uint32_t park_group = 0;         // next group to write out
-    // One group is written out per step, in three parts placed in three consecutive phases so that each phase keeps
-    // enough vector-ALU slack under its MFMAs: (a) LDS reads and the address, (b) the arithmetic, (c) the stores.
-    // The store data of consecutive steps alternates between two register sets: the compiler makes an instruction that
-    // overwrites the data registers of a store wait until that store has completed, and with one set every step would
-    // wait for the previous step's stores (a full memory round trip).
-    struct DrainRegs {
-        uint2 lo16, hi16;
-        uint4 nlo, nhi;
-        uint32_t mterm;
-        int32_t *dst;
-    } drain_regs = {};
-    i32x4 park_data[2][2] = {};
-    auto drain_a = [&]() __attribute__((always_inline)) {
-        if constexpr (kPark) {
-            // lane-dependent parts stay 32-bit (one register, trivially recomputed); the 64-bit part is wave-uniform
-            const int row = 4 * (int)park_group + (lane >> 4), col = 4 * (lane & 15);
-            const int16_t *src = parked(row) + col;
-            drain_regs.lo16 = *reinterpret_cast<const uint2 *>(src);
-            drain_regs.hi16 = *reinterpret_cast<const uint2 *>(src + 64);
-            drain_regs.mterm = park_mtab[wave][row];
-            // (no branch on needRW: it would split the block in which this work is spread between the MFMAs; park()
-            // always fills the table)
-            drain_regs.nlo = *reinterpret_cast<const uint4 *>(&rw_table[wave][col]);
-            drain_regs.nhi = *reinterpret_cast<const uint4 *>(&rw_table[wave][64 + col]);
-            int32_t *dst_wave = g.epi.C + (park_m + 4 * (int64_t)park_group) * g.epi.ldc + park_n;
-            drain_regs.dst = dst_wave + ((uint32_t)(lane >> 4) * (uint32_t)g.epi.ldc + (uint32_t)col);
-            ++park_group;
-        }
-    };
-    auto drain_b = [&](auto which_tag) __attribute__((always_inline)) {
-        constexpr int kSet = decltype(which_tag)::value;
-        if constexpr (kPark) {
-            const int sh = mc.alpha_shift;
-            const DrainRegs &d = drain_regs;
-            i32x4 &lo = park_data[kSet][0], &hi = park_data[kSet][1];
-            lo[0] = (int32_t)(((d.lo16.x & 0xFFFFu) << sh) + d.nlo.x + d.mterm);
-            lo[1] = (int32_t)(((d.lo16.x >> 16) << sh) + d.nlo.y + d.mterm);
-            lo[2] = (int32_t)(((d.lo16.y & 0xFFFFu) << sh) + d.nlo.z + d.mterm);
-            lo[3] = (int32_t)(((d.lo16.y >> 16) << sh) + d.nlo.w + d.mterm);
-            hi[0] = (int32_t)(((d.hi16.x & 0xFFFFu) << sh) + d.nhi.x + d.mterm);
-            hi[1] = (int32_t)(((d.hi16.x >> 16) << sh) + d.nhi.y + d.mterm);
-            hi[2] = (int32_t)(((d.hi16.y & 0xFFFFu) << sh) + d.nhi.z + d.mterm);
-            hi[3] = (int32_t)(((d.hi16.y >> 16) << sh) + d.nhi.w + d.mterm);
-        }
-    };
-    auto drain_c = [&](auto which_tag) __attribute__((always_inline)) {
-        constexpr int kSet = decltype(which_tag)::value;
-        if constexpr (kPark) {
-            // plain (write-back) stores: acknowledged by L2; a streaming store is only acknowledged by memory, and the
-            // in-order memory counter would then hold up the next operand loads
-            *reinterpret_cast<i32x4 *>(drain_regs.dst) = park_data[kSet][0];
-            *reinterpret_cast<i32x4 *>(drain_regs.dst + 64) = park_data[kSet][1];
-            // keep the other set's registers occupied here, so that this step's values cannot be given the same ones
-            asm volatile("" : "+v"(park_data[1 - kSet][0]), "+v"(park_data[1 - kSet][1]));
-        }
-    };
-
     // All phases of step `c`; `f` / `cur` enter holding the operands / words of its phase (0, 0) and leave holding
     // those of phase (0, 0) of step `n`.
     constexpr int kOpsPhaseFp4 = WB * (7 + 7 + 2 + (kChunk ? 2 : 0));
-    // vector-ALU instructions the three drain parts add to the phases they sit in
-    constexpr int kOpsDrainA = 14, kOpsDrainB = 28, kOpsDrainC = 2;
-    // drain_tag: std::integral_constant<int, -1> = no drain in this step, 0 / 1 = drain with that register set
-    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur, auto drain_tag) __attribute__((always_inline)) {
-        constexpr int kDrainSet = decltype(drain_tag)::value;
-        constexpr bool kDrainHere = kDrainSet >= 0;
-        using Set = std::integral_constant<int, (kDrainSet >= 0 ? kDrainSet : 0)>;
-        // phase index within the step -> drain part to run under its MFMAs and the extra instruction count
-        auto drain_part = [&](int phase) __attribute__((always_inline)) {
-            if constexpr (kDrainHere) {
-                if (phase == 0) drain_a();
-                if (phase == 1) drain_b(Set{});
-                if (phase == 2) drain_c(Set{});
-            }
-        };
+    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < WPL; ++t) {
             if constexpr (kFp4) {
                 // one phase per word: a 32x32x64 FP4 instruction consumes all 32 bits a lane holds
                 Frags g;
                 Words nxt;
-                drain_part(t);
                 count(cur);
                 if (t + 1 < WPL)
                     prep(c, t + 1, nxt);
@@ -524,43 +430,26 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                     prep(n, 0, nxt);
                 expand(nxt, 0, g);
                 multiply(f);
-                if (kDrainHere && t == 0)
-                    interleave(std::integral_constant<int, kOpsPhaseFp4 + kOpsDrainA>{});
-                else if (kDrainHere && t == 1)
-                    interleave(std::integral_constant<int, kOpsPhaseFp4 + kOpsDrainB>{});
-                else if (kDrainHere && t == 2)
-                    interleave(std::integral_constant<int, kOpsPhaseFp4 + kOpsDrainC>{});
-                else
-                    interleave(std::integral_constant<int, kOpsPhaseFp4>{});
+                interleave(std::integral_constant<int, kOpsPhaseFp4>{});
                 __builtin_amdgcn_sched_barrier(0);
                 f = g;
                 cur = nxt;
             } else {
                 // phase (t, 0): multiply, meanwhile count the words in use and expand their second half
                 Frags g;
-                drain_part(2 * t);
                 count(cur);
                 expand(cur, 1, g);
                 multiply(f);
-                if (kDrainHere && t == 0)
-                    interleave(std::integral_constant<int, kOpsPhase0 + kOpsDrainA>{});
-                else if (kDrainHere && t == 1)
-                    interleave(std::integral_constant<int, kOpsPhase0 + kOpsDrainC>{});
-                else
-                    interleave(std::integral_constant<int, kOpsPhase0>{});
+                interleave(std::integral_constant<int, kOpsPhase0>{});
                 __builtin_amdgcn_sched_barrier(0);
                 // phase (t, 1): multiply, meanwhile fetch and expand the first half of the following slot
-                drain_part(2 * t + 1);
                 if (t + 1 < WPL)
                     prep(c, t + 1, cur);
                 else
                     prep(n, 0, cur);
                 expand(cur, 0, f);
                 multiply(g);
-                if (kDrainHere && t == 0)
-                    interleave(std::integral_constant<int, kOpsPhase1 + kOpsDrainB>{});
-                else
-                    interleave(std::integral_constant<int, kOpsPhase1>{});
+                interleave(std::integral_constant<int, kOpsPhase1>{});
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
@@ -721,14 +610,14 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                             val[1] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 1])) + t4.y + mterm);
                             val[2] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 2])) + t4.z + mterm);
                             val[3] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 3])) + t4.w + mterm);
-                            *reinterpret_cast<i32x4 *>(c_rows(r) + col) = val;
+                            *reinterpret_cast<i32x4 *>(&c_rows[wave][r][col]) = val;
                         }
                     __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
                     __builtin_amdgcn_wave_barrier();
                     i32x4 v[8];
 #pragma unroll
                     for (int it = 0; it < 8; ++it)
-                        v[it] = *reinterpret_cast<const i32x4 *>(c_rows(4 * it + out_row) + out_col);
+                        v[it] = *reinterpret_cast<const i32x4 *>(&c_rows[wave][4 * it + out_row][out_col]);
                     __builtin_amdgcn_sched_barrier(0);
                     int32_t *dst = g.epi.C + (m_wave + bj * 32 + out_row) * g.epi.ldc + n_wave + pr * 64 + out_col;
 #pragma unroll
@@ -737,36 +626,6 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                     __builtin_amdgcn_wave_barrier();
                 }
             }
-        }
-    };
-    // the raw sums of the finished accumulators as uint16 into this wave's LDS tile, the row terms into their table,
-    // this lane's column terms into registers; then the first group is read back
-    auto park = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
-        if constexpr (kPark) {
-            row_sums();
-            if (kg == 0) {
-#pragma unroll
-                for (int bj = 0; bj < WB; ++bj) park_mtab[wave][bj * 32 + r] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
-                if (!mc.needRW) {  // row_sums leaves the column-term table alone then: zero it for drain_one
-#pragma unroll
-                    for (int b = 0; b < WB; ++b) rw_table[wave][b * 32 + r] = 0u;
-                }
-            }
-#pragma unroll
-            for (int bj = 0; bj < WB; ++bj)
-#pragma unroll
-                for (int bi = 0; bi < WB; ++bi)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const int col = bi * 32 + 8 * q + 4 * kg;
-                        const uint32_t s0 = acc_to_sum(acc[bi][bj][4 * q + 0]), s1 = acc_to_sum(acc[bi][bj][4 * q + 1]);
-                        const uint32_t s2 = acc_to_sum(acc[bi][bj][4 * q + 2]), s3 = acc_to_sum(acc[bi][bj][4 * q + 3]);
-                        const uint2 packed = make_uint2((s0 & 0xFFFFu) | (s1 << 16), (s2 & 0xFFFFu) | (s3 << 16));
-                        *reinterpret_cast<uint2 *>(parked(bj * 32 + r) + col) = packed;
-                    }
-            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): tile and tables are in LDS
-            __builtin_amdgcn_wave_barrier();
-            park_m = m_wave, park_n = n_wave, park_group = 0;
         }
     };
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
@@ -811,69 +670,33 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
 #ifdef QNN_MFMA_TRACE
     if (g_trace && threadIdx.x == 0) g_trace[(blockIdx.x * 8 + 7) * 8 + 7] = __builtin_amdgcn_s_memrealtime();
 #endif
-    bool is_parked = false;  // a tile sits in LDS and is being written out (wave-uniform)
-    // One tile's steps.  kDrain: 32 drain calls are spread over the first 30 steps and the two peeled ones (the host
-    // guarantees msteps >= 32 with kPark).  Returns the finished tile's origin and whether another tile follows; the
-    // next tile's first step is already in flight then.
-    auto run_tile = [&](auto drain_tag, int64_t &m_done, int64_t &n_done, uint32_t &vb_next, bool &more) __attribute__((always_inline)) {
-        constexpr bool kDrain = decltype(drain_tag)::value;
+    while (true) {
         QNN_STAMP(0);
         clear();
         QNN_STAMP(1);
-        uint32_t s = 0;
-        if constexpr (kDrain) {
-            for (; s < 30; s += 2) {
-                fetch(cur, s + 1, buf1);
-                __builtin_amdgcn_sched_barrier(0);
-                compute(buf0, buf1, frags, words, std::integral_constant<int, 0>{});
-                fetch(cur, s + 2, buf0);
-                __builtin_amdgcn_sched_barrier(0);
-                compute(buf1, buf0, frags, words, std::integral_constant<int, 1>{});
-            }
-        }
-        for (; s + 2 < mc.msteps; s += 2) {
+        for (uint32_t s = 0; s + 2 < mc.msteps; s += 2) {
             fetch(cur, s + 1, buf1);
             __builtin_amdgcn_sched_barrier(0);
-            compute(buf0, buf1, frags, words, std::integral_constant<int, -1>{});
+            compute(buf0, buf1, frags, words);
             fetch(cur, s + 2, buf0);
             __builtin_amdgcn_sched_barrier(0);
-            compute(buf1, buf0, frags, words, std::integral_constant<int, -1>{});
+            compute(buf1, buf0, frags, words);
         }
         QNN_STAMP(2);
         fetch(cur, mc.msteps - 1, buf1);
         __builtin_amdgcn_sched_barrier(0);
-        compute(buf0, buf1, frags, words, std::integral_constant<int, kDrain ? 0 : -1>{});
+        compute(buf0, buf1, frags, words);
         QNN_STAMP(3);
         // the operand rows of this tile are not needed any more: move on to the next tile's
-        m_done = cur.m_wave, n_done = cur.n_wave;
-        vb_next = vb + gridDim.x;
-        more = vb_next < total_tiles;
+        const int64_t m_done = cur.m_wave, n_done = cur.n_wave;
+        const uint32_t vb_next = vb + gridDim.x;
+        const bool more = vb_next < total_tiles;
         locate(more ? vb_next : vb, cur);  // without a next tile the loads are repeated and ignored
         fetch(cur, 0, buf0);
         __builtin_amdgcn_sched_barrier(0);
-        compute(buf1, buf0, frags, words, std::integral_constant<int, kDrain ? 1 : -1>{});
+        compute(buf1, buf0, frags, words);
         QNN_STAMP(4);
-    };
-    while (true) {
-        int64_t m_done, n_done;
-        uint32_t vb_next;
-        bool more;
-        if (kPark && is_parked)
-            run_tile(std::true_type{}, m_done, n_done, vb_next, more);
-        else
-            run_tile(std::false_type{}, m_done, n_done, vb_next, more);
-        // parked tile (if any) is completely written out by now; park this one if it qualifies and work follows
-        bool park_now = false;
-        if constexpr (kPark) {
-            const bool interior = m_done + WTILE <= g.M && n_done + WTILE <= g.N;
-            park_now = more && interior;
-        }
-        if (park_now) {
-            park(m_done, n_done);
-        } else {
-            finish(m_done, n_done);
-        }
-        is_parked = park_now;
+        finish(m_done, n_done);
         QNN_STAMP(5);
 #ifdef QNN_MFMA_TRACE
         if (g_trace && threadIdx.x == 0 && trace_tile < 8)
@@ -942,9 +765,6 @@ struct Variant {
     KernelFn fn_vec, fn_any;  // rows aligned to the load width (vector loads) / any layout (word loads)
     KernelFn fp4_vec, fp4_any;  // the same on the FP4 matrix-core path (single 0/1 or +-1 planes only), else null
 };
-// single planes, aligned rows, int32 output parked in LDS: [0] int8 path, [1] FP4 path
-const KernelFn kParkKernels[2] = {gemm_mfma_kernel<1, 1, 4, true, false, false, false, false, true>,
-                                  gemm_mfma_kernel<1, 1, 4, true, false, false, true, false, true>};
 // left operand given as uint8 codes, one weight plane: [0] int32 output, [1] thresholded output
 const KernelFn kByteKernels[2] = {gemm_mfma_kernel<1, 1, 1, true, false, false, false, true>,
                                   gemm_mfma_kernel<1, 1, 1, true, false, true, false, true>};
@@ -1063,17 +883,7 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
     }
     const int64_t total = tiles_m * tiles_n;
     const unsigned grid = (unsigned)(total < cus ? total : cus);
-    // parking needs: single planes, vector loads, int32 output that fits int16 and takes 16-byte stores, >= 32 steps,
-    // and more than one tile per workgroup (the last tile of a workgroup is always stored directly)
-    bool park = false;
-    if (!g.A.rows_are_bytes && !g.A.rows_are_pixels && !g.epi.T && vec && g.pa.count == 1 && g.pw.count == 1 &&
-        v->WPL == 4 && mc.msteps >= 32 && total > cus && g.epi.ldc % 4 == 0 && g.epi.ldc < (1 << 28) &&
-        reinterpret_cast<uintptr_t>(g.epi.C) % 16 == 0 && mc.alpha_shift >= 0) {
-        // single planes are 0/1 codes, so the raw sum S is at most the number of processed positions
-        park = (int64_t)mc.msteps * 2 * v->WPL * 32 < 32768;
-    }
     const KernelFn fn = g.A.rows_are_bytes ? kByteKernels[g.epi.T ? 1 : 0]
-                        : park             ? kParkKernels[fp4 ? 1 : 0]
                         : fp4              ? (vec ? v->fp4_vec : v->fp4_any)
                                            : (vec ? v->fn_vec : v->fn_any);
     hipLaunchKernelGGL(fn, dim3(grid), dim3(kThreads), 0, s, g, mc, (uint32_t)tiles_m,

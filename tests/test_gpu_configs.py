@@ -97,9 +97,9 @@ def test_config5_lstm_gates_int4(seed):
 
 @pytest.mark.parametrize("engine", [0, 2, 3])
 @pytest.mark.parametrize("M,N,ldc", [(4200, 4200, 4200), (4200, 4197, 4197), (4104, 4360, 4400)])
-def test_large_ragged_gemm_parked_and_edge_tiles(seed, M, N, ldc, engine):
-    """More tiles than compute units, K = 8192 and ragged edges: interior tiles take the parked-output path (when the
-    row pitch allows 16-byte stores), edge tiles the bounds-checked one, in the same launch."""
+def test_large_ragged_gemm_interior_and_edge_tiles(seed, M, N, ldc, engine):
+    """More tiles than compute units, K = 8192 and ragged edges: interior tiles take the row-contiguous 16-byte store
+    path (when the row pitch allows it), edge tiles the bounds-checked one, in the same launch."""
     K = 8192
     a = qi.pm1(seed, 60, (M, K))
     w = qi.pm1(seed, 61, (N, K))
