@@ -21,7 +21,7 @@
 //   * The vector-ALU work of the next 16 MFMAs is placed between the current ones (scheduling groups).
 //   * A wave owns a 128 x 128 tile (4 x 4 blocks of 32 x 32, 256 accumulator registers), a workgroup 2 x 2 waves,
 //     one persistent workgroup per compute unit.
-// Epilogues: int32 sums (row-contiguous 16-byte stores through an LDS transpose), or the comparison with the folded
+// Epilogues: int32 sums (four consecutive n per lane = one 16-byte store), or the comparison with the folded
 // BatchNorm threshold, re-packed along n (Alg. 4: a^b = Sign(BatchNorm(a))).
 #include <cstring>
 #include <type_traits>
@@ -218,9 +218,6 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     uint32_t trace_tile = 0;
 #endif
     __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
-    // per wave: 32 rows x 64 columns of a wave tile (rows padded by 4 ints to spread the banks), see epilogue_rows
-    constexpr int kRowPitch = 64 + 4;
-    __shared__ __attribute__((aligned(16))) int32_t c_rows[kSign ? 1 : kThreads / 64][kSign ? 1 : 32][kSign ? 4 : kRowPitch];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in a scalar register
     const int r = lane & 31, kg = lane >> 5;
@@ -416,9 +413,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     // All phases of step `c`; `f` / `cur` enter holding the operands / words of its phase (0, 0) and leave holding
     // those of phase (0, 0) of step `n`.
     constexpr int kOpsPhaseFp4 = WB * (7 + 7 + 2 + (kChunk ? 2 : 0));
-    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur) __attribute__((always_inline)) {
+    // `issue_loads` (the fetch of the following step into `n`) runs inside the first phase, so that its address
+    // arithmetic also sits between matrix-core instructions instead of in front of them.
+    constexpr int kOpsFetch = 3 * WB * (kBytesA ? 3 : (PA + PW));
+    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur, auto issue_loads) __attribute__((always_inline)) {
 #pragma unroll
         for (int t = 0; t < WPL; ++t) {
+            if (t == 0) issue_loads();
             if constexpr (kFp4) {
                 // one phase per word: a 32x32x64 FP4 instruction consumes all 32 bits a lane holds
                 Frags g;
@@ -430,7 +431,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                     prep(n, 0, nxt);
                 expand(nxt, 0, g);
                 multiply(f);
-                interleave(std::integral_constant<int, kOpsPhaseFp4>{});
+                if (t == 0)
+                    interleave(std::integral_constant<int, kOpsPhaseFp4 + kOpsFetch>{});
+                else
+                    interleave(std::integral_constant<int, kOpsPhaseFp4>{});
                 __builtin_amdgcn_sched_barrier(0);
                 f = g;
                 cur = nxt;
@@ -440,7 +444,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                 count(cur);
                 expand(cur, 1, g);
                 multiply(f);
-                interleave(std::integral_constant<int, kOpsPhase0>{});
+                if (t == 0)
+                    interleave(std::integral_constant<int, kOpsPhase0 + kOpsFetch>{});
+                else
+                    interleave(std::integral_constant<int, kOpsPhase0>{});
                 __builtin_amdgcn_sched_barrier(0);
                 // phase (t, 1): multiply, meanwhile fetch and expand the first half of the following slot
                 if (t + 1 < WPL)
@@ -584,50 +591,6 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             __builtin_amdgcn_sched_barrier(0);
         }
     };
-    // int32 output of a wave tile that lies completely inside C: the accumulators of 32 rows (m) x 64 columns (n) at a
-    // time are transposed through LDS so that every store instruction writes four complete 256-byte row segments
-    // (straight from the accumulator layout an instruction would touch 32 rows with 32 bytes each).  The eight LDS
-    // reads of a pass are issued together and only then the eight stores, so that LDS latency is paid once per pass.
-    auto epilogue_rows = [&](const int64_t m_wave, const int64_t n_wave, auto scale) __attribute__((always_inline)) {
-        if constexpr (!kSign) {
-            row_sums();
-            const int out_row = lane >> 4, out_col = (lane & 15) * 4;
-#pragma unroll
-            for (int bj = 0; bj < WB; ++bj) {
-                const uint32_t mterm = mc.cRA * (uint32_t)ra[bj] + mc.c0;
-#pragma unroll
-                for (int pr = 0; pr < WB / 2; ++pr) {
-#pragma unroll
-                    for (int b2 = 0; b2 < 2; ++b2)
-#pragma unroll
-                        for (int q = 0; q < 4; ++q) {
-                            const int bi = 2 * pr + b2;
-                            const int col = b2 * 32 + 8 * q + 4 * kg;
-                            uint4 t4 = make_uint4(0u, 0u, 0u, 0u);
-                            if (mc.needRW) t4 = *reinterpret_cast<const uint4 *>(&rw_table[wave][pr * 64 + col]);
-                            i32x4 val;
-                            val[0] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 0])) + t4.x + mterm);
-                            val[1] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 1])) + t4.y + mterm);
-                            val[2] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 2])) + t4.z + mterm);
-                            val[3] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + 3])) + t4.w + mterm);
-                            *reinterpret_cast<i32x4 *>(&c_rows[wave][r][col]) = val;
-                        }
-                    __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the rows are in LDS
-                    __builtin_amdgcn_wave_barrier();
-                    i32x4 v[8];
-#pragma unroll
-                    for (int it = 0; it < 8; ++it)
-                        v[it] = *reinterpret_cast<const i32x4 *>(&c_rows[wave][4 * it + out_row][out_col]);
-                    __builtin_amdgcn_sched_barrier(0);
-                    int32_t *dst = g.epi.C + (m_wave + bj * 32 + out_row) * g.epi.ldc + n_wave + pr * 64 + out_col;
-#pragma unroll
-                    for (int it = 0; it < 8; ++it)
-                        __builtin_nontemporal_store(v[it], reinterpret_cast<i32x4 *>(dst + (int64_t)(4 * it) * g.epi.ldc));
-                    __builtin_amdgcn_wave_barrier();
-                }
-            }
-        }
-    };
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
         const bool interior = m_wave + WTILE <= g.M && n_wave + WTILE <= g.N;
         const bool wide = kSign || ((g.epi.ldc % 4 == 0) && (reinterpret_cast<uintptr_t>(g.epi.C) % 16 == 0));
@@ -635,18 +598,14 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         if (mc.alpha_shift >= 0) {
             const int sh = mc.alpha_shift;
             auto scale = [sh](uint32_t x) { return x << sh; };
-            if (fast && !kSign)
-                epilogue_rows(m_wave, n_wave, scale);
-            else if (fast)
+            if (fast)
                 epilogue(m_wave, n_wave, scale, std::true_type{});
             else
                 epilogue(m_wave, n_wave, scale, std::false_type{});
         } else {
             const uint32_t al = mc.alpha;
             auto scale = [al](uint32_t x) { return x * al; };
-            if (fast && !kSign)
-                epilogue_rows(m_wave, n_wave, scale);
-            else if (fast)
+            if (fast)
                 epilogue(m_wave, n_wave, scale, std::true_type{});
             else
                 epilogue(m_wave, n_wave, scale, std::false_type{});
@@ -675,26 +634,18 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         clear();
         QNN_STAMP(1);
         for (uint32_t s = 0; s + 2 < mc.msteps; s += 2) {
-            fetch(cur, s + 1, buf1);
-            __builtin_amdgcn_sched_barrier(0);
-            compute(buf0, buf1, frags, words);
-            fetch(cur, s + 2, buf0);
-            __builtin_amdgcn_sched_barrier(0);
-            compute(buf1, buf0, frags, words);
+            compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 1, buf1); });
+            compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 2, buf0); });
         }
         QNN_STAMP(2);
-        fetch(cur, mc.msteps - 1, buf1);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(buf0, buf1, frags, words);
+        compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, mc.msteps - 1, buf1); });
         QNN_STAMP(3);
         // the operand rows of this tile are not needed any more: move on to the next tile's
         const int64_t m_done = cur.m_wave, n_done = cur.n_wave;
         const uint32_t vb_next = vb + gridDim.x;
         const bool more = vb_next < total_tiles;
         locate(more ? vb_next : vb, cur);  // without a next tile the loads are repeated and ignored
-        fetch(cur, 0, buf0);
-        __builtin_amdgcn_sched_barrier(0);
-        compute(buf1, buf0, frags, words);
+        compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, 0, buf0); });
         QNN_STAMP(4);
         finish(m_done, n_done);
         QNN_STAMP(5);
