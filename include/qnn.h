@@ -139,7 +139,8 @@ int qnn_fold_batchnorm(const double *gamma, const double *beta, const double *me
  * T, flip: HOST arrays of n_layers - 1 DEVICE pointers (flip, or any flip[l], may be NULL).
  * logits: DEVICE int32 [batch][ld_logits].  workspace: DEVICE, 256-byte aligned, at least
  * qnn_binary_mlp_workspace_bytes(...) bytes, contents undefined before and after.
- * 2 <= n_layers <= QNN_MAX_LAYERS, 1 <= in_bits <= 8. */
+ * 2 <= n_layers <= QNN_MAX_LAYERS, 1 <= in_bits <= 8.  `engine` is a preference: a layer that the requested engine
+ * cannot take runs on the library's choice. */
 int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers,
                            const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
                            const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,

@@ -303,7 +303,7 @@ int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_
     int32_t coef[QNN_MAX_PLANES];
     for (int p = 0; p < in_bits; ++p) coef[p] = 1 << p;
     bool first_done = false;
-    if (in_bits == 8 && (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA)) {
+    if (in_bits == 8 && engine != QNN_ENGINE_VALU) {
         GemmArgs g;
         std::memset(&g, 0, sizeof(g));
         g.A.base = reinterpret_cast<const uint32_t *>(x);
@@ -317,32 +317,45 @@ int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_
         g.epi = Epilogue{nullptr, 0, T[0], flip ? flip[0] : nullptr, act[0], ldw(dims[1])};
         g.M = batch, g.N = dims[1], g.K = dims[0], g.Kw = words_for(dims[0]);
         if (int rc = check_range(g)) return rc;
-        if (mfma_supports(g) && (engine == QNN_ENGINE_MFMA || mfma_preferred(g))) {
+        if (mfma_supports(g) && (engine != QNN_ENGINE_AUTO || mfma_preferred(g))) {
             if (!aligned4(W[0]) || !aligned4(T[0])) return fail(QNN_ERR_ALIGN, "mlp: pointer not 4-byte aligned");
             if (int rc = launch_gemm_mfma(g, static_cast<hipStream_t>(stream))) return rc;
             first_done = true;
         }
     }
+    // `engine` is a preference here: a layer whose product the requested engine cannot take runs on the library's
+    // choice instead (a refusal enqueues nothing, so the retry is clean).
+    auto with_fallback = [&](auto &&call) {
+        int rc = call(engine);
+        if (rc == QNN_ERR_UNSUPPORTED && engine != QNN_ENGINE_AUTO) rc = call((int)QNN_ENGINE_AUTO);
+        return rc;
+    };
     if (!first_done) {
         if (int rc = qnn_pack_bitplanes(x, batch, dims[0], ldx, in_bits, planes, ld0, plane_stride, stream)) return rc;
-        if (int rc = qnn_bitplane_gemm_sign(planes, in_bits, coef, QNN_PLANE_BIT, ld0, plane_stride, W[0], 1, kOne,
-                                            QNN_PLANE_SIGN, words_for(dims[0]), 0, T[0], flip ? flip[0] : nullptr,
-                                            act[0], ldw(dims[1]), batch, dims[1], dims[0], engine, stream))
+        if (int rc = with_fallback([&](int e) {
+                return qnn_bitplane_gemm_sign(planes, in_bits, coef, QNN_PLANE_BIT, ld0, plane_stride, W[0], 1, kOne,
+                                              QNN_PLANE_SIGN, words_for(dims[0]), 0, T[0], flip ? flip[0] : nullptr,
+                                              act[0], ldw(dims[1]), batch, dims[1], dims[0], e, stream);
+            }))
             return rc;
     }
     // step 2: hidden layers, product + threshold fused
     int cur = 0;
     for (int l = 1; l < n_layers - 1; ++l) {
-        if (int rc = qnn_binary_gemm_sign(act[cur], ldw(dims[l]), W[l], words_for(dims[l]), T[l],
-                                          flip ? flip[l] : nullptr, act[cur ^ 1], ldw(dims[l + 1]), batch,
-                                          dims[l + 1], dims[l], engine, stream))
+        if (int rc = with_fallback([&](int e) {
+                return qnn_binary_gemm_sign(act[cur], ldw(dims[l]), W[l], words_for(dims[l]), T[l],
+                                            flip ? flip[l] : nullptr, act[cur ^ 1], ldw(dims[l + 1]), batch,
+                                            dims[l + 1], dims[l], e, stream);
+            }))
             return rc;
         cur ^= 1;
     }
     // step 3: output layer, integer sums
     const int L = n_layers - 1;
-    return qnn_binary_gemm_ex(act[cur], ldw(dims[L]), W[L], words_for(dims[L]), logits, ld_logits, batch, dims[L + 1],
-                              dims[L], engine, stream);
+    return with_fallback([&](int e) {
+        return qnn_binary_gemm_ex(act[cur], ldw(dims[L]), W[L], words_for(dims[L]), logits, ld_logits, batch,
+                                  dims[L + 1], dims[L], e, stream);
+    });
 }
 
 int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
