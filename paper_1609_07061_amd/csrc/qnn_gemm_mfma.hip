@@ -218,12 +218,28 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     uint32_t trace_tile = 0;
 #endif
     __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
+    __shared__ __attribute__((aligned(16))) int32_t thr_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
+    __shared__ __attribute__((aligned(16))) uint32_t flip_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in a scalar register
     const int r = lane & 31, kg = lane >> 5;
     const uint32_t Kw = (uint32_t)g.Kw;
     const uint32_t total_tiles = tiles_m * tiles_n;
     const int64_t Nw = (g.N + 31) / 32;
+    // thresholds / flip flags of the tile being finished: n = n_wave + lane and n_wave + 64 + lane (clamped into range)
+    int32_t thr_T[2] = {0, 0};
+    uint32_t thr_F[2] = {0u, 0u};
+    auto load_thresholds = [&](const int64_t n_wave) __attribute__((always_inline)) {
+        if constexpr (kSign) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                int64_t n = n_wave + 64 * h + lane;
+                if (n > g.N - 1) n = g.N - 1;
+                thr_T[h] = g.epi.T[n];
+                thr_F[h] = g.epi.flip ? (uint32_t)g.epi.flip[n] : 0u;
+            }
+        }
+    };
 
     // Where this lane's operand rows live for one tile (rows past the edge are clamped: computed, never stored).
     struct Tile {
@@ -416,7 +432,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     // `issue_loads` (the fetch of the following step into `n`) runs inside the first phase, so that its address
     // arithmetic also sits between matrix-core instructions instead of in front of them.
     constexpr int kOpsFetch = 3 * WB * (kBytesA ? 3 : (PA + PW));
-    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur, auto issue_loads) __attribute__((always_inline)) {
+    // last_tag (std::true_type for the last step of a tile): the operands of the following step, which belongs to the
+    // next tile, are then prepared after the epilogue instead, so that they do not occupy 40 registers during it.
+    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur, auto issue_loads, auto last_tag) __attribute__((always_inline)) {
+        constexpr bool kLastStep = decltype(last_tag)::value;
 #pragma unroll
         for (int t = 0; t < WPL; ++t) {
             if (t == 0) issue_loads();
@@ -425,11 +444,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                 Frags g;
                 Words nxt;
                 count(cur);
-                if (t + 1 < WPL)
+                if (t + 1 < WPL) {
                     prep(c, t + 1, nxt);
-                else
+                    expand(nxt, 0, g);
+                } else if (!kLastStep) {
                     prep(n, 0, nxt);
-                expand(nxt, 0, g);
+                    expand(nxt, 0, g);
+                }
                 multiply(f);
                 if (t == 0)
                     interleave(std::integral_constant<int, kOpsPhaseFp4 + kOpsFetch>{});
@@ -450,11 +471,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                     interleave(std::integral_constant<int, kOpsPhase0>{});
                 __builtin_amdgcn_sched_barrier(0);
                 // phase (t, 1): multiply, meanwhile fetch and expand the first half of the following slot
-                if (t + 1 < WPL)
+                if (t + 1 < WPL) {
                     prep(c, t + 1, cur);
-                else
+                    expand(cur, 0, f);
+                } else if (!kLastStep) {
                     prep(n, 0, cur);
-                expand(cur, 0, f);
+                    expand(cur, 0, f);
+                }
                 multiply(g);
                 interleave(std::integral_constant<int, kOpsPhase1>{});
                 __builtin_amdgcn_sched_barrier(0);
@@ -464,7 +487,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
 
     // both k-groups of a row hold partial row sums; the weight-row sums are needed per accumulator register (n varies
     // with the register), so they go through a small per-wave LDS table and come back as broadcasts
-    auto row_sums = [&]() __attribute__((always_inline)) {
+    auto row_sums = [&](const int r, const int kg) __attribute__((always_inline)) {
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
             ra[b] = sum_halves(ra[b]);
@@ -485,7 +508,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     // kFast: the wave tile lies completely inside C and C allows 16-byte stores, so nothing needs a bounds check.
     auto epilogue = [&](const int64_t m_wave, const int64_t n_wave, auto scale, auto fast_tag) __attribute__((always_inline)) {
         constexpr bool kFast = decltype(fast_tag)::value;
-        row_sums();
+        // The lane coordinates are re-derived here behind an opaque copy, so that none of the index arithmetic of the
+        // epilogue is computed once before the tile loop and then kept (or spilled and reloaded: a reload waits on the
+        // in-order memory counter, i.e. on every store issued before it) across the main loop.
+        int lane_opaque = (int)(threadIdx.x & 63);
+        asm volatile("" : "+v"(lane_opaque));
+        const int lane = lane_opaque, r = lane & 31, kg = lane >> 5;
+        row_sums(r, kg);
         int64_t m_of[WB];
         uint32_t mterm[WB];
 #pragma unroll
@@ -493,29 +522,22 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             m_of[bj] = m_wave + bj * 32 + r;
             mterm[bj] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
         }
-        // Thresholds and flip flags of one block of 32 n as this lane sees them (register v <-> n = 8 (v / 4) + 4 kg +
-        // v mod 4).  All loads of a block are issued back to back, from clamped (always valid) addresses and without
-        // any data-dependent branch, and are consumed one block later.
-        int32_t T_next[16];
-        uint32_t F_next[16];
-        auto load_thresholds = [&](const int64_t n_first, int32_t (&T)[16], uint32_t (&F)[16]) {
-            int64_t idx[16];
+        // Thresholds: the 128 values of this wave tile were loaded (two per lane, coalesced) while the last step was
+        // being computed; here they go, clamped and minus one, into a per-wave LDS table, and the flip flags go into
+        // a second table already shifted to the bit position their n has in a lane's partial output word
+        // (n mod 32 = 8 q + 4 kg + i  ->  bit 8 q + i).  The blocks below read both like the column terms.
+        if constexpr (kSign) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int64_t n = n_first + 8 * (v >> 2) + 4 * kg + (v & 3);
-                idx[v] = (kFast || n < g.N) ? n : g.N - 1;
+            for (int h = 0; h < 2; ++h) {
+                const int nl = 64 * h + lane;
+                const int32_t t = thr_T[h];
+                const int32_t tc = t < -(1 << 30) ? -(1 << 30) : (t > (1 << 30) ? (1 << 30) : t);
+                thr_table[wave][nl] = tc - 1;
+                flip_table[wave][nl] = thr_F[h] != 0 ? (1u << ((nl & 0x18) | (nl & 3))) : 0u;
             }
-#pragma unroll
-            for (int v = 0; v < 16; ++v) T[v] = g.epi.T[idx[v]];
-            if (g.epi.flip) {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) F[v] = g.epi.flip[idx[v]];
-            } else {
-#pragma unroll
-                for (int v = 0; v < 16; ++v) F[v] = 0u;
-            }
-        };
-        if constexpr (kSign) load_thresholds(n_wave, T_next, F_next);
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tables are in LDS
+            __builtin_amdgcn_wave_barrier();
+        }
 #pragma unroll
         for (int bi = 0; bi < WB; ++bi) {
             const int64_t n_blk = n_wave + bi * 32;
@@ -547,22 +569,27 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                     }
                 }
             } else {
-                // thresholds of this block of n were requested one block ahead (their latency hides behind the
-                // previous block's compares); request the next block's now
                 // e[v] = T - 1 - (part of C that depends on n only): C >= T  <=>  e[v] - (rest of C) < 0.  All terms
                 // are below 2^30 in magnitude (the host checks the bound of C, thresholds are clamped to it, which
                 // does not change any comparison), so the differences cannot wrap.
                 int32_t e[16];
                 uint32_t flips = 0, live_bits = 0;  // at the bit positions 8 (v / 4) + v mod 4 of the partial word
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int32_t Tc = T_next[v] < -(1 << 30) ? -(1 << 30) : (T_next[v] > (1 << 30) ? (1 << 30) : T_next[v]);
-                    e[v] = Tc - 1 - (int32_t)nterm[v];
-                    const uint32_t pos = 1u << (8 * (v >> 2) + (v & 3));
-                    if (F_next[v] != 0) flips |= pos;
-                    if (kFast || n_blk + 8 * (v >> 2) + 4 * kg + (v & 3) < g.N) live_bits |= pos;
+                for (int q = 0; q < 4; ++q) {
+                    const int col = bi * 32 + 8 * q + 4 * kg;
+                    const int4 t4 = *reinterpret_cast<const int4 *>(&thr_table[wave][col]);
+                    const uint4 f4 = *reinterpret_cast<const uint4 *>(&flip_table[wave][col]);
+                    e[4 * q + 0] = t4.x - (int32_t)nterm[4 * q + 0], e[4 * q + 1] = t4.y - (int32_t)nterm[4 * q + 1];
+                    e[4 * q + 2] = t4.z - (int32_t)nterm[4 * q + 2], e[4 * q + 3] = t4.w - (int32_t)nterm[4 * q + 3];
+                    flips |= f4.x | f4.y | f4.z | f4.w;
                 }
-                if (bi + 1 < WB) load_thresholds(n_blk + 32, T_next, F_next);
+                if constexpr (kFast) {
+                    live_bits = 0x0F0F0F0Fu;
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (n_blk + 8 * (v >> 2) + 4 * kg + (v & 3) < g.N) live_bits |= 1u << (8 * (v >> 2) + (v & 3));
+                }
                 const int64_t word = n_blk >> 5;
 #pragma unroll
                 for (int bj = 0; bj < WB; ++bj) {
@@ -634,21 +661,27 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         clear();
         QNN_STAMP(1);
         for (uint32_t s = 0; s + 2 < mc.msteps; s += 2) {
-            compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 1, buf1); });
-            compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 2, buf0); });
+            compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 1, buf1); }, std::false_type{});
+            compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 2, buf0); }, std::false_type{});
         }
         QNN_STAMP(2);
-        compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, mc.msteps - 1, buf1); });
+        compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, mc.msteps - 1, buf1); }, std::false_type{});
         QNN_STAMP(3);
         // the operand rows of this tile are not needed any more: move on to the next tile's
         const int64_t m_done = cur.m_wave, n_done = cur.n_wave;
         const uint32_t vb_next = vb + gridDim.x;
         const bool more = vb_next < total_tiles;
         locate(more ? vb_next : vb, cur);  // without a next tile the loads are repeated and ignored
-        compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, 0, buf0); });
+        compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) {
+            fetch(cur, 0, buf0);
+            load_thresholds(n_done);  // for the epilogue that follows this step
+        }, std::true_type{});
         QNN_STAMP(4);
         finish(m_done, n_done);
         QNN_STAMP(5);
+        // first operands of the next tile (its first step was loaded during the last step above)
+        prep(buf0, 0, words);
+        expand(words, 0, frags);
 #ifdef QNN_MFMA_TRACE
         if (g_trace && threadIdx.x == 0 && trace_tile < 8)
             g_trace[(blockIdx.x * 8 + trace_tile) * 8 + 6] = __builtin_amdgcn_s_memrealtime();
