@@ -845,8 +845,9 @@ bool mfma_supports(const GemmArgs &g, bool fp4) {
 }
 
 bool mfma_preferred(const GemmArgs &g) {
-    // small products are latency bound and better served by the finer tiles of the vector-ALU engine
-    return ceil_div(g.M, BM) * ceil_div(g.N, BN) >= 32 && g.K >= 256;
+    // small or skinny products (a 10-neuron output layer fills 10 of a tile's 256 columns) are better served by the
+    // finer tiles of the vector-ALU engine
+    return ceil_div(g.M, BM) * ceil_div(g.N, BN) >= 32 && g.K >= 256 && g.M >= 128 && g.N >= 128;
 }
 
 int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
