@@ -226,6 +226,61 @@ __global__ __launch_bounds__(kThreads) void gemm_valu_kernel(const GemmArgs g, u
     }
 }
 
+// Skinny product (at most 16 output neurons, e.g. the output layer of Alg. 4's MLP): the tiled kernel above would
+// spend a 64-column tile on a handful of columns.  Here a workgroup owns 64 rows of A; chunks of 128 packed words of
+// these rows and of all weight rows are staged in LDS (coalesced loads), and thread t counts disagreements for row
+// t / 4 against neurons 4 (t mod 4) .. + 3, reading four words of its row and its four neurons' words with 128-bit LDS
+// reads.  Sign x sign single planes, int32 output.
+constexpr int kSkinnyMaxN = 16;
+constexpr int kSkinnyRows = 64;
+constexpr int kSkinnyChunk = 128;  // words per staged chunk
+__global__ __launch_bounds__(kThreads) void gemm_skinny_kernel(const GemmArgs g) {
+    constexpr int kPitchA = kSkinnyChunk + 4;  // keeps 16-byte alignment, spreads rows over the banks
+    __shared__ __attribute__((aligned(16))) uint32_t sA[kSkinnyRows][kPitchA];
+    __shared__ __attribute__((aligned(16))) uint32_t sWt[kSkinnyChunk][kSkinnyMaxN];  // [word][neuron]
+    const int t = threadIdx.x, row = t >> 2, grp = t & 3;
+    const int64_t m0 = (int64_t)blockIdx.x * kSkinnyRows;
+    const int Kw = (int)g.Kw;
+    uint32_t cnt[4] = {0u, 0u, 0u, 0u};
+    for (int k0 = 0; k0 < Kw; k0 += kSkinnyChunk) {
+        // stage: consecutive threads take consecutive words of a row (rows and words past the ends read as zero)
+        for (int i = t; i < kSkinnyRows * kSkinnyChunk; i += kThreads) {
+            const int rr = i / kSkinnyChunk, j = i - rr * kSkinnyChunk;
+            const int64_t m = m0 + rr;
+            sA[rr][j] = (m < g.M && k0 + j < Kw) ? g.A.base[m * g.A.ld + k0 + j] : 0u;
+        }
+        for (int i = t; i < kSkinnyMaxN * kSkinnyChunk; i += kThreads) {
+            const int n = i / kSkinnyChunk, j = i - n * kSkinnyChunk;
+            sWt[j][n] = (n < g.N && k0 + j < Kw) ? g.W[(int64_t)n * g.ldw + k0 + j] : 0u;
+        }
+        __syncthreads();
+#pragma unroll 2
+        for (int j = 0; j < kSkinnyChunk; j += 4) {
+            const uint4 a = *reinterpret_cast<const uint4 *>(&sA[row][j]);
+            const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) {
+                const uint4 w = *reinterpret_cast<const uint4 *>(&sWt[j + jj][grp * 4]);
+                cnt[0] += __builtin_popcount(aw[jj] ^ w.x);
+                cnt[1] += __builtin_popcount(aw[jj] ^ w.y);
+                cnt[2] += __builtin_popcount(aw[jj] ^ w.z);
+                cnt[3] += __builtin_popcount(aw[jj] ^ w.w);
+            }
+        }
+        __syncthreads();
+    }
+    const int64_t m = m0 + row;
+    if (m < g.M) {
+        const int32_t coef = g.pa.coef[0] * g.pw.coef[0];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int n = grp * 4 + i;
+            // agreements minus disagreements; the zero words past the end of K agree in both operands
+            if (n < g.N) g.epi.C[m * g.epi.ldc + n] = coef * ((int32_t)g.K - 2 * (int32_t)cnt[i]);
+        }
+    }
+}
+
 template <int TM, int TN, bool kPixels, bool kSign>
 int launch_modes(const GemmArgs &g, hipStream_t s) {
     constexpr int BM = 16 * TM, BN = 16 * TN;
@@ -252,6 +307,11 @@ int launch_gemm_valu(const GemmArgs &g, hipStream_t s) {
     const bool pixels = g.A.rows_are_pixels != 0;
     // the large tile only when it still yields a few workgroups per compute unit
     const bool big = ceil_div(g.M, 128) * ceil_div(g.N, 128) >= 512;
+    if (!pixels && !sign && g.N <= kSkinnyMaxN && g.M >= 256 && g.pa.count == 1 && g.pw.count == 1 &&
+        g.pa.mode == QNN_PLANE_SIGN && g.pw.mode == QNN_PLANE_SIGN && ceil_div(g.M, kSkinnyRows) <= 0x7FFFFFFFLL) {
+        hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)ceil_div(g.M, kSkinnyRows)), dim3(kThreads), 0, s, g);
+        return check_launch("gemm_skinny");
+    }
     if (pixels) {
         if (sign) return fail(QNN_ERR_UNSUPPORTED, "conv: thresholded output is not provided");
         return big ? launch_modes<8, 8, true, false>(g, s) : launch_modes<4, 4, true, false>(g, s);

@@ -110,6 +110,22 @@ def test_binary_gemm(seed, M, N, K, engine):
     assert np.array_equal(host(got), want)
 
 
+@pytest.mark.parametrize("M,N,K", [(256, 1, 32), (300, 8, 1000), (1000, 9, 4096), (257, 16, 16384), (4000, 10, 700),
+                                   (300, 16, 16416), (255, 10, 512)])
+def test_binary_gemm_skinny_outputs(seed, M, N, K):
+    """Few output neurons (an MLP's output layer): AUTO and VALU take the one-row-per-wave kernel when it applies
+    (at most 16 neurons, at least 256 rows) and the tiled one otherwise."""
+    a = qi.pm1(seed, 20, (M, K))
+    w = qi.pm1(seed, 21, (N, K))
+    want = oracle.gemm_pm1(a, w)
+    for engine in (0, 1):
+        out = torch.full((M, N + 3), 99, dtype=torch.int32, device="cuda")
+        q.qnn_binary_gemm(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, out=out[:, :N], engine=engine)
+        got = host(out)
+        assert np.array_equal(got[:, :N], want)
+        assert (got[:, N:] == 99).all()
+
+
 @pytest.mark.parametrize("engine", ENGINES)
 def test_binary_gemm_strided_operands_and_output(seed, engine):
     M, N, K = 70, 90, 200  # 7 words per row, held in rows of 9 / 12 words; C rows of 100
