@@ -55,7 +55,7 @@ struct Code {
 struct MfmaConst {
     Code a, w;
     uint32_t alpha, cRA, cRW, c0;  // C = alpha * S + cRA * RA[m] + cRW * RW[n] + c0   (mod 2^32)
-    int needRA, needRW;
+    int needRW;  // cRW != 0: the weight-row sums are needed (the activation-row sums are always formed)
     int alpha_shift;  // alpha == 1 << alpha_shift, or -1 if alpha is not a positive power of two
     uint32_t msteps;  // macro steps of 2 * WPL words, rounded up to an even count
 };
@@ -111,12 +111,7 @@ __device__ __forceinline__ void load_words(const uint32_t *row, uint32_t j0, uin
         const bool ok = live && j0 < Kw;
         mask = ok ? 0xFFFFFFFFu : 0u;
         const uint32_t *p = row + (ok ? j0 : 0u);
-        if constexpr (WPL == 8) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(p);
-            const uint4 u = *reinterpret_cast<const uint4 *>(p + 4);
-            out[0] = v.x, out[1] = v.y, out[2] = v.z, out[3] = v.w;
-            out[4] = u.x, out[5] = u.y, out[6] = u.z, out[7] = u.w;
-        } else if constexpr (WPL == 4) {
+        if constexpr (WPL == 4) {
             const uint4 v = *reinterpret_cast<const uint4 *>(p);
             out[0] = v.x, out[1] = v.y, out[2] = v.z, out[3] = v.w;
         } else if constexpr (WPL == 2) {
@@ -814,7 +809,6 @@ bool prepare(const GemmArgs &g, bool fp4, const Variant *&var, MfmaConst &mc, bo
     mc.cRA = (uint32_t)(aA * bW);
     mc.cRW = (uint32_t)(bA * aW);
     mc.c0 = (uint32_t)(g.K * bA * bW - aA * aW * npad * xA0 * xW0);
-    mc.needRA = mc.cRA != 0;
     mc.needRW = mc.cRW != 0;
     // the row sums are over the true K: RA = sum_p d_p pop_p - K * off; fold the constant part into c0
     mc.c0 += (uint32_t)(aA * bW * (g.K * xA0)) + (uint32_t)(bA * aW * (g.K * xW0));
