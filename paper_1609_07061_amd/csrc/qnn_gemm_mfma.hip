@@ -331,7 +331,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     };
     struct Words {
         uint32_t a[WB][PA], w[WB][PW];
-        uint32_t ab[kBytesA ? WB : 1][8];  // byte operand: x - 128 as int8, zero beyond K
+        uint32_t ab[kBytesA ? WB : 1][8];  // byte operand: x - 128 as int8 (beyond K: whatever was read; the weights'
+                                           // zero tail bits cancel it in the product)
+        uint32_t ab_ones[2];               // 0x01010101 for a 16-byte half inside the row, else 0: row-sum multiplier
     };
     // words of slot t of a step, masks applied here, at the point of use, so that the loads stay in flight until now
     auto prep = [&](const Step &c, int t, Words &o) __attribute__((always_inline)) {
@@ -342,7 +344,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                 o.a[b][p] = kBytesA ? 0u : (kChunk ? (c.A[b][p][t] & c.maskA[b]) : c.A[b][p][t]);
             if constexpr (kBytesA) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) o.ab[b][i] = (c.Ab[b][i] ^ 0x80808080u) & c.maskAb[i >> 2];
+                for (int i = 0; i < 8; ++i) o.ab[b][i] = c.Ab[b][i] ^ 0x80808080u;
+                o.ab_ones[0] = c.maskAb[0] & 0x01010101u, o.ab_ones[1] = c.maskAb[1] & 0x01010101u;
             }
 #pragma unroll
             for (int p = 0; p < PW; ++p) o.w[b][p] = kChunk ? (c.W[b][p][t] & c.maskW) : c.W[b][p][t];
@@ -356,7 +359,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         for (int b = 0; b < WB; ++b) {
             if constexpr (kBytesA) {
 #pragma unroll
-                for (int i = 0; i < 8; ++i) ra[b] = __builtin_amdgcn_sdot4((int)o.ab[b][i], 0x01010101, ra[b], false);
+                for (int i = 0; i < 8; ++i)
+                    ra[b] = __builtin_amdgcn_sdot4((int)o.ab[b][i], (int)o.ab_ones[i >> 2], ra[b], false);
             }
 #pragma unroll
             for (int p = 0; p < (kBytesA ? 0 : PA); ++p) {
@@ -779,7 +783,7 @@ bool prepare(const GemmArgs &g, bool fp4, const Variant *&var, MfmaConst &mc, bo
     const bool bytes = g.A.rows_are_bytes != 0;
     int64_t aA, bA, xA0, aW, bW, xW0;
     if (bytes) {
-        // x8 = code - 128 (zero beyond K), true value = x8 + 128; rows of 16-byte aligned chunks only
+        // x8 = code - 128, true value = x8 + 128; rows of 16-byte aligned chunks only
         if (fp4 || g.pw.count != 1 || g.K % 16 || g.A.ld % 16 || reinterpret_cast<uintptr_t>(g.A.base) % 16) return false;
         var = &kBytes;
         std::memset(&mc.a, 0, sizeof(mc.a));

@@ -301,7 +301,7 @@ def test_mlp_forward_first_layer_from_codes(seed, batch, dims, ldx, engine):
     T[0] = qi.uniform_int(seed, 89, (dims[1],), -3000, 3000)
     flip = [qi.bernoulli_bits(seed, 90 + l, (dims[l + 1],)) for l in range(len(dims) - 2)]
     want = oracle.mlp(x, W, T, flip)
-    xb = np.zeros((batch, ldx), dtype=np.uint8)
+    xb = qi.uniform_int(seed, 95, (batch, ldx), 0, 255, dtype=np.uint8)  # garbage in the row padding
     xb[:, : dims[0]] = x
     xd = dev(xb)[:, : dims[0]]
     got = _engine_or_skip(q.qnn_binary_mlp_forward, xd, 8, dims, [dev(np_pack_pm1(w)) for w in W],
