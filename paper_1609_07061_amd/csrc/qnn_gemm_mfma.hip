@@ -215,6 +215,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
     __shared__ __attribute__((aligned(16))) int32_t thr_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
     __shared__ __attribute__((aligned(16))) uint32_t flip_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
+    // int32 epilogue: per wave two 32 x 32 staging blocks, through which a block is turned from the accumulator layout
+    // (a lane = one row) into whole 128-byte lines per row
+    __shared__ __attribute__((aligned(16))) int32_t stage[kSign ? 1 : kThreads / 64][kSign ? 4 : 2 * 32 * 32];
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);  // wave-uniform, kept in a scalar register
     const int r = lane & 31, kg = lane >> 5;
@@ -537,6 +540,15 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the tables are in LDS
             __builtin_amdgcn_wave_barrier();
         }
+        // kFast int32 output: lines of the block before the current one, read from LDS and not stored yet; lane
+        // (row = lane / 8, 16-byte unit = lane mod 8) of store j writes row 8 j + lane / 8 of the block
+        i32x4 pend[4];
+        int32_t *const line_base = kSign ? nullptr : g.epi.C + (m_wave + (lane >> 3)) * g.epi.ldc + n_wave + 4 * (lane & 7);
+        auto store_lines = [&](const int pbi, const int pbj) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<i32x4 *>(line_base + (int64_t)(pbj * 32 + 8 * j) * g.epi.ldc + pbi * 32) = pend[j];
+        };
 #pragma unroll
         for (int bi = 0; bi < WB; ++bi) {
             const int64_t n_blk = n_wave + bi * 32;
@@ -558,13 +570,36 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                         for (int i = 0; i < 4; ++i)
                             val[i] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + i])) + nterm[4 * q + i] + mterm[bj]);
                         if constexpr (kFast) {
-                            *reinterpret_cast<i32x4 *>(row + 8 * q) = val;
+                            // 16-byte unit c = 2 q + kg of row r; the unit index is swizzled with the row so that
+                            // neither this write (16 rows, one unit each, per pass) nor the read below (2 rows, all
+                            // units) puts two lanes of a pass on one LDS bank
+                            int32_t *blk = &stage[wave][((bi * WB + bj) & 1) * 1024];
+                            *reinterpret_cast<i32x4 *>(blk + r * 32 + 4 * ((2 * q + kg) ^ ((r >> 1) & 7))) = val;
                         } else if (m_of[bj] < g.M) {
                             const int64_t n0 = n_blk + 8 * q + 4 * kg;
 #pragma unroll
                             for (int i = 0; i < 4; ++i)
                                 if (n0 + i < g.N) row[8 * q + i] = val[i];
                         }
+                    }
+                    if constexpr (kFast) {
+                        // Read the block back as 8 rows x 128 bytes per instruction, so that the stores write whole
+                        // lines: a store instruction that scatters 32-byte pieces over 32 rows costs more than twice
+                        // the memory traffic of one that writes complete lines.  LDS operations of a wave execute in
+                        // order, so only the compiler has to be kept from reordering them.  The lines are stored one
+                        // block later, which hides the LDS round trip behind the next block's arithmetic.
+                        __builtin_amdgcn_wave_barrier();
+                        const int32_t *blk = &stage[wave][((bi * WB + bj) & 1) * 1024];
+                        i32x4 line[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int R = 8 * j + (lane >> 3);
+                            line[j] = *reinterpret_cast<const i32x4 *>(blk + R * 32 + 4 * ((lane & 7) ^ ((R >> 1) & 7)));
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                        if (bi + bj > 0) store_lines((bi * WB + bj - 1) / WB, (bi * WB + bj - 1) % WB);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) pend[j] = line[j];
                     }
                 }
             } else {
@@ -616,6 +651,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if constexpr (kFast && !kSign) store_lines(WB - 1, WB - 1);
     };
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
         const bool interior = m_wave + WTILE <= g.M && n_wave + WTILE <= g.N;
