@@ -132,8 +132,15 @@ def main():
         D3 = torch.empty_like(C3)
         for _ in range(3):
             D3.copy_(C3)  # 268 435 456 bytes read + the same written per call
+        # two more kernels of known size, with the plain loads / stores the GEMM itself uses: a fill (268 435 456 bytes
+        # written, nothing read) and the sign+pack kernel (268 435 456 bytes read, 8 388 608 written)
+        xf = torch.randn((n, n), dtype=torch.float32, device="cuda")
+        pk = torch.empty((n, n // 32), dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            D3.zero_()
+            q.qnn_pack_sign(xf, out=pk)
         torch.cuda.synchronize()
-        del D3
+        del D3, xf, pk
 
     # ---------------------------------------------------------------- C3 with sign+pack from fp32 included
     if "c3" in only:
