@@ -1,7 +1,8 @@
 // Bandwidth-bound kernels of the path: sign-binarize + pack (Sec. 2.1 Eq. (1), Sec. 6), bit-plane split + pack
 // (Sec. 2.6 Eq. (FirstLayer)), and threshold + pack (Alg. 4, Sign(BatchNorm(.)) with BatchNorm folded to an integer
 // threshold).  All three turn one predicate per element into packed words with a wavefront ballot: lane l of a
-// 64-wide wave owns element 64*c + l of the wave's chunk, so one ballot yields two finished 32-bit words.
+// 64-wide wave owns element 64*c + l of the wave's chunk, so one ballot yields two finished 32-bit words.  Long aligned
+// float rows have a second sign+pack kernel that loads 16 bytes per lane and combines nibbles across lanes instead.
 #include "qnn_internal.h"
 
 namespace qnn {
@@ -47,6 +48,48 @@ __global__ __launch_bounds__(kBlock) void pack_sign_kernel(const uint32_t *__res
         }
         const int64_t w = k0 / 32 + lane;
         if (lane < 2 * kUnroll && w < Kw) out[r * ldo + w] = mine;
+    }
+}
+
+// Same for rows made of whole, 16-byte aligned groups of four floats: every lane loads 16 bytes at a time, so a wave
+// has 8 KiB in flight with 8 loads of 1 KiB each.  Load c brings in words 8c .. 8c+7 of the chunk's 64 words: lanes
+// 8g .. 8g+7 hold word 8c + g as eight float4 (lane 8g + s: elements 4s .. 4s+3, i.e. bits 4s .. 4s+3).  The eight
+// nibbles are OR-ed across the group with three DPP steps and lane 8g + c keeps the result, so lane 8g + s ends up with
+// word 8s + g and one store instruction writes the chunk's 256 contiguous bytes (lanes permuted within them).
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+__global__ __launch_bounds__(kBlock) void pack_sign_vec4_kernel(const uint32_t *__restrict__ x, int64_t rows, int64_t K,
+                                                                int64_t ldx, uint32_t *__restrict__ out, int64_t ldo,
+                                                                int64_t chunks_per_row, int64_t total_chunks) {
+    constexpr int kLoads = 8, kChunk = kLoads * kWave * 4;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int grp = lane >> 3, sub = lane & 7;
+    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t Kw = (K + 31) / 32;
+    for (int64_t chunk = wave0; chunk < total_chunks; chunk += wave_stride) {
+        const int64_t r = chunk / chunks_per_row;
+        const int64_t k0 = (chunk - r * chunks_per_row) * kChunk;
+        const uint32_t *row = x + r * ldx;
+        u32x4 v[kLoads];
+#pragma unroll
+        for (int c = 0; c < kLoads; ++c) {
+            const int64_t k = k0 + (c * 64 + lane) * 4;  // K is a multiple of 4: all four inside or outside
+            const u32x4 minus = {0x80000001u, 0x80000001u, 0x80000001u, 0x80000001u};
+            v[c] = (k < K) ? __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(row + k)) : minus;
+        }
+        uint32_t mine = 0;
+#pragma unroll
+        for (int c = 0; c < kLoads; ++c) {
+            uint32_t nib = (sign_is_plus(v[c][0]) ? 1u : 0u) | (sign_is_plus(v[c][1]) ? 2u : 0u) |
+                           (sign_is_plus(v[c][2]) ? 4u : 0u) | (sign_is_plus(v[c][3]) ? 8u : 0u);
+            uint32_t w = nib << (4 * sub);
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xF, 0xF, true);   // lane ^ 1
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E, 0xF, 0xF, true);   // lane ^ 2
+            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xF, 0xF, true);  // mirror within 8 lanes
+            if (sub == c) mine = w;
+        }
+        const int64_t w_idx = k0 / 32 + sub * 8 + grp;
+        if (w_idx < Kw) out[r * ldo + w_idx] = mine;
     }
 }
 
@@ -122,6 +165,13 @@ int grid_for(int64_t total_chunks) {
 }  // namespace
 
 int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo, hipStream_t s) {
+    if (K >= 2048 && K % 4 == 0 && ldx % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0) {
+        const int64_t cpr = ceil_div(K, (int64_t)2048);
+        const int64_t total = rows * cpr;
+        hipLaunchKernelGGL(pack_sign_vec4_kernel, dim3(grid_for(total)), dim3(kBlock), 0, s,
+                           reinterpret_cast<const uint32_t *>(x), rows, K, ldx, out, ldo, cpr, total);
+        return check_launch("pack_sign");
+    }
     constexpr int kUnroll = 8;  // 512 elements (2 KiB of floats) in flight per wave
     const int64_t cpr = ceil_div(K, (int64_t)kUnroll * kWave);
     const int64_t total = rows * cpr;

@@ -99,7 +99,8 @@ def test_config5_lstm_gates_int4(seed):
 @pytest.mark.parametrize("M,N,ldc", [(4200, 4200, 4200), (4200, 4197, 4197), (4104, 4360, 4400)])
 def test_large_ragged_gemm_interior_and_edge_tiles(seed, M, N, ldc, engine):
     """More tiles than compute units, K = 8192 and ragged edges: interior tiles take the row-contiguous 16-byte store
-    path (when the row pitch allows it), edge tiles the bounds-checked one, in the same launch."""
+    path (when the row pitch allows it: blocks staged through LDS and stored as whole lines), edge tiles the
+    bounds-checked one, in the same launch."""
     K = 8192
     a = qi.pm1(seed, 60, (M, K))
     w = qi.pm1(seed, 61, (N, K))

@@ -63,6 +63,31 @@ def test_pack_sign_every_edge_value_in_every_lane():
     assert np.array_equal(host_u32(q.qnn_pack_sign(dev(x))), oracle.pack_bits(oracle.sign(x)))
 
 
+@pytest.mark.parametrize("rows,K", [(5, 2048), (3, 2052), (7, 4100), (2, 6148), (64, 8192), (3, 2050), (2, 4099)])
+def test_pack_sign_long_rows(seed, rows, K):
+    """Rows of 2048 elements and more made of whole aligned groups of four take the 16-byte-load kernel (several
+    chunks per row, ragged last chunk); K = 2050 and 4099 stay on the one-element-per-lane kernel."""
+    x = qi.with_special_floats(qi.normal_f32(seed, 14, (rows, K)), seed, 15)
+    assert np.array_equal(host_u32(q.qnn_pack_sign(dev(x))), oracle.pack_bits(oracle.sign(x)))
+
+
+def test_pack_sign_long_rows_strided_and_edge_values(seed):
+    """16-byte-load kernel on a strided view (pitch 2304 floats, output pitch 80 words): padding stays untouched, and
+    every special value visits every position of a four-element group and of a 32-bit word."""
+    rows, K, ldx, ldo = 67, 2240, 2304, 80
+    sp = qi.special_floats()
+    buf = np.stack([np.roll(np.resize(sp, ldx), i) for i in range(rows)]).astype(np.float32)
+    buf[::3] = qi.normal_f32(seed, 16, (len(buf[::3]), ldx))
+    out = torch.full((rows, ldo), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    q.qnn_pack_sign(dev(buf)[:, :K], out=out[:, :K // 32])
+    got = host_u32(out)
+    assert np.array_equal(got[:, :K // 32], oracle.pack_bits(oracle.sign(buf[:, :K])))
+    assert (got[:, K // 32:] == 0x5A5A5A5A).all()
+    # a view that starts 4 bytes off the 16-byte grid must give the same bits through the other kernel
+    got2 = host_u32(q.qnn_pack_sign(dev(buf)[:, 1:K + 1]))
+    assert np.array_equal(got2, oracle.pack_bits(oracle.sign(buf[:, 1:K + 1])))
+
+
 # ------------------------------------------------------------------ S1b pack_bitplanes
 @pytest.mark.parametrize("rows,K,nbits", [(1, 1, 1), (3, 33, 2), (5, 64, 4), (4, 257, 8), (10, 784, 8), (7, 2048, 4),
                                           (6, 255, 3)])
