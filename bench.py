@@ -151,6 +151,19 @@ def main():
                                         "frac_of_hbm_peak": (n * n * 4 + n * n / 8) / (msp * 1e-3) / 1e9 / HBM_PEAK_GBS}
         extra["c3_tops_including_pack_of_both_operands_from_fp32"] = ops3 / ((ms3 + 2 * msp) * 1e-3) / 1e12
         del xf, pk
+        # the two other bandwidth-bound kernels of the path at the same size: the stand-alone threshold + repack over
+        # the 8192^2 int32 product, and the bit-plane split of 8-bit codes
+        thr = torch.zeros((n,), dtype=torch.int32, device="cuda")
+        tb = torch.empty((n, n // 32), dtype=torch.int32, device="cuda")
+        mst, _ = time_steps(lambda: q.qnn_threshold_sign(C3, thr, None, out=tb), sec_steps, sec_warm)
+        gb = (n * n * 4 + n * n / 8 + n * 4) / (mst * 1e-3) / 1e9
+        extra["threshold_sign_8192x8192"] = {"ms": mst, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
+        codes = torch.randint(0, 256, (n, n), dtype=torch.uint8, device="cuda")
+        pl = torch.empty((8, n, n // 32), dtype=torch.int32, device="cuda")
+        msb, _ = time_steps(lambda: q.qnn_pack_bitplanes(codes, 8, out=pl), sec_steps, sec_warm)
+        gb = (n * n + n * n) / (msb * 1e-3) / 1e9
+        extra["pack_bitplanes_8192x8192_8bit"] = {"ms": msb, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
+        del thr, tb, codes, pl
 
     # ---------------------------------------------------------------- C2: MNIST-shaped MLP forward
     if "c2" in only:

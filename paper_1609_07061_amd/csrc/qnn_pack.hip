@@ -57,6 +57,15 @@ __global__ __launch_bounds__(kBlock) void pack_sign_kernel(const uint32_t *__res
 // nibbles are OR-ed across the group with three DPP steps and lane 8g + c keeps the result, so lane 8g + s ends up with
 // word 8s + g and one store instruction writes the chunk's 256 contiguous bytes (lanes permuted within them).
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef int32_t i32x4 __attribute__((ext_vector_type(4)));
+
+// OR of x over the eight lanes 8g .. 8g+7, in each of them (all lanes of the wave must be active).
+__device__ __forceinline__ uint32_t or_over_8_lanes(uint32_t x) {
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0xB1, 0xF, 0xF, true);   // lane ^ 1
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x4E, 0xF, 0xF, true);   // lane ^ 2
+    x |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x141, 0xF, 0xF, true);  // mirror within 8 lanes
+    return x;
+}
 __global__ __launch_bounds__(kBlock) void pack_sign_vec4_kernel(const uint32_t *__restrict__ x, int64_t rows, int64_t K,
                                                                 int64_t ldx, uint32_t *__restrict__ out, int64_t ldo,
                                                                 int64_t chunks_per_row, int64_t total_chunks) {
@@ -82,10 +91,7 @@ __global__ __launch_bounds__(kBlock) void pack_sign_vec4_kernel(const uint32_t *
         for (int c = 0; c < kLoads; ++c) {
             uint32_t nib = (sign_is_plus(v[c][0]) ? 1u : 0u) | (sign_is_plus(v[c][1]) ? 2u : 0u) |
                            (sign_is_plus(v[c][2]) ? 4u : 0u) | (sign_is_plus(v[c][3]) ? 8u : 0u);
-            uint32_t w = nib << (4 * sub);
-            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0xB1, 0xF, 0xF, true);   // lane ^ 1
-            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x4E, 0xF, 0xF, true);   // lane ^ 2
-            w |= (uint32_t)__builtin_amdgcn_update_dpp(0, (int)w, 0x141, 0xF, 0xF, true);  // mirror within 8 lanes
+            const uint32_t w = or_over_8_lanes(nib << (4 * sub));
             if (sub == c) mine = w;
         }
         const int64_t w_idx = k0 / 32 + sub * 8 + grp;
@@ -127,6 +133,47 @@ __global__ __launch_bounds__(kBlock) void pack_bitplanes_kernel(const uint8_t *_
     }
 }
 
+// Rows of whole, 4-byte aligned groups of four codes: a lane loads four codes at a time (a wave: 256 contiguous bytes
+// per load).  For plane p the four bits of a lane become a nibble with one multiply ((x >> p) & 0x01010101 holds them
+// at bits 0, 8, 16, 24; times 0x01020408 moves them to bits 24 .. 27, and no two partial products meet), the eight
+// nibbles of a word are combined as in pack_sign_vec4_kernel, and lane 8g + s (s < kLoads) stores word 8s + g.
+template <int kLoads>
+__global__ __launch_bounds__(kBlock) void pack_bitplanes_vec4_kernel(const uint8_t *__restrict__ v, int64_t rows,
+                                                                     int64_t K, int64_t ldv, int nbits,
+                                                                     uint32_t *__restrict__ planes, int64_t ld,
+                                                                     int64_t plane_stride, int64_t chunks_per_row,
+                                                                     int64_t total_chunks) {
+    static_assert(kLoads >= 1 && kLoads <= 8, "a lane keeps one word: at most eight loads per chunk");
+    constexpr int kChunk = kLoads * kWave * 4;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int grp = lane >> 3, sub = lane & 7;
+    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t Kw = (K + 31) / 32;
+    for (int64_t chunk = wave0; chunk < total_chunks; chunk += wave_stride) {
+        const int64_t r = chunk / chunks_per_row;
+        const int64_t k0 = (chunk - r * chunks_per_row) * kChunk;
+        const uint8_t *row = v + r * ldv;
+        uint32_t code[kLoads];
+#pragma unroll
+        for (int c = 0; c < kLoads; ++c) {
+            const int64_t k = k0 + (c * kWave + lane) * 4;  // K is a multiple of 4: all four inside or outside
+            code[c] = (k < K) ? __builtin_nontemporal_load(reinterpret_cast<const uint32_t *>(row + k)) : 0u;
+        }
+        const int64_t w_idx = k0 / 32 + sub * 8 + grp;
+        for (int p = 0; p < nbits; ++p) {
+            uint32_t mine = 0;
+#pragma unroll
+            for (int c = 0; c < kLoads; ++c) {
+                const uint32_t nib = (((code[c] >> p) & 0x01010101u) * 0x01020408u) >> 24;
+                const uint32_t w = or_over_8_lanes(nib << (4 * sub));
+                if (sub == c) mine = w;
+            }
+            if (sub < kLoads && w_idx < Kw) planes[p * plane_stride + r * ld + w_idx] = mine;
+        }
+    }
+}
+
 // Threshold: one wave owns 64 consecutive neurons (their T and flip stay in registers) and walks down kRows rows.
 constexpr int kThreshRows = 16;
 __global__ __launch_bounds__(kBlock) void threshold_sign_kernel(const int32_t *__restrict__ C, int64_t ldc, int64_t M,
@@ -152,6 +199,60 @@ __global__ __launch_bounds__(kBlock) void threshold_sign_kernel(const int32_t *_
             unsigned long long mask = __ballot(live && ((c >= t) != f));
             uint32_t mine = (lane == 0) ? (uint32_t)mask : (uint32_t)(mask >> 32);
             if (lane < 2 && w < Nw) out[m * ldo + w] = mine;
+        }
+    }
+}
+
+// Rows of whole, 16-byte aligned groups of four sums: a wave owns 256 consecutive neurons (a lane four of them, their
+// thresholds and flips in registers) and walks down the rows eight at a time: eight loads of 1 KiB contiguous each in
+// flight, then per row the lane's four comparisons as a nibble, combined over the eight lanes of a word; lane 8g + s
+// keeps word g of row s of the eight.
+constexpr int kThreshVecRows = 32;
+__global__ __launch_bounds__(kBlock) void threshold_sign_vec4_kernel(const int32_t *__restrict__ C, int64_t ldc,
+                                                                     int64_t M, int64_t N, const int32_t *__restrict__ T,
+                                                                     const uint8_t *__restrict__ flip,
+                                                                     uint32_t *__restrict__ out, int64_t ldo) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int grp = lane >> 3, sub = lane & 7;
+    const int64_t n_wave0 = ((int64_t)blockIdx.x * kWavesPerBlock + wave) * (4 * kWave);
+    if (n_wave0 >= N) return;  // wave-uniform
+    const int64_t n = n_wave0 + 4 * lane;
+    const bool live = n < N;  // N is a multiple of 4: all four inside or outside
+    int32_t t[4] = {0, 0, 0, 0};
+    uint32_t flips = 0;
+    if (live) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            t[i] = T[n + i];
+            if (flip && flip[n + i] != 0) flips |= 1u << i;
+        }
+    }
+    const uint32_t live_nib = live ? 0xFu : 0u;
+    const int64_t Nw = (N + 31) / 32;
+    const int64_t w = n_wave0 / 32 + grp;
+    for (int64_t m0 = (int64_t)blockIdx.y * kThreshVecRows; m0 < M; m0 += (int64_t)gridDim.y * kThreshVecRows) {
+        for (int it = 0; it < kThreshVecRows / 8; ++it) {
+            const int64_t mb = m0 + it * 8;
+            if (mb >= M) break;  // wave-uniform
+            i32x4 c4[8];
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                const int64_t m = mb + c;
+                const i32x4 zero = {0, 0, 0, 0};
+                c4[c] = (live && m < M) ? __builtin_nontemporal_load(reinterpret_cast<const i32x4 *>(C + m * ldc + n)) : zero;
+            }
+            uint32_t mine = 0;
+#pragma unroll
+            for (int c = 0; c < 8; ++c) {
+                uint32_t nib = (c4[c][0] >= t[0] ? 1u : 0u) | (c4[c][1] >= t[1] ? 2u : 0u) |
+                               (c4[c][2] >= t[2] ? 4u : 0u) | (c4[c][3] >= t[3] ? 8u : 0u);
+                nib = (nib ^ flips) & live_nib;
+                const uint32_t word = or_over_8_lanes(nib << (4 * sub));
+                if (sub == c) mine = word;
+            }
+            const int64_t m = mb + sub;
+            if (m < M && w < Nw) out[m * ldo + w] = mine;
         }
     }
 }
@@ -182,6 +283,14 @@ int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint3
 
 int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,
                           int64_t ld, int64_t plane_stride, hipStream_t s) {
+    if (K >= 512 && K % 4 == 0 && ldv % 4 == 0 && reinterpret_cast<uintptr_t>(v) % 4 == 0) {
+        const bool big = K >= 2048;
+        const int64_t cpr = ceil_div(K, (int64_t)(big ? 2048 : 1024));
+        const int64_t total = rows * cpr;
+        hipLaunchKernelGGL(big ? pack_bitplanes_vec4_kernel<8> : pack_bitplanes_vec4_kernel<4>, dim3(grid_for(total)),
+                           dim3(kBlock), 0, s, v, rows, K, ldv, nbits, planes, ld, plane_stride, cpr, total);
+        return check_launch("pack_bitplanes");
+    }
     constexpr int kUnroll = 4;
     const int64_t cpr = ceil_div(K, (int64_t)kUnroll * kWave);
     const int64_t total = rows * cpr;
@@ -192,6 +301,15 @@ int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv
 
 int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
                           uint32_t *out, int64_t ldo, hipStream_t s) {
+    if (N >= 256 && N % 4 == 0 && ldc % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0) {
+        const int64_t vx = ceil_div(N, (int64_t)kWavesPerBlock * 4 * kWave);
+        int64_t vy = ceil_div(M, (int64_t)kThreshVecRows);
+        if (vy > 32768) vy = 32768;  // the kernel strides over the remaining row groups
+        if (vx > 0x7FFFFFFF) return fail(QNN_ERR_SHAPE, "threshold_sign: N too large");
+        hipLaunchKernelGGL(threshold_sign_vec4_kernel, dim3((unsigned)vx, (unsigned)vy), dim3(kBlock), 0, s, C, ldc, M,
+                           N, T, flip, out, ldo);
+        return check_launch("threshold_sign");
+    }
     const int64_t gx = ceil_div(N, (int64_t)kBlock);
     int64_t gy = ceil_div(M, (int64_t)kThreshRows);
     if (gy > 32768) gy = 32768;  // the kernel strides over the remaining row groups

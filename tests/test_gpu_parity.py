@@ -107,7 +107,64 @@ def test_pack_bitplanes_twos_complement_codes(seed):
     assert np.array_equal(host_u32(q.qnn_pack_bitplanes(dev(codes), 4)), want)
 
 
+@pytest.mark.parametrize("rows,K,nbits", [(5, 512, 8), (3, 784, 8), (9, 1028, 3), (7, 2048, 2), (4, 2052, 4),
+                                          (2, 4100, 1), (64, 8192, 8), (3, 786, 8), (2, 2049, 4)])
+def test_pack_bitplanes_long_rows(seed, rows, K, nbits):
+    """Rows of 512 codes and more made of whole aligned groups of four take the 4-byte-load kernel (1024- or
+    2048-code chunks, ragged last chunk); K = 786 and 2049 stay on the one-code-per-lane kernel."""
+    v = qi.uniform_int(seed, 19, (rows, K), 0, (1 << nbits) - 1)
+    planes = oracle.split_planes(v, nbits)
+    want = np.stack([oracle.pack_bits(planes[p].astype(np.int8)) for p in range(nbits)])
+    assert np.array_equal(host_u32(q.qnn_pack_bitplanes(dev(v.astype(np.uint8)), nbits)), want)
+
+
+def test_pack_bitplanes_long_rows_strided(seed):
+    """4-byte-load kernel on a strided view with padded output planes: padding untouched; a view one byte off the
+    4-byte grid gives the same through the other kernel."""
+    rows, K, ldv, nbits, ldo = 37, 1200, 1280, 8, 40
+    buf = qi.uniform_int(seed, 20, (rows, ldv), 0, 255).astype(np.uint8)
+    out = torch.full((nbits, rows, ldo), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    q.qnn_pack_bitplanes(dev(buf)[:, :K], nbits, out=out[:, :, :38])
+    got = host_u32(out)
+    planes = oracle.split_planes(buf[:, :K].astype(np.int64), nbits)
+    want = np.stack([oracle.pack_bits(planes[p].astype(np.int8)) for p in range(nbits)])
+    assert np.array_equal(got[:, :, :38], want)
+    assert (got[:, :, 38:] == 0x5A5A5A5A).all()
+    planes1 = oracle.split_planes(buf[:, 1:K + 1].astype(np.int64), nbits)
+    want1 = np.stack([oracle.pack_bits(planes1[p].astype(np.int8)) for p in range(nbits)])
+    assert np.array_equal(host_u32(q.qnn_pack_bitplanes(dev(buf)[:, 1:K + 1], nbits)), want1)
+
+
 # ------------------------------------------------------------------ S4 threshold_sign
+@pytest.mark.parametrize("M,N", [(37, 256), (9, 260), (70, 1024), (33, 4100), (8, 512), (1, 300)])
+@pytest.mark.parametrize("with_flip", [False, True])
+def test_threshold_sign_wide_rows(seed, M, N, with_flip):
+    """N >= 256 and a multiple of 4 takes the 16-byte-load kernel: row counts that are not multiples of 8, a last
+    span of fewer than 256 neurons, sums equal to their threshold, extreme thresholds."""
+    Cm = qi.uniform_int(seed, 21, (M, N), -70, 70)
+    T = qi.uniform_int(seed, 22, (N,), -64, 64)
+    T[0], T[1], T[N - 1] = -(2**31), 2**31 - 1, -(2**31)
+    flip = qi.bernoulli_bits(seed, 23, (N,)) if with_flip else None
+    want = oracle.pack_bits(oracle.threshold(Cm, T, flip))
+    got = host_u32(q.qnn_threshold_sign(dev(Cm), dev(T), dev(flip) if with_flip else None))
+    assert np.array_equal(got, want)
+
+
+def test_threshold_sign_wide_rows_strided(seed):
+    M, N, ldc, ldo = 45, 520, 640, 20
+    buf = qi.uniform_int(seed, 24, (M, ldc), -70, 70)
+    T = qi.uniform_int(seed, 25, (N,), -64, 64)
+    flip = qi.bernoulli_bits(seed, 26, (N,))
+    out = torch.full((M, ldo), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    q.qnn_threshold_sign(dev(buf)[:, :N], dev(T), dev(flip), out=out[:, :17])
+    got = host_u32(out)
+    assert np.array_equal(got[:, :17], oracle.pack_bits(oracle.threshold(buf[:, :N], T, flip)))
+    assert (got[:, 17:] == 0x5A5A5A5A).all()
+    # one element off the 16-byte grid: the other kernel, same answer
+    got1 = host_u32(q.qnn_threshold_sign(dev(buf)[:, 1:N + 1], dev(T), dev(flip)))
+    assert np.array_equal(got1, oracle.pack_bits(oracle.threshold(buf[:, 1:N + 1], T, flip)))
+
+
 @pytest.mark.parametrize("M,N", [(1, 1), (3, 31), (5, 64), (17, 65), (40, 4096), (33, 1000)])
 @pytest.mark.parametrize("with_flip", [False, True])
 def test_threshold_sign(seed, M, N, with_flip):
