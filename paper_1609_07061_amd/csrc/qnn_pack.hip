@@ -174,6 +174,47 @@ __global__ __launch_bounds__(kBlock) void pack_bitplanes_vec4_kernel(const uint8
     }
 }
 
+// Rows of whole, 16-byte aligned groups of 16 codes: a lane owns 32 consecutive codes (two 16-byte loads), i.e. one
+// output word of every plane, so nothing crosses lanes and a wave stores 256 contiguous bytes per plane.  The four
+// bits of plane p in a dword sit at bits p, 8+p, 16+p, 24+p; OR-ing the dword with itself shifted left by 7 and the
+// result with itself shifted left by 14 brings them together at bits 21+p .. 24+p (every other copy falls outside
+// that window), from where a funnel shift appends them to the word: 5 full-rate instructions per dword and plane.
+__global__ __launch_bounds__(kBlock) void pack_bitplanes_word_kernel(const uint8_t *__restrict__ v, int64_t rows,
+                                                                     int64_t K, int64_t ldv, int nbits,
+                                                                     uint32_t *__restrict__ planes, int64_t ld,
+                                                                     int64_t plane_stride, int64_t chunks_per_row,
+                                                                     int64_t total_chunks) {
+    constexpr int kChunk = kWave * 32;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t Kw = (K + 31) / 32;
+    for (int64_t chunk = wave0; chunk < total_chunks; chunk += wave_stride) {
+        const int64_t r = chunk / chunks_per_row;
+        const int64_t k0 = (chunk - r * chunks_per_row) * kChunk;
+        const int64_t k = k0 + 32 * lane;
+        const uint8_t *src = v + r * ldv + k;
+        u32x4 lo = {0u, 0u, 0u, 0u}, hi = {0u, 0u, 0u, 0u};  // K is a multiple of 16: a half is all inside or outside
+        if (k < K) lo = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src));
+        if (k + 16 < K) hi = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(src + 16));
+        const uint32_t d[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        const int64_t w = k0 / 32 + lane;
+        for (int p = 0; p < nbits; ++p) {
+            const uint32_t mask = 0x01010101u << p;
+            const uint32_t sh = 21u + (uint32_t)p;
+            uint32_t acc = 0;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                uint32_t t = d[j] & mask;
+                t |= t << 7;
+                t |= t << 14;
+                acc = __builtin_amdgcn_alignbit(t >> sh, acc, 4);  // (acc >> 4) | (nibble << 28)
+            }
+            if (w < Kw) planes[p * plane_stride + r * ld + w] = acc;
+        }
+    }
+}
+
 // Threshold: one wave owns 64 consecutive neurons (their T and flip stay in registers) and walks down kRows rows.
 constexpr int kThreshRows = 16;
 __global__ __launch_bounds__(kBlock) void threshold_sign_kernel(const int32_t *__restrict__ C, int64_t ldc, int64_t M,
@@ -283,6 +324,13 @@ int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint3
 
 int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,
                           int64_t ld, int64_t plane_stride, hipStream_t s) {
+    if (K >= 1024 && K % 16 == 0 && ldv % 16 == 0 && reinterpret_cast<uintptr_t>(v) % 16 == 0) {
+        const int64_t cpr = ceil_div(K, (int64_t)2048);
+        const int64_t total = rows * cpr;
+        hipLaunchKernelGGL(pack_bitplanes_word_kernel, dim3(grid_for(total)), dim3(kBlock), 0, s, v, rows, K, ldv, nbits,
+                           planes, ld, plane_stride, cpr, total);
+        return check_launch("pack_bitplanes");
+    }
     if (K >= 512 && K % 4 == 0 && ldv % 4 == 0 && reinterpret_cast<uintptr_t>(v) % 4 == 0) {
         const bool big = K >= 2048;
         const int64_t cpr = ceil_div(K, (int64_t)(big ? 2048 : 1024));

@@ -108,10 +108,12 @@ def test_pack_bitplanes_twos_complement_codes(seed):
 
 
 @pytest.mark.parametrize("rows,K,nbits", [(5, 512, 8), (3, 784, 8), (9, 1028, 3), (7, 2048, 2), (4, 2052, 4),
-                                          (2, 4100, 1), (64, 8192, 8), (3, 786, 8), (2, 2049, 4)])
+                                          (2, 4100, 1), (64, 8192, 8), (3, 786, 8), (2, 2049, 4), (5, 1024, 8),
+                                          (3, 1040, 5), (6, 2064, 8), (2, 4112, 3), (9, 6160, 7)])
 def test_pack_bitplanes_long_rows(seed, rows, K, nbits):
-    """Rows of 512 codes and more made of whole aligned groups of four take the 4-byte-load kernel (1024- or
-    2048-code chunks, ragged last chunk); K = 786 and 2049 stay on the one-code-per-lane kernel."""
+    """Rows of 1024 codes and more made of whole aligned groups of 16 take the kernel in which a lane owns a whole
+    output word (K = 1024, 1040, 2048, 2064, 4112, 6160, 8192: half-used words, ragged last chunk); shorter ones and
+    multiples of 4 only the 4-byte-load kernel; K = 786 and 2049 stay on the one-code-per-lane kernel."""
     v = qi.uniform_int(seed, 19, (rows, K), 0, (1 << nbits) - 1)
     planes = oracle.split_planes(v, nbits)
     want = np.stack([oracle.pack_bits(planes[p].astype(np.int8)) for p in range(nbits)])
@@ -121,7 +123,7 @@ def test_pack_bitplanes_long_rows(seed, rows, K, nbits):
 def test_pack_bitplanes_long_rows_strided(seed):
     """4-byte-load kernel on a strided view with padded output planes: padding untouched; a view one byte off the
     4-byte grid gives the same through the other kernel."""
-    rows, K, ldv, nbits, ldo = 37, 1200, 1280, 8, 40
+    rows, K, ldv, nbits, ldo = 37, 1200, 1280, 8, 40  # 1200 = 16 * 75: the word-per-lane kernel; K + 4 below: 4-byte
     buf = qi.uniform_int(seed, 20, (rows, ldv), 0, 255).astype(np.uint8)
     out = torch.full((nbits, rows, ldo), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
     q.qnn_pack_bitplanes(dev(buf)[:, :K], nbits, out=out[:, :, :38])
@@ -130,6 +132,10 @@ def test_pack_bitplanes_long_rows_strided(seed):
     want = np.stack([oracle.pack_bits(planes[p].astype(np.int8)) for p in range(nbits)])
     assert np.array_equal(got[:, :, :38], want)
     assert (got[:, :, 38:] == 0x5A5A5A5A).all()
+    K4 = K + 4
+    planes4 = oracle.split_planes(buf[:, :K4].astype(np.int64), nbits)
+    want4 = np.stack([oracle.pack_bits(planes4[p].astype(np.int8)) for p in range(nbits)])
+    assert np.array_equal(host_u32(q.qnn_pack_bitplanes(dev(buf)[:, :K4], nbits)), want4)
     planes1 = oracle.split_planes(buf[:, 1:K + 1].astype(np.int64), nbits)
     want1 = np.stack([oracle.pack_bits(planes1[p].astype(np.int8)) for p in range(nbits)])
     assert np.array_equal(host_u32(q.qnn_pack_bitplanes(dev(buf)[:, 1:K + 1], nbits)), want1)
