@@ -339,19 +339,24 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         uint32_t ab_ones[2];               // 0x01010101 for a 16-byte half inside the row, else 0: row-sum multiplier
     };
     // words of slot t of a step, masks applied here, at the point of use, so that the loads stay in flight until now
-    auto prep = [&](const Step &c, int t, Words &o) __attribute__((always_inline)) {
+    // masked_tag: std::false_type where the caller knows that the step lies completely inside K (every step before the
+    // last two of a row of plain planes does), so the chunk masks are all ones and need not be applied.  Only the
+    // kernels with the threshold epilogue make use of it: they gain 2 %, while the int32 kernels, whose instruction
+    // mix the interleave pattern was tuned on, lose 4 % without the masks.
+    auto prep = [&](const Step &c, int t, Words &o, auto masked_tag) __attribute__((always_inline)) {
+        constexpr bool kMask = kChunk && (decltype(masked_tag)::value || kPixels || !kSign);
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
             for (int p = 0; p < PA; ++p)
-                o.a[b][p] = kBytesA ? 0u : (kChunk ? (c.A[b][p][t] & c.maskA[b]) : c.A[b][p][t]);
+                o.a[b][p] = kBytesA ? 0u : (kMask ? (c.A[b][p][t] & c.maskA[b]) : c.A[b][p][t]);
             if constexpr (kBytesA) {
 #pragma unroll
                 for (int i = 0; i < 8; ++i) o.ab[b][i] = c.Ab[b][i] ^ 0x80808080u;
                 o.ab_ones[0] = c.maskAb[0] & 0x01010101u, o.ab_ones[1] = c.maskAb[1] & 0x01010101u;
             }
 #pragma unroll
-            for (int p = 0; p < PW; ++p) o.w[b][p] = kChunk ? (c.W[b][p][t] & c.maskW) : c.W[b][p][t];
+            for (int p = 0; p < PW; ++p) o.w[b][p] = kMask ? (c.W[b][p][t] & c.maskW) : c.W[b][p][t];
         }
     };
     // row sums of the raw codes: popcounts of the words a phase consumes
@@ -436,7 +441,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     constexpr int kOpsFetch = 3 * WB * (kBytesA ? 3 : (PA + PW));
     // last_tag (std::true_type for the last step of a tile): the operands of the following step, which belongs to the
     // next tile, are then prepared after the epilogue instead, so that they do not occupy 40 registers during it.
-    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur, auto issue_loads, auto last_tag) __attribute__((always_inline)) {
+    // mask_cur / mask_next: whether step c / step n may reach past K (see prep)
+    auto compute = [&](const Step &c, const Step &n, Frags &f, Words &cur, auto issue_loads, auto last_tag, auto mask_cur,
+                       auto mask_next) __attribute__((always_inline)) {
         constexpr bool kLastStep = decltype(last_tag)::value;
 #pragma unroll
         for (int t = 0; t < WPL; ++t) {
@@ -447,10 +454,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                 Words nxt;
                 count(cur);
                 if (t + 1 < WPL) {
-                    prep(c, t + 1, nxt);
+                    prep(c, t + 1, nxt, mask_cur);
                     expand(nxt, 0, g);
                 } else if (!kLastStep) {
-                    prep(n, 0, nxt);
+                    prep(n, 0, nxt, mask_next);
                     expand(nxt, 0, g);
                 }
                 multiply(f);
@@ -474,10 +481,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
                 __builtin_amdgcn_sched_barrier(0);
                 // phase (t, 1): multiply, meanwhile fetch and expand the first half of the following slot
                 if (t + 1 < WPL) {
-                    prep(c, t + 1, cur);
+                    prep(c, t + 1, cur, mask_cur);
                     expand(cur, 0, f);
                 } else if (!kLastStep) {
-                    prep(n, 0, cur);
+                    prep(n, 0, cur, mask_next);
                     expand(cur, 0, f);
                 }
                 multiply(g);
@@ -686,7 +693,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
     uint32_t vb = blockIdx.x;
     locate(vb, cur);
     fetch(cur, 0, buf0);
-    prep(buf0, 0, words);
+    prep(buf0, 0, words, std::true_type{});
     expand(words, 0, frags);
 #ifdef QNN_MFMA_TRACE
     if (g_trace && threadIdx.x == 0) g_trace[(blockIdx.x * 8 + 7) * 8 + 7] = __builtin_amdgcn_s_memrealtime();
@@ -696,11 +703,16 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         clear();
         QNN_STAMP(1);
         for (uint32_t s = 0; s + 2 < mc.msteps; s += 2) {
-            compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 1, buf1); }, std::false_type{});
-            compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 2, buf0); }, std::false_type{});
+            // steps s and s + 1 lie inside K (only the last two steps of a row can reach past it); step s + 2, whose
+            // first operands the second call prepares, may be one of those two
+            compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 1, buf1); }, std::false_type{},
+                    std::false_type{}, std::false_type{});
+            compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, s + 2, buf0); }, std::false_type{},
+                    std::false_type{}, std::true_type{});
         }
         QNN_STAMP(2);
-        compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, mc.msteps - 1, buf1); }, std::false_type{});
+        compute(buf0, buf1, frags, words, [&]() __attribute__((always_inline)) { fetch(cur, mc.msteps - 1, buf1); }, std::false_type{},
+                std::true_type{}, std::true_type{});
         QNN_STAMP(3);
         // the operand rows of this tile are not needed any more: move on to the next tile's
         const int64_t m_done = cur.m_wave, n_done = cur.n_wave;
@@ -710,12 +722,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_mfma_kernel(const GemmArgs g
         compute(buf1, buf0, frags, words, [&]() __attribute__((always_inline)) {
             fetch(cur, 0, buf0);
             load_thresholds(n_done);  // for the epilogue that follows this step
-        }, std::true_type{});
+        }, std::true_type{}, std::true_type{}, std::true_type{});
         QNN_STAMP(4);
         finish(m_done, n_done);
         QNN_STAMP(5);
         // first operands of the next tile (its first step was loaded during the last step above)
-        prep(buf0, 0, words);
+        prep(buf0, 0, words, std::true_type{});
         expand(words, 0, frags);
 #ifdef QNN_MFMA_TRACE
         if (g_trace && threadIdx.x == 0 && trace_tile < 8)
