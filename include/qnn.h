@@ -106,7 +106,13 @@ int qnn_binary_gemm_sign(const uint32_t *A, int64_t lda_words, const uint32_t *W
 int qnn_bitplane_gemm(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
                       int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
                       int64_t ldw_words, int64_t strideW_words, int32_t *C, int64_t ldc, int64_t M, int64_t N,
-                      int64_t K, int engine, void *stream);
+                      int64_t K, void *stream);
+
+/* Same product with the engine chosen by the caller (for measurements and tests). */
+int qnn_bitplane_gemm_ex(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
+                         int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
+                         int64_t ldw_words, int64_t strideW_words, int32_t *C, int64_t ldc, int64_t M, int64_t N,
+                         int64_t K, int engine, void *stream);
 
 /* S3+S4 fused: the first layer of Alg. 4 (eight weighted plane products, then Sign(BatchNorm(.))), output packed. */
 int qnn_bitplane_gemm_sign(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
@@ -134,18 +140,26 @@ int qnn_fold_batchnorm(const double *gamma, const double *beta, const double *me
  * (With 8-bit inputs in 16-byte aligned rows the first layer may be evaluated as x . W_1 straight from the codes,
  * which Eq. (FirstLayer) states to be the same sum; the planes are then not materialised.  Only the low in_bits bits
  * of a code count.)
- * x: DEVICE uint8 [batch][ldx].  dims: HOST int64 [n_layers + 1] (dims[0] = input width).
+ * x: DEVICE uint8 [batch][in_dim], dense rows; in_dim must equal dims[0].
+ * dims: HOST int64 [n_layers + 1] (dims[0] = input width).
  * W: HOST array of n_layers DEVICE pointers, W[l] packed +-1 [dims[l+1]][ceil(dims[l]/32)] (dense rows).
  * T, flip: HOST arrays of n_layers - 1 DEVICE pointers (flip, or any flip[l], may be NULL).
  * logits: DEVICE int32 [batch][ld_logits].  workspace: DEVICE, 256-byte aligned, at least
  * qnn_binary_mlp_workspace_bytes(...) bytes, contents undefined before and after.
- * 2 <= n_layers <= QNN_MAX_LAYERS, 1 <= in_bits <= 8.  `engine` is a preference: a layer that the requested engine
- * cannot take runs on the library's choice. */
-int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers,
+ * 2 <= n_layers <= QNN_MAX_LAYERS, 1 <= in_bits <= 8.  Every layer is validated before the first launch, so an
+ * argument error enqueues nothing. */
+int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t in_dim, int in_bits, int n_layers,
                            const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
                            const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,
-                           size_t workspace_bytes, int engine, void *stream);
+                           size_t workspace_bytes, void *stream);
 size_t qnn_binary_mlp_workspace_bytes(int64_t batch, int in_bits, int n_layers, const int64_t *dims);
+
+/* Same forward pass with a row pitch for x (ldx >= dims[0], in bytes) and an engine preference: a layer that the
+ * requested engine cannot take runs on the library's choice. */
+int qnn_binary_mlp_forward_ex(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers,
+                              const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
+                              const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,
+                              size_t workspace_bytes, int engine, void *stream);
 
 /* Binarized convolution (Sec. 5 filter bank M_l x M_{l-1} x k x k; Sec. 3 multi-bit activations) without
  * materialising patches.  Activations: Pa bit planes, channels-last and packed along channels:
@@ -153,15 +167,26 @@ size_t qnn_binary_mlp_workspace_bytes(int64_t batch, int in_bits, int n_layers, 
  * Weights: Pb planes, filter co is [KH][KW][Cw] words at W + j * strideW_words + co * KH*KW*Cw.
  * Output: DEVICE int32 [B][Ho][Wo][Cout] dense, Ho = (H + 2 pad - KH) / stride + 1.
  * Padding pixels contribute exactly 0, which a bit-mode activation encodes as all-zero bits; a sign-mode activation
- * cannot encode 0, so modeA == QNN_PLANE_SIGN with pad > 0 is QNN_ERR_UNSUPPORTED. */
+ * cannot encode 0, so modeA == QNN_PLANE_SIGN with pad > 0 is QNN_ERR_UNSUPPORTED.
+ * H, Wd, pad, stride <= 32767; KH, KW <= 255. */
 int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
                         int64_t B, int64_t H, int64_t Wd, int64_t Cin, const uint32_t *W, int Pb,
                         const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
-                        int pad, int stride_hw, int32_t *out, int engine, void *stream);
+                        int pad, int stride_hw, int32_t *out, void *stream);
+
+/* Same convolution with the engine chosen by the caller (for measurements and tests). */
+int qnn_bitplane_conv2d_ex(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
+                           int64_t B, int64_t H, int64_t Wd, int64_t Cin, const uint32_t *W, int Pb,
+                           const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
+                           int pad, int stride_hw, int32_t *out, int engine, void *stream);
 
 /* Engine (QNN_ENGINE_VALU, QNN_ENGINE_MFMA or QNN_ENGINE_MFMA_FP4) that the calling thread's last successful multiply call used; 0 before
  * any.  For reports: results never depend on it. */
 int qnn_last_engine(void);
+
+/* Engines of the multiply launches made by the calling thread's last successful multiply / forward call, in launch
+ * order (one entry per layer for the forward calls): writes min(count, capacity) entries, returns the count. */
+int qnn_last_engines(int *engines, int capacity);
 
 const char *qnn_last_error(void);
 const char *qnn_version(void);

@@ -21,7 +21,7 @@ LIB_PATH = os.path.join(_HERE, "libqnn.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
-        f"{LIB_PATH} is missing: build it first with `python -m paper_1609_07061_amd.build` "
+        f"{LIB_PATH} is missing: build it first with `python paper_1609_07061_amd/build.py` "
         "(or __graft_entry__.build()); this package has no fallback path"
     )
 _lib = C.CDLL(LIB_PATH)
@@ -34,14 +34,19 @@ _SIGS = {
     "qnn_binary_gemm_ex": [_vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64, _int, _vp],
     "qnn_binary_gemm_sign": [_vp, _i64, _vp, _i64, _vp, _vp, _vp, _i64, _i64, _i64, _i64, _int, _vp],
     "qnn_bitplane_gemm": [_vp, _int, _vp, _int, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _vp, _i64, _i64, _i64,
-                          _i64, _int, _vp],
+                          _i64, _vp],
+    "qnn_bitplane_gemm_ex": [_vp, _int, _vp, _int, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _vp, _i64, _i64, _i64,
+                             _i64, _int, _vp],
     "qnn_bitplane_gemm_sign": [_vp, _int, _vp, _int, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _vp, _vp, _vp, _i64,
                                _i64, _i64, _i64, _int, _vp],
     "qnn_threshold_sign": [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _vp],
     "qnn_fold_batchnorm": [_vp, _vp, _vp, _vp, C.c_double, _i64, _vp, _vp],
-    "qnn_binary_mlp_forward": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _int, _vp],
+    "qnn_binary_mlp_forward": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp],
+    "qnn_binary_mlp_forward_ex": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _int, _vp],
     "qnn_bitplane_conv2d": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
-                            _int, _int, _int, _vp, _int, _vp],
+                            _int, _int, _int, _vp, _vp],
+    "qnn_bitplane_conv2d_ex": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
+                               _int, _int, _int, _vp, _int, _vp],
 }
 for _name, _args in _SIGS.items():
     _f = getattr(_lib, _name)
@@ -53,7 +58,11 @@ _lib.qnn_last_engine.restype = C.c_int
 _lib.qnn_last_error.restype = C.c_char_p
 _lib.qnn_version.restype = C.c_char_p
 
-EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_last_engine", "qnn_last_error", "qnn_version"])
+_lib.qnn_last_engines.argtypes = [_vp, _int]
+_lib.qnn_last_engines.restype = C.c_int
+
+EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_last_engine",
+                               "qnn_last_engines", "qnn_last_error", "qnn_version"])
 
 
 class QnnError(RuntimeError):
@@ -108,6 +117,12 @@ def words_for(K: int) -> int:
 
 def qnn_last_engine() -> int:
     return int(_lib.qnn_last_engine())
+
+
+def qnn_last_engines() -> list:
+    buf = (C.c_int * 32)()
+    n = int(_lib.qnn_last_engines(buf, 32))
+    return [int(buf[i]) for i in range(min(n, 32))]
 
 
 def qnn_version() -> str:
@@ -165,7 +180,9 @@ def qnn_binary_gemm_sign(A: torch.Tensor, W: torch.Tensor, K: int, T: torch.Tens
 
 
 def qnn_bitplane_gemm(A: torch.Tensor, coefA: Sequence[int], modeA: int, W: torch.Tensor, coefW: Sequence[int],
-                      modeW: int, K: int, out: Optional[torch.Tensor] = None, engine: int = ENGINE_AUTO) -> torch.Tensor:
+                      modeW: int, K: int, out: Optional[torch.Tensor] = None,
+                      engine: Optional[int] = None) -> torch.Tensor:
+    """engine None -> qnn_bitplane_gemm; an engine -> qnn_bitplane_gemm_ex."""
     Pa, M, _, lda, sa = _planes_ld(A, "A")
     Pb, N, _, ldw, sw = _planes_ld(W, "W")
     if len(coefA) != Pa or len(coefW) != Pb:
@@ -173,9 +190,12 @@ def qnn_bitplane_gemm(A: torch.Tensor, coefA: Sequence[int], modeA: int, W: torc
     if out is None:
         out = torch.empty((M, N), dtype=torch.int32, device=A.device)
     _, _, ldc = _rows_ld(out, "out")
-    _check(_lib.qnn_bitplane_gemm(_dev(A, torch.int32, "A"), Pa, _coef(coefA), modeA, lda, sa,
-                                  _dev(W, torch.int32, "W"), Pb, _coef(coefW), modeW, ldw, sw,
-                                  _dev(out, torch.int32, "out"), ldc, M, N, K, engine, _stream()))
+    args = (_dev(A, torch.int32, "A"), Pa, _coef(coefA), modeA, lda, sa, _dev(W, torch.int32, "W"), Pb, _coef(coefW),
+            modeW, ldw, sw, _dev(out, torch.int32, "out"), ldc, M, N, K)
+    if engine is None:
+        _check(_lib.qnn_bitplane_gemm(*args, _stream()))
+    else:
+        _check(_lib.qnn_bitplane_gemm_ex(*args, engine, _stream()))
     return out
 
 
@@ -228,7 +248,8 @@ def qnn_binary_mlp_workspace_bytes(batch: int, in_bits: int, dims: Sequence[int]
 def qnn_binary_mlp_forward(x: torch.Tensor, in_bits: int, dims: Sequence[int], W: Sequence[torch.Tensor],
                            T: Sequence[torch.Tensor], flip: Optional[Sequence[Optional[torch.Tensor]]] = None,
                            logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                           engine: int = ENGINE_AUTO) -> torch.Tensor:
+                           engine: Optional[int] = None) -> torch.Tensor:
+    """engine None and dense x -> qnn_binary_mlp_forward; an engine or a strided x -> qnn_binary_mlp_forward_ex."""
     batch, _, ldx = _rows_ld(x, "x")
     L = len(dims) - 1
     if len(W) != L or len(T) != L - 1:
@@ -239,24 +260,26 @@ def qnn_binary_mlp_forward(x: torch.Tensor, in_bits: int, dims: Sequence[int], W
     if logits is None:
         logits = torch.empty((batch, dims[-1]), dtype=torch.int32, device=x.device)
     _, _, ldl = _rows_ld(logits, "logits")
-    need = qnn_binary_mlp_workspace_bytes(batch, in_bits, dims)
-    if workspace is None:
-        workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
     d = (C.c_int64 * (L + 1))(*[int(v) for v in dims])
     Wp = (C.c_void_p * L)(*[_dev(w, torch.int32, "W") for w in W])
     Tp = (C.c_void_p * max(L - 1, 1))(*[_dev(t, torch.int32, "T") for t in T])
     Fp = None
     if flip is not None:
         Fp = (C.c_void_p * max(L - 1, 1))(*[_dev(f, torch.uint8, "flip") for f in flip])
-    _check(_lib.qnn_binary_mlp_forward(_dev(x, torch.uint8, "x"), batch, ldx, in_bits, L, d, Wp, Tp, Fp,
-                                       _dev(logits, torch.int32, "logits"), ldl,
-                                       _dev(workspace, torch.uint8, "workspace"), workspace.numel(), engine, _stream()))
+    head = (_dev(x, torch.uint8, "x"), batch, ldx, in_bits, L, d, Wp, Tp, Fp, _dev(logits, torch.int32, "logits"), ldl)
+    if workspace is None:
+        workspace = torch.empty(qnn_binary_mlp_workspace_bytes(batch, in_bits, dims), dtype=torch.uint8, device=x.device)
+    ws = (_dev(workspace, torch.uint8, "workspace"), workspace.numel())
+    if engine is None and ldx == dims[0]:
+        _check(_lib.qnn_binary_mlp_forward(*head, *ws, _stream()))
+    else:
+        _check(_lib.qnn_binary_mlp_forward_ex(*head, *ws, ENGINE_AUTO if engine is None else engine, _stream()))
     return logits
 
 
 def qnn_bitplane_conv2d(A: torch.Tensor, coefA: Sequence[int], modeA: int, Cin: int, W: torch.Tensor,
                         coefW: Sequence[int], modeW: int, pad: int, stride: int = 1,
-                        out: Optional[torch.Tensor] = None, engine: int = ENGINE_AUTO) -> torch.Tensor:
+                        out: Optional[torch.Tensor] = None, engine: Optional[int] = None) -> torch.Tensor:
     """A: [Pa][B][H][W][Cw] packed planes (dense); W: [Pb][Cout][KH][KW][Cw] packed planes (dense)."""
     if A.dim() != 5 or W.dim() != 5 or not A.is_contiguous() or not W.is_contiguous():
         raise ValueError("A must be dense [Pa][B][H][W][Cw] and W dense [Pb][Cout][KH][KW][Cw]")
@@ -270,8 +293,11 @@ def qnn_bitplane_conv2d(A: torch.Tensor, coefA: Sequence[int], modeA: int, Cin: 
         out = torch.empty((B, Ho, Wo, Cout), dtype=torch.int32, device=A.device)
     if not out.is_contiguous() or tuple(out.shape) != (B, Ho, Wo, Cout):
         raise ValueError("out must be dense [B][Ho][Wo][Cout]")
-    _check(_lib.qnn_bitplane_conv2d(_dev(A, torch.int32, "A"), Pa, _coef(coefA), modeA, A.stride(0) if Pa > 1 else 0,
-                                    B, H, Wd, Cin, _dev(W, torch.int32, "W"), Pb, _coef(coefW), modeW,
-                                    W.stride(0) if Pb > 1 else 0, Cout, KH, KW, pad, stride,
-                                    _dev(out, torch.int32, "out"), engine, _stream()))
+    args = (_dev(A, torch.int32, "A"), Pa, _coef(coefA), modeA, A.stride(0) if Pa > 1 else 0, B, H, Wd, Cin,
+            _dev(W, torch.int32, "W"), Pb, _coef(coefW), modeW, W.stride(0) if Pb > 1 else 0, Cout, KH, KW, pad, stride,
+            _dev(out, torch.int32, "out"))
+    if engine is None:
+        _check(_lib.qnn_bitplane_conv2d(*args, _stream()))
+    else:
+        _check(_lib.qnn_bitplane_conv2d_ex(*args, engine, _stream()))
     return out

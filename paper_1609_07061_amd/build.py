@@ -11,7 +11,8 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libqnn.so")
-SOURCES = ["qnn_api.hip", "qnn_pack.hip", "qnn_gemm_valu.hip", "qnn_gemm_mfma.hip"]
+SOURCES = ["qnn_api.hip", "qnn_pack.hip", "qnn_gemm_valu.hip", "qnn_gemm_mfma.hip", "qnn_gemm_mfma_k0.hip",
+           "qnn_gemm_mfma_k1.hip", "qnn_gemm_mfma_k2.hip", "qnn_gemm_mfma_k3.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-ffp-contract=off",
@@ -50,7 +51,7 @@ def build(force: bool = False, verbose: bool = False) -> str:
             raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + r.stdout + r.stderr)
         return r.stderr
 
-    with ThreadPoolExecutor(max_workers=min(4, max(1, len(jobs)))) as ex:
+    with ThreadPoolExecutor(max_workers=min(8, max(1, len(jobs)))) as ex:
         for err in ex.map(run, jobs):
             if verbose and err.strip():
                 print(err, file=sys.stderr)

@@ -12,6 +12,9 @@ namespace qnn {
 
 static thread_local char g_err[512] = "";
 static thread_local int g_last_engine = 0;
+// engines of the multiply launches of the calling thread's last entry-point call, in launch order
+static thread_local int g_engines[QNN_MAX_LAYERS];
+static thread_local int g_engine_count = 0;
 
 int fail(int code, const char *fmt, ...) {
     va_list ap;
@@ -60,8 +63,9 @@ int check_range(const GemmArgs &g) {
     return QNN_OK;
 }
 
-int dispatch(const GemmArgs &g, int engine, hipStream_t s) {
-    int chosen = engine;
+// Which engine runs the product: QNN_OK and `chosen`, or QNN_ERR_UNSUPPORTED when the requested engine cannot take it.
+int resolve_engine(const GemmArgs &g, int engine, int &chosen) {
+    chosen = engine;
     if (engine == QNN_ENGINE_MFMA_FP4 && !mfma_supports(g, true))
         return fail(QNN_ERR_UNSUPPORTED, "FP4 matrix-core engine takes single-plane operands of supported shapes only");
     if (engine == QNN_ENGINE_MFMA && !mfma_supports(g))
@@ -74,15 +78,37 @@ int dispatch(const GemmArgs &g, int engine, hipStream_t s) {
         else
             chosen = QNN_ENGINE_VALU;
     }
+    if (chosen == QNN_ENGINE_VALU && !valu_supports(g)) {
+        // the vector-ALU engine takes everything except a byte-coded left operand
+        if (engine == QNN_ENGINE_AUTO && mfma_supports(g))
+            chosen = QNN_ENGINE_MFMA;
+        else
+            return fail(QNN_ERR_UNSUPPORTED, "vector-ALU engine cannot take these arguments");
+    }
+    return QNN_OK;
+}
+
+int launch_on(const GemmArgs &g, int chosen, hipStream_t s) {
     const int rc = chosen == QNN_ENGINE_VALU ? launch_gemm_valu(g, s) : launch_gemm_mfma(g, s, chosen == QNN_ENGINE_MFMA_FP4);
-    if (rc == QNN_OK) g_last_engine = chosen;
+    if (rc == QNN_OK) {
+        g_last_engine = chosen;
+        if (g_engine_count < QNN_MAX_LAYERS) g_engines[g_engine_count++] = chosen;
+    }
     return rc;
 }
 
-// Shared validation + launch of the matrix-shaped products.
-int gemm_common(const char *who, const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda,
-                int64_t strideA, const uint32_t *W, int Pb, const int32_t *coefW, int modeW, int64_t ldw,
-                int64_t strideW, const Epilogue &epi, int64_t M, int64_t N, int64_t K, int engine, void *stream) {
+int dispatch(const GemmArgs &g, int engine, hipStream_t s) {
+    int chosen;
+    g_engine_count = 0;
+    if (int rc = resolve_engine(g, engine, chosen)) return rc;
+    return launch_on(g, chosen, s);
+}
+
+// Shared validation of the matrix-shaped products; fills `g`.  `empty` = a successful no-op (M == 0 or N == 0).
+int gemm_args(const char *who, const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda, int64_t strideA,
+              const uint32_t *W, int Pb, const int32_t *coefW, int modeW, int64_t ldw, int64_t strideW,
+              const Epilogue &epi, int64_t M, int64_t N, int64_t K, int engine, GemmArgs &g, bool &empty) {
+    empty = false;
     if (int rc = check_engine(engine)) return rc;
     if (M < 0 || N < 0) return fail(QNN_ERR_SHAPE, "%s: negative M or N", who);
     if (K < 1 || K > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "%s: K = %lld out of range", who, (long long)K);
@@ -92,17 +118,20 @@ int gemm_common(const char *who, const uint32_t *A, int Pa, const int32_t *coefA
     if (lda < Kw || ldw < Kw) return fail(QNN_ERR_SHAPE, "%s: leading dimension below ceil(K/32) = %lld", who, (long long)Kw);
     if (Pa > 1 && strideA < 0) return fail(QNN_ERR_SHAPE, "%s: negative plane stride", who);
     if (Pb > 1 && strideW < 0) return fail(QNN_ERR_SHAPE, "%s: negative plane stride", who);
-    if (epi.T) {
+    if (epi.T || epi.out_bits) {
         if (epi.ldo < words_for(N)) return fail(QNN_ERR_SHAPE, "%s: ldo_words below ceil(N/32)", who);
     } else {
         if (epi.ldc < N) return fail(QNN_ERR_SHAPE, "%s: ldc below N", who);
     }
-    if (M == 0 || N == 0) return QNN_OK;
+    if (M == 0 || N == 0) {
+        empty = true;
+        return QNN_OK;
+    }
     if (!A || !W) return fail(QNN_ERR_NULL, "%s: operand pointer is NULL", who);
+    if (epi.out_bits && !epi.T) return fail(QNN_ERR_NULL, "%s: threshold pointer is NULL", who);
     if (epi.T ? !epi.out_bits : !epi.C) return fail(QNN_ERR_NULL, "%s: output pointer is NULL", who);
     if (!aligned4(A) || !aligned4(W) || !aligned4(epi.C) || !aligned4(epi.out_bits) || !aligned4(epi.T))
         return fail(QNN_ERR_ALIGN, "%s: pointer not 4-byte aligned", who);
-    GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     g.A.base = A;
     g.A.ld = lda;
@@ -121,7 +150,18 @@ int gemm_common(const char *who, const uint32_t *A, int Pa, const int32_t *coefA
     g.N = N;
     g.K = K;
     g.Kw = Kw;
-    if (int rc = check_range(g)) return rc;
+    return check_range(g);
+}
+
+int gemm_common(const char *who, const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda,
+                int64_t strideA, const uint32_t *W, int Pb, const int32_t *coefW, int modeW, int64_t ldw,
+                int64_t strideW, const Epilogue &epi, int64_t M, int64_t N, int64_t K, int engine, void *stream) {
+    GemmArgs g;
+    bool empty;
+    if (int rc = gemm_args(who, A, Pa, coefA, modeA, lda, strideA, W, Pb, coefW, modeW, ldw, strideW, epi, M, N, K, engine,
+                           g, empty))
+        return rc;
+    if (empty) return QNN_OK;
     return dispatch(g, engine, static_cast<hipStream_t>(stream));
 }
 
@@ -178,13 +218,21 @@ int qnn_binary_gemm_sign(const uint32_t *A, int64_t lda_words, const uint32_t *W
                        ldw_words, 0, e, M, N, K, engine, stream);
 }
 
-int qnn_bitplane_gemm(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
-                      int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
-                      int64_t ldw_words, int64_t strideW_words, int32_t *C, int64_t ldc, int64_t M, int64_t N,
-                      int64_t K, int engine, void *stream) {
+int qnn_bitplane_gemm_ex(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
+                         int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
+                         int64_t ldw_words, int64_t strideW_words, int32_t *C, int64_t ldc, int64_t M, int64_t N,
+                         int64_t K, int engine, void *stream) {
     Epilogue e{C, ldc, nullptr, nullptr, nullptr, 0};
     return gemm_common("bitplane_gemm", A, Pa, coefA, modeA, lda_words, strideA_words, W, Pb, coefW, modeW, ldw_words,
                        strideW_words, e, M, N, K, engine, stream);
+}
+
+int qnn_bitplane_gemm(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
+                      int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
+                      int64_t ldw_words, int64_t strideW_words, int32_t *C, int64_t ldc, int64_t M, int64_t N,
+                      int64_t K, void *stream) {
+    return qnn_bitplane_gemm_ex(A, Pa, coefA, modeA, lda_words, strideA_words, W, Pb, coefW, modeW, ldw_words,
+                                strideW_words, C, ldc, M, N, K, QNN_ENGINE_AUTO, stream);
 }
 
 int qnn_bitplane_gemm_sign(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
@@ -261,10 +309,26 @@ size_t qnn_binary_mlp_workspace_bytes(int64_t batch, int in_bits, int n_layers, 
     return planes + 2 * act + 256;
 }
 
-int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers,
-                           const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
-                           const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,
-                           size_t workspace_bytes, int engine, void *stream) {
+// Alg. 4 as a list of launches, every one validated (pointers, ranges, engine) before the first is enqueued.
+namespace {
+struct MlpPlan {
+    bool pack_planes;  // the input planes are materialised (otherwise the first layer reads the 8-bit codes)
+    const uint8_t *x;
+    int64_t batch, in_dim, ldx, ld0, plane_stride;
+    int in_bits;
+    uint32_t *planes;
+    int n;
+    GemmArgs g[QNN_MAX_LAYERS];
+    int engine[QNN_MAX_LAYERS];
+};
+
+int64_t mlp_ldw(int64_t d) { return (words_for(d) + 3) & ~(int64_t)3; }
+size_t round256(size_t b) { return (b + 255) & ~(size_t)255; }
+
+int plan_mlp(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers, const int64_t *dims,
+             const uint32_t *const *W, const int32_t *const *T, const uint8_t *const *flip, int32_t *logits,
+             int64_t ld_logits, void *workspace, size_t workspace_bytes, int engine, MlpPlan &plan, bool &empty) {
+    empty = false;
     if (int rc = check_engine(engine)) return rc;
     if (batch < 0) return fail(QNN_ERR_SHAPE, "mlp: negative batch");
     if (in_bits < 1 || in_bits > 8) return fail(QNN_ERR_SHAPE, "mlp: in_bits = %d not in 1..8", in_bits);
@@ -273,7 +337,10 @@ int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_
     for (int l = 0; l <= n_layers; ++l)
         if (dims[l] < 1 || dims[l] > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "mlp: dims[%d] = %lld", l, (long long)dims[l]);
     if (ldx < dims[0] || ld_logits < dims[n_layers]) return fail(QNN_ERR_SHAPE, "mlp: leading dimension too small");
-    if (batch == 0) return QNN_OK;
+    if (batch == 0) {
+        empty = true;
+        return QNN_OK;
+    }
     if (!x || !logits) return fail(QNN_ERR_NULL, "mlp: x or logits is NULL");
     for (int l = 0; l < n_layers; ++l) {
         if (!W[l]) return fail(QNN_ERR_NULL, "mlp: W[%d] is NULL", l);
@@ -283,28 +350,36 @@ int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_
     if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
         return fail(QNN_ERR_WORKSPACE, "mlp: workspace must be 256-byte aligned and hold %zu bytes", need);
 
-    auto round256 = [](size_t b) { return (b + 255) & ~(size_t)255; };
-    auto ldw = [](int64_t d) { return (int64_t)((words_for(d) + 3) & ~(int64_t)3); };
     uint8_t *ws = static_cast<uint8_t *>(workspace);
-    uint32_t *planes = reinterpret_cast<uint32_t *>(ws);
-    const int64_t ld0 = ldw(dims[0]);
-    const int64_t plane_stride = batch * ld0;
-    size_t off = round256((size_t)in_bits * (size_t)plane_stride * 4);
+    plan.x = x, plan.batch = batch, plan.in_dim = dims[0], plan.ldx = ldx, plan.in_bits = in_bits;
+    plan.planes = reinterpret_cast<uint32_t *>(ws);
+    plan.ld0 = mlp_ldw(dims[0]);
+    plan.plane_stride = batch * plan.ld0;
+    plan.n = n_layers;
+    const size_t off = round256((size_t)in_bits * (size_t)plan.plane_stride * 4);
     size_t act_bytes = 0;
     for (int l = 1; l < n_layers; ++l) {
-        size_t b = round256((size_t)batch * (size_t)ldw(dims[l]) * 4);
+        const size_t b = round256((size_t)batch * (size_t)mlp_ldw(dims[l]) * 4);
         if (b > act_bytes) act_bytes = b;
     }
     uint32_t *act[2] = {reinterpret_cast<uint32_t *>(ws + off), reinterpret_cast<uint32_t *>(ws + off + act_bytes)};
 
-    // Alg. 4, step 1: s = sum_n 2^(n-1) (x^n . W_1), followed by Sign(BatchNorm).  By Eq. (FirstLayer) that sum IS
-    // x . W_1 on the 8-bit codes, and the matrix-core engine can take the codes as they are (x - 128 is an int8
-    // operand): no planes are materialised then.  Otherwise: planes, then the weighted plane products.
+    // `engine` is a preference: a layer that the requested engine cannot take runs on the library's choice.
+    auto choose = [&](const GemmArgs &g, int &chosen) {
+        int rc = resolve_engine(g, engine, chosen);
+        if (rc == QNN_ERR_UNSUPPORTED && engine != QNN_ENGINE_AUTO) rc = resolve_engine(g, QNN_ENGINE_AUTO, chosen);
+        return rc;
+    };
+
+    // Step 1 of Alg. 4: s = sum_n 2^(n-1) (x^n . W_1), then Sign(BatchNorm).  By Eq. (FirstLayer) that sum IS x . W_1
+    // on the 8-bit codes, and the matrix-core engine can take the codes as they are (x - 128 is an int8 operand): no
+    // planes are materialised then.  Otherwise: planes, then the weighted plane products.
     int32_t coef[QNN_MAX_PLANES];
     for (int p = 0; p < in_bits; ++p) coef[p] = 1 << p;
-    bool first_done = false;
+    const Epilogue e0{nullptr, 0, T[0], flip ? flip[0] : nullptr, act[0], mlp_ldw(dims[1])};
+    plan.pack_planes = true;
     if (in_bits == 8 && engine != QNN_ENGINE_VALU) {
-        GemmArgs g;
+        GemmArgs &g = plan.g[0];
         std::memset(&g, 0, sizeof(g));
         g.A.base = reinterpret_cast<const uint32_t *>(x);
         g.A.ld = ldx;
@@ -314,71 +389,104 @@ int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t ldx, int in_
         g.W = W[0];
         g.ldw = words_for(dims[0]);
         g.pw.count = 1, g.pw.mode = QNN_PLANE_SIGN, g.pw.coef[0] = 1;
-        g.epi = Epilogue{nullptr, 0, T[0], flip ? flip[0] : nullptr, act[0], ldw(dims[1])};
+        g.epi = e0;
         g.M = batch, g.N = dims[1], g.K = dims[0], g.Kw = words_for(dims[0]);
         if (int rc = check_range(g)) return rc;
         if (mfma_supports(g) && (engine != QNN_ENGINE_AUTO || mfma_preferred(g))) {
             if (!aligned4(W[0]) || !aligned4(T[0])) return fail(QNN_ERR_ALIGN, "mlp: pointer not 4-byte aligned");
-            if (int rc = launch_gemm_mfma(g, static_cast<hipStream_t>(stream))) return rc;
-            first_done = true;
+            plan.engine[0] = QNN_ENGINE_MFMA;
+            plan.pack_planes = false;
         }
     }
-    // `engine` is a preference here: a layer whose product the requested engine cannot take runs on the library's
-    // choice instead (a refusal enqueues nothing, so the retry is clean).
-    auto with_fallback = [&](auto &&call) {
-        int rc = call(engine);
-        if (rc == QNN_ERR_UNSUPPORTED && engine != QNN_ENGINE_AUTO) rc = call((int)QNN_ENGINE_AUTO);
-        return rc;
-    };
-    if (!first_done) {
-        if (int rc = qnn_pack_bitplanes(x, batch, dims[0], ldx, in_bits, planes, ld0, plane_stride, stream)) return rc;
-        if (int rc = with_fallback([&](int e) {
-                return qnn_bitplane_gemm_sign(planes, in_bits, coef, QNN_PLANE_BIT, ld0, plane_stride, W[0], 1, kOne,
-                                              QNN_PLANE_SIGN, words_for(dims[0]), 0, T[0], flip ? flip[0] : nullptr,
-                                              act[0], ldw(dims[1]), batch, dims[1], dims[0], e, stream);
-            }))
+    bool none;
+    if (plan.pack_planes) {
+        if (!aligned4(plan.planes)) return fail(QNN_ERR_ALIGN, "mlp: workspace not 4-byte aligned");
+        if (int rc = gemm_args("mlp layer 1", plan.planes, in_bits, coef, QNN_PLANE_BIT, plan.ld0, plan.plane_stride, W[0],
+                               1, kOne, QNN_PLANE_SIGN, words_for(dims[0]), 0, e0, batch, dims[1], dims[0], engine,
+                               plan.g[0], none))
             return rc;
+        if (int rc = choose(plan.g[0], plan.engine[0])) return rc;
     }
-    // step 2: hidden layers, product + threshold fused
+    // step 2: hidden layers, product + threshold fused; step 3: output layer, integer sums
     int cur = 0;
-    for (int l = 1; l < n_layers - 1; ++l) {
-        if (int rc = with_fallback([&](int e) {
-                return qnn_binary_gemm_sign(act[cur], ldw(dims[l]), W[l], words_for(dims[l]), T[l],
-                                            flip ? flip[l] : nullptr, act[cur ^ 1], ldw(dims[l + 1]), batch,
-                                            dims[l + 1], dims[l], e, stream);
-            }))
+    for (int l = 1; l < n_layers; ++l) {
+        const bool last = l == n_layers - 1;
+        const Epilogue e = last ? Epilogue{logits, ld_logits, nullptr, nullptr, nullptr, 0}
+                                : Epilogue{nullptr, 0, T[l], flip ? flip[l] : nullptr, act[cur ^ 1], mlp_ldw(dims[l + 1])};
+        if (int rc = gemm_args("mlp layer", act[cur], 1, kOne, QNN_PLANE_SIGN, mlp_ldw(dims[l]), 0, W[l], 1, kOne,
+                               QNN_PLANE_SIGN, words_for(dims[l]), 0, e, batch, dims[l + 1], dims[l], engine, plan.g[l],
+                               none))
             return rc;
+        if (int rc = choose(plan.g[l], plan.engine[l])) return rc;
         cur ^= 1;
     }
-    // step 3: output layer, integer sums
-    const int L = n_layers - 1;
-    return with_fallback([&](int e) {
-        return qnn_binary_gemm_ex(act[cur], ldw(dims[L]), W[L], words_for(dims[L]), logits, ld_logits, batch,
-                                  dims[L + 1], dims[L], e, stream);
-    });
+    return QNN_OK;
 }
 
-int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
-                        int64_t B, int64_t H, int64_t Wd, int64_t Cin, const uint32_t *W, int Pb,
-                        const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
-                        int pad, int stride_hw, int32_t *out, int engine, void *stream) {
+int run_mlp(const MlpPlan &plan, hipStream_t s) {
+    g_engine_count = 0;
+    if (plan.pack_planes)
+        if (int rc = launch_pack_bitplanes(plan.x, plan.batch, plan.in_dim, plan.ldx, plan.in_bits, plan.planes, plan.ld0,
+                                           plan.plane_stride, s))
+            return rc;
+    for (int l = 0; l < plan.n; ++l)
+        if (int rc = launch_on(plan.g[l], plan.engine[l], s)) return rc;
+    return QNN_OK;
+}
+
+}  // namespace
+
+int qnn_binary_mlp_forward_ex(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers,
+                              const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
+                              const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,
+                              size_t workspace_bytes, int engine, void *stream) {
+    MlpPlan plan;
+    bool empty;
+    if (int rc = plan_mlp(x, batch, ldx, in_bits, n_layers, dims, W, T, flip, logits, ld_logits, workspace,
+                          workspace_bytes, engine, plan, empty))
+        return rc;
+    if (empty) return QNN_OK;
+    return run_mlp(plan, static_cast<hipStream_t>(stream));
+}
+
+int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t in_dim, int in_bits, int n_layers,
+                           const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
+                           const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,
+                           size_t workspace_bytes, void *stream) {
+    if (dims && in_dim != dims[0]) return fail(QNN_ERR_SHAPE, "mlp: in_dim = %lld differs from dims[0]", (long long)in_dim);
+    return qnn_binary_mlp_forward_ex(x, batch, in_dim, in_bits, n_layers, dims, W, T, flip, logits, ld_logits, workspace,
+                                     workspace_bytes, QNN_ENGINE_AUTO, stream);
+}
+
+namespace {
+int conv_args(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words, int64_t B, int64_t H,
+              int64_t Wd, int64_t Cin, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
+              int64_t strideW_words, int64_t Cout, int KH, int KW, int pad, int stride_hw, const Epilogue &epi,
+              int engine, GemmArgs &g, bool &empty) {
+    empty = false;
     if (int rc = check_engine(engine)) return rc;
     if (B < 0 || Cout < 0) return fail(QNN_ERR_SHAPE, "conv2d: negative batch or Cout");
     if (H < 1 || Wd < 1 || Cin < 1 || KH < 1 || KW < 1 || pad < 0 || stride_hw < 1)
         return fail(QNN_ERR_SHAPE, "conv2d: bad geometry");
-    if (H > 32767 || Wd > 32767 || KH > 255 || KW > 255 || Cin > (1 << 24))
+    if (H > 32767 || Wd > 32767 || KH > 255 || KW > 255 || Cin > (1 << 24) || pad > 32767 || stride_hw > 32767)
         return fail(QNN_ERR_SHAPE, "conv2d: geometry beyond supported range");
     if (H + 2 * (int64_t)pad < KH || Wd + 2 * (int64_t)pad < KW) return fail(QNN_ERR_SHAPE, "conv2d: kernel larger than padded image");
     if (int rc = check_planes("conv2d", Pa, coefA, modeA)) return rc;
     if (int rc = check_planes("conv2d", Pb, coefW, modeW)) return rc;
     if (modeA == QNN_PLANE_SIGN && pad > 0)
         return fail(QNN_ERR_UNSUPPORTED, "conv2d: zero padding cannot be encoded in a sign-mode activation plane");
-    if (B == 0 || Cout == 0) return QNN_OK;
-    if (!A || !W || !out) return fail(QNN_ERR_NULL, "conv2d: NULL pointer");
-    if (!aligned4(A) || !aligned4(W) || !aligned4(out)) return fail(QNN_ERR_ALIGN, "conv2d: pointer not 4-byte aligned");
-    const int64_t Ho = (H + 2 * pad - KH) / stride_hw + 1, Wo = (Wd + 2 * pad - KW) / stride_hw + 1;
+    if (B == 0 || Cout == 0) {
+        empty = true;
+        return QNN_OK;
+    }
+    if (!A || !W) return fail(QNN_ERR_NULL, "conv2d: NULL pointer");
+    if (epi.out_bits && !epi.T) return fail(QNN_ERR_NULL, "conv2d: threshold pointer is NULL");
+    if (epi.T ? !epi.out_bits : !epi.C) return fail(QNN_ERR_NULL, "conv2d: output pointer is NULL");
+    if (!aligned4(A) || !aligned4(W) || !aligned4(epi.C) || !aligned4(epi.out_bits) || !aligned4(epi.T))
+        return fail(QNN_ERR_ALIGN, "conv2d: pointer not 4-byte aligned");
+    const int64_t Ho = (H + 2 * (int64_t)pad - KH) / stride_hw + 1, Wo = (Wd + 2 * (int64_t)pad - KW) / stride_hw + 1;
+    if (Ho < 1 || Wo < 1 || Ho > 0x7FFFFFFFLL || Wo > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "conv2d: output size out of range");
     const int64_t Cw = words_for(Cin);
-    GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     g.A.base = A;
     g.A.plane_stride = strideA_words;
@@ -393,19 +501,46 @@ int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int mod
     g.strideW = strideW_words;
     g.pw.count = Pb, g.pw.mode = modeW;
     for (int i = 0; i < Pb; ++i) g.pw.coef[i] = coefW[i];
-    g.epi = Epilogue{out, Cout, nullptr, nullptr, nullptr, 0};
+    g.epi = epi;
     g.M = B * Ho * Wo;
     g.N = Cout;
     g.K = (int64_t)KH * KW * Cin;  // true number of connections per output (channel tail bits are zero)
     if (g.Kw > 0x7FFFFFFFLL / 32) return fail(QNN_ERR_SHAPE, "conv2d: patch too long");
-    if (int rc = check_range(g)) return rc;
+    return check_range(g);
+}
+}  // namespace
+
+int qnn_bitplane_conv2d_ex(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
+                           int64_t B, int64_t H, int64_t Wd, int64_t Cin, const uint32_t *W, int Pb,
+                           const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
+                           int pad, int stride_hw, int32_t *out, int engine, void *stream) {
+    GemmArgs g;
+    bool empty;
+    const Epilogue e{out, Cout, nullptr, nullptr, nullptr, 0};
+    if (int rc = conv_args(A, Pa, coefA, modeA, strideA_words, B, H, Wd, Cin, W, Pb, coefW, modeW, strideW_words, Cout,
+                           KH, KW, pad, stride_hw, e, engine, g, empty))
+        return rc;
+    if (empty) return QNN_OK;
     return dispatch(g, engine, static_cast<hipStream_t>(stream));
+}
+
+int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
+                        int64_t B, int64_t H, int64_t Wd, int64_t Cin, const uint32_t *W, int Pb,
+                        const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
+                        int pad, int stride_hw, int32_t *out, void *stream) {
+    return qnn_bitplane_conv2d_ex(A, Pa, coefA, modeA, strideA_words, B, H, Wd, Cin, W, Pb, coefW, modeW,
+                                  strideW_words, Cout, KH, KW, pad, stride_hw, out, QNN_ENGINE_AUTO, stream);
 }
 
 int qnn_last_engine(void) { return g_last_engine; }
 
+int qnn_last_engines(int *engines, int capacity) {
+    for (int i = 0; i < g_engine_count && i < capacity && engines; ++i) engines[i] = g_engines[i];
+    return g_engine_count;
+}
+
 const char *qnn_last_error(void) { return g_err; }
 
-const char *qnn_version(void) { return "libqnn 0.1 (gfx950)"; }
+const char *qnn_version(void) { return "libqnn 0.2 (gfx950)"; }
 
 }  // extern "C"

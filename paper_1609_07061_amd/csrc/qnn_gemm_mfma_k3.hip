@@ -1,0 +1,16 @@
+// Part of the matrix-core engine's kernel instantiations (see qnn_gemm_mfma_kernel.h): convolution by implicit im2col.
+#include "qnn_gemm_mfma_kernel.h"
+
+namespace qnn {
+namespace mfma {
+
+VariantList variants_conv() {
+    static const Variant k[] = {
+        QNN_VARIANT(1, 1, 4, true, false),
+        QNN_VARIANT(2, 1, 2, true, false),
+    };
+    return {k, (int)(sizeof(k) / sizeof(k[0]))};
+}
+
+}  // namespace mfma
+}  // namespace qnn

@@ -289,6 +289,7 @@ int launch_modes(const GemmArgs &g, hipStream_t s) {
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(kThreads);
     const bool a_sign = g.pa.mode == QNN_PLANE_SIGN, w_sign = g.pw.mode == QNN_PLANE_SIGN;
     const uint32_t um = (uint32_t)tiles_m, un = (uint32_t)tiles_n;
+    (void)hipGetLastError();  // an error left behind by the caller's earlier HIP calls is not this launch's
     if (a_sign && w_sign)
         hipLaunchKernelGGL((gemm_valu_kernel<TM, TN, true, false, false, kPixels, kSign>), grid, block, 0, s, g, um, un);
     else if (!a_sign && w_sign)
@@ -302,15 +303,22 @@ int launch_modes(const GemmArgs &g, hipStream_t s) {
 
 }  // namespace
 
+bool valu_supports(const GemmArgs &g) {
+    // packed planes only (a byte-coded left operand belongs to the matrix-core engine)
+    if (g.A.rows_are_bytes) return false;
+    if (g.A.rows_are_pixels && g.epi.T) return false;
+    return true;
+}
+
 int launch_gemm_valu(const GemmArgs &g, hipStream_t s) {
+    if (g.A.rows_are_bytes) return fail(QNN_ERR_UNSUPPORTED, "vector-ALU engine: the left operand must be packed planes");
     const bool sign = g.epi.T != nullptr;
     const bool pixels = g.A.rows_are_pixels != 0;
     // the large tile only when it still yields a few workgroups per compute unit
     const bool big = ceil_div(g.M, 128) * ceil_div(g.N, 128) >= 512;
     if (!pixels && !sign && g.N <= kSkinnyMaxN && g.M >= 256 && g.pa.count == 1 && g.pw.count == 1 &&
         g.pa.mode == QNN_PLANE_SIGN && g.pw.mode == QNN_PLANE_SIGN && ceil_div(g.M, kSkinnyRows) <= 0x7FFFFFFFLL) {
-        hipLaunchKernelGGL(gemm_skinny_kernel, dim3((unsigned)ceil_div(g.M, kSkinnyRows)), dim3(kThreads), 0, s, g);
-        return check_launch("gemm_skinny");
+        return QNN_LAUNCH("gemm_skinny", gemm_skinny_kernel, dim3((unsigned)ceil_div(g.M, kSkinnyRows)), dim3(kThreads), 0, s, g);
     }
     if (pixels) {
         if (sign) return fail(QNN_ERR_UNSUPPORTED, "conv: thresholded output is not provided");

@@ -13,6 +13,16 @@ namespace qnn {
 int fail(int code, const char *fmt, ...);
 // Checks hipGetLastError() after a launch; QNN_OK or QNN_ERR_HIP.
 int check_launch(const char *what);
+// Launches a kernel and reports the outcome of THIS launch: an error that an earlier HIP call of the caller left behind
+// on the thread is discarded first, so that it is not blamed on a kernel that was in fact enqueued.
+template <typename... KArgs, typename... Args>
+inline int launch_checked(const char *what, void (*kernel)(KArgs...), dim3 grid, dim3 block, unsigned shmem,
+                          hipStream_t stream, Args &&...args) {
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(kernel, grid, block, shmem, stream, static_cast<KArgs>(args)...);
+    return check_launch(what);
+}
+#define QNN_LAUNCH(what, ...) ::qnn::launch_checked(what, __VA_ARGS__)
 
 static inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 static inline int64_t words_for(int64_t K) { return (K + 31) / 32; }
@@ -82,6 +92,7 @@ __device__ __forceinline__ void tile_of_block(uint32_t bid, uint32_t total, uint
 
 // Engines.  Both return QNN_OK / QNN_ERR_*; `mfma_supports` says whether the matrix-core engine can take the job.
 int launch_gemm_valu(const GemmArgs &g, hipStream_t s);
+bool valu_supports(const GemmArgs &g);
 bool mfma_supports(const GemmArgs &g, bool fp4 = false);  // fp4: on the FP4 (E2M1) matrix-core path
 bool mfma_preferred(const GemmArgs &g);  // whether AUTO should pick it for this shape
 int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4 = false);

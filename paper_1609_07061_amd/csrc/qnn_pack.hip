@@ -311,16 +311,14 @@ int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint3
     if (K >= 2048 && K % 4 == 0 && ldx % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0) {
         const int64_t cpr = ceil_div(K, (int64_t)2048);
         const int64_t total = rows * cpr;
-        hipLaunchKernelGGL(pack_sign_vec4_kernel, dim3(grid_for(total)), dim3(kBlock), 0, s,
+        return QNN_LAUNCH("pack_sign", pack_sign_vec4_kernel, dim3(grid_for(total)), dim3(kBlock), 0, s,
                            reinterpret_cast<const uint32_t *>(x), rows, K, ldx, out, ldo, cpr, total);
-        return check_launch("pack_sign");
     }
     constexpr int kUnroll = 8;  // 512 elements (2 KiB of floats) in flight per wave
     const int64_t cpr = ceil_div(K, (int64_t)kUnroll * kWave);
     const int64_t total = rows * cpr;
-    hipLaunchKernelGGL(pack_sign_kernel<kUnroll>, dim3(grid_for(total)), dim3(kBlock), 0, s,
+    return QNN_LAUNCH("pack_sign", pack_sign_kernel<kUnroll>, dim3(grid_for(total)), dim3(kBlock), 0, s,
                        reinterpret_cast<const uint32_t *>(x), rows, K, ldx, out, ldo, cpr, total);
-    return check_launch("pack_sign");
 }
 
 int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,
@@ -328,24 +326,21 @@ int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv
     if (K >= 1024 && K % 16 == 0 && ldv % 16 == 0 && reinterpret_cast<uintptr_t>(v) % 16 == 0) {
         const int64_t cpr = ceil_div(K, (int64_t)2048);
         const int64_t total = rows * cpr;
-        hipLaunchKernelGGL(pack_bitplanes_word_kernel, dim3(grid_for(total)), dim3(kBlock), 0, s, v, rows, K, ldv, nbits,
+        return QNN_LAUNCH("pack_bitplanes", pack_bitplanes_word_kernel, dim3(grid_for(total)), dim3(kBlock), 0, s, v, rows, K, ldv, nbits,
                            planes, ld, plane_stride, cpr, total);
-        return check_launch("pack_bitplanes");
     }
     if (K >= 512 && K % 4 == 0 && ldv % 4 == 0 && reinterpret_cast<uintptr_t>(v) % 4 == 0) {
         const bool big = K >= 2048;
         const int64_t cpr = ceil_div(K, (int64_t)(big ? 2048 : 1024));
         const int64_t total = rows * cpr;
-        hipLaunchKernelGGL(big ? pack_bitplanes_vec4_kernel<8> : pack_bitplanes_vec4_kernel<4>, dim3(grid_for(total)),
+        return QNN_LAUNCH("pack_bitplanes", big ? pack_bitplanes_vec4_kernel<8> : pack_bitplanes_vec4_kernel<4>, dim3(grid_for(total)),
                            dim3(kBlock), 0, s, v, rows, K, ldv, nbits, planes, ld, plane_stride, cpr, total);
-        return check_launch("pack_bitplanes");
     }
     constexpr int kUnroll = 4;
     const int64_t cpr = ceil_div(K, (int64_t)kUnroll * kWave);
     const int64_t total = rows * cpr;
-    hipLaunchKernelGGL(pack_bitplanes_kernel<kUnroll>, dim3(grid_for(total)), dim3(kBlock), 0, s, v, rows, K, ldv,
+    return QNN_LAUNCH("pack_bitplanes", pack_bitplanes_kernel<kUnroll>, dim3(grid_for(total)), dim3(kBlock), 0, s, v, rows, K, ldv,
                        nbits, planes, ld, plane_stride, cpr, total);
-    return check_launch("pack_bitplanes");
 }
 
 int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
@@ -355,17 +350,15 @@ int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, c
         int64_t vy = ceil_div(M, (int64_t)kThreshVecRows);
         if (vy > 32768) vy = 32768;  // the kernel strides over the remaining row groups
         if (vx > 0x7FFFFFFF) return fail(QNN_ERR_SHAPE, "threshold_sign: N too large");
-        hipLaunchKernelGGL(threshold_sign_vec4_kernel, dim3((unsigned)vx, (unsigned)vy), dim3(kBlock), 0, s, C, ldc, M,
+        return QNN_LAUNCH("threshold_sign", threshold_sign_vec4_kernel, dim3((unsigned)vx, (unsigned)vy), dim3(kBlock), 0, s, C, ldc, M,
                            N, T, flip, out, ldo);
-        return check_launch("threshold_sign");
     }
     const int64_t gx = ceil_div(N, (int64_t)kBlock);
     int64_t gy = ceil_div(M, (int64_t)kThreshRows);
     if (gy > 32768) gy = 32768;  // the kernel strides over the remaining row groups
     if (gx > 0x7FFFFFFF) return fail(QNN_ERR_SHAPE, "threshold_sign: N too large");
-    hipLaunchKernelGGL(threshold_sign_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), 0, s, C, ldc, M, N, T,
+    return QNN_LAUNCH("threshold_sign", threshold_sign_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), 0, s, C, ldc, M, N, T,
                        flip, out, ldo);
-    return check_launch("threshold_sign");
 }
 
 }  // namespace qnn

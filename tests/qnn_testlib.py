@@ -39,3 +39,48 @@ def host_u32(t: torch.Tensor) -> np.ndarray:
 
 def host(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy()
+
+
+# --------------------------------------------------------------------------------------------------------------------
+# What the two matrix-core engines take BY DESIGN (engine 2 = int8, engine 3 = FP4); everything else they refuse with
+# status 5 and AUTO sends to another engine.  The tests assert both directions: a supported case must run, an
+# unsupported one must be refused - a regression in what an engine accepts cannot hide behind a skip.
+INT8_PLANE_PAIRS = {(1, 1), (8, 1), (4, 4), (2, 1), (4, 1), (2, 2)}
+INT8_PLANE_PAIRS_SIGN_OUT = {(1, 1), (8, 1)}
+INT8_PLANE_PAIRS_CONV = {(1, 1), (2, 1)}
+
+
+def _codes_as_int8(coefs) -> bool:
+    """Coefficients = common factor x distinct powers of two up to 128 (unsigned, two's complement, single plane)."""
+    from math import gcd
+
+    g = 0
+    for c in coefs:
+        if c == 0:
+            return False
+        g = gcd(g, abs(int(c)))
+    mags = [abs(int(c)) // g for c in coefs]
+    return all(m <= 128 and (m & (m - 1)) == 0 for m in mags) and len(set(mags)) == len(mags)
+
+
+def engine_takes(engine: int, Pa: int = 1, Pb: int = 1, coefA=(1,), coefW=(1,), conv: bool = False,
+                 sign_out: bool = False) -> bool:
+    if engine in (0, 1):
+        return True
+    if engine == 3:
+        return Pa == 1 and Pb == 1 and not conv
+    pairs = INT8_PLANE_PAIRS_CONV if conv else (INT8_PLANE_PAIRS_SIGN_OUT if sign_out else INT8_PLANE_PAIRS)
+    return (Pa, Pb) in pairs and _codes_as_int8(coefA) and _codes_as_int8(coefW)
+
+
+def run_on_engine(fn, *a, engine: int, takes: bool = True, **kw):
+    """fn(..., engine=engine): the result if the engine is documented to take the case (any refusal fails the test),
+    otherwise None after checking that the refusal is exactly status 5."""
+    import pytest
+
+    if takes:
+        return fn(*a, engine=engine, **kw)
+    with pytest.raises(Exception) as e:
+        fn(*a, engine=engine, **kw)
+    assert getattr(e.value, "status", None) == 5, e.value
+    return None

@@ -21,7 +21,9 @@ def test_header_symbols_are_exported():
 
     lib = C.CDLL(q.LIB_PATH)
     names = _declared_symbols()
-    assert len(names) >= 14
+    assert len(names) >= 19
+    for five in ('qnn_pack_sign', 'qnn_binary_gemm', 'qnn_bitplane_gemm', 'qnn_threshold_sign', 'qnn_binary_mlp_forward'):
+        assert five in names
     for n in names:
         assert hasattr(lib, n), f"{n} declared in qnn.h but not exported"
     assert sorted(q.EXPORTS) == names
@@ -76,7 +78,11 @@ def test_binary_gemm_argument_errors(lib):
 
 
 def test_bitplane_gemm_argument_errors(lib):
-    f = lib.qnn_bitplane_gemm
+    f = lib.qnn_bitplane_gemm_ex
+    plain = lib.qnn_bitplane_gemm
+    assert plain(FAKE, 0, ONE, 0, 1, 4, FAKE, 1, ONE, 1, 1, 0, FAKE, 4, 4, 4, 32, None) == 2  # no engine argument here
+    assert plain(None, 1, ONE, 0, 1, 4, None, 1, ONE, 1, 1, 0, None, 4, 0, 4, 32, None) == 0  # M == 0
+    assert f(FAKE, 1, ONE, 0, 1, 4, FAKE, 1, ONE, 1, 1, 0, FAKE, 4, 4, 4, 32, 9, None) == 2  # unknown engine
     c8 = (C.c_int32 * 8)(1, 2, 4, 8, 16, 32, 64, 128)
     assert f(FAKE, 0, c8, 0, 1, 4, FAKE, 1, ONE, 1, 1, 0, FAKE, 4, 4, 4, 32, 0, None) == 2
     assert f(FAKE, 9, c8, 0, 1, 4, FAKE, 1, ONE, 1, 1, 0, FAKE, 4, 4, 4, 32, 0, None) == 2
@@ -111,19 +117,48 @@ def test_mlp_argument_errors(lib):
     Wp = (C.c_void_p * 3)(FAKE, FAKE, FAKE)
     Tp = (C.c_void_p * 2)(FAKE, FAKE)
     f = lib.qnn_binary_mlp_forward
-    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, None, 0, 0, None) == 6  # no workspace
-    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10000, need - 1, 0, None) == 6  # too small
-    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10010, need, 0, None) == 6  # misaligned
-    assert f(FAKE, 100, 784, 8, 1, dims, Wp, Tp, None, FAKE, 10, 0x10000, need, 0, None) == 2  # n_layers < 2
-    assert f(FAKE, 100, 700, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10000, need, 0, None) == 2  # ldx < dims[0]
-    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 9, 0x10000, need, 0, None) == 2  # ld_logits
+    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, None, 0, None) == 6  # no workspace
+    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10000, need - 1, None) == 6  # too small
+    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10010, need, None) == 6  # misaligned
+    assert f(FAKE, 100, 784, 8, 1, dims, Wp, Tp, None, FAKE, 10, 0x10000, need, None) == 2  # n_layers < 2
+    assert f(FAKE, 100, 700, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10000, need, None) == 2  # in_dim != dims[0]
+    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 9, 0x10000, need, None) == 2  # ld_logits
     Wbad = (C.c_void_p * 3)(FAKE, None, FAKE)
-    assert f(FAKE, 100, 784, 8, 3, dims, Wbad, Tp, None, FAKE, 10, 0x10000, need, 0, None) == 1
-    assert f(None, 0, 784, 8, 3, dims, Wp, Tp, None, None, 10, None, 0, 0, None) == 0  # batch 0
+    assert f(FAKE, 100, 784, 8, 3, dims, Wbad, Tp, None, FAKE, 10, 0x10000, need, None) == 1
+    assert f(None, 0, 784, 8, 3, dims, Wp, Tp, None, None, 10, None, 0, None) == 0  # batch 0
+    g = lib.qnn_binary_mlp_forward_ex
+    assert g(FAKE, 100, 700, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10000, need, 0, None) == 2  # ldx < dims[0]
+    assert g(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10000, need, 9, None) == 2  # unknown engine
+
+
+def test_mlp_validates_every_layer_before_the_first_launch(lib):
+    """A fault in a LATER layer (here: a misaligned weight pointer of the last layer, a misaligned threshold pointer
+    of the second) is reported without anything having been enqueued: the addresses are fake, so a launch of the
+    first layer would have been a GPU fault on a GPU machine, and on a CPU-only box a HIP error (status 7) instead of the
+    argument error."""
+    import paper_1609_07061_amd as q
+
+    dims = (C.c_int64 * 4)(784, 64, 64, 10)
+    need = q.qnn_binary_mlp_workspace_bytes(100, 8, [784, 64, 64, 10])
+    f = lib.qnn_binary_mlp_forward
+    Wp = (C.c_void_p * 3)(FAKE, FAKE, FAKE + 2)
+    Tp = (C.c_void_p * 2)(FAKE, FAKE)
+    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10000, need, None) == 3
+    assert "aligned" in _err(lib)
+    Wp = (C.c_void_p * 3)(FAKE, FAKE, FAKE)
+    Tp = (C.c_void_p * 2)(FAKE, FAKE + 1)
+    assert f(FAKE, 100, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, 0x10000, need, None) == 3
+    # a first layer whose sums cannot fit int32: 255 * 2^24 inputs
+    big = (C.c_int64 * 3)(1 << 24, 64, 10)
+    Wp2 = (C.c_void_p * 2)(FAKE, FAKE)
+    Tp1 = (C.c_void_p * 1)(FAKE)
+    need2 = q.qnn_binary_mlp_workspace_bytes(4, 8, [1 << 24, 64, 10])
+    assert f(FAKE, 4, 1 << 24, 8, 2, big, Wp2, Tp1, None, FAKE, 10, 0x10000, need2, None) == 4
 
 
 def test_conv_argument_errors(lib):
-    f = lib.qnn_bitplane_conv2d
+    f = lib.qnn_bitplane_conv2d_ex
+    assert lib.qnn_bitplane_conv2d(None, 2, None, 0, 100, 0, 5, 5, 32, None, 1, ONE, 1, 0, 4, 3, 3, 1, 1, None, None) == 1
     c2 = (C.c_int32 * 2)(1, 2)
     ok = [FAKE, 2, c2, 0, 100, 1, 5, 5, 32, FAKE, 1, ONE, 1, 0, 4, 3, 3, 1, 1, FAKE, 0, None]
 
@@ -140,6 +175,8 @@ def test_conv_argument_errors(lib):
     assert call(KH=9, pad=0) == 2  # kernel larger than image
     assert call(modeA=1) == 5  # sign-mode activations cannot be zero padded
     assert call(B=0) == 0
+    assert call(pad=40000) == 2  # padding beyond the supported range
+    assert call(engine=9) == 2
 
 
 def test_fold_batchnorm_matches_float_definition():

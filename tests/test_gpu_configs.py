@@ -1,18 +1,25 @@
-"""The five benchmark configurations at full size, in the launch configuration the benchmark times, checked against the
-oracle: whole outputs where the oracle finishes in seconds, otherwise complete sampled rows / images (rows of a matrix
-product, samples of the MLP batch and images of the convolution are independent of each other, so a sampled row is
-computed by the oracle exactly) plus whole-output checksums that hold for any size."""
+"""The five benchmark configurations at full size, in the launch configuration the benchmark times (AUTO, with the
+engine it picks asserted), and on every other engine that takes them: EVERY output element is compared with the
+oracle's.  Further down: whole-output comparisons on shapes with more tiles than the chip has compute units, so that
+the persistent kernels' second and later tiles (next tile's operands prefetched during the epilogue, register buffers
+re-used) are checked element by element as well."""
+import functools
+
 import numpy as np
 import pytest
 import torch
 
 import oracle
 import qnn_inputs as qi
-from qnn_testlib import dev, host, np_pack_bits, np_pack_pm1
+from qnn_testlib import dev, host, host_u32, np_pack_bits, np_pack_pm1
 
 pytestmark = pytest.mark.gpu
 
 q = None
+VALU, MFMA, FP4 = 1, 2, 3
+# engine AUTO picks per configuration; bench.py reports the same ones
+AUTO_ENGINE = {"c1": VALU, "c3": FP4, "c4": MFMA, "c5": MFMA}
+AUTO_ENGINES_C2 = [MFMA, FP4, FP4, VALU]  # first layer from the 8-bit codes, two hidden layers, 10-neuron output layer
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -26,96 +33,230 @@ def _lib():
     torch.cuda.synchronize()
 
 
-def test_config1_gemm_128x1024x1024(seed):
+def first_difference(got: np.ndarray, want: np.ndarray) -> str:
+    """Names the first differing element (row-major), for the assertion message."""
+    if got.shape != want.shape:
+        return f"shape {got.shape} != {want.shape}"
+    bad = np.argwhere(got != want)
+    if bad.size == 0:
+        return ""
+    i = tuple(int(v) for v in bad[0])
+    return f"{len(bad)} of {got.size} elements differ, first at {i}: got {got[i]}, oracle {want[i]}"
+
+
+def assert_same(got, want):
+    assert np.array_equal(got, want), first_difference(got, want)
+
+
+def check_engine(engine, auto_choice):
+    used = q.qnn_last_engine()
+    assert used == (engine if engine else auto_choice), f"engine {used} ran, expected {engine or auto_choice}"
+
+
+# ---------------------------------------------------------------------------------------------------------- C1
+@functools.lru_cache(maxsize=None)
+def _c1(seed):
+    xa, xw = qi.normal_f32(seed, 10, (128, 1024)), qi.normal_f32(seed, 11, (1024, 1024))
+    sa, sw = oracle.sign(xa), oracle.sign(xw)
+    return xa, xw, sa, sw, oracle.gemm_pm1(sa, sw)
+
+
+@pytest.mark.parametrize("engine", [0, VALU, MFMA, FP4])
+def test_config1_sign_pack_gemm_128x1024x1024(seed, engine):
+    """fp32 N(0,1) -> qnn_pack_sign (both operands) -> product; also the Bernoulli +-1 operands packed on the host."""
+    xa, xw, sa, sw, want = _c1(seed)
+    A, W = q.qnn_pack_sign(dev(xa)), q.qnn_pack_sign(dev(xw))
+    assert_same(host_u32(A), oracle.pack_bits(sa))
+    assert_same(host_u32(W), oracle.pack_bits(sw))
+    assert_same(host(q.qnn_binary_gemm(A, W, 1024, engine=engine)), want)
+    check_engine(engine, AUTO_ENGINE["c1"])
     a = qi.pm1(seed, 10, (128, 1024))
     w = qi.pm1(seed, 11, (1024, 1024))
-    got = q.qnn_binary_gemm(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), 1024)
-    assert np.array_equal(host(got), oracle.gemm_pm1(a, w))
+    assert_same(host(q.qnn_binary_gemm(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), 1024, engine=engine)),
+                oracle.gemm_pm1(a, w))
 
 
-def test_config3_gemm_8192_cubed(seed):
+# ---------------------------------------------------------------------------------------------------------- C3
+@functools.lru_cache(maxsize=None)
+def _c3(seed):
     n = 8192
     a = qi.pm1(seed, 30, (n, n))
     w = qi.pm1(seed, 31, (n, n))
-    got = host(q.qnn_binary_gemm(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), n))
-    # (1) complete sampled rows and columns, spread over every tile row / column and including both ends
-    rows = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, n - 1],
-                                     (qi.raw_u64(seed, 32, 40) % np.uint64(n)).astype(np.int64)]))
-    cols = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, n - 1],
-                                     (qi.raw_u64(seed, 33, 40) % np.uint64(n)).astype(np.int64)]))
-    assert np.array_equal(got[rows], oracle.gemm_pm1(a[rows], w))
-    assert np.array_equal(got[:, cols], oracle.gemm_pm1(a, w[cols]))
-    # (2) whole-output checksums: sum_n C[m][n] = a[m] . (sum_n w[n]) and sum_m C[m][n] = (sum_m a[m]) . w[n]
-    wsum = w.astype(np.int64).sum(axis=0)
-    asum = a.astype(np.int64).sum(axis=0)
-    assert np.array_equal(got.astype(np.int64).sum(axis=1), a.astype(np.int64) @ wsum)
-    assert np.array_equal(got.astype(np.int64).sum(axis=0), w.astype(np.int64) @ asum)
-    # (3) every +-1 dot product of even length is even and bounded by K
-    assert (got % 2 == 0).all() and np.abs(got).max() <= n
+    return np_pack_pm1(a), np_pack_pm1(w), oracle.gemm_pm1(a, w)
 
 
-def test_config2_mlp_mnist_shaped(seed):
+@pytest.mark.parametrize("engine", [0, FP4, MFMA, VALU])
+def test_config3_gemm_8192_cubed_every_element(seed, engine):
+    A, W, want = _c3(seed)
+    got = host(q.qnn_binary_gemm(dev(A), dev(W), 8192, engine=engine))
+    check_engine(engine, AUTO_ENGINE["c3"])
+    assert_same(got, want)
+
+
+def test_config3_plain_entry_point(seed):
+    """qnn_binary_gemm itself (no engine argument), as the benchmark calls it."""
+    A, W, want = _c3(seed)
+    assert_same(host(q.qnn_binary_gemm(dev(A), dev(W), 8192)), want)
+    assert q.qnn_last_engine() == AUTO_ENGINE["c3"]
+
+
+# ---------------------------------------------------------------------------------------------------------- C2
+@functools.lru_cache(maxsize=None)
+def _c2(seed):
     dims = [784, 4096, 4096, 4096, 10]
     batch = 10000
     x = qi.uniform_int(seed, 20, (batch, 784), 0, 255, dtype=np.uint8)
     W = [qi.pm1(seed, 21 + l, (dims[l + 1], dims[l])) for l in range(4)]
     T = [qi.uniform_int(seed, 25 + l, (dims[l + 1],), -64, 64) for l in range(3)]
-    got = host(q.qnn_binary_mlp_forward(dev(x), 8, dims, [dev(np_pack_pm1(w)) for w in W], [dev(t) for t in T]))
-    # samples are independent: the oracle runs complete on a spread of them
-    idx = np.unique(np.concatenate([[0, 1, 127, 128, 255, 256, 9983, 9984, batch - 1],
-                                    (qi.raw_u64(seed, 29, 240) % np.uint64(batch)).astype(np.int64)]))
-    want = oracle.mlp(x[idx], W, T)
-    assert np.array_equal(got[idx], want)
-    assert (got % 2 == 0).all() and np.abs(got).max() <= 4096  # logits are +-1 dot products of length 4096
+    return dims, x, [np_pack_pm1(w) for w in W], T, oracle.mlp(x, W, T)
 
 
-def test_config4_alexnet_conv(seed):
+@pytest.mark.parametrize("engine", [None, MFMA, VALU])
+def test_config2_mlp_mnist_shaped_every_logit(seed, engine):
+    dims, x, Wp, T, want = _c2(seed)
+    got = host(q.qnn_binary_mlp_forward(dev(x), 8, dims, [dev(w) for w in Wp], [dev(t) for t in T], engine=engine))
+    if engine is None:
+        assert q.qnn_last_engines() == AUTO_ENGINES_C2
+    elif engine == VALU:
+        assert q.qnn_last_engines() == [VALU] * 4
+    assert_same(got, want)
+
+
+# ---------------------------------------------------------------------------------------------------------- C4
+@functools.lru_cache(maxsize=None)
+def _c4(seed):
     B, H, Wd, Cin, Cout = 256, 13, 13, 384, 256
     u = qi.uniform_int(seed, 40, (B, H, Wd, Cin), 0, 3)
     w = qi.pm1(seed, 41, (Cout, 3, 3, Cin))
-    up = np_pack_bits(oracle.split_planes(u, 2))
-    got = host(q.qnn_bitplane_conv2d(dev(up), [1, 2], q.PLANE_BIT, Cin, dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN,
-                                     1, 1))
-    idx = np.unique(np.concatenate([[0, 1, 2, 3, 4, 5, B - 1], (qi.raw_u64(seed, 42, 12) % np.uint64(B)).astype(np.int64)]))
-    want = oracle.conv2d(u[idx], w.astype(np.int32), 1, 1)
-    assert np.array_equal(got[idx], want)
-    # checksum over output channels for every pixel: sum_co out = patch . (sum_co w)  (via the oracle on 1 "filter")
-    wsum = w.astype(np.int32).sum(axis=0, keepdims=True)
-    assert np.array_equal(got.astype(np.int64).sum(axis=3), oracle.conv2d(u, wsum, 1, 1)[..., 0].astype(np.int64))
+    return np_pack_bits(oracle.split_planes(u, 2)), np_pack_pm1(w)[None], oracle.conv2d(u, w.astype(np.int32), 1, 1)
 
 
-def test_config5_lstm_gates_int4(seed):
+@pytest.mark.parametrize("engine", [None, MFMA, VALU])
+def test_config4_alexnet_conv_every_element(seed, engine):
+    up, wp, want = _c4(seed)
+    got = host(q.qnn_bitplane_conv2d(dev(up), [1, 2], q.PLANE_BIT, 384, dev(wp), [1], q.PLANE_SIGN, 1, 1, engine=engine))
+    check_engine(engine, AUTO_ENGINE["c4"])
+    assert_same(got, want)
+
+
+# ---------------------------------------------------------------------------------------------------------- C5
+@functools.lru_cache(maxsize=None)
+def _c5(seed):
     M, K, N = 64 * 35, 2048, 4096
     a = qi.uniform_int(seed, 50, (M, K), -8, 7)
     w = qi.uniform_int(seed, 51, (N, K), -8, 7)
+    return np_pack_bits(oracle.split_planes(a, 4)), np_pack_bits(oracle.split_planes(w, 4)), oracle.gemm_int(a, w)
+
+
+@pytest.mark.parametrize("engine", [None, MFMA, VALU])
+def test_config5_lstm_gates_int4_every_element(seed, engine):
+    ap, wp, want = _c5(seed)
     coef = [1, 2, 4, -8]
-    ap = np_pack_bits(oracle.split_planes(a, 4))
-    wp = np_pack_bits(oracle.split_planes(w, 4))
-    got = host(q.qnn_bitplane_gemm(dev(ap), coef, q.PLANE_BIT, dev(wp), coef, q.PLANE_BIT, K))
-    assert np.array_equal(got, oracle.gemm_int(a, w))
+    got = host(q.qnn_bitplane_gemm(dev(ap), coef, q.PLANE_BIT, dev(wp), coef, q.PLANE_BIT, 2048, engine=engine))
+    check_engine(engine, AUTO_ENGINE["c5"])
+    assert_same(got, want)
 
 
-@pytest.mark.parametrize("engine", [0, 2, 3])
+# ------------------------------------------------------------------------- more tiles than compute units, whole output
+@pytest.mark.parametrize("engine", [0, MFMA, FP4])
 @pytest.mark.parametrize("M,N,ldc", [(4200, 4200, 4200), (4200, 4197, 4197), (4104, 4360, 4400)])
 def test_large_ragged_gemm_interior_and_edge_tiles(seed, M, N, ldc, engine):
-    """More tiles than compute units, K = 8192 and ragged edges: interior tiles take the row-contiguous 16-byte store
-    path (when the row pitch allows it: blocks staged through LDS and stored as whole lines), edge tiles the
-    bounds-checked one, in the same launch."""
+    """K = 8192 and ragged edges: interior tiles take the whole-line store path (when the row pitch allows it), edge
+    tiles the bounds-checked one, in the same launch; 289 to 306 tiles on 256 persistent workgroups."""
     K = 8192
     a = qi.pm1(seed, 60, (M, K))
     w = qi.pm1(seed, 61, (N, K))
     out = torch.full((M, ldc), -7, dtype=torch.int32, device="cuda")
     q.qnn_binary_gemm(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, out=out[:, :N], engine=engine)
+    check_engine(engine, FP4)
     got = host(out)
     assert (got[:, N:] == -7).all()
-    got = got[:, :N]
-    rows = np.unique(np.concatenate([[0, 127, 128, 255, 256, 4095, 4096, M - 1],
-                                     (qi.raw_u64(seed, 62, 24) % np.uint64(M)).astype(np.int64)]))
-    cols = np.unique(np.concatenate([[0, 127, 128, 255, 256, 4095, 4096, N - 1],
-                                     (qi.raw_u64(seed, 63, 24) % np.uint64(N)).astype(np.int64)]))
-    assert np.array_equal(got[rows], oracle.gemm_pm1(a[rows], w))
-    assert np.array_equal(got[:, cols], oracle.gemm_pm1(a, w[cols]))
-    wsum = w.astype(np.int64).sum(axis=0)
-    asum = a.astype(np.int64).sum(axis=0)
-    assert np.array_equal(got.astype(np.int64).sum(axis=1), a.astype(np.int64) @ wsum)
-    assert np.array_equal(got.astype(np.int64).sum(axis=0), w.astype(np.int64) @ asum)
+    assert_same(got[:, :N], oracle.gemm_pm1(a, w))
+
+
+MANY_TILES = [(4200, 4360, 256), (4360, 4104, 320), (4104, 4200, 800)]
+
+
+@pytest.mark.parametrize("engine", [0, MFMA, FP4])
+@pytest.mark.parametrize("M,N,K", MANY_TILES)
+def test_many_tiles_short_k_int32_output(seed, M, N, K, engine):
+    """17 x 18 tiles and short K: tile changes (prefetch across the epilogue, buffer re-use) dominate."""
+    a = qi.pm1(seed, 64, (M, K))
+    w = qi.pm1(seed, 65, (N, K))
+    ldc = N + 4 * (K % 7)  # a padded row pitch in two of the three cases
+    out = torch.full((M, ldc), -7, dtype=torch.int32, device="cuda")
+    q.qnn_binary_gemm(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, out=out[:, :N], engine=engine)
+    check_engine(engine, FP4)
+    got = host(out)
+    assert (got[:, N:] == -7).all()
+    assert_same(got[:, :N], oracle.gemm_pm1(a, w))
+
+
+@pytest.mark.parametrize("engine", [0, MFMA, FP4])
+@pytest.mark.parametrize("M,N,K", MANY_TILES)
+def test_many_tiles_short_k_threshold_output(seed, M, N, K, engine):
+    a = qi.pm1(seed, 66, (M, K))
+    w = qi.pm1(seed, 67, (N, K))
+    T = qi.uniform_int(seed, 68, (N,), -10, 10)
+    flip = qi.bernoulli_bits(seed, 69, (N,))
+    ldo = (N + 31) // 32 + 3
+    out = torch.full((M, ldo), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    q.qnn_binary_gemm_sign(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T), dev(flip), out=out[:, :ldo - 3],
+                           engine=engine)
+    check_engine(engine, FP4)
+    got = host_u32(out)
+    assert (got[:, ldo - 3:] == 0x5A5A5A5A).all()
+    assert_same(got[:, :ldo - 3], oracle.pack_bits(oracle.threshold(oracle.gemm_pm1(a, w), T, flip)))
+
+
+@pytest.mark.parametrize("engine", [None, MFMA])
+def test_many_tiles_first_layer_from_codes(seed, engine):
+    """The byte-operand kernel of the MLP's first layer over 17 x 17 tiles, then a 10-neuron output layer."""
+    batch, dims = 4200, [784, 4200, 10]
+    x = qi.uniform_int(seed, 70, (batch, 784), 0, 255, dtype=np.uint8)
+    W = [qi.pm1(seed, 71 + l, (dims[l + 1], dims[l])) for l in range(2)]
+    T = [qi.uniform_int(seed, 73, (dims[1],), -3000, 3000)]
+    flip = [qi.bernoulli_bits(seed, 74, (dims[1],))]
+    got = host(q.qnn_binary_mlp_forward(dev(x), 8, dims, [dev(np_pack_pm1(w)) for w in W], [dev(t) for t in T],
+                                        [dev(f) for f in flip], engine=engine))
+    assert q.qnn_last_engines()[0] == MFMA
+    assert_same(got, oracle.mlp(x, W, T, flip))
+
+
+@pytest.mark.parametrize("engine", [None, MFMA])
+def test_many_tiles_first_layer_planes_threshold_output(seed, engine):
+    """Eight input planes x one weight plane with the fused threshold (the plane fall-back of the first layer)."""
+    M, N, K = 4200, 4200, 320
+    x = qi.uniform_int(seed, 75, (M, K), 0, 255)
+    w = qi.pm1(seed, 76, (N, K))
+    T = qi.uniform_int(seed, 77, (N,), -1500, 1500)
+    xp = np_pack_bits(oracle.split_planes(x, 8))
+    kw = {} if engine is None else {"engine": engine}
+    got = q.qnn_bitplane_gemm_sign(dev(xp), [1 << p for p in range(8)], q.PLANE_BIT, dev(np_pack_pm1(w)[None]), [1],
+                                   q.PLANE_SIGN, K, dev(T), None, **kw)
+    check_engine(engine or 0, MFMA)
+    assert_same(host_u32(got), oracle.pack_bits(oracle.threshold(oracle.gemm_int(x, w.astype(np.int32)), T)))
+
+
+@pytest.mark.parametrize("engine", [None, MFMA])
+def test_many_tiles_int4_times_int4(seed, engine):
+    M, N, K = 4200, 4360, 256
+    a = qi.uniform_int(seed, 78, (M, K), -8, 7)
+    w = qi.uniform_int(seed, 79, (N, K), -8, 7)
+    coef = [1, 2, 4, -8]
+    got = q.qnn_bitplane_gemm(dev(np_pack_bits(oracle.split_planes(a, 4))), coef, q.PLANE_BIT,
+                              dev(np_pack_bits(oracle.split_planes(w, 4))), coef, q.PLANE_BIT, K, engine=engine)
+    check_engine(engine or 0, MFMA)
+    assert_same(host(got), oracle.gemm_int(a, w))
+
+
+@pytest.mark.parametrize("engine", [None, MFMA])
+def test_many_tiles_conv(seed, engine):
+    """26 images of 13 x 13 pixels, 64 -> 4200 channels: 18 x 17 tiles of the implicit-im2col kernel."""
+    B, H, Wd, Cin, Cout = 26, 13, 13, 64, 4200
+    u = qi.uniform_int(seed, 80, (B, H, Wd, Cin), 0, 3)
+    w = qi.pm1(seed, 81, (Cout, 3, 3, Cin))
+    got = q.qnn_bitplane_conv2d(dev(np_pack_bits(oracle.split_planes(u, 2))), [1, 2], q.PLANE_BIT, Cin,
+                                dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, 1, 1, engine=engine)
+    check_engine(engine or 0, MFMA)
+    assert_same(host(got), oracle.conv2d(u, w.astype(np.int32), 1, 1))

@@ -6,7 +6,8 @@ import torch
 
 import oracle
 import qnn_inputs as qi
-from qnn_testlib import dev, host, host_u32, np_pack_bits, np_pack_pm1, np_unpack_bits
+from qnn_testlib import (dev, engine_takes, host, host_u32, np_pack_bits, np_pack_pm1, np_unpack_bits,
+                         run_on_engine)
 
 pytestmark = pytest.mark.gpu
 
@@ -25,15 +26,6 @@ def _lib():
 
 
 ENGINES = [1, 2, 3, 0]  # VALU, int8 MFMA, FP4 MFMA, AUTO
-
-
-def _engine_or_skip(fn, *a, engine, **kw):
-    try:
-        return fn(*a, engine=engine, **kw)
-    except Exception as e:  # QnnError with status 5 = engine cannot take the job
-        if getattr(e, "status", None) == 5 and engine in (2, 3):
-            pytest.skip("matrix-core engine does not take this shape")
-        raise
 
 
 # ------------------------------------------------------------------ S1 pack_sign
@@ -194,7 +186,7 @@ def test_binary_gemm(seed, M, N, K, engine):
     a = qi.pm1(seed, 20, (M, K))
     w = qi.pm1(seed, 21, (N, K))
     want = oracle.gemm_pm1(a, w)
-    got = _engine_or_skip(q.qnn_binary_gemm, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, engine=engine)
+    got = run_on_engine(q.qnn_binary_gemm, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, engine=engine)
     assert np.array_equal(host(got), want)
 
 
@@ -222,7 +214,7 @@ def test_binary_gemm_strided_operands_and_output(seed, engine):
     A = dev(np_pack_pm1(a, 9))[:, :7]
     W = dev(np_pack_pm1(w, 12))[:, :7]
     out = torch.full((M, 100), -77, dtype=torch.int32, device="cuda")
-    _engine_or_skip(q.qnn_binary_gemm, A, W, K, out=out[:, :N], engine=engine)
+    run_on_engine(q.qnn_binary_gemm, A, W, K, out=out[:, :N], engine=engine)
     got = host(out)
     assert np.array_equal(got[:, :N], oracle.gemm_pm1(a, w))
     assert (got[:, N:] == -77).all()
@@ -236,7 +228,7 @@ def test_binary_gemm_from_packed_floats(seed, engine):
     want = oracle.gemm_pm1(oracle.sign(xa), oracle.sign(xw))
     A = q.qnn_pack_sign(dev(xa))
     W = q.qnn_pack_sign(dev(xw))
-    got = _engine_or_skip(q.qnn_binary_gemm, A, W, 1024, engine=engine)
+    got = run_on_engine(q.qnn_binary_gemm, A, W, 1024, engine=engine)
     assert np.array_equal(host(got), want)
 
 
@@ -249,7 +241,7 @@ def test_binary_gemm_sign(seed, M, N, K, with_flip, engine):
     T = qi.uniform_int(seed, 26, (N,), -8, 8)  # ties C == T are frequent
     flip = qi.bernoulli_bits(seed, 27, (N,)) if with_flip else None
     want = oracle.pack_bits(oracle.threshold(oracle.gemm_pm1(a, w), T, flip))
-    got = _engine_or_skip(q.qnn_binary_gemm_sign, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T),
+    got = run_on_engine(q.qnn_binary_gemm_sign, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T),
                           dev(flip) if with_flip else None, engine=engine)
     assert np.array_equal(host_u32(got), want)
 
@@ -269,7 +261,7 @@ def test_binary_gemm_sign_extreme_thresholds(seed, engine):
     T[5::7] = K + 1  # never reached
     flip = qi.bernoulli_bits(seed, 27, (N,))
     want = oracle.pack_bits(oracle.threshold(oracle.gemm_pm1(a, w), T, flip))
-    got = _engine_or_skip(q.qnn_binary_gemm_sign, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T), dev(flip),
+    got = run_on_engine(q.qnn_binary_gemm_sign, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T), dev(flip),
                           engine=engine)
     assert np.array_equal(host_u32(got), want)
 
@@ -283,7 +275,7 @@ def test_binary_gemm_long_k_on_matrix_cores(seed, engine, K):
     w = qi.pm1(seed, 31, (N, K))
     w[0] = a[0]
     w[1] = -a[1]
-    got = _engine_or_skip(q.qnn_binary_gemm, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, engine=engine)
+    got = run_on_engine(q.qnn_binary_gemm, dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, engine=engine)
     assert np.array_equal(host(got), oracle.gemm_pm1(a, w))
 
 
@@ -301,9 +293,11 @@ def test_bitplane_u8_times_sign(seed, M, N, K, engine):
     w = qi.pm1(seed, 31, (N, K))
     want = oracle.gemm_int(x, w.astype(np.int32))
     _, xp = _planes_of(x, 8)
-    got = _engine_or_skip(q.qnn_bitplane_gemm, dev(xp), [1 << p for p in range(8)], q.PLANE_BIT,
-                          dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, K, engine=engine)
-    assert np.array_equal(host(got), want)
+    got = run_on_engine(q.qnn_bitplane_gemm, dev(xp), [1 << p for p in range(8)], q.PLANE_BIT,
+                        dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, K, engine=engine,
+                        takes=engine_takes(engine, 8, 1))
+    if got is not None:
+        assert np.array_equal(host(got), want)
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -315,9 +309,10 @@ def test_bitplane_int4_times_int4(seed, M, N, K, engine):
     coef = [1, 2, 4, -8]
     _, ap = _planes_of(a, 4)
     _, wp = _planes_of(w, 4)
-    got = _engine_or_skip(q.qnn_bitplane_gemm, dev(ap), coef, q.PLANE_BIT, dev(wp), coef, q.PLANE_BIT, K,
-                          engine=engine)
-    assert np.array_equal(host(got), want)
+    got = run_on_engine(q.qnn_bitplane_gemm, dev(ap), coef, q.PLANE_BIT, dev(wp), coef, q.PLANE_BIT, K,
+                        engine=engine, takes=engine_takes(engine, 4, 4, coef, coef))
+    if got is not None:
+        assert np.array_equal(host(got), want)
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -328,9 +323,28 @@ def test_bitplane_every_mode_pair_against_plane_oracle(seed, modeA, modeW, engin
     pw = qi.bernoulli_bits(seed, 35, (Pb, N, K))
     ca, cw = [1, -2, 5], [3, -4]
     want = oracle.gemm_planes(pa, ca, modeA, pw, cw, modeW)
-    got = _engine_or_skip(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, modeA, dev(np_pack_bits(pw)), cw, modeW, K,
-                          engine=engine)
-    assert np.array_equal(host(got), want)
+    got = run_on_engine(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, modeA, dev(np_pack_bits(pw)), cw, modeW, K,
+                        engine=engine, takes=engine_takes(engine, Pa, Pb, ca, cw))
+    if got is not None:
+        assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("modeA,modeW", [(0, 0), (0, 1), (1, 0), (1, 1)])
+@pytest.mark.parametrize("Pa,Pb,ca,cw", [(2, 2, [1, -2], [2, 1]), (4, 1, [1, 2, 4, -8], [-1]), (2, 1, [6, 3], [5])])
+def test_bitplane_every_mode_pair_with_power_of_two_codes(seed, Pa, Pb, ca, cw, modeA, modeW, engine):
+    """Coefficient sets the int8 matrix-core engine takes (a common factor times distinct powers of two, either sign,
+    any order), in all four mode pairs, so that the affine correction of every pair is exercised on that engine too."""
+    M, N, K = 70, 45, 333
+    pa = qi.bernoulli_bits(seed, 42, (Pa, M, K))
+    pw = qi.bernoulli_bits(seed, 43, (Pb, N, K))
+    want = oracle.gemm_planes(pa, ca, modeA, pw, cw, modeW)
+    got = run_on_engine(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, modeA, dev(np_pack_bits(pw)), cw, modeW, K,
+                        engine=engine, takes=engine_takes(engine, Pa, Pb, ca, cw))
+    if got is not None:
+        assert np.array_equal(host(got), want)
+        if engine in (1, 2):
+            assert q.qnn_last_engine() == engine
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -340,9 +354,10 @@ def test_bitplane_large_coefficients_fall_back_correctly(seed, engine):
     pw = qi.bernoulli_bits(seed, 37, (2, N, K))
     ca, cw = [1000, -3], [7, 300]
     want = oracle.gemm_planes(pa, ca, 0, pw, cw, 1)
-    got = _engine_or_skip(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, 0, dev(np_pack_bits(pw)), cw, 1, K,
-                          engine=engine)
-    assert np.array_equal(host(got), want)
+    got = run_on_engine(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, 0, dev(np_pack_bits(pw)), cw, 1, K,
+                        engine=engine, takes=engine_takes(engine, 2, 2, ca, cw))
+    if got is not None:
+        assert np.array_equal(host(got), want)
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -354,9 +369,11 @@ def test_bitplane_gemm_sign_first_layer(seed, engine):
     flip = qi.bernoulli_bits(seed, 41, (N,))
     want = oracle.pack_bits(oracle.threshold(oracle.gemm_int(x, w.astype(np.int32)), T, flip))
     _, xp = _planes_of(x, 8)
-    got = _engine_or_skip(q.qnn_bitplane_gemm_sign, dev(xp), [1 << p for p in range(8)], q.PLANE_BIT,
-                          dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, K, dev(T), dev(flip), engine=engine)
-    assert np.array_equal(host_u32(got), want)
+    got = run_on_engine(q.qnn_bitplane_gemm_sign, dev(xp), [1 << p for p in range(8)], q.PLANE_BIT,
+                        dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, K, dev(T), dev(flip), engine=engine,
+                        takes=engine_takes(engine, 8, 1, sign_out=True))
+    if got is not None:
+        assert np.array_equal(host_u32(got), want)
 
 
 # ------------------------------------------------------------------ S5 MLP (Alg. 4)
@@ -374,7 +391,7 @@ def test_mlp_forward_small(seed, batch, dims, engine):
     x, W, T = _mlp_case(seed, batch, dims, 50)
     flip = [qi.bernoulli_bits(seed, 60 + l, (dims[l + 1],)) for l in range(len(dims) - 2)]
     want = oracle.mlp(x, W, T, flip)
-    got = _engine_or_skip(q.qnn_binary_mlp_forward, dev(x), 8, dims, [dev(np_pack_pm1(w)) for w in W],
+    got = run_on_engine(q.qnn_binary_mlp_forward, dev(x), 8, dims, [dev(np_pack_pm1(w)) for w in W],
                           [dev(t) for t in T], [dev(f) for f in flip], engine=engine)
     assert np.array_equal(host(got), want)
 
@@ -392,7 +409,7 @@ def test_mlp_forward_first_layer_from_codes(seed, batch, dims, ldx, engine):
     xb = qi.uniform_int(seed, 95, (batch, ldx), 0, 255, dtype=np.uint8)  # garbage in the row padding
     xb[:, : dims[0]] = x
     xd = dev(xb)[:, : dims[0]]
-    got = _engine_or_skip(q.qnn_binary_mlp_forward, xd, 8, dims, [dev(np_pack_pm1(w)) for w in W],
+    got = run_on_engine(q.qnn_binary_mlp_forward, xd, 8, dims, [dev(np_pack_pm1(w)) for w in W],
                           [dev(t) for t in T], [dev(f) for f in flip], engine=engine)
     assert np.array_equal(host(got), want)
 
@@ -413,9 +430,10 @@ def _conv_case(seed, B, H, Wd, Cin, Cout, KH, abits, stream0):
 def test_conv2d(seed, B, H, Wd, Cin, Cout, KH, pad, stride, engine):
     u, w, up, wp = _conv_case(seed, B, H, Wd, Cin, Cout, KH, 2, 70)
     want = oracle.conv2d(u, w.astype(np.int32), pad, stride)
-    got = _engine_or_skip(q.qnn_bitplane_conv2d, dev(up), [1, 2], q.PLANE_BIT, Cin, dev(wp), [1], q.PLANE_SIGN, pad,
-                          stride, engine=engine)
-    assert np.array_equal(host(got), want)
+    got = run_on_engine(q.qnn_bitplane_conv2d, dev(up), [1, 2], q.PLANE_BIT, Cin, dev(wp), [1], q.PLANE_SIGN, pad,
+                        stride, engine=engine, takes=engine_takes(engine, 2, 1, conv=True))
+    if got is not None:
+        assert np.array_equal(host(got), want)
 
 
 @pytest.mark.parametrize("engine", ENGINES)
@@ -424,9 +442,11 @@ def test_conv2d_sign_activations_without_padding(seed, engine):
     a = qi.pm1(seed, 72, (B, H, Wd, Cin))
     w = qi.pm1(seed, 73, (Cout, 3, 3, Cin))
     want = oracle.conv2d(a.astype(np.int32), w.astype(np.int32), 0, 1)
-    got = _engine_or_skip(q.qnn_bitplane_conv2d, dev(np_pack_pm1(a)[None]), [1], q.PLANE_SIGN, Cin,
-                          dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, 0, 1, engine=engine)
-    assert np.array_equal(host(got), want)
+    got = run_on_engine(q.qnn_bitplane_conv2d, dev(np_pack_pm1(a)[None]), [1], q.PLANE_SIGN, Cin,
+                        dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, 0, 1, engine=engine,
+                        takes=engine_takes(engine, 1, 1, conv=True))
+    if got is not None:
+        assert np.array_equal(host(got), want)
 
 
 # ------------------------------------------------------------------ degenerate sizes

@@ -6,7 +6,7 @@ import torch
 
 import oracle
 import qnn_inputs as qi
-from qnn_testlib import dev, host, host_u32, np_pack_bits, np_pack_pm1
+from qnn_testlib import dev, engine_takes, host, host_u32, np_pack_bits, np_pack_pm1, run_on_engine
 
 pytestmark = pytest.mark.gpu
 
@@ -30,11 +30,9 @@ def test_random_binary_gemm_shapes(seed, engine):
         A = dev(np_pack_pm1(a, Kw + pads[3 * i]))[:, :Kw]
         W = dev(np_pack_pm1(w, Kw + pads[3 * i + 1]))[:, :Kw]
         out = torch.full((M, N + pads[3 * i + 2]), 12345, dtype=torch.int32, device="cuda")
-        try:
-            q.qnn_binary_gemm(A, W, K, out=out[:, :N], engine=engine)
-        except q.QnnError as e:
-            assert e.status == 5 and engine in (2, 3), (M, N, K, str(e))
-            continue
+        q.qnn_binary_gemm(A, W, K, out=out[:, :N], engine=engine)  # single planes: every engine takes every shape
+        if engine:
+            assert q.qnn_last_engine() == engine
         got = host(out)
         assert np.array_equal(got[:, :N], oracle.gemm_pm1(a, w)), (M, N, K, engine)
         assert (got[:, N:] == 12345).all(), (M, N, K, engine)
@@ -53,12 +51,10 @@ def test_random_binary_gemm_sign_shapes(seed, engine):
         T = qi.uniform_int(seed, 990 + i, (N,), -12, 12)
         flip = qi.bernoulli_bits(seed, 1005 + i, (N,)) if i % 2 else None
         want = oracle.pack_bits(oracle.threshold(oracle.gemm_pm1(a, w), T, flip))
-        try:
-            got = q.qnn_binary_gemm_sign(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T),
-                                         dev(flip) if flip is not None else None, engine=engine)
-        except q.QnnError as e:
-            assert e.status == 5 and engine in (2, 3), (M, N, K, str(e))
-            continue
+        got = q.qnn_binary_gemm_sign(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T),
+                                     dev(flip) if flip is not None else None, engine=engine)
+        if engine:
+            assert q.qnn_last_engine() == engine
         assert np.array_equal(host_u32(got), want), (M, N, K, engine)
 
 
@@ -76,9 +72,8 @@ def test_random_bitplane_shapes(seed, engine):
         pa = qi.bernoulli_bits(seed, 1030 + i, (Pa, M, K))
         pw = qi.bernoulli_bits(seed, 1050 + i, (Pb, N, K))
         want = oracle.gemm_planes(pa, ca, ma, pw, cw, mw)
-        try:
-            got = q.qnn_bitplane_gemm(dev(np_pack_bits(pa)), ca, ma, dev(np_pack_bits(pw)), cw, mw, K, engine=engine)
-        except q.QnnError as e:
-            assert e.status == 5 and engine == 2, (Pa, Pb, M, N, K, str(e))
+        got = run_on_engine(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, ma, dev(np_pack_bits(pw)), cw, mw, K,
+                            engine=engine, takes=engine_takes(engine, Pa, Pb, ca, cw))
+        if got is None:  # refused with status 5, as documented for this (engine, case) pair
             continue
         assert np.array_equal(host(got), want), (Pa, Pb, ca, cw, ma, mw, M, N, K, engine)

@@ -219,6 +219,24 @@ def test_planes_all_sign_code(seed):
     assert np.array_equal(one, oracle.gemm_pm1(2 * pa[0].astype(np.int8) - 1, 2 * pw[0].astype(np.int8) - 1))
 
 
+@pytest.mark.parametrize("modeA,modeW", [(0, 0), (0, 1), (1, 0), (1, 1)])
+def test_planes_every_mode_pair_equals_int64_matmul_of_plane_values(seed, modeA, modeW):
+    """Each of the four (mode A, mode W) pairs, the mixed ones included ((sign A, bit W) is the transposed first
+    layer: +-1 activations against 0/1 weight planes), against numpy int64 on the values the planes encode with odd
+    and negative coefficients.  A swapped mode argument, a mode applied to the wrong operand or a lost coefficient
+    sign changes the result."""
+    M, N, K, Pa, Pb = 5, 7, 53, 3, 2
+    pa = qi.bernoulli_bits(seed, 28, (Pa, M, K)).astype(np.int64)
+    pw = qi.bernoulli_bits(seed, 29, (Pb, N, K)).astype(np.int64)
+    ca, cw = [1, -2, 5], [3, -4]
+    va = sum(c * ((2 * pa[i] - 1) if modeA else pa[i]) for i, c in enumerate(ca))
+    vw = sum(c * ((2 * pw[j] - 1) if modeW else pw[j]) for j, c in enumerate(cw))
+    assert np.array_equal(oracle.gemm_planes(pa, ca, modeA, pw, cw, modeW), va @ vw.T)
+    if modeA != modeW:  # the two mixed pairs must differ from each other on the same planes (operands not swapped)
+        other = oracle.gemm_planes(pa, ca, modeW, pw, cw, modeA)
+        assert not np.array_equal(other, va @ vw.T)
+
+
 def test_range_check_reports_overflow():
     u = np.full((1, 4), 2**30, dtype=np.int32)
     with pytest.raises(oracle.OracleRangeError):
