@@ -161,6 +161,19 @@ int qnn_binary_mlp_forward_ex(const uint8_t *x, int64_t batch, int64_t ldx, int 
                               const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *workspace,
                               size_t workspace_bytes, int engine, void *stream);
 
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): qnn_binary_mlp_forward without the workspace argument.  The scratch memory is an array
+ * of qnn_static_scratch_bytes() bytes (32 MiB) that is part of the library's code object; every GPU the library runs
+ * on holds its own copy until the process ends.  The call allocates and frees nothing.  A network and batch whose
+ * qnn_binary_mlp_workspace_bytes() exceeds the array is refused with QNN_ERR_WORKSPACE.  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (different streams or threads) race; calls ordered
+ * on one stream do not.  Nothing in the array needs to be cleared between calls (every word that is read has been
+ * written earlier in the same call). */
+int qnn_binary_mlp_forward_static(const uint8_t *x, int64_t batch, int64_t in_dim, int in_bits, int n_layers,
+                                  const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
+                                  const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *stream);
+size_t qnn_static_scratch_bytes(void);
+
 /* Binarized convolution (Sec. 5 filter bank M_l x M_{l-1} x k x k; Sec. 3 multi-bit activations) without
  * materialising patches.  Activations: Pa bit planes, channels-last and packed along channels:
  * plane i of pixel (b, y, x) is Cw = ceil(Cin/32) words at A + i * strideA_words + ((b*H + y)*Wd + x) * Cw.

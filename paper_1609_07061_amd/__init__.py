@@ -43,6 +43,7 @@ _SIGS = {
     "qnn_fold_batchnorm": [_vp, _vp, _vp, _vp, C.c_double, _i64, _vp, _vp],
     "qnn_binary_mlp_forward": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp],
     "qnn_binary_mlp_forward_ex": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _int, _vp],
+    "qnn_binary_mlp_forward_static": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp],
     "qnn_bitplane_conv2d": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
                             _int, _int, _int, _vp, _vp],
     "qnn_bitplane_conv2d_ex": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
@@ -54,6 +55,7 @@ for _name, _args in _SIGS.items():
     _f.restype = C.c_int
 _lib.qnn_binary_mlp_workspace_bytes.argtypes = [_i64, _int, _int, _vp]
 _lib.qnn_binary_mlp_workspace_bytes.restype = _sz
+_lib.qnn_static_scratch_bytes.restype = _sz
 _lib.qnn_last_engine.restype = C.c_int
 _lib.qnn_last_error.restype = C.c_char_p
 _lib.qnn_version.restype = C.c_char_p
@@ -61,7 +63,7 @@ _lib.qnn_version.restype = C.c_char_p
 _lib.qnn_last_engines.argtypes = [_vp, _int]
 _lib.qnn_last_engines.restype = C.c_int
 
-EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_last_engine",
+EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_static_scratch_bytes", "qnn_last_engine",
                                "qnn_last_engines", "qnn_last_error", "qnn_version"])
 
 
@@ -245,11 +247,16 @@ def qnn_binary_mlp_workspace_bytes(batch: int, in_bits: int, dims: Sequence[int]
     return int(_lib.qnn_binary_mlp_workspace_bytes(batch, in_bits, len(dims) - 1, d))
 
 
+def qnn_static_scratch_bytes() -> int:
+    return int(_lib.qnn_static_scratch_bytes())
+
+
 def qnn_binary_mlp_forward(x: torch.Tensor, in_bits: int, dims: Sequence[int], W: Sequence[torch.Tensor],
                            T: Sequence[torch.Tensor], flip: Optional[Sequence[Optional[torch.Tensor]]] = None,
                            logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                           engine: Optional[int] = None) -> torch.Tensor:
-    """engine None and dense x -> qnn_binary_mlp_forward; an engine or a strided x -> qnn_binary_mlp_forward_ex."""
+                           engine: Optional[int] = None, static_scratch: bool = False) -> torch.Tensor:
+    """engine None and dense x -> qnn_binary_mlp_forward; an engine or a strided x -> qnn_binary_mlp_forward_ex;
+    static_scratch -> qnn_binary_mlp_forward_static (no workspace: the library's built-in scratch array)."""
     batch, _, ldx = _rows_ld(x, "x")
     L = len(dims) - 1
     if len(W) != L or len(T) != L - 1:
@@ -267,6 +274,11 @@ def qnn_binary_mlp_forward(x: torch.Tensor, in_bits: int, dims: Sequence[int], W
     if flip is not None:
         Fp = (C.c_void_p * max(L - 1, 1))(*[_dev(f, torch.uint8, "flip") for f in flip])
     head = (_dev(x, torch.uint8, "x"), batch, ldx, in_bits, L, d, Wp, Tp, Fp, _dev(logits, torch.int32, "logits"), ldl)
+    if static_scratch:
+        if engine is not None or ldx != dims[0]:
+            raise ValueError("the static-scratch entry point takes dense rows and no engine")
+        _check(_lib.qnn_binary_mlp_forward_static(*head, _stream()))
+        return logits
     if workspace is None:
         workspace = torch.empty(qnn_binary_mlp_workspace_bytes(batch, in_bits, dims), dtype=torch.uint8, device=x.device)
     ws = (_dev(workspace, torch.uint8, "workspace"), workspace.numel())

@@ -5,8 +5,15 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 
 #include "qnn_internal.h"
+
+// Scratch memory of qnn_binary_mlp_forward_static, the entry point for callers that cannot allocate: every GPU the
+// library runs on holds its own copy of this array until the process ends.  In host code the name is only a handle
+// for hipGetSymbolAddress; kernels receive the looked-up device address as an ordinary argument.
+static constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace qnn {
 
@@ -434,6 +441,26 @@ int run_mlp(const MlpPlan &plan, hipStream_t s) {
     return QNN_OK;
 }
 
+// Device memory of the entry point that must not allocate: one array per GPU, held until the process ends.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the calling thread's current device's copy of `scratch` (looked up once per device).
+int static_scratch(void *&ptr) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+        return fail(QNN_ERR_HIP, "static scratch: no current device below %d", kMaxDevices);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return fail(QNN_ERR_HIP, "static scratch: hipGetSymbolAddress: %s", hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    ptr = g_scratch_ptr[dev];
+    return QNN_OK;
+}
 }  // namespace
 
 int qnn_binary_mlp_forward_ex(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_layers,
@@ -456,6 +483,32 @@ int qnn_binary_mlp_forward(const uint8_t *x, int64_t batch, int64_t in_dim, int 
     if (dims && in_dim != dims[0]) return fail(QNN_ERR_SHAPE, "mlp: in_dim = %lld differs from dims[0]", (long long)in_dim);
     return qnn_binary_mlp_forward_ex(x, batch, in_dim, in_bits, n_layers, dims, W, T, flip, logits, ld_logits, workspace,
                                      workspace_bytes, QNN_ENGINE_AUTO, stream);
+}
+
+size_t qnn_static_scratch_bytes(void) { return kStaticScratchBytes; }
+
+int qnn_binary_mlp_forward_static(const uint8_t *x, int64_t batch, int64_t in_dim, int in_bits, int n_layers,
+                                  const int64_t *dims, const uint32_t *const *W, const int32_t *const *T,
+                                  const uint8_t *const *flip, int32_t *logits, int64_t ld_logits, void *stream) {
+    if (dims && in_dim != dims[0]) return fail(QNN_ERR_SHAPE, "mlp: in_dim = %lld differs from dims[0]", (long long)in_dim);
+    const size_t need = qnn_binary_mlp_workspace_bytes(batch, in_bits, n_layers, dims);
+    if (need > kStaticScratchBytes)
+        return fail(QNN_ERR_WORKSPACE, "mlp (static scratch): this network and batch need %zu bytes of scratch, the "
+                                       "built-in buffer holds %zu", need, kStaticScratchBytes);
+    // arguments first (with a stand-in address that is never used), so that an argument error or an empty batch
+    // does not depend on the device at all; then the real plan on this device's array
+    MlpPlan plan;
+    bool empty;
+    if (int rc = plan_mlp(x, batch, in_dim, in_bits, n_layers, dims, W, T, flip, logits, ld_logits,
+                          reinterpret_cast<void *>(uintptr_t(256)), kStaticScratchBytes, QNN_ENGINE_AUTO, plan, empty))
+        return rc;
+    if (empty) return QNN_OK;
+    void *ws = nullptr;
+    if (int rc = static_scratch(ws)) return rc;
+    if (int rc = plan_mlp(x, batch, in_dim, in_bits, n_layers, dims, W, T, flip, logits, ld_logits, ws,
+                          kStaticScratchBytes, QNN_ENGINE_AUTO, plan, empty))
+        return rc;
+    return run_mlp(plan, static_cast<hipStream_t>(stream));
 }
 
 namespace {

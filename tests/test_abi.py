@@ -21,7 +21,7 @@ def test_header_symbols_are_exported():
 
     lib = C.CDLL(q.LIB_PATH)
     names = _declared_symbols()
-    assert len(names) >= 19
+    assert len(names) >= 20
     for five in ('qnn_pack_sign', 'qnn_binary_gemm', 'qnn_bitplane_gemm', 'qnn_threshold_sign', 'qnn_binary_mlp_forward'):
         assert five in names
     for n in names:
@@ -154,6 +154,24 @@ def test_mlp_validates_every_layer_before_the_first_launch(lib):
     Tp1 = (C.c_void_p * 1)(FAKE)
     need2 = q.qnn_binary_mlp_workspace_bytes(4, 8, [1 << 24, 64, 10])
     assert f(FAKE, 4, 1 << 24, 8, 2, big, Wp2, Tp1, None, FAKE, 10, 0x10000, need2, None) == 4
+
+
+def test_static_scratch_entry_point_argument_errors(lib):
+    """The entry point for callers that cannot allocate refuses what does not fit its built-in 32 MiB array, and
+    validates like qnn_binary_mlp_forward; nothing here reaches the GPU."""
+    import paper_1609_07061_amd as q
+
+    assert q.qnn_static_scratch_bytes() == 32 << 20
+    f = lib.qnn_binary_mlp_forward_static
+    dims = (C.c_int64 * 4)(784, 4096, 4096, 10)
+    Wp = (C.c_void_p * 3)(FAKE, FAKE, FAKE)
+    Tp = (C.c_void_p * 2)(FAKE, FAKE)
+    assert q.qnn_binary_mlp_workspace_bytes(10000, 8, [784, 4096, 4096, 10]) <= 32 << 20
+    assert q.qnn_binary_mlp_workspace_bytes(40000, 8, [784, 4096, 4096, 10]) > 32 << 20
+    assert f(FAKE, 40000, 784, 8, 3, dims, Wp, Tp, None, FAKE, 10, None) == 6
+    assert "built-in" in _err(lib)
+    assert f(FAKE, 100, 700, 8, 3, dims, Wp, Tp, None, FAKE, 10, None) == 2  # in_dim != dims[0]
+    assert f(None, 0, 784, 8, 3, dims, Wp, Tp, None, None, 10, None) == 0  # batch 0: no-op, the array is not touched
 
 
 def test_conv_argument_errors(lib):
