@@ -2,17 +2,25 @@
 """Benchmark of the QNN hot path on one MI355X.
 
 Primary line (the driver's contract): binary-GEMM throughput at 8192^3 on packed +-1 operands (1 +-1 MAC = 2 ops),
-inputs resident in HBM, one step = one qnn_binary_gemm call.  The same JSON line carries the MNIST-shaped MLP forward
-(samples/s) and the other configurations as secondary figures, the roofline of the dominant kernel measured with HIP
-events on the launch stream, and the CPU oracle timed on this machine's host cores on a bounded sample.
+inputs resident in HBM, one step = one qnn_binary_gemm call: W untimed calls, then exactly K calls between two HIP
+events on the launch stream.  The same JSON line carries the second half of the metric (MNIST-shaped MLP forward,
+samples/s, with its own roofline fraction), the other configurations as secondary figures (each at least 50 timed calls
+after at least 10 warm-up calls, whatever --steps says, and each reported only if a sample of its output equals the
+oracle's), the shader clock observed before and after the timed region, per-call durations (median, minimum), the
+roofline of the dominant kernel, and the CPU oracle timed on this machine's host cores on a bounded sample.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--engine auto|valu|mfma] [--only c3|c2|c1|c4|c5]
+Order of work: all host-side preparation first (inputs, oracle expectations), then the GPU work back to back -
+secondary configurations, then the primary one - so that the primary's few warm-up calls do not have to bring the card up
+from idle clocks by themselves; the clock actually seen is in the line (`sclk_mhz`).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--engine auto|valu|mfma|fp4] [--only c3,c2,c1,c4,c5]
 """
 from __future__ import annotations
 
 import argparse
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -23,10 +31,13 @@ for _p in (ROOT, os.path.join(ROOT, "tests")):
 
 import numpy as np  # noqa: E402
 
+NOMINAL_MHZ = 2400.0
 VALU_PEAK_TOPS = 256 * 64 * 32 * 2.4e9 / 1e12  # 256 CUs x 64 lanes/clk x (32 MAC per xor+bcnt pair = 32 ops/lane/clk) x 2.4 GHz
 MFMA_I8_PEAK_TOPS = 5000.0                     # dense int8 matrix-core peak, 2 ops per MAC
 MFMA_FP4_PEAK_TOPS = 10100.0                   # dense FP4 matrix-core peak
 HBM_PEAK_GBS = 8000.0
+ENGINE_NAMES = {1: "valu", 2: "mfma", 3: "fp4", 4: "mfma_lds"}
+ENGINE_PEAK = {1: VALU_PEAK_TOPS, 2: MFMA_I8_PEAK_TOPS, 3: MFMA_FP4_PEAK_TOPS, 4: MFMA_I8_PEAK_TOPS}
 
 
 def log(*a):
@@ -41,29 +52,41 @@ def time_steps(fn, steps, warmup):
         fn()
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
     e0.record()
     for _ in range(steps):
         fn()
     e1.record()
     torch.cuda.synchronize()
-    wall_ms = (time.perf_counter() - t0) * 1e3 / steps
-    return e0.elapsed_time(e1) / steps, wall_ms
+    return e0.elapsed_time(e1) / steps
+
+
+def per_call_ms(fn, calls):
+    """One event pair per call (all on the launch stream, no host synchronization in between)."""
+    import torch
+
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(calls + 1)]
+    ev[0].record()
+    for i in range(calls):
+        fn()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    return [ev[i].elapsed_time(ev[i + 1]) for i in range(calls)]
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
-    ap.add_argument("--warmup", type=int, default=200,
-                    help="untimed calls first; the card needs some hundred launches to raise its shader clock from idle")
+    ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--engine", default="auto", choices=["auto", "valu", "mfma", "fp4"])
-    ap.add_argument("--only", default="", help="comma list of c1,c2,c3,c4,c5 (default: all)")
+    ap.add_argument("--only", default="", help="comma list of c1,c2,c3,c4,c5 (default: all; c3 always runs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--primary-first", action="store_true",
+                    help="time the primary configuration before the secondary ones (from idle clocks)")
     ap.add_argument("--traffic-probe", action="store_true",
-                    help="also run a plain 256 MiB device copy (known size) so that rocprofv3 --pmc FETCH_SIZE / "
-                         "WRITE_SIZE readings of the GEMM can be scaled by what the same counter reads for the copy")
+                    help="also run kernels of known size (a 256 MiB device copy, a fill, the sign+pack kernel) so that "
+                         "rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings of the GEMM can be scaled by them")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on one GPU only (every configuration is measured whole on one MI355X); "
@@ -72,120 +95,142 @@ def main():
 
     import torch
 
+    import oracle
     import paper_1609_07061_amd as q
     import qnn_inputs as qi
     from qnn_testlib import dev, np_pack_bits, np_pack_pm1
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    engine = {"auto": q.ENGINE_AUTO, "valu": q.ENGINE_VALU, "mfma": q.ENGINE_MFMA, "fp4": q.ENGINE_MFMA_FP4}[args.engine]
+    engine = {"auto": None, "valu": q.ENGINE_VALU, "mfma": q.ENGINE_MFMA, "fp4": q.ENGINE_MFMA_FP4}[args.engine]
     only = set(filter(None, args.only.split(","))) or {"c1", "c2", "c3", "c4", "c5"}
     seed = qi.SEED_BASE
     steps, warmup = args.steps, args.warmup
-    sec_steps = max(5, steps // 5)
-    sec_warm = max(3, warmup // 10)
+    sec_steps, sec_warm = max(50, steps // 5), max(10, warmup // 10)
     extra = {}
+    jobs = []  # (name, closure run on the GPU phase)
 
-    # ---------------------------------------------------------------- C3: 8192^3 binary GEMM (primary)
+    def frac_fields(ops, ms, eng):
+        tops = ops / (ms * 1e-3) / 1e12
+        return {"engine": ENGINE_NAMES[eng], "integer_tops": tops, "frac_of_engine_peak": tops / ENGINE_PEAK[eng]}
+
+    # ================================================================ host-side preparation (no GPU timing yet)
     n = 8192
-    log("[bench] generating C3 operands")
+    log("[bench] preparing inputs and oracle expectations")
     a3 = qi.pm1(seed, 30, (n, n))
     w3 = qi.pm1(seed, 31, (n, n))
     A3, W3 = dev(np_pack_pm1(a3)), dev(np_pack_pm1(w3))
     C3 = torch.empty((n, n), dtype=torch.int32, device="cuda")
+    rows3 = np.unique(np.concatenate([[0, 255, 256, 4095, 4096, n - 1], (qi.raw_u64(seed, 32, 10) % np.uint64(n)).astype(np.int64)]))
+    want3 = oracle.gemm_pm1(a3[rows3], w3)
     ops3 = 2.0 * n * n * n
-    ms3, wall3 = time_steps(lambda: q.qnn_binary_gemm(A3, W3, n, out=C3, engine=engine), steps, warmup)
-    tops3 = ops3 / (ms3 * 1e-3) / 1e12
-    log(f"[bench] C3 8192^3: {ms3:.4f} ms/step, {tops3:.1f} binary TOPS")
-    # spot check of the timed output against the oracle (a few complete rows)
-    import oracle
 
-    rows = np.array([0, 4095, 8191])
-    assert np.array_equal(C3[rows].cpu().numpy(), oracle.gemm_pm1(a3[rows], w3)), "C3 output differs from the oracle"
-    used = q.qnn_last_engine()
-    used_name = {q.ENGINE_VALU: "valu", q.ENGINE_MFMA: "mfma", q.ENGINE_MFMA_FP4: "fp4"}[used]
-    if used == q.ENGINE_MFMA_FP4:
-        roof = {"bound": "mfma", "achieved": tops3, "peak": MFMA_FP4_PEAK_TOPS, "unit": "TOP/s",
-                "frac": tops3 / MFMA_FP4_PEAK_TOPS, "traffic": None, "kernel": "gemm_mfma_kernel<fp4>",
-                "peak_dtype": "fp4 (E2M1) dense MFMA, fp32 accumulate"}
-    elif used == q.ENGINE_MFMA:
-        roof = {"bound": "mfma", "achieved": tops3, "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
-                "frac": tops3 / MFMA_I8_PEAK_TOPS, "traffic": None, "kernel": "gemm_mfma_kernel",
-                "peak_dtype": "int8 dense MFMA, int32 accumulate"}
-    else:
-        roof = {"bound": "alu", "achieved": tops3, "peak": VALU_PEAK_TOPS, "unit": "TOP/s",
-                "frac": tops3 / VALU_PEAK_TOPS, "traffic": None, "kernel": "gemm_valu_kernel",
-                "peak_dtype": "integer vector ALU: one xor and one popcount-accumulate per 32 MACs"}
-    roof["frac_of_int8_mfma_peak"] = tops3 / MFMA_I8_PEAK_TOPS
-    roof["frac_of_valu_xor_popcount_peak"] = tops3 / VALU_PEAK_TOPS
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
-        try:
-            t = json.load(open(tpath)).get(roof["kernel"] + "@c3")
-            if t:
-                roof["traffic"] = t["fetch_bytes"] + t["write_bytes"]  # HBM bytes per launch, measured (profiles/)
-                roof["traffic_detail"] = t
-        except Exception:
-            pass
+    def run_c3():
+        if engine is None:
+            q.qnn_binary_gemm(A3, W3, n, out=C3)  # the plain entry point, as a user calls it
+        else:
+            q.qnn_binary_gemm(A3, W3, n, out=C3, engine=engine)
 
-    if args.traffic_probe:
-        D3 = torch.empty_like(C3)
-        for _ in range(3):
-            D3.copy_(C3)  # 268 435 456 bytes read + the same written per call
-        # two more kernels of known size, with the plain loads / stores the GEMM itself uses: a fill (268 435 456 bytes
-        # written, nothing read) and the sign+pack kernel (268 435 456 bytes read, 8 388 608 written)
-        xf = torch.randn((n, n), dtype=torch.float32, device="cuda")
-        pk = torch.empty((n, n // 32), dtype=torch.int32, device="cuda")
-        for _ in range(3):
-            D3.zero_()
-            q.qnn_pack_sign(xf, out=pk)
-        torch.cuda.synchronize()
-        del D3, xf, pk
-
-    # ---------------------------------------------------------------- C3 with sign+pack from fp32 included
-    if "c3" in only:
-        xf = torch.randn((n, n), dtype=torch.float32, device="cuda")  # values are irrelevant to the cost
-        pk = torch.empty((n, n // 32), dtype=torch.int32, device="cuda")
-        msp, _ = time_steps(lambda: q.qnn_pack_sign(xf, out=pk), sec_steps, sec_warm)
-        extra["pack_sign_8192x8192"] = {"ms": msp, "GBps": (n * n * 4 + n * n / 8) / (msp * 1e-3) / 1e9,
-                                        "frac_of_hbm_peak": (n * n * 4 + n * n / 8) / (msp * 1e-3) / 1e9 / HBM_PEAK_GBS}
-        extra["c3_tops_including_pack_of_both_operands_from_fp32"] = ops3 / ((ms3 + 2 * msp) * 1e-3) / 1e12
-        del xf, pk
-        # the two other bandwidth-bound kernels of the path at the same size: the stand-alone threshold + repack over
-        # the 8192^2 int32 product, and the bit-plane split of 8-bit codes
-        thr = torch.zeros((n,), dtype=torch.int32, device="cuda")
-        tb = torch.empty((n, n // 32), dtype=torch.int32, device="cuda")
-        mst, _ = time_steps(lambda: q.qnn_threshold_sign(C3, thr, None, out=tb), sec_steps, sec_warm)
-        gb = (n * n * 4 + n * n / 8 + n * 4) / (mst * 1e-3) / 1e9
-        extra["threshold_sign_8192x8192"] = {"ms": mst, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
-        codes = torch.randint(0, 256, (n, n), dtype=torch.uint8, device="cuda")
-        pl = torch.empty((8, n, n // 32), dtype=torch.int32, device="cuda")
-        msb, _ = time_steps(lambda: q.qnn_pack_bitplanes(codes, 8, out=pl), sec_steps, sec_warm)
-        gb = (n * n + n * n) / (msb * 1e-3) / 1e9
-        extra["pack_bitplanes_8192x8192_8bit"] = {"ms": msb, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
-        del thr, tb, codes, pl
-
-    # ---------------------------------------------------------------- C2: MNIST-shaped MLP forward
     if "c2" in only:
         dims = [784, 4096, 4096, 4096, 10]
         batch = 10000
-        x2 = dev(qi.uniform_int(seed, 20, (batch, 784), 0, 255, dtype=np.uint8))
-        W2 = [dev(np_pack_pm1(qi.pm1(seed, 21 + l, (dims[l + 1], dims[l])))) for l in range(4)]
-        T2 = [dev(qi.uniform_int(seed, 25 + l, (dims[l + 1],), -64, 64)) for l in range(3)]
-        ws = torch.empty(q.qnn_binary_mlp_workspace_bytes(batch, 8, dims), dtype=torch.uint8, device="cuda")
-        lg = torch.empty((batch, 10), dtype=torch.int32, device="cuda")
-        ms2, _ = time_steps(lambda: q.qnn_binary_mlp_forward(x2, 8, dims, W2, T2, logits=lg, workspace=ws, engine=engine),
-                            sec_steps, sec_warm)
-        bin_mac = batch * (8 * 784 * 4096 + 2 * 4096 * 4096 + 4096 * 10)
-        int_mac = batch * (784 * 4096 + 2 * 4096 * 4096 + 4096 * 10)
-        extra["c2_mlp_forward"] = {"ms": ms2, "samples_per_s": batch / (ms2 * 1e-3),
-                                   "binary_tops_bitplane_accounting": 2.0 * bin_mac / (ms2 * 1e-3) / 1e12,
-                                   "effective_integer_tmacs": int_mac / (ms2 * 1e-3) / 1e12}
-        log(f"[bench] C2 MLP: {ms2:.4f} ms, {batch / (ms2 * 1e-3):.0f} samples/s")
+        x2h = qi.uniform_int(seed, 20, (batch, 784), 0, 255, dtype=np.uint8)
+        W2h = [qi.pm1(seed, 21 + l, (dims[l + 1], dims[l])) for l in range(4)]
+        T2h = [qi.uniform_int(seed, 25 + l, (dims[l + 1],), -64, 64) for l in range(3)]
+        idx2 = np.unique(np.concatenate([[0, 255, 256, 9999], (qi.raw_u64(seed, 29, 60) % np.uint64(batch)).astype(np.int64)]))
+        want2 = oracle.mlp(x2h[idx2], W2h, T2h)
+        x2 = dev(x2h)
+        W2 = [dev(np_pack_pm1(w)) for w in W2h]
+        T2 = [dev(t) for t in T2h]
+        ws2 = torch.empty(q.qnn_binary_mlp_workspace_bytes(batch, 8, dims), dtype=torch.uint8, device="cuda")
+        lg2 = torch.empty((batch, 10), dtype=torch.int32, device="cuda")
 
-    # ---------------------------------------------------------------- C1: small GEMM + sign-binarize (latency)
+        def run_c2():
+            q.qnn_binary_mlp_forward(x2, 8, dims, W2, T2, logits=lg2, workspace=ws2, engine=engine)
+
+        def job_c2():
+            ms2 = time_steps(run_c2, sec_steps, sec_warm)
+            engines = q.qnn_last_engines()
+            ok = np.array_equal(lg2[idx2].cpu().numpy(), want2)
+            int_mac = [batch * dims[l] * dims[l + 1] for l in range(4)]
+            # per-layer time at the peak of the engine that ran it (output layer: its HBM bytes at the HBM peak)
+            t_roof = 0.0
+            for l in range(3):
+                t_roof += 2.0 * int_mac[l] / (ENGINE_PEAK[engines[l]] * 1e12)
+            out_bytes = batch * 128 * 4 + 10 * 128 * 4 + batch * 10 * 4
+            t_roof += out_bytes / (HBM_PEAK_GBS * 1e9)
+            # the output layer alone (10 neurons: bound by reading the 5 MB of packed activations)
+            act = torch.zeros((batch, 128), dtype=torch.int32, device="cuda")
+            ms_out = time_steps(lambda: q.qnn_binary_gemm(act, W2[3], 4096, out=lg2), sec_steps, sec_warm)
+            extra["c2_mlp_forward"] = {
+                "parity_sample_ok": bool(ok), "ms": ms2 if ok else None,
+                "samples_per_s": batch / (ms2 * 1e-3) if ok else None,
+                "engines_per_layer": [ENGINE_NAMES[e] for e in engines],
+                "effective_integer_tmacs": sum(int_mac) / (ms2 * 1e-3) / 1e12 if ok else None,
+                "binary_tops_bitplane_accounting": 2.0 * (int_mac[0] * 8 + sum(int_mac[1:])) / (ms2 * 1e-3) / 1e12 if ok else None,
+                "output_layer": {"ms": ms_out, "GBps": out_bytes / (ms_out * 1e-3) / 1e9,
+                                 "frac_of_hbm_peak": out_bytes / (ms_out * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            }
+            extra["roofline_c2"] = {
+                "bound": "mfma", "unit": "ms", "sum_of_layer_times_at_peak_ms": t_roof * 1e3, "measured_ms": ms2,
+                "frac": t_roof * 1e3 / ms2 if ok else None,
+                "peaks": "layer 1 int8 MFMA 5000 TOP/s, hidden layers FP4 MFMA 10100 TOP/s (as run), output layer HBM 8 TB/s",
+            }
+            log(f"[bench] C2 MLP: {ms2:.4f} ms, {batch / (ms2 * 1e-3):.0f} samples/s, parity sample {'ok' if ok else 'FAILED'}")
+
+        jobs.append(job_c2)
+
+    if "c4" in only:
+        B, H, Wd, Cin, Cout = 256, 13, 13, 384, 256
+        u4 = qi.uniform_int(seed, 40, (B, H, Wd, Cin), 0, 3)
+        w4 = qi.pm1(seed, 41, (Cout, 3, 3, Cin))
+        idx4 = np.array([0, 100, B - 1])
+        want4 = oracle.conv2d(u4[idx4], w4.astype(np.int32), 1, 1)
+        up4 = dev(np.stack([np_pack_bits((u4 >> p) & 1) for p in range(2)]))
+        wp4 = dev(np_pack_pm1(w4)[None])
+        o4 = torch.empty((B, H, Wd, Cout), dtype=torch.int32, device="cuda")
+
+        def job_c4():
+            ms4 = time_steps(lambda: q.qnn_bitplane_conv2d(up4, [1, 2], q.PLANE_BIT, Cin, wp4, [1], q.PLANE_SIGN, 1, 1,
+                                                           out=o4, engine=engine), sec_steps, sec_warm)
+            eng = q.qnn_last_engine()
+            ok = np.array_equal(o4[idx4].cpu().numpy(), want4)
+            imac = B * H * Wd * 9 * Cin * Cout
+            extra["c4_conv_alexnet"] = {"parity_sample_ok": bool(ok), "ms": ms4 if ok else None,
+                                        "effective_integer_tmacs": imac / (ms4 * 1e-3) / 1e12 if ok else None,
+                                        "binary_tops_bitplane_accounting": 2.0 * 2 * imac / (ms4 * 1e-3) / 1e12 if ok else None,
+                                        **(frac_fields(2.0 * imac, ms4, eng) if ok else {})}
+
+        jobs.append(job_c4)
+
+    if "c5" in only:
+        M5, K5, N5 = 2240, 2048, 4096
+        a5 = qi.uniform_int(seed, 50, (M5, K5), -8, 7)
+        w5 = qi.uniform_int(seed, 51, (N5, K5), -8, 7)
+        idx5 = np.unique(np.concatenate([[0, 255, 256, M5 - 1], (qi.raw_u64(seed, 52, 28) % np.uint64(M5)).astype(np.int64)]))
+        want5 = oracle.gemm_int(a5[idx5], w5)
+        ap5 = dev(np.stack([np_pack_bits((a5 >> p) & 1) for p in range(4)]))
+        wp5 = dev(np.stack([np_pack_bits((w5 >> p) & 1) for p in range(4)]))
+        o5 = torch.empty((M5, N5), dtype=torch.int32, device="cuda")
+        coef = [1, 2, 4, -8]
+
+        def job_c5():
+            ms5 = time_steps(lambda: q.qnn_bitplane_gemm(ap5, coef, q.PLANE_BIT, wp5, coef, q.PLANE_BIT, K5, out=o5,
+                                                         engine=engine), sec_steps, sec_warm)
+            eng = q.qnn_last_engine()
+            ok = np.array_equal(o5[idx5].cpu().numpy(), want5)
+            imac = M5 * N5 * K5
+            extra["c5_lstm_int4"] = {"parity_sample_ok": bool(ok), "ms": ms5 if ok else None,
+                                     "effective_integer_tmacs": imac / (ms5 * 1e-3) / 1e12 if ok else None,
+                                     "binary_tops_bitplane_accounting": 2.0 * 16 * imac / (ms5 * 1e-3) / 1e12 if ok else None,
+                                     **(frac_fields(2.0 * imac, ms5, eng) if ok else {})}
+
+        jobs.append(job_c5)
+
     if "c1" in only:
-        xa, xw = dev(qi.normal_f32(seed, 10, (128, 1024))), dev(qi.normal_f32(seed, 11, (1024, 1024)))
+        xa_h, xw_h = qi.normal_f32(seed, 10, (128, 1024)), qi.normal_f32(seed, 11, (1024, 1024))
+        want1 = oracle.gemm_pm1(oracle.sign(xa_h), oracle.sign(xw_h))
+        xa, xw = dev(xa_h), dev(xw_h)
         A1 = torch.empty((128, 32), dtype=torch.int32, device="cuda")
         W1 = torch.empty((1024, 32), dtype=torch.int32, device="cuda")
         C1 = torch.empty((128, 1024), dtype=torch.int32, device="cuda")
@@ -195,38 +240,116 @@ def main():
             q.qnn_pack_sign(xw, out=W1)
             q.qnn_binary_gemm(A1, W1, 1024, out=C1, engine=engine)
 
-        ms1, wall1 = time_steps(c1, max(steps, 50), 10)
-        ms1g, _ = time_steps(lambda: q.qnn_binary_gemm(A1, W1, 1024, out=C1, engine=engine), max(steps, 50), 10)
-        extra["c1_pack_pack_gemm_128x1024x1024"] = {"us_gpu": ms1 * 1e3, "us_wall": wall1 * 1e3, "us_gemm_only": ms1g * 1e3}
+        def job_c1():
+            ms1 = time_steps(c1, max(sec_steps, 100), sec_warm)
+            ok = np.array_equal(C1.cpu().numpy(), want1)
+            ms1g = time_steps(lambda: q.qnn_binary_gemm(A1, W1, 1024, out=C1, engine=engine), max(sec_steps, 100), sec_warm)
+            # cold: 72 rotating copies of the fp32 inputs (325 MB > the 256 MB last-level cache), one event pair per call
+            nset = 72
+            xas = [xa.clone() for _ in range(nset)]
+            xws = [xw.clone() for _ in range(nset)]
+            state = {"i": 0}
 
-    # ---------------------------------------------------------------- C4: AlexNet-shaped conv, 1-bit W x 2-bit A
-    if "c4" in only:
-        B, H, Wd, Cin, Cout = 256, 13, 13, 384, 256
-        u = qi.uniform_int(seed, 40, (B, H, Wd, Cin), 0, 3)
-        up = dev(np.stack([np_pack_bits((u >> p) & 1) for p in range(2)]))
-        wp = dev(np_pack_pm1(qi.pm1(seed, 41, (Cout, 3, 3, Cin)))[None])
-        o4 = torch.empty((B, H, Wd, Cout), dtype=torch.int32, device="cuda")
-        ms4, _ = time_steps(lambda: q.qnn_bitplane_conv2d(up, [1, 2], q.PLANE_BIT, Cin, wp, [1], q.PLANE_SIGN, 1, 1,
-                                                          out=o4, engine=engine), sec_steps, sec_warm)
-        imac = B * H * Wd * 9 * Cin * Cout
-        extra["c4_conv_alexnet"] = {"ms": ms4, "binary_tops_bitplane_accounting": 2.0 * 2 * imac / (ms4 * 1e-3) / 1e12,
-                                    "effective_integer_tmacs": imac / (ms4 * 1e-3) / 1e12}
+            def c1_cold():
+                i = state["i"] % nset
+                state["i"] += 1
+                q.qnn_pack_sign(xas[i], out=A1)
+                q.qnn_pack_sign(xws[i], out=W1)
+                q.qnn_binary_gemm(A1, W1, 1024, out=C1, engine=engine)
 
-    # ---------------------------------------------------------------- C5: 4-bit x 4-bit LSTM gate GEMM
-    if "c5" in only:
-        M, K, N = 2240, 2048, 4096
-        a5 = qi.uniform_int(seed, 50, (M, K), -8, 7)
-        w5 = qi.uniform_int(seed, 51, (N, K), -8, 7)
-        ap5 = dev(np.stack([np_pack_bits((a5 >> p) & 1) for p in range(4)]))
-        wp5 = dev(np.stack([np_pack_bits((w5 >> p) & 1) for p in range(4)]))
-        o5 = torch.empty((M, N), dtype=torch.int32, device="cuda")
-        coef = [1, 2, 4, -8]
-        ms5, _ = time_steps(lambda: q.qnn_bitplane_gemm(ap5, coef, q.PLANE_BIT, wp5, coef, q.PLANE_BIT, K, out=o5,
-                                                        engine=engine), sec_steps, sec_warm)
-        extra["c5_lstm_int4"] = {"ms": ms5, "binary_tops_bitplane_accounting": 2.0 * 16 * M * N * K / (ms5 * 1e-3) / 1e12,
-                                 "effective_integer_tmacs": M * N * K / (ms5 * 1e-3) / 1e12}
+            for _ in range(nset):
+                c1_cold()
+            cold = per_call_ms(c1_cold, 2 * nset)
+            extra["c1_pack_pack_gemm_128x1024x1024"] = {
+                "parity_ok": bool(ok), "us_warm": ms1 * 1e3 if ok else None, "us_gemm_only_warm": ms1g * 1e3,
+                "us_cold_inputs_median": statistics.median(cold) * 1e3, "us_cold_inputs_min": min(cold) * 1e3,
+                "note": "three launches (two sign+pack, one product); cold = fp32 inputs rotated over 325 MB"}
 
-    # ---------------------------------------------------------------- CPU baseline: the oracle, as it stands
+        jobs.append(job_c1)
+
+    if "c3" in only:
+        def job_bw():
+            # the bandwidth-bound kernels of the path at 8192 x 8192: sign+pack from fp32, threshold+repack of the int32
+            # product, bit-plane split of 8-bit codes
+            xf = torch.randn((n, n), dtype=torch.float32, device="cuda")  # values are irrelevant to the cost
+            pk = torch.empty((n, n // 32), dtype=torch.int32, device="cuda")
+            msp = time_steps(lambda: q.qnn_pack_sign(xf, out=pk), sec_steps, sec_warm)
+            gb = (n * n * 4 + n * n / 8) / (msp * 1e-3) / 1e9
+            extra["pack_sign_8192x8192"] = {"ms": msp, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
+            del xf, pk
+            thr = torch.zeros((n,), dtype=torch.int32, device="cuda")
+            tb = torch.empty((n, n // 32), dtype=torch.int32, device="cuda")
+            mst = time_steps(lambda: q.qnn_threshold_sign(C3, thr, None, out=tb), sec_steps, sec_warm)
+            gb = (n * n * 4 + n * n / 8 + n * 4) / (mst * 1e-3) / 1e9
+            extra["threshold_sign_8192x8192"] = {"ms": mst, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
+            codes = torch.randint(0, 256, (n, n), dtype=torch.uint8, device="cuda")
+            pl = torch.empty((8, n, n // 32), dtype=torch.int32, device="cuda")
+            msb = time_steps(lambda: q.qnn_pack_bitplanes(codes, 8, out=pl), sec_steps, sec_warm)
+            gb = (n * n + n * n) / (msb * 1e-3) / 1e9
+            extra["pack_bitplanes_8192x8192_8bit"] = {"ms": msb, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
+
+        jobs.append(job_bw)
+
+    # ================================================================ GPU work, back to back
+    primary = {}
+
+    def job_primary():
+        primary["sclk_before"] = q.qnn_probe_shader_clock()
+        primary["ms"] = time_steps(run_c3, steps, warmup)
+        primary["sclk_after"] = q.qnn_probe_shader_clock()
+        primary["engine"] = q.qnn_last_engine()
+        primary["parity"] = bool(np.array_equal(C3[rows3].cpu().numpy(), want3))
+        calls = per_call_ms(run_c3, 60)
+        primary["per_call"] = calls
+        primary["sclk_end"] = q.qnn_probe_shader_clock()
+
+    log("[bench] GPU phase")
+    order = [job_primary] + jobs if args.primary_first else jobs + [job_primary]
+    for job in order:
+        job()
+    ms3 = primary["ms"]
+    assert primary["parity"], "C3 output differs from the oracle: no throughput is reported"
+    tops3 = ops3 / (ms3 * 1e-3) / 1e12
+    used = primary["engine"]
+    used_name = ENGINE_NAMES[used]
+    sclk = 0.5 * (primary["sclk_before"] + primary["sclk_after"])
+    log(f"[bench] C3 8192^3: {ms3:.4f} ms/step, {tops3:.1f} binary TOPS, shader clock {primary['sclk_before']:.0f} -> "
+        f"{primary['sclk_after']:.0f} MHz")
+    extra["c3_tops_including_pack_of_both_operands_from_fp32"] = (
+        ops3 / ((ms3 + 2 * extra["pack_sign_8192x8192"]["ms"]) * 1e-3) / 1e12 if "pack_sign_8192x8192" in extra else None)
+
+    peak = ENGINE_PEAK[used]
+    roof = {"bound": "alu" if used == 1 else "mfma", "achieved": tops3, "peak": peak, "unit": "TOP/s", "frac": tops3 / peak,
+            "traffic": None,
+            "kernel": {1: "gemm_valu_kernel", 2: "gemm_mfma_kernel", 3: "gemm_mfma_kernel<fp4>"}[used],
+            "peak_dtype": {1: "integer vector ALU: one xor and one popcount-accumulate per 32 MACs",
+                           2: "int8 dense MFMA, int32 accumulate",
+                           3: "fp4 (E2M1) dense MFMA, fp32 accumulate"}[used],
+            "frac_at_observed_clock": tops3 / (peak * sclk / NOMINAL_MHZ) if sclk == sclk and sclk > 0 else None,
+            "frac_of_int8_mfma_peak": tops3 / MFMA_I8_PEAK_TOPS,
+            "frac_of_valu_xor_popcount_peak": tops3 / VALU_PEAK_TOPS}
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            t = json.load(open(tpath)).get(roof["kernel"] + "@c3")
+            if t:
+                roof["traffic"] = t["fetch_bytes"] + t["write_bytes"]  # HBM bytes per launch from the committed rocprofv3 runs
+                roof["traffic_detail"] = t
+        except Exception:
+            pass
+
+    if args.traffic_probe:
+        D3 = torch.empty_like(C3)
+        xf = torch.randn((n, n), dtype=torch.float32, device="cuda")
+        pk = torch.empty((n, n // 32), dtype=torch.int32, device="cuda")
+        for _ in range(3):
+            D3.copy_(C3)  # 268 435 456 bytes read + the same written per call
+            D3.zero_()    # 268 435 456 bytes written, nothing read
+            q.qnn_pack_sign(xf, out=pk)  # 268 435 456 bytes read, 8 388 608 written
+        torch.cuda.synchronize()
+        del D3, xf, pk
+
+    # ================================================================ CPU baseline: the oracle, as it stands
     cpu = None
     if not args.no_cpu_baseline:
         log("[bench] timing the CPU oracle on a sample of C3")
@@ -246,8 +369,9 @@ def main():
                "kind": "oracle",
                "sample": f"{reps} x the first {nrows} of 8192 rows of the C3 product (plain int8 multiply-accumulate, {dt:.1f} s)"}
 
+    calls = primary["per_call"]
     out = {
-        "metric": "binary GEMM TOPS (1 +-1 MAC = 2 ops) at 8192^3",
+        "metric": "binary GEMM TOPS (1 +-1 MAC = 2 ops) at 8192^3 + MLP forward samples/sec",
         "value": tops3,
         "unit": "TOPS",
         "n_gpus": 1,
@@ -262,9 +386,16 @@ def main():
                   "valu": "u32 bit-packed +-1 operands, xor + popcount, int32 accumulate"}[used_name],
         "data": "synthetic (seeded Bernoulli(0.5) +-1 operands; stands in for the paper's 8192^3 benchmark matrices)",
         "config": {"workload": "C3: 8192x8192x8192 binary GEMM on packed +-1 operands, int32 output",
-                   "engine": used_name, "M": n, "N": n, "K": n},
+                   "engine": used_name, "M": n, "N": n, "K": n,
+                   "order": "primary first" if args.primary_first else "primary after the secondary configurations"},
         "mlp_forward_samples_per_s": extra.get("c2_mlp_forward", {}).get("samples_per_s"),
+        "sclk_mhz": {"before_timed_region": primary["sclk_before"], "after_timed_region": primary["sclk_after"],
+                     "after_per_call_pass": primary["sclk_end"], "nominal": NOMINAL_MHZ},
+        "per_call_ms": {"calls": len(calls), "median": statistics.median(calls), "min": min(calls),
+                        "first5": calls[:5], "last5": calls[-5:],
+                        "note": "a separate pass after the timed region, one event pair per call"},
         "roofline": roof,
+        "roofline_c2": extra.pop("roofline_c2", None),
         "cpu_baseline": cpu,
         "secondary": extra,
         "paper_context": "paper reports only ratios on a GTX750: XNOR kernel 23x its baseline kernel, 3.4x cuBLAS at 8192^3; MLP 7x",

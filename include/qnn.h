@@ -58,8 +58,11 @@ typedef enum {
     QNN_ENGINE_AUTO = 0, /* library's choice for the shape */
     QNN_ENGINE_VALU = 1, /* 32 connections per xor/and + popcount-accumulate pair (Sec. 6 Eq. (popc)) */
     QNN_ENGINE_MFMA = 2, /* bits expanded on chip to int8 and contracted on the matrix cores */
-    QNN_ENGINE_MFMA_FP4 = 3 /* single-plane operands expanded to FP4 zeros and ones, contracted on the matrix cores with
-                               fp32 accumulation (exact: the sums are integers far below 2^24) */
+    QNN_ENGINE_MFMA_FP4 = 3, /* single-plane operands expanded to FP4 zeros and ones, contracted on the matrix cores
+                                with fp32 accumulation (exact: the sums are integers far below 2^24) */
+    QNN_ENGINE_MFMA_LDS = 4 /* as QNN_ENGINE_MFMA for operands of several bit planes: a workgroup merges the planes
+                               into int8 once, in LDS (16-byte aligned operands with rows of whole groups of four
+                               words, plane counts 1, 2, 4 or 8, coefficients a common factor times 1, 2, 4, ...) */
 } qnn_engine;
 
 #define QNN_MAX_PLANES 8
@@ -193,6 +196,16 @@ int qnn_bitplane_conv2d_ex(const uint32_t *A, int Pa, const int32_t *coefA, int 
                            const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
                            int pad, int stride_hw, int32_t *out, int engine, void *stream);
 
+/* Convolution with Sign(BatchNorm(.)) fused (a layer of a binarized ConvNet, Alg. 4 with the filter banks of Sec. 5 and
+ * App. A): bit[b][y][x][co] = (sum >= T[co]) xor flip[co], written packed along the output channels, which are the
+ * next layer's input channels: out_bits is DEVICE uint32 [B][Ho][Wo][ceil(Cout/32)] dense, tail bits zero.
+ * T: DEVICE int32 [Cout]; flip: DEVICE uint8 [Cout] or NULL.  Other arguments as qnn_bitplane_conv2d_ex. */
+int qnn_bitplane_conv2d_sign(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t strideA_words,
+                             int64_t B, int64_t H, int64_t Wd, int64_t Cin, const uint32_t *W, int Pb,
+                             const int32_t *coefW, int modeW, int64_t strideW_words, int64_t Cout, int KH, int KW,
+                             int pad, int stride_hw, const int32_t *T, const uint8_t *flip, uint32_t *out_bits,
+                             int engine, void *stream);
+
 /* Engine (QNN_ENGINE_VALU, QNN_ENGINE_MFMA or QNN_ENGINE_MFMA_FP4) that the calling thread's last successful multiply call used; 0 before
  * any.  For reports: results never depend on it. */
 int qnn_last_engine(void);
@@ -200,6 +213,16 @@ int qnn_last_engine(void);
 /* Engines of the multiply launches made by the calling thread's last successful multiply / forward call, in launch
  * order (one entry per layer for the forward calls): writes min(count, capacity) entries, returns the count. */
 int qnn_last_engines(int *engines, int capacity);
+
+/* Measurement helper, not a step of the path: one wave spins for some ten microseconds and writes to
+ * out3 (DEVICE, three uint64, 8-byte aligned) {elapsed shader-clock cycles, elapsed ticks of the constant 100 MHz
+ * real-time counter, a checksum}; 100 * out3[0] / out3[1] is the shader clock in MHz at that moment. */
+int qnn_probe_shader_clock(unsigned long long *out3, void *stream);
+
+/* Measurement helper: one wave writes to out3 (DEVICE, three uint64, 8-byte aligned) {shader-clock counter, 100 MHz
+ * real-time counter, id of the accelerator die it ran on}, in stream order.  Two stamps around a stretch of work on
+ * one stream, taken on the same die, give the average shader clock over that stretch. */
+int qnn_stamp_clocks(unsigned long long *out3, void *stream);
 
 const char *qnn_last_error(void);
 const char *qnn_version(void);

@@ -14,7 +14,7 @@ from typing import Optional, Sequence
 import torch
 
 PLANE_BIT, PLANE_SIGN = 0, 1
-ENGINE_AUTO, ENGINE_VALU, ENGINE_MFMA, ENGINE_MFMA_FP4 = 0, 1, 2, 3
+ENGINE_AUTO, ENGINE_VALU, ENGINE_MFMA, ENGINE_MFMA_FP4, ENGINE_MFMA_LDS = 0, 1, 2, 3, 4
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqnn.so")
@@ -40,12 +40,16 @@ _SIGS = {
     "qnn_bitplane_gemm_sign": [_vp, _int, _vp, _int, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _vp, _vp, _vp, _i64,
                                _i64, _i64, _i64, _int, _vp],
     "qnn_threshold_sign": [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _vp],
+    "qnn_probe_shader_clock": [_vp, _vp],
+    "qnn_stamp_clocks": [_vp, _vp],
     "qnn_fold_batchnorm": [_vp, _vp, _vp, _vp, C.c_double, _i64, _vp, _vp],
     "qnn_binary_mlp_forward": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp],
     "qnn_binary_mlp_forward_ex": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _int, _vp],
     "qnn_binary_mlp_forward_static": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp],
     "qnn_bitplane_conv2d": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
                             _int, _int, _int, _vp, _vp],
+    "qnn_bitplane_conv2d_sign": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
+                                 _int, _int, _int, _vp, _vp, _vp, _int, _vp],
     "qnn_bitplane_conv2d_ex": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
                                _int, _int, _int, _vp, _int, _vp],
 }
@@ -125,6 +129,27 @@ def qnn_last_engines() -> list:
     buf = (C.c_int * 32)()
     n = int(_lib.qnn_last_engines(buf, 32))
     return [int(buf[i]) for i in range(min(n, 32))]
+
+
+def qnn_probe_shader_clock() -> float:
+    """Shader clock in MHz right now (synchronizes: measurement helper only)."""
+    out = torch.zeros(3, dtype=torch.int64, device="cuda")
+    _check(_lib.qnn_probe_shader_clock(out.data_ptr(), _stream()))
+    c, r, _ = out.cpu().tolist()
+    return 100.0 * c / r if r else float("nan")
+
+
+def qnn_stamp_clocks(out: torch.Tensor) -> None:
+    """Enqueues a stamp {shader-clock counter, 100 MHz counter, die id} into out (int64[3] on the GPU)."""
+    _check(_lib.qnn_stamp_clocks(_dev(out, torch.int64, "out"), _stream()))
+
+
+def average_shader_clock_mhz(stamp0: torch.Tensor, stamp1: torch.Tensor) -> Optional[float]:
+    """Average shader clock between two stamps (None if they were taken on different dies or are degenerate)."""
+    a, b = stamp0.cpu().tolist(), stamp1.cpu().tolist()
+    if a[2] != b[2] or b[1] <= a[1] or b[0] <= a[0]:
+        return None
+    return 100.0 * (b[0] - a[0]) / (b[1] - a[1])
 
 
 def qnn_version() -> str:
@@ -312,4 +337,29 @@ def qnn_bitplane_conv2d(A: torch.Tensor, coefA: Sequence[int], modeA: int, Cin: 
         _check(_lib.qnn_bitplane_conv2d(*args, _stream()))
     else:
         _check(_lib.qnn_bitplane_conv2d_ex(*args, engine, _stream()))
+    return out
+
+
+def qnn_bitplane_conv2d_sign(A: torch.Tensor, coefA: Sequence[int], modeA: int, Cin: int, W: torch.Tensor,
+                             coefW: Sequence[int], modeW: int, pad: int, stride: int, T: torch.Tensor,
+                             flip: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None,
+                             engine: int = ENGINE_AUTO) -> torch.Tensor:
+    """A: [Pa][B][H][W][Cw], W: [Pb][Cout][KH][KW][Cw] (dense) -> packed bits [B][Ho][Wo][ceil(Cout/32)]."""
+    if A.dim() != 5 or W.dim() != 5 or not A.is_contiguous() or not W.is_contiguous():
+        raise ValueError("A must be dense [Pa][B][H][W][Cw] and W dense [Pb][Cout][KH][KW][Cw]")
+    Pa, B, H, Wd, Cw = A.shape
+    Pb, Cout, KH, KW, Cw2 = W.shape
+    if Cw != words_for(Cin) or Cw2 != Cw:
+        raise ValueError("channel words do not match Cin")
+    Ho = (H + 2 * pad - KH) // stride + 1
+    Wo = (Wd + 2 * pad - KW) // stride + 1
+    if out is None:
+        out = torch.empty((B, Ho, Wo, words_for(Cout)), dtype=torch.int32, device=A.device)
+    if not out.is_contiguous() or tuple(out.shape) != (B, Ho, Wo, words_for(Cout)):
+        raise ValueError("out must be dense [B][Ho][Wo][ceil(Cout/32)]")
+    _check(_lib.qnn_bitplane_conv2d_sign(_dev(A, torch.int32, "A"), Pa, _coef(coefA), modeA, A.stride(0) if Pa > 1 else 0,
+                                         B, H, Wd, Cin, _dev(W, torch.int32, "W"), Pb, _coef(coefW), modeW,
+                                         W.stride(0) if Pb > 1 else 0, Cout, KH, KW, pad, stride,
+                                         _dev(T, torch.int32, "T"), _dev(flip, torch.uint8, "flip"),
+                                         _dev(out, torch.int32, "out"), engine, _stream()))
     return out

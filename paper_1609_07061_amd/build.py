@@ -11,8 +11,9 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libqnn.so")
-SOURCES = ["qnn_api.hip", "qnn_pack.hip", "qnn_gemm_valu.hip", "qnn_gemm_mfma.hip", "qnn_gemm_mfma_k0.hip",
-           "qnn_gemm_mfma_k1.hip", "qnn_gemm_mfma_k2.hip", "qnn_gemm_mfma_k3.hip"]
+SOURCES = ["qnn_api.hip", "qnn_probe.hip", "qnn_pack.hip", "qnn_gemm_valu.hip", "qnn_gemm_mfma.hip", "qnn_gemm_mfma_k0.hip",
+           "qnn_gemm_mfma_k1.hip", "qnn_gemm_mfma_k2.hip", "qnn_gemm_mfma_k3.hip", "qnn_gemm_mfma_k4.hip", "qnn_gemm_stage_k0.hip",
+           "qnn_gemm_stage_k1.hip", "qnn_gemm_stage_k2.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc", "-ffp-contract=off",
@@ -30,17 +31,33 @@ def _stale(target: str, deps: list[str]) -> bool:
     return any(os.path.getmtime(d) > t for d in deps)
 
 
+def _deps(path: str, seen: set | None = None) -> list[str]:
+    """The file and, recursively, the project headers it includes with #include "..."."""
+    import re
+
+    seen = set() if seen is None else seen
+    if path in seen or not os.path.exists(path):
+        return []
+    seen.add(path)
+    out = [path]
+    for name in re.findall(r'^\s*#\s*include\s+"([^"]+)"', open(path).read(), flags=re.M):
+        for d in (os.path.dirname(path), CSRC, os.path.join(ROOT, "include")):
+            cand = os.path.join(d, name)
+            if os.path.exists(cand):
+                out += _deps(cand, seen)
+                break
+    return out
+
+
 def build(force: bool = False, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
-    headers = [os.path.join(CSRC, "qnn_internal.h"), os.path.join(ROOT, "include", "qnn.h"), os.path.abspath(__file__)]
-    headers += [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]
     jobs = []
     objs = []
     for src in SOURCES:
         s = os.path.join(CSRC, src)
         o = os.path.join(OBJ, src + ".o")
         objs.append(o)
-        if force or _stale(o, [s] + headers):
+        if force or _stale(o, _deps(s)):
             jobs.append([HIPCC, *FLAGS, "-c", s, "-o", o])
 
     def run(cmd):

@@ -1,6 +1,7 @@
 // Matrix-core engine of the binary / bit-plane matrix product: host side (operand codes, epilogue constants, choice of
 // the kernel instantiation, launch).  The kernel itself is in qnn_gemm_mfma_kernel.h.
 #include "qnn_gemm_mfma_kernel.h"
+#include "qnn_gemm_stage_kernel.h"
 
 namespace qnn {
 
@@ -57,9 +58,38 @@ bool make_code(const Planes &pl, Code &c, int64_t &alpha, int64_t &beta, int64_t
 }
 
 
+// Epilogue constants of C = aA aW (S - npad xA0 xW0) + aA bW RA[m] + bA aW RW[n] + K bA bW for a kernel that processes
+// Kproc >= K elements per row (the surplus reads as zero bits); false if the sums could leave the exact range.
+bool fill_consts(const GemmArgs &g, int64_t aA, int64_t bA, int64_t xA0, int64_t aW, int64_t bW, int64_t xW0,
+                 int64_t Kproc, MfmaConst &mc) {
+    if (g.epi.T) {
+        // the threshold epilogue compares through differences, which must not wrap: |C| < 2^30
+        long double bound = (long double)g.K;
+        long double sa = 0, sw = 0;
+        for (int p = 0; p < g.pa.count; ++p) sa += g.pa.coef[p] < 0 ? -(long double)g.pa.coef[p] : g.pa.coef[p];
+        for (int p = 0; p < g.pw.count; ++p) sw += g.pw.coef[p] < 0 ? -(long double)g.pw.coef[p] : g.pw.coef[p];
+        if (bound * sa * sw >= 1073741824.0L) return false;
+    }
+    if (Kproc >= 131072) return false;  // |S| <= Kproc * 2^14 must stay below 2^31
+    const int64_t npad = Kproc - g.K;
+    mc.msteps = 0;
+    mc.alpha = (uint32_t)(aA * aW);
+    mc.cRA = (uint32_t)(aA * bW);
+    mc.cRW = (uint32_t)(bA * aW);
+    mc.c0 = (uint32_t)(g.K * bA * bW - aA * aW * npad * xA0 * xW0);
+    mc.needRW = mc.cRW != 0;
+    // the row sums are over the true K: RA = sum_p d_p pop_p - K * off; fold the constant part into c0
+    mc.c0 += (uint32_t)(aA * bW * (g.K * xA0)) + (uint32_t)(bA * aW * (g.K * xW0));
+    mc.alpha_shift = -1;
+    for (int sh = 0; sh < 31; ++sh)
+        if (aA * aW == ((int64_t)1 << sh)) mc.alpha_shift = sh;
+    return true;
+}
+
 const Variant *find_variant(const GemmArgs &g) {
     const bool pixels = g.A.rows_are_pixels != 0, sign = g.epi.T != nullptr;
-    const VariantList lists[] = {variants_fp4(), variants_first_layer(), variants_multibit(), variants_conv()};
+    const VariantList lists[] = {variants_fp4(), variants_first_layer(), variants_multibit(), variants_conv(),
+                                   variants_conv_sign()};
     for (const VariantList &l : lists)
         for (int i = 0; i < l.n; ++i) {
             const Variant &v = l.v[i];
@@ -85,30 +115,10 @@ bool prepare(const GemmArgs &g, bool fp4, const Variant *&var, MfmaConst &mc, bo
         if (fp4 && !var->fp4_vec) return false;
         if (!make_code(g.pa, mc.a, aA, bA, xA0) || !make_code(g.pw, mc.w, aW, bW, xW0)) return false;
     }
-    if (g.epi.T) {
-        // the threshold epilogue compares through differences, which must not wrap: |C| < 2^30
-        long double bound = (long double)g.K;
-        long double sa = 0, sw = 0;
-        for (int p = 0; p < g.pa.count; ++p) sa += g.pa.coef[p] < 0 ? -(long double)g.pa.coef[p] : g.pa.coef[p];
-        for (int p = 0; p < g.pw.count; ++p) sw += g.pw.coef[p] < 0 ? -(long double)g.pw.coef[p] : g.pw.coef[p];
-        if (bound * sa * sw >= 1073741824.0L) return false;
-    }
     const int64_t step_words = 2 * var->WPL;
     const int64_t msteps = 2 * ceil_div(g.Kw, 2 * step_words);
-    const int64_t Kproc = msteps * step_words * 32;
-    if (Kproc >= 131072) return false;  // |S| <= Kproc * 2^14 must stay below 2^31
-    const int64_t npad = Kproc - g.K;
+    if (!fill_consts(g, aA, bA, xA0, aW, bW, xW0, msteps * step_words * 32, mc)) return false;
     mc.msteps = (uint32_t)msteps;
-    mc.alpha = (uint32_t)(aA * aW);
-    mc.cRA = (uint32_t)(aA * bW);
-    mc.cRW = (uint32_t)(bA * aW);
-    mc.c0 = (uint32_t)(g.K * bA * bW - aA * aW * npad * xA0 * xW0);
-    mc.needRW = mc.cRW != 0;
-    // the row sums are over the true K: RA = sum_p d_p pop_p - K * off; fold the constant part into c0
-    mc.c0 += (uint32_t)(aA * bW * (g.K * xA0)) + (uint32_t)(bA * aW * (g.K * xW0));
-    mc.alpha_shift = -1;
-    for (int sh = 0; sh < 31; ++sh)
-        if (aA * aW == ((int64_t)1 << sh)) mc.alpha_shift = sh;
     // vector loads need every row (of every plane) to start at a multiple of the load width and to be made of whole
     // chunks, so that a chunk is either all inside or all outside the row
     const int wpl = var->WPL;
@@ -138,14 +148,7 @@ bool mfma_preferred(const GemmArgs &g) {
     return ceil_div(g.M, BM) * ceil_div(g.N, BN) >= 32 && g.K >= 256 && g.M >= 128 && g.N >= 128;
 }
 
-int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
-    const Variant *v;
-    MfmaConst mc;
-    bool vec;
-    if (!prepare(g, fp4, v, mc, vec)) return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
-    const int64_t tiles_m = ceil_div(g.M, BM), tiles_n = ceil_div(g.N, BN);
-    if (tiles_m * tiles_n > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "gemm: too many tiles");
-    // one persistent workgroup per compute unit (each takes 512 registers per lane, so one fits)
+static int compute_units() {
     static thread_local int cus = 0;
     if (cus == 0) {
         int dev = 0, n = 0;
@@ -154,6 +157,18 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
             n = 256;
         cus = n;
     }
+    return cus;
+}
+
+int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
+    const Variant *v;
+    MfmaConst mc;
+    bool vec;
+    if (!prepare(g, fp4, v, mc, vec)) return fail(QNN_ERR_UNSUPPORTED, "matrix-core engine cannot take these arguments");
+    const int64_t tiles_m = ceil_div(g.M, BM), tiles_n = ceil_div(g.N, BN);
+    if (tiles_m * tiles_n > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "gemm: too many tiles");
+    // one persistent workgroup per compute unit (each takes 512 registers per lane, so one fits)
+    const int cus = compute_units();
     const int64_t total = tiles_m * tiles_n;
     const unsigned grid = (unsigned)(total < cus ? total : cus);
     const KernelFn fn = g.A.rows_are_bytes ? byte_kernels()[g.epi.T ? 1 : 0]
@@ -161,6 +176,82 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
                                            : (vec ? v->fn_vec : v->fn_any);
     return QNN_LAUNCH("gemm_mfma", fn, dim3(grid), dim3(kThreads), 0, s, g, mc, (uint32_t)tiles_m,
                        (uint32_t)tiles_n);
+}
+
+// ------------------------------------------------------------------------------------------------ staged kernels
+namespace {
+
+using stage::StageConst;
+typedef void (*StageFn)(const GemmArgs, const MfmaConst, const StageConst, uint32_t, uint32_t);
+
+// One operand for the merge network: bit position q of the code comes from plane order[q]; false if the positions
+// are not exactly 0 .. P-1 or the plane count has no network.
+bool stage_operand(const Planes &pl, const Code &c, int64_t plane_stride, int64_t (&off)[QNN_MAX_PLANES],
+                   uint32_t (&inv)[QNN_MAX_PLANES], int32_t (&d)[QNN_MAX_PLANES]) {
+    const int P = pl.count;
+    if (P != 1 && P != 2 && P != 4 && P != 8) return false;
+    for (int q = 0; q < QNN_MAX_PLANES; ++q) off[q] = 0, inv[q] = 0, d[q] = 0;
+    uint32_t seen = 0;
+    for (int p = 0; p < P; ++p) {
+        const int q = c.lg[p];
+        if (q < 0 || q >= P || (seen & (1u << q))) return false;
+        seen |= 1u << q;
+        off[q] = (int64_t)p * plane_stride;
+        inv[q] = c.inv[p];
+        d[q] = c.d[p];
+    }
+    return true;
+}
+
+bool aligned16(const void *p) { return reinterpret_cast<uintptr_t>(p) % 16 == 0; }
+
+bool prepare_stage(const GemmArgs &g, MfmaConst &mc, StageConst &sc, StageFn &fn) {
+    const bool pix = g.A.rows_are_pixels != 0, sign = g.epi.T != nullptr;
+    if (g.A.rows_are_bytes) return false;
+    std::memset(&sc, 0, sizeof(sc));
+    int64_t aA, bA, xA0, aW, bW, xW0;
+    if (!make_code(g.pa, mc.a, aA, bA, xA0) || !make_code(g.pw, mc.w, aW, bW, xW0)) return false;
+    if (!stage_operand(g.pa, mc.a, g.A.plane_stride, sc.offA, sc.invA, sc.dA)) return false;
+    if (!stage_operand(g.pw, mc.w, g.strideW, sc.offW, sc.invW, sc.dW)) return false;
+    sc.biasA = mc.a.bias, sc.biasW = mc.w.bias;
+    // 16-byte loads: every row of every plane starts on a 16-byte boundary and holds whole groups of four words
+    const bool w_vec = aligned16(g.W) && g.ldw % 4 == 0 && (g.pw.count == 1 || g.strideW % 4 == 0) && g.Kw % 4 == 0;
+    const bool a_vec = aligned16(g.A.base) && (g.pa.count == 1 || g.A.plane_stride % 4 == 0) &&
+                       (pix ? g.A.Cw % 4 == 0 : (g.A.ld % 4 == 0 && g.Kw % 4 == 0));
+    if (!a_vec || !w_vec) return false;
+    // the kernel addresses rows with 32-bit offsets from a plane's base
+    const long double a_span = pix ? 4.0L * (long double)g.M / ((long double)g.A.Ho * g.A.Wo) * g.A.H * g.A.Wd * g.A.Cw
+                                   : 4.0L * (long double)g.M * g.A.ld;
+    if (a_span >= 4294967296.0L || 4.0L * (long double)g.N * g.ldw >= 4294967296.0L) return false;
+    const int64_t nmacro = ceil_div(g.Kw, 4);
+    sc.nmacro = (uint32_t)nmacro;
+    if (!fill_consts(g, aA, bA, xA0, aW, bW, xW0, nmacro * 4 * 32, mc)) return false;
+    fn = stage::find_kernel(g.pa.count, g.pw.count, pix ? stage::kPixelPlanes : stage::kPlanes, sign);
+    return fn != nullptr;
+}
+
+}  // namespace
+
+bool stage_supports(const GemmArgs &g) {
+    MfmaConst mc;
+    StageConst sc;
+    StageFn fn;
+    return prepare_stage(g, mc, sc, fn);
+}
+
+int launch_gemm_stage(const GemmArgs &g, hipStream_t s) {
+    MfmaConst mc;
+    StageConst sc;
+    StageFn fn;
+    if (!prepare_stage(g, mc, sc, fn))
+        return fail(QNN_ERR_UNSUPPORTED, "staged matrix-core kernels cannot take these arguments");
+    const int64_t tiles_m = ceil_div(g.M, 256), tiles_n = ceil_div(g.N, 256);
+    if (tiles_m * tiles_n > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "gemm: too many tiles");
+    const int64_t total = tiles_m * tiles_n;
+    const int cus = compute_units();
+    const unsigned grid = (unsigned)(total < cus ? total : cus);
+    return QNN_LAUNCH("gemm_stage", fn, dim3(grid), dim3(stage::kThreads), 0, s, g, mc, sc, (uint32_t)tiles_m,
+                      (uint32_t)tiles_n);
 }
 
 }  // namespace qnn

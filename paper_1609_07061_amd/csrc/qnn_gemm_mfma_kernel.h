@@ -727,6 +727,7 @@ VariantList variants_fp4();
 VariantList variants_first_layer();
 VariantList variants_multibit();
 VariantList variants_conv();
+VariantList variants_conv_sign();
 // left operand given as uint8 codes, one weight plane: [0] int32 output, [1] thresholded output
 const KernelFn *byte_kernels();
 

@@ -306,7 +306,6 @@ int launch_modes(const GemmArgs &g, hipStream_t s) {
 bool valu_supports(const GemmArgs &g) {
     // packed planes only (a byte-coded left operand belongs to the matrix-core engine)
     if (g.A.rows_are_bytes) return false;
-    if (g.A.rows_are_pixels && g.epi.T) return false;
     return true;
 }
 
@@ -321,7 +320,7 @@ int launch_gemm_valu(const GemmArgs &g, hipStream_t s) {
         return QNN_LAUNCH("gemm_skinny", gemm_skinny_kernel, dim3((unsigned)ceil_div(g.M, kSkinnyRows)), dim3(kThreads), 0, s, g);
     }
     if (pixels) {
-        if (sign) return fail(QNN_ERR_UNSUPPORTED, "conv: thresholded output is not provided");
+        if (sign) return big ? launch_modes<8, 8, true, true>(g, s) : launch_modes<4, 4, true, true>(g, s);
         return big ? launch_modes<8, 8, true, false>(g, s) : launch_modes<4, 4, true, false>(g, s);
     }
     if (sign) return big ? launch_modes<8, 8, false, true>(g, s) : launch_modes<4, 4, false, true>(g, s);

@@ -96,6 +96,9 @@ bool valu_supports(const GemmArgs &g);
 bool mfma_supports(const GemmArgs &g, bool fp4 = false);  // fp4: on the FP4 (E2M1) matrix-core path
 bool mfma_preferred(const GemmArgs &g);  // whether AUTO should pick it for this shape
 int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4 = false);
+// The same engine's kernel for operands of several bit planes, which expands them once per workgroup into LDS.
+bool stage_supports(const GemmArgs &g);
+int launch_gemm_stage(const GemmArgs &g, hipStream_t s);
 
 int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo, hipStream_t s);
 int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,

@@ -16,9 +16,9 @@ from qnn_testlib import dev, host, host_u32, np_pack_bits, np_pack_pm1
 pytestmark = pytest.mark.gpu
 
 q = None
-VALU, MFMA, FP4 = 1, 2, 3
+VALU, MFMA, FP4, MFMA_LDS = 1, 2, 3, 4
 # engine AUTO picks per configuration; bench.py reports the same ones
-AUTO_ENGINE = {"c1": VALU, "c3": FP4, "c4": MFMA, "c5": MFMA}
+AUTO_ENGINE = {"c1": VALU, "c3": FP4, "c4": MFMA_LDS, "c5": MFMA_LDS}
 AUTO_ENGINES_C2 = [MFMA, FP4, FP4, VALU]  # first layer from the 8-bit codes, two hidden layers, 10-neuron output layer
 
 
@@ -131,7 +131,7 @@ def _c4(seed):
     return np_pack_bits(oracle.split_planes(u, 2)), np_pack_pm1(w)[None], oracle.conv2d(u, w.astype(np.int32), 1, 1)
 
 
-@pytest.mark.parametrize("engine", [None, MFMA, VALU])
+@pytest.mark.parametrize("engine", [None, MFMA_LDS, MFMA, VALU])
 def test_config4_alexnet_conv_every_element(seed, engine):
     up, wp, want = _c4(seed)
     got = host(q.qnn_bitplane_conv2d(dev(up), [1, 2], q.PLANE_BIT, 384, dev(wp), [1], q.PLANE_SIGN, 1, 1, engine=engine))
@@ -148,7 +148,7 @@ def _c5(seed):
     return np_pack_bits(oracle.split_planes(a, 4)), np_pack_bits(oracle.split_planes(w, 4)), oracle.gemm_int(a, w)
 
 
-@pytest.mark.parametrize("engine", [None, MFMA, VALU])
+@pytest.mark.parametrize("engine", [None, MFMA_LDS, MFMA, VALU])
 def test_config5_lstm_gates_int4_every_element(seed, engine):
     ap, wp, want = _c5(seed)
     coef = [1, 2, 4, -8]
@@ -223,10 +223,10 @@ def test_many_tiles_first_layer_from_codes(seed, engine):
     assert_same(got, oracle.mlp(x, W, T, flip))
 
 
-@pytest.mark.parametrize("engine", [None, MFMA])
+@pytest.mark.parametrize("engine", [None, MFMA_LDS, MFMA])
 def test_many_tiles_first_layer_planes_threshold_output(seed, engine):
     """Eight input planes x one weight plane with the fused threshold (the plane fall-back of the first layer)."""
-    M, N, K = 4200, 4200, 320
+    M, N, K = 4200, 4200, 384
     x = qi.uniform_int(seed, 75, (M, K), 0, 255)
     w = qi.pm1(seed, 76, (N, K))
     T = qi.uniform_int(seed, 77, (N,), -1500, 1500)
@@ -234,11 +234,11 @@ def test_many_tiles_first_layer_planes_threshold_output(seed, engine):
     kw = {} if engine is None else {"engine": engine}
     got = q.qnn_bitplane_gemm_sign(dev(xp), [1 << p for p in range(8)], q.PLANE_BIT, dev(np_pack_pm1(w)[None]), [1],
                                    q.PLANE_SIGN, K, dev(T), None, **kw)
-    check_engine(engine or 0, MFMA)
+    check_engine(engine or 0, MFMA_LDS)
     assert_same(host_u32(got), oracle.pack_bits(oracle.threshold(oracle.gemm_int(x, w.astype(np.int32)), T)))
 
 
-@pytest.mark.parametrize("engine", [None, MFMA])
+@pytest.mark.parametrize("engine", [None, MFMA_LDS, MFMA])
 def test_many_tiles_int4_times_int4(seed, engine):
     M, N, K = 4200, 4360, 256
     a = qi.uniform_int(seed, 78, (M, K), -8, 7)
@@ -246,17 +246,19 @@ def test_many_tiles_int4_times_int4(seed, engine):
     coef = [1, 2, 4, -8]
     got = q.qnn_bitplane_gemm(dev(np_pack_bits(oracle.split_planes(a, 4))), coef, q.PLANE_BIT,
                               dev(np_pack_bits(oracle.split_planes(w, 4))), coef, q.PLANE_BIT, K, engine=engine)
-    check_engine(engine or 0, MFMA)
+    check_engine(engine or 0, MFMA_LDS)
     assert_same(host(got), oracle.gemm_int(a, w))
 
 
+@pytest.mark.parametrize("Cin,auto", [(64, MFMA), (128, MFMA_LDS)])
 @pytest.mark.parametrize("engine", [None, MFMA])
-def test_many_tiles_conv(seed, engine):
-    """26 images of 13 x 13 pixels, 64 -> 4200 channels: 18 x 17 tiles of the implicit-im2col kernel."""
-    B, H, Wd, Cin, Cout = 26, 13, 13, 64, 4200
+def test_many_tiles_conv(seed, engine, Cin, auto):
+    """26 images of 13 x 13 pixels, 64 or 128 -> 4200 channels: 18 x 17 tiles of the implicit-im2col kernels (128
+    channels are four words per pixel, which AUTO gives to the kernel that merges the planes in LDS)."""
+    B, H, Wd, Cout = 26, 13, 13, 4200
     u = qi.uniform_int(seed, 80, (B, H, Wd, Cin), 0, 3)
     w = qi.pm1(seed, 81, (Cout, 3, 3, Cin))
     got = q.qnn_bitplane_conv2d(dev(np_pack_bits(oracle.split_planes(u, 2))), [1, 2], q.PLANE_BIT, Cin,
                                 dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, 1, 1, engine=engine)
-    check_engine(engine or 0, MFMA)
+    check_engine(engine or 0, auto)
     assert_same(host(got), oracle.conv2d(u, w.astype(np.int32), 1, 1))

@@ -26,6 +26,7 @@ def _lib():
 
 
 ENGINES = [1, 2, 3, 0]  # VALU, int8 MFMA, FP4 MFMA, AUTO
+PLANE_ENGINES = [1, 2, 3, 4, 0]  # ... and the int8 kernel that merges planes once per workgroup, for multi-plane operands
 
 
 # ------------------------------------------------------------------ S1 pack_sign
@@ -286,8 +287,9 @@ def _planes_of(v, nbits):
     return p, np_pack_bits(p)
 
 
-@pytest.mark.parametrize("engine", ENGINES)
-@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (9, 11, 100), (70, 130, 784), (130, 70, 33), (256, 512, 800)])
+@pytest.mark.parametrize("engine", PLANE_ENGINES)
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (9, 11, 100), (70, 130, 784), (130, 70, 33), (256, 512, 800), (300, 260, 1024),
+                                   (70, 33, 128)])
 def test_bitplane_u8_times_sign(seed, M, N, K, engine):
     x = qi.uniform_int(seed, 30, (M, K), 0, 255)
     w = qi.pm1(seed, 31, (N, K))
@@ -295,13 +297,15 @@ def test_bitplane_u8_times_sign(seed, M, N, K, engine):
     _, xp = _planes_of(x, 8)
     got = run_on_engine(q.qnn_bitplane_gemm, dev(xp), [1 << p for p in range(8)], q.PLANE_BIT,
                         dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, K, engine=engine,
-                        takes=engine_takes(engine, 8, 1))
+                        takes=engine_takes(engine, 8, 1, [1 << p for p in range(8)], row_words=(K + 31) // 32))
     if got is not None:
         assert np.array_equal(host(got), want)
+        if engine:
+            assert q.qnn_last_engine() == engine
 
 
-@pytest.mark.parametrize("engine", ENGINES)
-@pytest.mark.parametrize("M,N,K", [(5, 7, 70), (64, 64, 2048), (150, 200, 257)])
+@pytest.mark.parametrize("engine", PLANE_ENGINES)
+@pytest.mark.parametrize("M,N,K", [(5, 7, 70), (64, 64, 2048), (150, 200, 257), (300, 520, 384)])
 def test_bitplane_int4_times_int4(seed, M, N, K, engine):
     a = qi.uniform_int(seed, 32, (M, K), -8, 7)
     w = qi.uniform_int(seed, 33, (N, K), -8, 7)
@@ -310,7 +314,7 @@ def test_bitplane_int4_times_int4(seed, M, N, K, engine):
     _, ap = _planes_of(a, 4)
     _, wp = _planes_of(w, 4)
     got = run_on_engine(q.qnn_bitplane_gemm, dev(ap), coef, q.PLANE_BIT, dev(wp), coef, q.PLANE_BIT, K,
-                        engine=engine, takes=engine_takes(engine, 4, 4, coef, coef))
+                        engine=engine, takes=engine_takes(engine, 4, 4, coef, coef, row_words=(K + 31) // 32))
     if got is not None:
         assert np.array_equal(host(got), want)
 
@@ -329,21 +333,22 @@ def test_bitplane_every_mode_pair_against_plane_oracle(seed, modeA, modeW, engin
         assert np.array_equal(host(got), want)
 
 
-@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("engine", PLANE_ENGINES)
 @pytest.mark.parametrize("modeA,modeW", [(0, 0), (0, 1), (1, 0), (1, 1)])
-@pytest.mark.parametrize("Pa,Pb,ca,cw", [(2, 2, [1, -2], [2, 1]), (4, 1, [1, 2, 4, -8], [-1]), (2, 1, [6, 3], [5])])
+@pytest.mark.parametrize("Pa,Pb,ca,cw", [(2, 2, [1, -2], [2, 1]), (4, 1, [1, 2, 4, -8], [-1]), (2, 1, [6, 3], [5]),
+                                         (4, 4, [-8, 4, 2, 1], [3, 6, 12, -24]), (8, 1, [1 << p for p in range(7)] + [-128], [7])])
 def test_bitplane_every_mode_pair_with_power_of_two_codes(seed, Pa, Pb, ca, cw, modeA, modeW, engine):
     """Coefficient sets the int8 matrix-core engine takes (a common factor times distinct powers of two, either sign,
     any order), in all four mode pairs, so that the affine correction of every pair is exercised on that engine too."""
-    M, N, K = 70, 45, 333
+    M, N, K = 70, 45, 384 if engine == 4 else 333
     pa = qi.bernoulli_bits(seed, 42, (Pa, M, K))
     pw = qi.bernoulli_bits(seed, 43, (Pb, N, K))
     want = oracle.gemm_planes(pa, ca, modeA, pw, cw, modeW)
     got = run_on_engine(q.qnn_bitplane_gemm, dev(np_pack_bits(pa)), ca, modeA, dev(np_pack_bits(pw)), cw, modeW, K,
-                        engine=engine, takes=engine_takes(engine, Pa, Pb, ca, cw))
+                        engine=engine, takes=engine_takes(engine, Pa, Pb, ca, cw, row_words=(K + 31) // 32))
     if got is not None:
         assert np.array_equal(host(got), want)
-        if engine in (1, 2):
+        if engine in (1, 2, 4):
             assert q.qnn_last_engine() == engine
 
 
@@ -360,9 +365,10 @@ def test_bitplane_large_coefficients_fall_back_correctly(seed, engine):
         assert np.array_equal(host(got), want)
 
 
-@pytest.mark.parametrize("engine", ENGINES)
-def test_bitplane_gemm_sign_first_layer(seed, engine):
-    M, N, K = 100, 200, 784
+@pytest.mark.parametrize("engine", PLANE_ENGINES)
+@pytest.mark.parametrize("K", [784, 896])
+def test_bitplane_gemm_sign_first_layer(seed, engine, K):
+    M, N = 100, 200
     x = qi.uniform_int(seed, 38, (M, K), 0, 255)
     w = qi.pm1(seed, 39, (N, K))
     T = qi.uniform_int(seed, 40, (N,), -3000, 3000)
@@ -371,7 +377,8 @@ def test_bitplane_gemm_sign_first_layer(seed, engine):
     _, xp = _planes_of(x, 8)
     got = run_on_engine(q.qnn_bitplane_gemm_sign, dev(xp), [1 << p for p in range(8)], q.PLANE_BIT,
                         dev(np_pack_pm1(w)[None]), [1], q.PLANE_SIGN, K, dev(T), dev(flip), engine=engine,
-                        takes=engine_takes(engine, 8, 1, sign_out=True))
+                        takes=engine_takes(engine, 8, 1, [1 << p for p in range(8)], sign_out=True,
+                                           row_words=(K + 31) // 32))
     if got is not None:
         assert np.array_equal(host_u32(got), want)
 
@@ -423,17 +430,41 @@ def _conv_case(seed, B, H, Wd, Cin, Cout, KH, abits, stream0):
     return u, w, up, wp
 
 
-@pytest.mark.parametrize("engine", ENGINES)
+@pytest.mark.parametrize("engine", PLANE_ENGINES)
 @pytest.mark.parametrize("B,H,Wd,Cin,Cout,KH,pad,stride", [(2, 5, 6, 7, 4, 3, 1, 1), (3, 13, 13, 96, 40, 3, 1, 1),
                                                            (2, 8, 7, 40, 33, 5, 2, 2), (1, 4, 4, 64, 8, 1, 0, 1),
-                                                           (4, 13, 13, 384, 256, 3, 1, 1)])
+                                                           (4, 13, 13, 384, 256, 3, 1, 1), (3, 9, 10, 128, 70, 3, 1, 2)])
 def test_conv2d(seed, B, H, Wd, Cin, Cout, KH, pad, stride, engine):
     u, w, up, wp = _conv_case(seed, B, H, Wd, Cin, Cout, KH, 2, 70)
     want = oracle.conv2d(u, w.astype(np.int32), pad, stride)
     got = run_on_engine(q.qnn_bitplane_conv2d, dev(up), [1, 2], q.PLANE_BIT, Cin, dev(wp), [1], q.PLANE_SIGN, pad,
-                        stride, engine=engine, takes=engine_takes(engine, 2, 1, conv=True))
+                        stride, engine=engine, takes=engine_takes(engine, 2, 1, [1, 2], conv=True, row_words=(Cin + 31) // 32))
     if got is not None:
         assert np.array_equal(host(got), want)
+
+
+@pytest.mark.parametrize("engine", PLANE_ENGINES)
+@pytest.mark.parametrize("abits,B,H,Wd,Cin,Cout,KH,pad,stride", [(2, 2, 5, 6, 7, 4, 3, 1, 1), (2, 3, 13, 13, 128, 70, 3, 1, 1),
+                                                                 (1, 3, 8, 8, 128, 100, 3, 1, 1), (1, 2, 9, 7, 40, 33, 3, 0, 2),
+                                                                 (2, 5, 13, 13, 384, 256, 3, 1, 1), (1, 5, 16, 16, 256, 256, 3, 1, 1)])
+def test_conv2d_with_fused_threshold(seed, abits, B, H, Wd, Cin, Cout, KH, pad, stride, engine):
+    """A layer of a binarized ConvNet: convolution, Sign(BatchNorm(.)) as threshold (ties, flips, extreme values), output
+    packed along the channels.  One-bit activations here are 0/1 codes (zero padding is exact for them)."""
+    u, w, up, wp = _conv_case(seed, B, H, Wd, Cin, Cout, KH, abits, 74)
+    T = qi.uniform_int(seed, 76, (Cout,), -20, 20)
+    T[0], T[Cout - 1] = -(2**31), 2**31 - 1
+    flip = qi.bernoulli_bits(seed, 77, (Cout,))
+    sums = oracle.conv2d(u, w.astype(np.int32), pad, stride)
+    Bo, Ho, Wo, _ = sums.shape
+    want = oracle.pack_bits(oracle.threshold(sums.reshape(-1, Cout), T, flip)).reshape(Bo, Ho, Wo, -1)
+    ca = [1, 2][:abits]
+    got = run_on_engine(q.qnn_bitplane_conv2d_sign, dev(up), ca, q.PLANE_BIT, Cin, dev(wp), [1], q.PLANE_SIGN, pad, stride,
+                        dev(T), dev(flip), engine=engine,
+                        takes=engine_takes(engine, abits, 1, ca, conv=True, sign_out=True, row_words=(Cin + 31) // 32))
+    if got is not None:
+        assert np.array_equal(host_u32(got), want)
+        if engine:
+            assert q.qnn_last_engine() == engine
 
 
 @pytest.mark.parametrize("engine", ENGINES)
