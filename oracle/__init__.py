@@ -178,5 +178,40 @@ def conv2d(u: np.ndarray, w: np.ndarray, pad: int, stride: int = 1) -> np.ndarra
     return out
 
 
+def maxpool2x2(u: np.ndarray) -> np.ndarray:
+    """int [B][H][W][C] -> int32 [B][H//2][W//2][C]."""
+    u = _c(u, np.int32)
+    B, H, Wd, Cc = u.shape
+    out = np.empty((B, H // 2, Wd // 2, Cc), dtype=np.int32)
+    _check(lib().qo_maxpool2x2(_p(u), C.c_int64(B), C.c_int64(H), C.c_int64(Wd), C.c_int64(Cc), _p(out)), "maxpool2x2")
+    return out
+
+
+def convnet(x: np.ndarray, conv_w: list, pool: list, fc_w: list, T: list, flip: list | None = None) -> np.ndarray:
+    """x uint8 [B][H][W][C0]; conv_w[l] int8 +-1 [cout][3][3][cin]; pool[l] 0/1; fc_w[j] int8 +-1 [out][in] with `in`
+    of the first one counting the last feature map in (y, x, c) order; T[l] int32 for every layer but the last."""
+    x = _c(x, np.uint8)
+    B, H, Wd, C0 = x.shape
+    Ws = [_c(w, np.int8) for w in list(conv_w) + list(fc_w)]
+    L = len(Ws)
+    Ts = [_c(t, np.int32) for t in T]
+    assert len(Ts) == L - 1 and len(pool) == len(conv_w)
+    cout = np.array([w.shape[0] for w in conv_w], dtype=np.int64)
+    pl = np.array([1 if p else 0 for p in pool], dtype=np.int32)
+    fc_out = np.array([w.shape[0] for w in fc_w], dtype=np.int64)
+    Wp = (C.c_void_p * L)(*[w.ctypes.data for w in Ws])
+    Tp = (C.c_void_p * max(L - 1, 1))(*[t.ctypes.data for t in Ts])
+    Fs = []
+    Fp = None
+    if flip is not None:
+        Fs = [_c(f, np.uint8) for f in flip]
+        Fp = (C.c_void_p * max(L - 1, 1))(*[f.ctypes.data for f in Fs])
+    out = np.empty((B, int(fc_out[-1])), dtype=np.int32)
+    rc = lib().qo_convnet(_p(x), C.c_int64(B), C.c_int64(H), C.c_int64(Wd), C.c_int64(C0), C.c_int(len(conv_w)),
+                          _p(cout), _p(pl), C.c_int(len(fc_w)), _p(fc_out), Wp, Tp, Fp, _p(out))
+    _check(rc, "convnet")
+    return out
+
+
 def num_threads() -> int:
     return int(lib().qo_num_threads())

@@ -14,8 +14,9 @@
  *
  * Parity pins (tests marked "not gpu"): fp32 GEMM on +-1 matrices, the agreement-count identity of Eq. (popc),
  * brute force over all sign vectors for tiny K, Eq. (FirstLayer) (planes vs integer values), a library
- * convolution in fp64, the float BatchNorm formula evaluated in double, and hand-written expected bits for
- * float edge values.  No function here is "parity unpinned".
+ * convolution in fp64, the float BatchNorm formula evaluated in double, hand-written expected bits for
+ * float edge values, a library max-pooling, and the float pipeline conv -> max-pool -> BatchNorm -> sign of a library
+ * in fp64 for the ConvNet.  No function here is "parity unpinned".
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -224,6 +225,123 @@ int qo_conv2d(const int32_t *u, int64_t B, int64_t H, int64_t Wd, int64_t Ci, co
                     out[((b * Ho + y) * Wo + xo) * Co + co] = (int32_t)acc;
                 }
     return bad ? QO_ERR_RANGE : QO_OK;
+}
+
+/* 2 x 2 max-pooling with stride 2 on integer feature maps (App. A, CIFAR-10 ConvNet: "convolution and 2 x 2 max-pooling
+ * layers" followed by "BatchNorm and Binarization layers", i.e. the pooling acts on the convolution's sums).
+ * u is [B][H][W][C] (channels last), out is [B][H/2][W/2][C]; a last odd row / column is dropped (floor), as the
+ * deep-learning frameworks do by default. */
+int qo_maxpool2x2(const int32_t *u, int64_t B, int64_t H, int64_t Wd, int64_t C, int32_t *out) {
+    int64_t Ho = H / 2, Wo = Wd / 2;
+    for (int64_t b = 0; b < B; ++b)
+        for (int64_t y = 0; y < Ho; ++y)
+            for (int64_t x = 0; x < Wo; ++x)
+                for (int64_t c = 0; c < C; ++c) {
+                    int32_t m = u[((b * H + 2 * y) * Wd + 2 * x) * C + c];
+                    for (int dy = 0; dy < 2; ++dy)
+                        for (int dx = 0; dx < 2; ++dx) {
+                            int32_t v = u[((b * H + 2 * y + dy) * Wd + 2 * x + dx) * C + c];
+                            if (v > m) m = v;
+                        }
+                    out[((b * Ho + y) * Wo + x) * C + c] = m;
+                }
+    return QO_OK;
+}
+
+/* Alg. 4 for a binarized ConvNet of the shape of App. A (CIFAR-10 ConvNet table): a run of 3 x 3 "same" convolutions
+ * (zero padding, stride 1), some followed by 2 x 2 max-pooling, each followed by Sign(BatchNorm(.)) given as a folded
+ * threshold; then fully connected layers on the flattened (y, x, c) feature map, the last one without threshold.
+ *   x        : uint8 [B][H][W][C0] (8-bit inputs: the first layer is the integer product of Sec. 2.6)
+ *   n_conv   : number of convolution layers; cout[l], pool[l] (0/1) for l < n_conv
+ *   n_fc     : number of fully connected layers (>= 1); fc_out[j]
+ *   W        : n_conv + n_fc pointers to +-1 weights: conv [cout][3][3][cin], fc [out][in]
+ *   T, flip  : n_conv + n_fc - 1 pointers (flip, or entries of it, may be NULL)
+ * Activations between layers are +-1; a padded position contributes exactly 0 to a convolution (it is not a -1).
+ * logits: int32 [B][fc_out[n_fc-1]]. */
+int qo_convnet(const uint8_t *x, int64_t B, int64_t H, int64_t Wd, int64_t C0, int n_conv, const int64_t *cout,
+               const int32_t *pool, int n_fc, const int64_t *fc_out, const int8_t *const *W, const int32_t *const *T,
+               const uint8_t *const *flip, int32_t *logits) {
+    if (n_conv < 0 || n_fc < 1) return QO_ERR_ARG;
+    int rc = QO_OK;
+    int64_t h = H, w = Wd, c = C0;
+    int32_t *act = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * H * Wd * C0));  /* integer values of the current map */
+    if (!act) return QO_ERR_NOMEM;
+    for (int64_t i = 0; i < B * H * Wd * C0; ++i) act[i] = (int32_t)x[i];
+    for (int l = 0; l < n_conv && rc == QO_OK; ++l) {
+        int64_t co = cout[l];
+        int32_t *w32 = (int32_t *)malloc(sizeof(int32_t) * (size_t)(co * 9 * c));
+        int32_t *sum = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * h * w * co));
+        if (!w32 || !sum) {
+            free(w32), free(sum), free(act);
+            return QO_ERR_NOMEM;
+        }
+        for (int64_t i = 0; i < co * 9 * c; ++i) w32[i] = (int32_t)W[l][i];
+        rc = qo_conv2d(act, B, h, w, c, w32, co, 3, 3, 1, 1, sum);
+        free(w32);
+        free(act);
+        act = NULL;
+        int64_t ho = h, wo = w;
+        if (rc == QO_OK && pool[l]) {
+            ho = h / 2, wo = w / 2;
+            int32_t *p = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * ho * wo * co));
+            if (!p) {
+                free(sum);
+                return QO_ERR_NOMEM;
+            }
+            qo_maxpool2x2(sum, B, h, w, co, p);
+            free(sum);
+            sum = p;
+        }
+        int8_t *s8 = (int8_t *)malloc((size_t)(B * ho * wo * co));
+        act = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * ho * wo * co));
+        if (!s8 || !act) {
+            free(s8), free(sum), free(act);
+            return QO_ERR_NOMEM;
+        }
+        if (rc == QO_OK) {
+            qo_threshold(sum, B * ho * wo, co, T[l], flip ? flip[l] : NULL, s8);
+            for (int64_t i = 0; i < B * ho * wo * co; ++i) act[i] = (int32_t)s8[i];
+        }
+        free(s8);
+        free(sum);
+        h = ho, w = wo, c = co;
+    }
+    /* fully connected layers on the map flattened in (y, x, c) order */
+    int64_t in = h * w * c;
+    for (int j = 0; j < n_fc && rc == QO_OK; ++j) {
+        int l = n_conv + j;
+        int64_t out = fc_out[j];
+        int last = j == n_fc - 1;
+        int32_t *w32 = (int32_t *)malloc(sizeof(int32_t) * (size_t)(out * in));
+        int32_t *sum = last ? logits : (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * out));
+        if (!w32 || !sum) {
+            free(w32);
+            if (!last) free(sum);
+            free(act);
+            return QO_ERR_NOMEM;
+        }
+        for (int64_t i = 0; i < out * in; ++i) w32[i] = (int32_t)W[l][i];
+        rc = qo_gemm_int(act, w32, B, out, in, sum);
+        free(w32);
+        if (!last) {
+            int8_t *s8 = (int8_t *)malloc((size_t)(B * out));
+            free(act);
+            act = (int32_t *)malloc(sizeof(int32_t) * (size_t)(B * out));
+            if (!s8 || !act) {
+                free(s8), free(sum), free(act);
+                return QO_ERR_NOMEM;
+            }
+            if (rc == QO_OK) {
+                qo_threshold(sum, B, out, T[l], flip ? flip[l] : NULL, s8);
+                for (int64_t i = 0; i < B * out; ++i) act[i] = (int32_t)s8[i];
+            }
+            free(s8);
+            free(sum);
+        }
+        in = out;
+    }
+    free(act);
+    return rc;
 }
 
 /* Number of threads the OpenMP loops above actually use (reported beside the CPU-baseline timing). */

@@ -350,3 +350,90 @@ def test_generator_is_frozen():
     assert qi.raw_u64(qi.SEED_BASE, 7, 3, offset=2)[0] == qi.raw_u64(qi.SEED_BASE, 7, 3)[2]
     assert qi.pm1(qi.SEED_BASE, 30, (2, 8)).tolist() == FROZEN_PM1
     assert qi.uniform_int(qi.SEED_BASE, 25, (6,), -64, 64).tolist() == FROZEN_UNIFORM
+
+
+# ---------------------------------------------------------------- ConvNet of App. A (CIFAR-10 ConvNet table)
+def test_maxpool_hand_values_and_library(seed):
+    """2 x 2 / stride 2 max-pooling on channels-last integer maps: a hand-written 4 x 4 case (negative values, the
+    maximum in every corner of a window), odd sizes dropped, and torch's max_pool2d in fp64 on random maps."""
+    u = np.array([[1, -5, 7, 7], [0, 2, -9, 8], [-1, -2, 3, 3], [-3, -4, 3, 4]], dtype=np.int32)[None, :, :, None]
+    assert oracle.maxpool2x2(u)[0, :, :, 0].tolist() == [[2, 8], [-1, 4]]
+    v = qi.uniform_int(seed, 70, (3, 7, 9, 5), -1000, 1000)
+    want = torch.nn.functional.max_pool2d(torch.from_numpy(v).double().permute(0, 3, 1, 2), 2).permute(0, 2, 3, 1)
+    got = oracle.maxpool2x2(v)
+    assert got.shape == (3, 3, 4, 5)
+    assert np.array_equal(got, want.numpy().astype(np.int32))
+
+
+def _float_convnet(x, conv_w, pool, fc_w, T, flip):
+    """The float definition with a library in fp64: conv ("same", zero padding) -> max-pool -> BatchNorm -> sign, then
+    fully connected layers on the (y, x, c)-flattened map.  BatchNorm parameters are chosen so that its zero crossing
+    lies half way between two integers: y = gamma * (s - (T - 0.5)), gamma = +1 (flip 0) or -1 (flip 1)."""
+    F = torch.nn.functional
+    a = torch.from_numpy(x.astype(np.float64)).permute(0, 3, 1, 2)  # NCHW
+    l = 0
+    for w, p in zip(conv_w, pool):
+        s = F.conv2d(a, torch.from_numpy(w.astype(np.float64)).permute(0, 3, 1, 2), padding=1)
+        if p:
+            s = F.max_pool2d(s, 2)
+        gamma = torch.from_numpy(np.where(flip[l] != 0, -1.0, 1.0))
+        mean = torch.from_numpy(T[l].astype(np.float64) - 0.5)
+        eps = 2.0 ** -20  # var + eps is exactly 1
+        y = F.batch_norm(s, mean, torch.full_like(mean, 1.0 - eps), gamma, torch.zeros_like(mean), False, 0.0, eps)
+        a = torch.where(y >= 0, 1.0, -1.0).double()
+        l += 1
+    a = a.permute(0, 2, 3, 1).reshape(a.shape[0], -1)  # (y, x, c) order
+    for j, w in enumerate(fc_w):
+        s = a @ torch.from_numpy(w.astype(np.float64)).T
+        if j == len(fc_w) - 1:
+            return s.numpy().astype(np.int64)
+        gamma = torch.from_numpy(np.where(flip[l] != 0, -1.0, 1.0))
+        y = gamma * (s - torch.from_numpy(T[l].astype(np.float64) - 0.5))
+        a = torch.where(y >= 0, 1.0, -1.0).double()
+        l += 1
+
+
+def _convnet_case(seed, B, H, Wd, C0, couts, pools, fcs, stream0):
+    x = qi.uniform_int(seed, stream0, (B, H, Wd, C0), 0, 255, dtype=np.uint8)
+    conv_w, cin = [], C0
+    for l, co in enumerate(couts):
+        conv_w.append(qi.pm1(seed, stream0 + 1 + l, (co, 3, 3, cin)))
+        cin = co
+    h, w = H, Wd
+    for p in pools:
+        if p:
+            h, w = h // 2, w // 2
+    fc_w, fin = [], h * w * cin
+    for j, fo in enumerate(fcs):
+        fc_w.append(qi.pm1(seed, stream0 + 20 + j, (fo, fin)))
+        fin = fo
+    widths = list(couts) + list(fcs[:-1])
+    T, flip = [], []
+    for l, n in enumerate(widths):
+        span = 2000 if l == 0 else 12  # first-layer sums are sums of 8-bit inputs
+        T.append(qi.uniform_int(seed, stream0 + 40 + l, (n,), -span, span))
+        flip.append(qi.bernoulli_bits(seed, stream0 + 60 + l, (n,)))
+    return x, conv_w, list(pools), fc_w, T, flip
+
+
+@pytest.mark.parametrize("B,H,Wd,C0,couts,pools,fcs", [(2, 8, 8, 3, [8, 8, 16, 16], [0, 1, 0, 1], [24, 10]),
+                                                      (3, 6, 10, 3, [5, 7], [1, 0], [9, 6, 4]),
+                                                      (2, 5, 7, 2, [6], [1], [3])])
+def test_convnet_equals_float_pipeline(seed, B, H, Wd, C0, couts, pools, fcs):
+    """Pins: zero padding of the +-1 maps (a padded tap adds 0, not -1), pooling before BatchNorm (so that a negative
+    BatchNorm scale turns the maximum into the deciding MINIMUM of the window), ties, the (y, x, c) flattening."""
+    x, conv_w, pools, fc_w, T, flip = _convnet_case(seed, B, H, Wd, C0, couts, pools, fcs, 1300)
+    got = oracle.convnet(x, conv_w, pools, fc_w, T, flip)
+    want = _float_convnet(x, conv_w, pools, fc_w, T, flip)
+    assert np.array_equal(got.astype(np.int64), want)
+
+
+def test_convnet_without_convolutions_is_the_mlp(seed):
+    """With no convolution layer and a 1 x 1 map the ConvNet forward is Alg. 4's MLP forward."""
+    B, dims = 7, [30, 12, 9, 5]
+    x = qi.uniform_int(seed, 1400, (B, dims[0]), 0, 255, dtype=np.uint8)
+    W = [qi.pm1(seed, 1401 + l, (dims[l + 1], dims[l])) for l in range(3)]
+    T = [qi.uniform_int(seed, 1405 + l, (dims[l + 1],), -300 if l == 0 else -4, 300 if l == 0 else 4) for l in range(2)]
+    flip = [qi.bernoulli_bits(seed, 1408 + l, (dims[l + 1],)) for l in range(2)]
+    got = oracle.convnet(x.reshape(B, 1, 1, dims[0]), [], [], W, T, flip)
+    assert np.array_equal(got, oracle.mlp(x, W, T, flip))
