@@ -214,7 +214,7 @@ int qnn_last_engine(void);
  * order (one entry per layer for the forward calls): writes min(count, capacity) entries, returns the count. */
 int qnn_last_engines(int *engines, int capacity);
 
-/* Measurement helper, not a step of the path: one wave spins for some ten microseconds and writes to
+/* Measurement helper, not a step of the path: one wave spins for a few microseconds and writes to
  * out3 (DEVICE, three uint64, 8-byte aligned) {elapsed shader-clock cycles, elapsed ticks of the constant 100 MHz
  * real-time counter, a checksum}; 100 * out3[0] / out3[1] is the shader clock in MHz at that moment. */
 int qnn_probe_shader_clock(unsigned long long *out3, void *stream);

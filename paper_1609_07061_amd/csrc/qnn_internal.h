@@ -106,4 +106,9 @@ int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv
 int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
                           uint32_t *out, int64_t ldo, hipStream_t s);
 
+int launch_pool_bits(const uint32_t *in, int64_t B, int H, int Wd, int Cw, const uint32_t *use_and, bool invert_all,
+                     uint32_t *out, hipStream_t s);
+int launch_flags(const uint8_t *flip, int64_t n, uint32_t *out_bits, uint8_t *out_inv, hipStream_t s);
+int launch_ones_plane(uint32_t *out, int64_t rows, int Cw, int C, hipStream_t s);
+
 }  // namespace qnn

@@ -299,6 +299,55 @@ __global__ __launch_bounds__(kBlock) void threshold_sign_vec4_kernel(const int32
     }
 }
 
+// 2 x 2 max-pooling of a binarized feature map, on the packed bits (App. A: "convolution and 2 x 2 max-pooling layers"
+// followed by "BatchNorm and Binarization layers").  Pooling acts on the convolution's sums and BatchNorm + sign come
+// after it; per channel BatchNorm is monotone, increasing for a positive scale and decreasing for a negative one, so
+// Sign(BatchNorm(max of the four sums)) is the OR of the four thresholded bits where the channel is not flipped and the
+// AND where it is (there the maximum sum gives the smallest BatchNorm output).  `use_and` holds one bit per channel
+// (packed like the data) saying which; `invert_all` swaps the roles for maps stored with inverted bits.
+// One thread per output word; in [B][H][W][Cw], out [B][H/2][W/2][Cw].
+__global__ __launch_bounds__(kBlock) void pool_bits_kernel(const uint32_t *__restrict__ in, int64_t B, int H, int Wd, int Cw,
+                                                           const uint32_t *__restrict__ use_and, uint32_t invert_all,
+                                                           uint32_t *__restrict__ out) {
+    const int Ho = H / 2, Wo = Wd / 2;
+    const int64_t total = B * Ho * Wo * Cw;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
+        const int c = (int)(i % Cw);
+        int64_t p = i / Cw;
+        const int xo = (int)(p % Wo);
+        p /= Wo;
+        const int yo = (int)(p % Ho);
+        const int64_t b = p / Ho;
+        const uint32_t *src = in + (((b * H + 2 * yo) * Wd + 2 * xo) * (int64_t)Cw + c);
+        const uint32_t v00 = src[0], v01 = src[Cw], v10 = src[(int64_t)Wd * Cw], v11 = src[(int64_t)Wd * Cw + Cw];
+        const uint32_t m = use_and[c] ^ invert_all;
+        out[i] = ((v00 | v01 | v10 | v11) & ~m) | ((v00 & v01 & v10 & v11) & m);
+    }
+}
+
+// Per-channel flags -> packed words and inverted byte flags (helpers of the ConvNet forward): out_bits[w] bit t =
+// (flip[32 w + t] != 0) for channels below n (flip == nullptr reads as all zero); out_inv[c] = !flip[c].
+__global__ __launch_bounds__(kBlock) void flags_kernel(const uint8_t *__restrict__ flip, int64_t n, uint32_t *__restrict__ out_bits,
+                                                       uint8_t *__restrict__ out_inv) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const bool f = (c < n && flip) ? (flip[c] != 0) : false;
+    const unsigned long long m = __ballot(f);
+    if (c < n) out_inv[c] = f ? 0 : 1;
+    const int64_t w = (c - lane) / 32;
+    if (lane == 0 && c - lane < n) out_bits[w] = (uint32_t)m;
+    if (lane == 32 && c - lane + 32 < n) out_bits[w + 1] = (uint32_t)(m >> 32);
+}
+
+// rows x Cw words with the first C bits of every row set (the "inside the image" plane of a +-1 feature map whose
+// zero padding must contribute exactly 0: value = plane0 - 2 * plane1, so 01 = +1, 11 = -1, 00 = 0).
+__global__ __launch_bounds__(kBlock) void ones_plane_kernel(uint32_t *__restrict__ out, int64_t rows, int Cw, int C) {
+    const int64_t total = rows * Cw;
+    const uint32_t tail = (C % 32) ? ((1u << (C % 32)) - 1u) : 0xFFFFFFFFu;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock)
+        out[i] = ((int)(i % Cw) == Cw - 1) ? tail : 0xFFFFFFFFu;
+}
+
 int grid_for(int64_t total_chunks) {
     int64_t blocks = ceil_div(total_chunks, kWavesPerBlock);
     const int64_t cap = 256 * 32;  // 256 CUs, plenty of resident waves each; the kernels stride over the rest
@@ -359,6 +408,26 @@ int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, c
     if (gx > 0x7FFFFFFF) return fail(QNN_ERR_SHAPE, "threshold_sign: N too large");
     return QNN_LAUNCH("threshold_sign", threshold_sign_kernel, dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), 0, s, C, ldc, M, N, T,
                        flip, out, ldo);
+}
+
+int launch_pool_bits(const uint32_t *in, int64_t B, int H, int Wd, int Cw, const uint32_t *use_and, bool invert_all,
+                     uint32_t *out, hipStream_t s) {
+    const int64_t total = B * (H / 2) * (Wd / 2) * Cw;
+    if (total == 0) return QNN_OK;
+    return QNN_LAUNCH("pool_bits", pool_bits_kernel, dim3(grid_for(ceil_div(total, (int64_t)kWave))), dim3(kBlock), 0, s, in, B,
+                      H, Wd, Cw, use_and, invert_all ? 0xFFFFFFFFu : 0u, out);
+}
+
+int launch_flags(const uint8_t *flip, int64_t n, uint32_t *out_bits, uint8_t *out_inv, hipStream_t s) {
+    if (n == 0) return QNN_OK;
+    return QNN_LAUNCH("flags", flags_kernel, dim3((unsigned)ceil_div(n, (int64_t)kBlock)), dim3(kBlock), 0, s, flip, n, out_bits,
+                      out_inv);
+}
+
+int launch_ones_plane(uint32_t *out, int64_t rows, int Cw, int C, hipStream_t s) {
+    if (rows * Cw == 0) return QNN_OK;
+    return QNN_LAUNCH("ones_plane", ones_plane_kernel, dim3(grid_for(ceil_div(rows * Cw, (int64_t)kWave))), dim3(kBlock), 0, s,
+                      out, rows, Cw, C);
 }
 
 }  // namespace qnn

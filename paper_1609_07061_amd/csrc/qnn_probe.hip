@@ -45,7 +45,7 @@ extern "C" int qnn_probe_shader_clock(unsigned long long *out3, void *stream) {
     if (!out3) return fail(QNN_ERR_NULL, "probe_shader_clock: NULL pointer");
     if (reinterpret_cast<uintptr_t>(out3) & 7u) return fail(QNN_ERR_ALIGN, "probe_shader_clock: pointer not 8-byte aligned");
     return QNN_LAUNCH("clock_probe", clock_probe_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), out3,
-                      (uint32_t)20000);
+                      (uint32_t)2000);
 }
 
 extern "C" int qnn_stamp_clocks(unsigned long long *out3, void *stream) {
