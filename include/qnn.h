@@ -206,6 +206,27 @@ int qnn_bitplane_conv2d_sign(const uint32_t *A, int Pa, const int32_t *coefA, in
                              int pad, int stride_hw, const int32_t *T, const uint8_t *flip, uint32_t *out_bits,
                              int engine, void *stream);
 
+/* Alg. 4 for a binarized ConvNet of the shape of App. A (CIFAR-10 ConvNet table): n_conv 3 x 3 "same" convolutions
+ * (zero padding, stride 1), layer l followed by 2 x 2 max-pooling if pool[l] != 0 (on the convolution's sums, before
+ * BatchNorm, as in the table), each followed by Sign(BatchNorm(.)) as a folded threshold; then n_fc fully connected
+ * layers on the feature map flattened in (y, x, c) order, the last one giving int32 sums.
+ * x: DEVICE uint8 [B][H][W][C0], in_bits-bit inputs (first layer = weighted bit-plane products, Sec. 2.6).
+ * cout, pool: HOST [n_conv]; fc_out: HOST [n_fc].  W: HOST array of n_conv + n_fc DEVICE pointers, packed +-1:
+ * convolution l is [cout][3][3][ceil(cin/32)] words, fully connected j is [out][ceil(in/32)] (dense rows).
+ * T, flip: HOST arrays of n_conv + n_fc - 1 DEVICE pointers (flip, or entries of it, may be NULL).
+ * A padded position contributes exactly 0 to a convolution (it is not a -1).  The channels of the last feature map
+ * must be a multiple of 32 unless that map is a single pixel (QNN_ERR_UNSUPPORTED otherwise).
+ * logits: DEVICE int32 [B][ld_logits].  workspace: DEVICE, 256-byte aligned, qnn_binary_convnet_workspace_bytes(...)
+ * bytes.  `engine` is a preference, as in qnn_binary_mlp_forward_ex.  Everything is validated before the first launch.
+ * 1 <= n_conv, 1 <= n_fc, n_conv + n_fc <= 2 * QNN_MAX_LAYERS. */
+int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t Wd, int64_t C0, int in_bits, int n_conv,
+                               const int64_t *cout, const int32_t *pool, int n_fc, const int64_t *fc_out,
+                               const uint32_t *const *W, const int32_t *const *T, const uint8_t *const *flip,
+                               int32_t *logits, int64_t ld_logits, void *workspace, size_t workspace_bytes, int engine,
+                               void *stream);
+size_t qnn_binary_convnet_workspace_bytes(int64_t B, int64_t H, int64_t Wd, int64_t C0, int in_bits, int n_conv,
+                                          const int64_t *cout, const int32_t *pool, int n_fc, const int64_t *fc_out);
+
 /* Engine (QNN_ENGINE_VALU, QNN_ENGINE_MFMA or QNN_ENGINE_MFMA_FP4) that the calling thread's last successful multiply call used; 0 before
  * any.  For reports: results never depend on it. */
 int qnn_last_engine(void);

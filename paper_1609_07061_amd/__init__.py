@@ -50,6 +50,8 @@ _SIGS = {
                             _int, _int, _int, _vp, _vp],
     "qnn_bitplane_conv2d_sign": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
                                  _int, _int, _int, _vp, _vp, _vp, _int, _vp],
+    "qnn_binary_convnet_forward": [_vp, _i64, _i64, _i64, _i64, _int, _int, _vp, _vp, _int, _vp, _vp, _vp, _vp, _vp, _i64,
+                                   _vp, _sz, _int, _vp],
     "qnn_bitplane_conv2d_ex": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
                                _int, _int, _int, _vp, _int, _vp],
 }
@@ -60,6 +62,8 @@ for _name, _args in _SIGS.items():
 _lib.qnn_binary_mlp_workspace_bytes.argtypes = [_i64, _int, _int, _vp]
 _lib.qnn_binary_mlp_workspace_bytes.restype = _sz
 _lib.qnn_static_scratch_bytes.restype = _sz
+_lib.qnn_binary_convnet_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _int, _int, _vp, _vp, _int, _vp]
+_lib.qnn_binary_convnet_workspace_bytes.restype = _sz
 _lib.qnn_last_engine.restype = C.c_int
 _lib.qnn_last_error.restype = C.c_char_p
 _lib.qnn_version.restype = C.c_char_p
@@ -67,7 +71,7 @@ _lib.qnn_version.restype = C.c_char_p
 _lib.qnn_last_engines.argtypes = [_vp, _int]
 _lib.qnn_last_engines.restype = C.c_int
 
-EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_static_scratch_bytes", "qnn_last_engine",
+EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_static_scratch_bytes", "qnn_binary_convnet_workspace_bytes", "qnn_last_engine",
                                "qnn_last_engines", "qnn_last_error", "qnn_version"])
 
 
@@ -363,3 +367,49 @@ def qnn_bitplane_conv2d_sign(A: torch.Tensor, coefA: Sequence[int], modeA: int, 
                                          _dev(T, torch.int32, "T"), _dev(flip, torch.uint8, "flip"),
                                          _dev(out, torch.int32, "out"), engine, _stream()))
     return out
+
+
+def _net_arrays(cout, pool, fc_out):
+    co = (C.c_int64 * len(cout))(*[int(v) for v in cout])
+    pl = (C.c_int32 * len(pool))(*[1 if v else 0 for v in pool])
+    fo = (C.c_int64 * len(fc_out))(*[int(v) for v in fc_out])
+    return co, pl, fo
+
+
+def qnn_binary_convnet_workspace_bytes(B: int, H: int, Wd: int, C0: int, in_bits: int, cout: Sequence[int],
+                                       pool: Sequence[int], fc_out: Sequence[int]) -> int:
+    co, pl, fo = _net_arrays(cout, pool, fc_out)
+    return int(_lib.qnn_binary_convnet_workspace_bytes(B, H, Wd, C0, in_bits, len(cout), co, pl, len(fc_out), fo))
+
+
+def qnn_binary_convnet_forward(x: torch.Tensor, in_bits: int, cout: Sequence[int], pool: Sequence[int],
+                               fc_out: Sequence[int], W: Sequence[torch.Tensor], T: Sequence[torch.Tensor],
+                               flip: Optional[Sequence[Optional[torch.Tensor]]] = None,
+                               logits: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                               engine: int = ENGINE_AUTO) -> torch.Tensor:
+    """x: uint8 [B][H][W][C0] (dense); W: packed +-1 weights, convolutions [cout][3][3][Cw], fully connected [out][Kw]."""
+    if x.dim() != 4 or not x.is_contiguous():
+        raise ValueError("x must be dense [B][H][W][C0]")
+    B, H, Wd, C0 = x.shape
+    L = len(cout) + len(fc_out)
+    if len(W) != L or len(T) != L - 1:
+        raise ValueError("need one W per layer and one T per layer but the last")
+    for w in W:
+        if not w.is_contiguous():
+            raise ValueError("weights must be dense")
+    if logits is None:
+        logits = torch.empty((B, fc_out[-1]), dtype=torch.int32, device=x.device)
+    _, _, ldl = _rows_ld(logits, "logits")
+    if workspace is None:
+        need = qnn_binary_convnet_workspace_bytes(B, H, Wd, C0, in_bits, cout, pool, fc_out)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=x.device)
+    co, pl, fo = _net_arrays(cout, pool, fc_out)
+    Wp = (C.c_void_p * L)(*[_dev(w, torch.int32, "W") for w in W])
+    Tp = (C.c_void_p * max(L - 1, 1))(*[_dev(t, torch.int32, "T") for t in T])
+    Fp = None
+    if flip is not None:
+        Fp = (C.c_void_p * max(L - 1, 1))(*[_dev(f, torch.uint8, "flip") for f in flip])
+    _check(_lib.qnn_binary_convnet_forward(_dev(x, torch.uint8, "x"), B, H, Wd, C0, in_bits, len(cout), co, pl, len(fc_out),
+                                           fo, Wp, Tp, Fp, _dev(logits, torch.int32, "logits"), ldl,
+                                           _dev(workspace, torch.uint8, "workspace"), workspace.numel(), engine, _stream()))
+    return logits

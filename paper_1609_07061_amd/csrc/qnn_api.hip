@@ -20,7 +20,7 @@ namespace qnn {
 static thread_local char g_err[512] = "";
 static thread_local int g_last_engine = 0;
 // engines of the multiply launches of the calling thread's last entry-point call, in launch order
-static thread_local int g_engines[QNN_MAX_LAYERS];
+static thread_local int g_engines[2 * QNN_MAX_LAYERS];
 static thread_local int g_engine_count = 0;
 
 int fail(int code, const char *fmt, ...) {
@@ -110,7 +110,7 @@ int launch_on(const GemmArgs &g, int chosen, hipStream_t s) {
         rc = launch_gemm_mfma(g, s, chosen == QNN_ENGINE_MFMA_FP4);
     if (rc == QNN_OK) {
         g_last_engine = chosen;
-        if (g_engine_count < QNN_MAX_LAYERS) g_engines[g_engine_count++] = chosen;
+        if (g_engine_count < 2 * QNN_MAX_LAYERS) g_engines[g_engine_count++] = chosen;
     }
     return rc;
 }
@@ -610,6 +610,246 @@ int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int mod
                         int pad, int stride_hw, int32_t *out, void *stream) {
     return qnn_bitplane_conv2d_ex(A, Pa, coefA, modeA, strideA_words, B, H, Wd, Cin, W, Pb, coefW, modeW,
                                   strideW_words, Cout, KH, KW, pad, stride_hw, out, QNN_ENGINE_AUTO, stream);
+}
+
+// ---------------------------------------------------------------------------------------------------- ConvNet forward
+// Alg. 4 for the binarized ConvNet of App. A: 3 x 3 "same" convolutions, some followed by 2 x 2 max-pooling, each
+// followed by Sign(BatchNorm(.)); then fully connected layers.  Everything between the 8-bit input and the int32 logits
+// stays packed.  A +-1 feature map that feeds a convolution is kept as the 2-bit two's-complement code of its values
+// (plane 0 = "inside the image" = all ones, plane 1 = "value is -1"; +1 = 01, -1 = 11), because the zero padding of a
+// "same" convolution must contribute exactly 0 and a single +-1 bit cannot say 0; the all-zero words that the
+// convolution kernels read outside the image are then the code of 0.  The threshold epilogue writes plane 1 directly
+// (the flip flags are inverted for those layers).  Max-pooling runs on the thresholded bits (see pool_bits_kernel).
+namespace {
+constexpr int kMaxNetLayers = 2 * QNN_MAX_LAYERS;
+struct NetStep {
+    enum Kind { kPack, kFlags, kOnes, kGemm, kPool } kind;
+    GemmArgs g;      // kGemm (convolution or fully connected)
+    int engine;      // kGemm
+    // kPack / kFlags / kOnes / kPool operands
+    const void *src;
+    void *dst, *dst2;
+    int64_t rows, n;
+    int a, b, c;
+    const uint32_t *mask;
+    bool invert;
+};
+struct NetPlan {
+    int n;
+    NetStep step[6 * kMaxNetLayers + 4];
+};
+
+struct NetLayout {
+    size_t planes0, flags, act[2], tmp, fc[2], total;
+    size_t flag_bits[kMaxNetLayers], flag_inv[kMaxNetLayers];
+};
+
+// Sizes of the workspace regions; false if the shapes are not valid.
+bool net_layout(int64_t B, int64_t H, int64_t Wd, int64_t C0, int in_bits, int n_conv, const int64_t *cout,
+                const int32_t *pool, int n_fc, const int64_t *fc_out, NetLayout &L) {
+    if (B < 0 || H < 1 || Wd < 1 || C0 < 1 || in_bits < 1 || in_bits > 8 || n_conv < 1 || n_fc < 1 ||
+        n_conv + n_fc > kMaxNetLayers || !cout || !pool || !fc_out)
+        return false;
+    if (H > 32767 || Wd > 32767 || C0 > (1 << 24)) return false;
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t at = off;
+        off += round256(bytes);
+        return at;
+    };
+    L.planes0 = take((size_t)in_bits * (size_t)(B * H * Wd) * (size_t)words_for(C0) * 4);
+    size_t act = 0, tmp = 0;
+    int64_t h = H, w = Wd;
+    for (int l = 0; l < n_conv; ++l) {
+        if (cout[l] < 1 || cout[l] > (1 << 24)) return false;
+        const size_t full = (size_t)(B * h * w) * (size_t)words_for(cout[l]) * 4;
+        if (pool[l]) {
+            if (full > tmp) tmp = full;
+            h /= 2, w /= 2;
+            if (h < 1 || w < 1) return false;
+        }
+        const size_t kept = 2 * (size_t)(B * h * w) * (size_t)words_for(cout[l]) * 4;  // two planes
+        if (kept > act) act = kept;
+    }
+    L.act[0] = take(act);
+    L.act[1] = take(act);
+    L.tmp = take(tmp);
+    size_t fc = 0;
+    for (int j = 0; j < n_fc; ++j) {
+        if (fc_out[j] < 1 || fc_out[j] > 0x7FFFFFFFLL) return false;
+        const size_t b = (size_t)B * (size_t)mlp_ldw(fc_out[j]) * 4;
+        if (j < n_fc - 1 && b > fc) fc = b;
+    }
+    L.fc[0] = take(fc);
+    L.fc[1] = take(fc);
+    L.flags = off;
+    for (int l = 0; l < n_conv + n_fc - 1; ++l) {
+        const int64_t n = l < n_conv ? cout[l] : fc_out[l - n_conv];
+        L.flag_bits[l] = take((size_t)words_for(n) * 4);
+        L.flag_inv[l] = take((size_t)n);
+    }
+    L.total = off + 256;
+    return true;
+}
+
+int run_net(const NetPlan &plan, hipStream_t s) {
+    g_engine_count = 0;
+    for (int i = 0; i < plan.n; ++i) {
+        const NetStep &st = plan.step[i];
+        int rc = QNN_OK;
+        switch (st.kind) {
+            case NetStep::kPack:
+                rc = launch_pack_bitplanes(static_cast<const uint8_t *>(st.src), st.rows, st.n, st.n, st.a,
+                                           static_cast<uint32_t *>(st.dst), st.b, st.rows * st.b, s);
+                break;
+            case NetStep::kFlags:
+                rc = launch_flags(static_cast<const uint8_t *>(st.src), st.n, static_cast<uint32_t *>(st.dst),
+                                  static_cast<uint8_t *>(st.dst2), s);
+                break;
+            case NetStep::kOnes:
+                rc = launch_ones_plane(static_cast<uint32_t *>(st.dst), st.rows, st.a, st.b, s);
+                break;
+            case NetStep::kGemm:
+                rc = launch_on(st.g, st.engine, s);
+                break;
+            case NetStep::kPool:
+                rc = launch_pool_bits(static_cast<const uint32_t *>(st.src), st.rows, st.a, st.b, st.c, st.mask, st.invert,
+                                      static_cast<uint32_t *>(st.dst), s);
+                break;
+        }
+        if (rc) return rc;
+    }
+    return QNN_OK;
+}
+}  // namespace
+
+size_t qnn_binary_convnet_workspace_bytes(int64_t B, int64_t H, int64_t Wd, int64_t C0, int in_bits, int n_conv,
+                                          const int64_t *cout, const int32_t *pool, int n_fc, const int64_t *fc_out) {
+    NetLayout L;
+    return net_layout(B, H, Wd, C0, in_bits, n_conv, cout, pool, n_fc, fc_out, L) ? L.total : 0;
+}
+
+int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t Wd, int64_t C0, int in_bits, int n_conv,
+                               const int64_t *cout, const int32_t *pool, int n_fc, const int64_t *fc_out,
+                               const uint32_t *const *W, const int32_t *const *T, const uint8_t *const *flip,
+                               int32_t *logits, int64_t ld_logits, void *workspace, size_t workspace_bytes, int engine,
+                               void *stream) {
+    if (int rc = check_engine(engine)) return rc;
+    NetLayout L;
+    if (!net_layout(B, H, Wd, C0, in_bits, n_conv, cout, pool, n_fc, fc_out, L))
+        return fail(QNN_ERR_SHAPE, "convnet: bad geometry, layer count or layer widths");
+    if (!W || !T) return fail(QNN_ERR_NULL, "convnet: W / T array is NULL");
+    if (ld_logits < fc_out[n_fc - 1]) return fail(QNN_ERR_SHAPE, "convnet: ld_logits below the output width");
+    if (B == 0) return QNN_OK;
+    if (!x || !logits) return fail(QNN_ERR_NULL, "convnet: x or logits is NULL");
+    const int n_layers = n_conv + n_fc;
+    for (int l = 0; l < n_layers; ++l) {
+        if (!W[l]) return fail(QNN_ERR_NULL, "convnet: W[%d] is NULL", l);
+        if (l < n_layers - 1 && !T[l]) return fail(QNN_ERR_NULL, "convnet: T[%d] is NULL", l);
+    }
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < L.total)
+        return fail(QNN_ERR_WORKSPACE, "convnet: workspace must be 256-byte aligned and hold %zu bytes", L.total);
+    if (B * H * Wd > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "convnet: too many pixels");
+
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    auto words = [&](size_t off) { return reinterpret_cast<uint32_t *>(ws + off); };
+    static thread_local NetPlan plan;  // large: kept out of the stack
+    plan.n = 0;
+    auto push = [&]() -> NetStep & {
+        NetStep &st = plan.step[plan.n++];
+        std::memset(&st, 0, sizeof(st));
+        return st;
+    };
+    auto choose = [&](const GemmArgs &g, int &chosen) {
+        int rc = resolve_engine(g, engine, chosen);
+        if (rc == QNN_ERR_UNSUPPORTED && engine != QNN_ENGINE_AUTO) rc = resolve_engine(g, QNN_ENGINE_AUTO, chosen);
+        return rc;
+    };
+    // per-layer flags: packed flip bits (for the pooling) and inverted flip bytes (for layers that emit plane 1)
+    for (int l = 0; l < n_layers - 1; ++l) {
+        NetStep &st = push();
+        st.kind = NetStep::kFlags;
+        st.src = flip ? flip[l] : nullptr;
+        st.n = l < n_conv ? cout[l] : fc_out[l - n_conv];
+        st.dst = ws + L.flag_bits[l];
+        st.dst2 = ws + L.flag_inv[l];
+    }
+    // the input's bit planes (Sec. 2.6): [in_bits][pixels][words per pixel]
+    const int64_t Cw0 = words_for(C0);
+    {
+        NetStep &st = push();
+        st.kind = NetStep::kPack;
+        st.src = x, st.dst = ws + L.planes0;
+        st.rows = B * H * Wd, st.n = C0, st.a = in_bits, st.b = (int)Cw0;
+    }
+    int32_t coef_in[QNN_MAX_PLANES];
+    for (int p = 0; p < in_bits; ++p) coef_in[p] = 1 << p;
+    static const int32_t kCoefPm1[2] = {1, -2};  // +1 = 01, -1 = 11, padding = 00
+    int64_t h = H, w = Wd, cin = C0;
+    int cur = 0;
+    const uint32_t *a_planes = words(L.planes0);
+    int a_count = in_bits;
+    const int32_t *a_coef = coef_in;
+    int64_t a_stride = B * H * Wd * Cw0;
+    bool empty;
+    for (int l = 0; l < n_conv; ++l) {
+        const bool last_conv = l == n_conv - 1;
+        const bool inverted = !last_conv;  // the output feeds another convolution: write plane 1 ("value is -1")
+        const int64_t co = cout[l], Cwo = words_for(co);
+        const int64_t ho = pool[l] ? h / 2 : h, wo = pool[l] ? w / 2 : w;
+        uint32_t *kept = words(L.act[cur ^ 1]);                       // plane 0 (ones) of the output, if it has one
+        uint32_t *kept_bits = inverted ? kept + B * ho * wo * Cwo : kept;  // where the output bits go
+        uint32_t *conv_dst = pool[l] ? words(L.tmp) : kept_bits;
+        const uint8_t *fl = inverted ? reinterpret_cast<const uint8_t *>(ws + L.flag_inv[l]) : (flip ? flip[l] : nullptr);
+        NetStep &st = push();
+        st.kind = NetStep::kGemm;
+        const Epilogue e{nullptr, 0, T[l], fl, conv_dst, Cwo};
+        if (int rc = conv_args(a_planes, a_count, a_coef, QNN_PLANE_BIT, a_stride, B, h, w, cin, W[l], 1, kOne, QNN_PLANE_SIGN, 0,
+                               co, 3, 3, 1, 1, e, engine, st.g, empty))
+            return rc;
+        if (int rc = choose(st.g, st.engine)) return rc;
+        if (pool[l]) {
+            NetStep &pl = push();
+            pl.kind = NetStep::kPool;
+            pl.src = conv_dst, pl.dst = kept_bits;
+            pl.rows = B, pl.a = (int)h, pl.b = (int)w, pl.c = (int)Cwo;
+            pl.mask = words(L.flag_bits[l]);
+            pl.invert = inverted;
+        }
+        if (inverted) {
+            NetStep &on = push();
+            on.kind = NetStep::kOnes;
+            on.dst = kept, on.rows = B * ho * wo, on.a = (int)Cwo, on.b = (int)co;
+        }
+        h = ho, w = wo, cin = co;
+        a_planes = kept, a_count = 2, a_coef = kCoefPm1, a_stride = B * h * w * Cwo;
+        cur ^= 1;
+    }
+    // fully connected layers on the map flattened in (y, x, c) order: the packed words of a sample are contiguous, and
+    // they are the packing of the flattened vector if the channels fill whole words (or the map is a single pixel)
+    if (cin % 32 != 0 && h * w > 1)
+        return fail(QNN_ERR_UNSUPPORTED, "convnet: the last feature map needs a multiple of 32 channels (or one pixel)");
+    int64_t in = h * w * cin;
+    const uint32_t *fa = a_planes;  // the last convolution wrote plain sign bits at the start of its buffer
+    int64_t fa_ld = h * w * words_for(cin);
+    int fcur = 0;
+    for (int j = 0; j < n_fc; ++j) {
+        const int l = n_conv + j;
+        const bool last = j == n_fc - 1;
+        const int64_t out = fc_out[j];
+        uint32_t *dst = words(L.fc[fcur]);
+        const Epilogue e = last ? Epilogue{logits, ld_logits, nullptr, nullptr, nullptr, 0}
+                                : Epilogue{nullptr, 0, T[l], flip ? flip[l] : nullptr, dst, mlp_ldw(out)};
+        NetStep &st = push();
+        st.kind = NetStep::kGemm;
+        if (int rc = gemm_args("convnet fc", fa, 1, kOne, QNN_PLANE_SIGN, fa_ld, 0, W[l], 1, kOne, QNN_PLANE_SIGN, words_for(in),
+                               0, e, B, out, in, engine, st.g, empty))
+            return rc;
+        if (int rc = choose(st.g, st.engine)) return rc;
+        fa = dst, fa_ld = mlp_ldw(out), in = out;
+        fcur ^= 1;
+    }
+    return run_net(plan, static_cast<hipStream_t>(stream));
 }
 
 int qnn_last_engine(void) { return g_last_engine; }
