@@ -21,7 +21,7 @@ def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C, OpenMP over output rows)."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
         cmd = ["gcc", "-std=c11", "-O3", "-march=native", "-fopenmp", "-fno-fast-math", "-shared", "-fPIC",
-               "-Wall", "-Wextra", "-o", _SO, _SRC]
+               "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _SO
 
@@ -210,6 +210,32 @@ def convnet(x: np.ndarray, conv_w: list, pool: list, fc_w: list, T: list, flip: 
     rc = lib().qo_convnet(_p(x), C.c_int64(B), C.c_int64(H), C.c_int64(Wd), C.c_int64(C0), C.c_int(len(conv_w)),
                           _p(cout), _p(pl), C.c_int(len(fc_w)), _p(fc_out), Wp, Tp, Fp, _p(out))
     _check(rc, "convnet")
+    return out
+
+
+def linear_quant(x: np.ndarray, step: float, qmin: int, qmax: int) -> np.ndarray:
+    """fp32 values -> int32 codes q = Clip(round(x / step), qmin, qmax) (single precision, ties to even)."""
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, dtype=np.int32)
+    rc = lib().qo_linear_quant(_p(x), C.c_int64(x.size), C.c_float(step), C.c_int32(qmin), C.c_int32(qmax), _p(out))
+    _check(rc, "linear_quant")
+    return out
+
+
+def ap2(x: np.ndarray):
+    """fp32 values -> (exponent round(log2 |x|) as int32, sign as int8 with 0 for x = 0 / NaN)."""
+    x = _c(x, np.float32)
+    e = np.empty(x.shape, dtype=np.int32)
+    s = np.empty(x.shape, dtype=np.int8)
+    _check(lib().qo_ap2(_p(x), C.c_int64(x.size), _p(e), _p(s)), "ap2")
+    return e, s
+
+
+def log_quant(x: np.ndarray, emin: int, emax: int) -> np.ndarray:
+    """fp32 values -> int8 codes: 0, or sign * (e - emin + 1) with e = min(round(log2 |x|), emax) >= emin."""
+    x = _c(x, np.float32)
+    out = np.empty(x.shape, dtype=np.int8)
+    _check(lib().qo_log_quant(_p(x), C.c_int64(x.size), C.c_int32(emin), C.c_int32(emax), _p(out)), "log_quant")
     return out
 
 

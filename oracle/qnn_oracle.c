@@ -20,6 +20,7 @@
  */
 #include <stddef.h>
 #include <stdint.h>
+#include <math.h>
 #include <stdlib.h>
 #include <string.h>
 #ifdef _OPENMP
@@ -342,6 +343,74 @@ int qo_convnet(const uint8_t *x, int64_t B, int64_t H, int64_t Wd, int64_t C0, i
     }
     free(act);
     return rc;
+}
+
+/* Linear quantization of Sec. 3, LinearQuant(x, step) = Clip(round(x / step) * step, minV, maxV), returned as the
+ * INTEGER code q = value / step (the bit-plane products consume codes; the value is q * step):
+ *   q = Clip(round(x / step), qmin, qmax),  qmin = minV / step, qmax = maxV / step.
+ * Readings (the paper's formula names the step "bitwidth" and leaves the rest open): the quotient is formed and
+ * rounded in single precision, the precision of the activations; round is to nearest with ties to even (the default
+ * of IEEE arithmetic and of the array libraries the paper used); NaN, which no comparison orders, quantizes like 0. */
+int qo_linear_quant(const float *x, int64_t n, float step, int32_t qmin, int32_t qmax, int32_t *q) {
+    if (!(step > 0.0f) || qmin > qmax) return QO_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float t = x[i] / step; /* volatile: no wider intermediate */
+        float r = nearbyintf(t);        /* default rounding mode: ties to even */
+        if (r != r) r = 0.0f;
+        int32_t v;
+        if (r <= (float)qmin)
+            v = qmin;
+        else if (r >= (float)qmax)
+            v = qmax;
+        else
+            v = (int32_t)r;
+        q[i] = v;
+    }
+    return QO_OK;
+}
+
+/* Approximate power of two (caption of Alg. 2): AP2(x) = sign(x) * 2^round(log2 |x|), evaluated in double precision
+ * on the single-precision input.  |x| is never exactly half way between two powers of two in the log domain
+ * (2^(e + 1/2) is irrational), so no tie rule is needed.  Writes the exponent round(log2 |x|) and the sign (+1 / -1);
+ * for x = 0 and NaN the sign is 0 (AP2(0) is read as 0; log2 0 has no value).  +-inf gives exponent INT32_MAX. */
+int qo_ap2(const float *x, int64_t n, int32_t *exponent, int8_t *sign) {
+    for (int64_t i = 0; i < n; ++i) {
+        double v = (double)x[i];
+        if (v != v || v == 0.0) {
+            sign[i] = 0;
+            exponent[i] = 0;
+            continue;
+        }
+        sign[i] = v > 0.0 ? 1 : -1;
+        double a = fabs(v);
+        if (isinf(a)) {
+            exponent[i] = INT32_MAX;
+            continue;
+        }
+        exponent[i] = (int32_t)floor(log2(a) + 0.5);
+    }
+    return QO_OK;
+}
+
+/* Logarithmic quantization of Sec. 3, LogQuant(x) = Clip(AP2(x), minV, maxV), as a signed code:
+ *   code = 0                          if x is 0 or NaN, or AP2(x) lies below 2^emin in magnitude,
+ *   code = sign(x) * (e - emin + 1)   otherwise, e = min(round(log2 |x|), emax);   value = sign * 2^(emin + |code| - 1).
+ * Reading: minV and maxV bound the MAGNITUDE (2^emin and 2^emax); what rounds below the smallest magnitude is
+ * flushed to zero, what rounds above the largest is clipped to it.  emax - emin + 1 <= 127. */
+int qo_log_quant(const float *x, int64_t n, int32_t emin, int32_t emax, int8_t *code) {
+    if (emin > emax || (int64_t)emax - emin + 1 > 127) return QO_ERR_ARG;
+    for (int64_t i = 0; i < n; ++i) {
+        int32_t e;
+        int8_t sg;
+        qo_ap2(x + i, 1, &e, &sg);
+        if (sg == 0 || e < emin) {
+            code[i] = 0;
+            continue;
+        }
+        if (e > emax) e = emax;
+        code[i] = (int8_t)(sg * (e - emin + 1));
+    }
+    return QO_OK;
 }
 
 /* Number of threads the OpenMP loops above actually use (reported beside the CPU-baseline timing). */

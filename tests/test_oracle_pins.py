@@ -437,3 +437,54 @@ def test_convnet_without_convolutions_is_the_mlp(seed):
     flip = [qi.bernoulli_bits(seed, 1408 + l, (dims[l + 1],)) for l in range(2)]
     got = oracle.convnet(x.reshape(B, 1, 1, dims[0]), [], [], W, T, flip)
     assert np.array_equal(got, oracle.mlp(x, W, T, flip))
+
+
+# ---------------------------------------------------------------- quantizers of Sec. 3 and AP2 of Alg. 2's caption
+def test_linear_quant_hand_values_and_library(seed):
+    """LinearQuant(x, step) = Clip(round(x / step) * step, minV, maxV) on hand-computed cases (step 0.25, range
+    [-2, 1.75] = codes [-8, 7]): interior values, both clips, ties to even, signed zero, NaN; then numpy's single
+    precision rint / clip on random values."""
+    x = np.array([0.26, 0.37, 0.38, 0.125, 0.375, -0.125, -0.375, 0.625, 5.0, -9.0, 1.75, 1.8, -2.0, 0.0, -0.0, np.nan,
+                  np.inf, -np.inf], dtype=np.float32)
+    want = [1, 1, 2, 0, 2, 0, -2, 2, 7, -8, 7, 7, -8, 0, 0, 0, 7, -8]
+    assert oracle.linear_quant(x, 0.25, -8, 7).tolist() == want
+    assert oracle.linear_quant(np.array([0.5, 1.5, 2.5, 3.5], dtype=np.float32), 1.0, 0, 3).tolist() == [0, 2, 2, 3]
+    v = qi.normal_f32(seed, 1800, (4000,)) * np.float32(3.0)
+    for step, lo, hi in [(0.1, 0, 15), (0.3, -8, 7), (1.0 / 3.0, -2, 1)]:
+        lib_q = np.clip(np.rint(v / np.float32(step)), lo, hi).astype(np.int32)  # float32 division, ties to even
+        assert np.array_equal(oracle.linear_quant(v, step, lo, hi), lib_q)
+    with pytest.raises(RuntimeError):
+        oracle.linear_quant(v, 0.0, 0, 3)
+
+
+def test_ap2_closed_forms_and_library(seed):
+    """AP2(x) = sign(x) 2^round(log2 |x|): exact powers of two map to themselves; 3 -> 4 (log2 3 = 1.58), 2.8 -> 2
+    (1.485), 2.83 -> 4 (1.5008), 0.7 -> 0.5 (-0.515), 0.71 -> 1 (-0.494); the two floats next to sqrt(2); a denormal;
+    then numpy's log2 / round in double on random values."""
+    x = np.array([1.0, 2.0, 0.5, -8.0, 3.0, -3.0, 2.8, 2.83, 0.7, 0.71, 0.0, -0.0, np.nan], dtype=np.float32)
+    e, s = oracle.ap2(x)
+    assert e.tolist() == [0, 1, -1, 3, 2, 2, 1, 2, -1, 0, 0, 0, 0]
+    assert s.tolist() == [1, 1, 1, -1, 1, -1, 1, 1, 1, 1, 0, 0, 0]
+    below, above = np.array([0x3FB504F3, 0x3FB504F4], dtype=np.uint32).view(np.float32)  # neighbours of sqrt(2)
+    assert oracle.ap2(np.array([below, above, below * 4, above / 8], dtype=np.float32))[0].tolist() == [0, 1, 2, -2]
+    assert oracle.ap2(np.array([2.0 ** -140, 3.0 * 2.0 ** -149], dtype=np.float32))[0].tolist() == [-140, -147]
+    v = qi.normal_f32(seed, 1801, (5000,)) * np.float32(40.0)
+    v = v[v != 0]
+    e, s = oracle.ap2(v)
+    assert np.array_equal(e, np.round(np.log2(np.abs(v.astype(np.float64)))).astype(np.int32))
+    assert np.array_equal(s, np.sign(v).astype(np.int8))
+    # the defining property: |x| / AP2(x) lies in [2^-1/2, 2^1/2)
+    ratio = np.abs(v.astype(np.float64)) / 2.0 ** e
+    assert (ratio >= 2 ** -0.5).all() and (ratio < 2 ** 0.5).all()
+
+
+def test_log_quant_hand_values():
+    """LogQuant(x) = Clip(AP2(x), minV, maxV) with magnitudes 2^-3 .. 2^2 (emin = -3, emax = 2): codes 1 .. 6 with the
+    sign; below 2^-3.5 flushed to 0, above clipped."""
+    x = np.array([1.0, -1.0, 0.125, 0.1, 0.09, 0.08, 4.0, 5.0, 100.0, -100.0, 0.0, np.nan, np.inf, -0.7, 3.0],
+                 dtype=np.float32)
+    #            1    -1   2^-3  ~2^-3 ~2^-3  <2^-3.5 2^2  2^2   clip   clip   0    nan     inf   2^-1  2^2
+    assert oracle.log_quant(x, -3, 2).tolist() == [4, -4, 1, 1, 1, 0, 6, 6, 6, -6, 0, 0, 6, -3, 6]
+    codes = oracle.log_quant(x, -3, 2).astype(np.int64)
+    vals = np.sign(codes) * 2.0 ** (-3 + np.abs(codes) - 1) * (codes != 0)
+    assert vals.tolist()[:7] == [1.0, -1.0, 0.125, 0.125, 0.125, 0.0, 4.0]
