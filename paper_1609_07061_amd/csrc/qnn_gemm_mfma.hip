@@ -1,6 +1,9 @@
 // Matrix-core engine of the binary / bit-plane matrix product: host side (operand codes, epilogue constants, choice of
 // the kernel instantiation, launch).  The kernel itself is in qnn_gemm_mfma_kernel.h.
+#include <cstdlib>
+
 #include "qnn_gemm_mfma_kernel.h"
+#include "qnn_gemm_panel_kernel.h"
 #include "qnn_gemm_stage_kernel.h"
 
 namespace qnn {
@@ -171,6 +174,22 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
     const int cus = compute_units();
     const int64_t total = tiles_m * tiles_n;
     const unsigned grid = (unsigned)(total < cus ? total : cus);
+    // single-plane products on the FP4 path whose rows are made of whole, aligned 16-byte groups: the panel-fed kernel
+    static const bool no_panel = std::getenv("QNN_NO_PANEL") != nullptr;
+    // (it addresses rows by 32-bit byte offsets from the operand's base)
+    const bool spans32 = 4.0L * (long double)g.M * g.A.ld < 4294967296.0L && 4.0L * (long double)g.N * g.ldw < 4294967296.0L;
+    if (fp4 && vec && spans32 && !no_panel && !g.A.rows_are_pixels && !g.A.rows_are_bytes && v->WPL == 4 &&
+        g.Kw % panel::kGroupWords == 0) {
+        const int64_t ngroups = ceil_div(g.Kw, panel::kGroupWords);
+        int64_t aA, bA, xA0, aW, bW, xW0;
+        MfmaConst pc = mc;
+        if (make_code(g.pa, pc.a, aA, bA, xA0) && make_code(g.pw, pc.w, aW, bW, xW0) &&
+            fill_consts(g, aA, bA, xA0, aW, bW, xW0, ngroups * panel::kGroupWords * 32, pc)) {
+            const panel::KernelFn pf = panel::find_kernel(g.epi.T != nullptr);
+            return QNN_LAUNCH("gemm_panel", pf, dim3(grid), dim3(panel::kThreads), 0, s, g, pc, (uint32_t)tiles_m,
+                              (uint32_t)tiles_n, (uint32_t)ngroups);
+        }
+    }
     const KernelFn fn = g.A.rows_are_bytes ? byte_kernels()[g.epi.T ? 1 : 0]
                         : fp4              ? (vec ? v->fp4_vec : v->fp4_any)
                                            : (vec ? v->fn_vec : v->fn_any);

@@ -1,0 +1,502 @@
+// Matrix-core engine, panel-fed kernel for single-plane products on the FP4 path (the binary product of Sec. 6,
+// Eq. (popc), and the hidden layers of Alg. 4).
+//
+// gemm_mfma_kernel lets every lane load the packed words of "its" operand row straight from global memory.  The 64
+// lanes of such a load touch 64 different 128-byte lines, and the address path of a compute unit handles one line per
+// cycle: 64 cycles per load instruction, 32 load instructions per workgroup and step, i.e. 2048 cycles, exactly the
+// time the matrix cores need for the 64 FP4 instructions of that step; and with one wave per SIMD every cycle a wave
+// waits for memory is lost.  A load whose neighbouring lanes read neighbouring 16-byte pieces of one line costs 16 to
+// 19 cycles (measured with a load-only kernel).  So here
+//   * the workgroup brings in the operand rows it shares as whole lines, a group of four steps (128 bytes of every
+//     row: 256 activation rows + 256 weight rows = 64 KiB) at a time, with loads that write straight to LDS
+//     (global_load_lds_dwordx4: no registers are held while the data is on its way), each wave 16 of them per group,
+//     issued right after the barrier that frees a group buffer, i.e. at least three steps (about 6000 cycles)
+//     before the data is needed; two group buffers take turns;
+//   * a 16-byte piece c of row r sits at piece c xor (r mod 8) of its LDS row (the lanes of a load pick their global
+//     piece accordingly; the order of pieces inside a line does not change the cost of the load), so that the reads
+//     (lanes = consecutive rows, same piece) use all banks;
+//   * every lane reads the 16 bytes of its row and k-group for the next step with one ds_read_b128 per 32-row block;
+//   * words become E2M1 operands in registers with ONE instruction per register: phase t of a step multiplies bit t of
+//     every nibble of the lane's four words, and a nibble with only bit 0 / 1 / 2 set is 0.5 / 1.0 / 2.0, which the
+//     block scale of the instruction (exact powers of two) turns into 1;
+//   * one workgroup barrier per group (between its third and fourth step: by then every wave holds the fourth step's
+//     words in registers and the next group is complete in the other buffer).
+// Requirements (otherwise gemm_mfma_kernel takes the product): one plane per operand, rows of whole 128-byte groups
+// starting on 16-byte boundaries, operands that span less than 4 GiB each.
+#pragma once
+#include "qnn_gemm_mfma_kernel.h"
+
+namespace qnn {
+namespace panel {
+
+using mfma::acc_to_sum;
+using mfma::expand_fp4;
+using mfma::i32x4;
+using mfma::MfmaConst;
+using mfma::or_halves;
+using mfma::sum_halves;
+using mfma::v16f;
+using mfma::v8i;
+
+constexpr int kThreads = 256;
+constexpr int WB = 4, WTILE = 128, BM = 256, BN = 256;
+constexpr int kRowBytes = 128;                 // bytes of a row per group: four steps of two 16-byte k-groups
+constexpr int kPanelBytes = BM * kRowBytes;    // one operand's 256 rows
+constexpr int kGroupBytes = 2 * kPanelBytes;   // activation panel, then weight panel
+constexpr int kGroupWords = kRowBytes / 4;
+
+__device__ __forceinline__ uint32_t word_of(const uint4 &v, int t) { return t == 0 ? v.x : (t == 1 ? v.y : (t == 2 ? v.z : v.w)); }
+
+// Schedule of one phase: 16 matrix-core instructions, each followed by its share of kValu vector-ALU instructions;
+// kDsRead LDS reads behind the first matrix-core instructions, kDsWrite LDS writes and then kVmem global loads behind
+// the following ones (one each).
+template <int kValu, int kDsRead, int kDsWrite, int kVmem, int... I>
+__device__ __forceinline__ void phase_groups(std::integer_sequence<int, I...>) {
+    constexpr int n = (int)sizeof...(I);
+    ((__builtin_amdgcn_sched_group_barrier(0x008, 1, 0),
+      __builtin_amdgcn_sched_group_barrier(0x002, kValu / n + (I < kValu % n ? 1 : 0), 0),
+      (I < kDsRead ? __builtin_amdgcn_sched_group_barrier(0x100, 1, 0) : (void)0),
+      (I < kDsWrite ? __builtin_amdgcn_sched_group_barrier(0x200, 1, 0) : (void)0),
+      (I >= kDsWrite && I < kDsWrite + kVmem ? __builtin_amdgcn_sched_group_barrier(0x020, 1, 0) : (void)0)),
+     ...);
+}
+
+// kSign: threshold epilogue (Alg. 4: a^b = Sign(BatchNorm(a))) instead of int32 sums.
+template <bool kSign>
+__global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
+                                                                  uint32_t tiles_n, uint32_t ngroups) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kGroupBytes];
+    __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
+    __shared__ __attribute__((aligned(16))) int32_t thr_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
+    __shared__ __attribute__((aligned(16))) uint32_t flip_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
+    // int32 epilogue: per wave one 32 x 32 staging block, through which a block is turned from the accumulator layout
+    // (a lane = one row) into whole 128-byte lines per row
+    __shared__ __attribute__((aligned(16))) int32_t stage[kSign ? 1 : kThreads / 64][kSign ? 4 : 32 * 32];
+
+    const int t = threadIdx.x;
+    const int lane = t & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+    const int r = lane & 31, kg = lane >> 5;
+    const int wm = wave >> 1, wn = wave & 1;
+    const uint32_t Kw = (uint32_t)g.Kw;
+    const uint32_t total_tiles = tiles_m * tiles_n;
+    const int64_t Nw = (g.N + 31) / 32;
+
+    // ------------------------------------------------------------------------------------------------ producer
+    // A load instruction of a wave covers 8 consecutive rows x 128 bytes and fills 1 KiB of LDS: lane i lands at
+    // 16 i behind the address in M0, i.e. in slot i mod 8 of row i / 8, so it fetches piece (i mod 8) xor (row mod 8).
+    // Per quarter (64 rows) of a panel wave w loads rows 8 w .. 8 w + 7 and 32 + 8 w .. 32 + 8 w + 7.  Rows are
+    // addressed by 32-bit byte offsets from the operand's base.
+    // The lane-dependent parts are re-derived behind an opaque copy wherever they are used: address arithmetic that the
+    // compiler computes once before the loops ends up spilled, and every reload in the main loop stalls the wave.
+    auto opaque = [](uint32_t x) __attribute__((always_inline)) {
+        asm volatile("" : "+v"(x));
+        return x;
+    };
+    const uint32_t tid = (uint32_t)t;
+    const uint32_t lds_base = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t *)lds);
+    // the group being loaded: tile p_vb (origin p_m0, p_n0), group p_G of its row
+    uint32_t p_vb = blockIdx.x, p_G = 0;
+    uint32_t p_m0 = 0, p_n0 = 0;
+    const uint32_t lda_bytes = (uint32_t)g.A.ld * 4u, ldw_bytes = (uint32_t)g.ldw * 4u;
+    const uint32_t last_m = (uint32_t)(g.M - 1), last_n = (uint32_t)(g.N - 1);
+    auto p_locate = [&]() __attribute__((always_inline)) {
+        uint32_t tm, tn;
+        tile_of_block(p_vb, total_tiles, tiles_m, tiles_n, tm, tn);
+        p_m0 = tm * (uint32_t)BM;
+        p_n0 = tn * (uint32_t)BN;
+    };
+    auto p_advance = [&]() __attribute__((always_inline)) {
+        ++p_G;
+        const bool wrap = p_G == ngroups;
+        const uint32_t nb = p_vb + gridDim.x;
+        // after the last tile the loads are repeated and never used
+        p_vb = (wrap && nb < total_tiles) ? nb : p_vb;
+        p_G = wrap ? 0u : p_G;
+        p_locate();
+    };
+    // 16 bytes per lane from base + voff to LDS address lds_addr + 16 * lane (the address travels in M0)
+    auto load_to_lds = [](const void *base, uint32_t voff, uint32_t lds_addr) __attribute__((always_inline)) {
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory");
+    };
+    // quarter q of the group at the cursor into the group buffer at byte offset buf
+    auto load_quarter = [&](const int q, const uint32_t buf) __attribute__((always_inline)) {
+        const uint32_t tt = opaque(tid);
+        const uint32_t pr = tt >> 3;                           // row of the quarter's first half (0..31)
+        const uint32_t piece = (tt & 7u) ^ ((tt >> 3) & 7u);   // slot xor (row mod 8)
+        const uint32_t jb = (p_G * kGroupWords + piece * 4u) * 4u;
+        const uint32_t dst = lds_base + buf + (uint32_t)(q * (64 * kRowBytes)) + (uint32_t)wave * (8u * kRowBytes);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            uint32_t m = p_m0 + (uint32_t)(64 * q + 32 * h) + pr;
+            m = m > last_m ? last_m : m;
+            load_to_lds(g.A.base, m * lda_bytes + jb, dst + (uint32_t)(h * 32 * kRowBytes));
+            uint32_t n = p_n0 + (uint32_t)(64 * q + 32 * h) + pr;
+            n = n > last_n ? last_n : n;
+            load_to_lds(g.W, n * ldw_bytes + jb, dst + (uint32_t)(kPanelBytes + h * 32 * kRowBytes));
+        }
+    };
+
+    // ------------------------------------------------------------------------------------------------ consumer
+    // lane (r, kg) of block b reads piece 2 q + kg of row 32 b + r at step q of a group
+    struct Step {
+        uint4 A[WB], W[WB];
+    };
+    auto fetch = [&](const int q, const uint32_t buf, Step &d) __attribute__((always_inline)) {
+        const uint32_t ln = opaque(tid) & 63u;
+        const uint32_t r = ln & 31u, kg = ln >> 5;
+        const uint32_t piece = ((kg ^ (r & 7u)) << 4) ^ (uint32_t)(q << 5);
+        const uint8_t *pa = lds + (buf + (uint32_t)(wm * WTILE * kRowBytes) + r * (uint32_t)kRowBytes + piece);
+        const uint8_t *pw = lds + (buf + (uint32_t)(kPanelBytes + wn * WTILE * kRowBytes) + r * (uint32_t)kRowBytes + piece);
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+            d.A[b] = *reinterpret_cast<const uint4 *>(pa + b * (32 * kRowBytes));
+            d.W[b] = *reinterpret_cast<const uint4 *>(pw + b * (32 * kRowBytes));
+        }
+    };
+
+    v16f acc[WB][WB];  // [n block][m block]
+    int32_t ra[WB], rw[WB];
+    auto clear = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int i = 0; i < WB; ++i) {
+            ra[i] = rw[i] = 0;
+#pragma unroll
+            for (int j = 0; j < WB; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+        }
+    };
+    struct Frags {
+        v8i a[WB], w[WB];
+    };
+    // Phase t of a step multiplies bit t of every nibble of the lane's four words (32 of its 128 elements of k; both
+    // operands use the same order).  An E2M1 nibble with only bit 0 set is 0.5, with bit 1 set 1.0, with bit 2 set 2.0,
+    // so for t = 0, 1, 2 one AND per word makes the operand and the block scale of the instruction (2, 1, 1/2 on
+    // both sides: exact powers of two) turns every product of two set bits into 1; bit 3 is the sign and is moved to
+    // bit 1 first.  20 vector-ALU instructions per 128 elements instead of 28 with shift-and-mask throughout.
+    auto expand = [&](const Step &c, const int tt, Frags &f) __attribute__((always_inline)) {
+        const uint32_t mask = tt == 0 ? 0x11111111u : (tt == 2 ? 0x44444444u : 0x22222222u);
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t a = word_of(c.A[b], j), w = word_of(c.W[b], j);
+                f.a[b][j] = (int)((tt == 3 ? a >> 2 : a) & mask);
+                f.w[b][j] = (int)((tt == 3 ? w >> 2 : w) & mask);
+            }
+#pragma unroll
+            for (int j = 4; j < 8; ++j) f.a[b][j] = f.w[b][j] = 0;
+        }
+    };
+    // row sums of the raw bits: one word of every row per phase.  Each sum is made opaque after its addition: left
+    // alone, the compiler keeps the counts of a whole loop trip in registers of their own and adds them up at the end
+    // (three-operand adds), which costs over a hundred registers and spills the sums themselves.
+    auto count = [&](const Step &c, const int tt) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+            ra[b] += (int32_t)__builtin_popcount(word_of(c.A[b], tt));
+            rw[b] += (int32_t)__builtin_popcount(word_of(c.W[b], tt));
+            asm("" : "+v"(ra[b]));
+            asm("" : "+v"(rw[b]));
+        }
+    };
+    // block scales of the four phases as E8M0 bytes (2^(e - 127)): 2, 1, 1/2, 1
+    const int scales = 0x7F7E7F80;
+    auto multiply = [&](const Frags &f, auto t_tag) __attribute__((always_inline)) {
+        constexpr int tt = decltype(t_tag)::value;
+#pragma unroll
+        for (int i = 0; i < WB; ++i)
+#pragma unroll
+            for (int j = 0; j < WB; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.w[i], f.a[j], acc[i][j], 4, 4, tt, scales, tt, scales);
+    };
+    // One step = four phases; each phase multiplies the operands made during the previous one and meanwhile counts
+    // one word per row and makes the next phase's operands.  `issue_fetch` (the LDS reads of the following step) runs
+    // inside the first phase; `produce(t)` is called in every phase (the fourth step of a group uses it to start the
+    // loads of a quarter of the group after the next).
+    auto compute = [&](const Step &c, const Step &n, Frags &f, auto issue_fetch, auto produce,
+                       auto last_tag) __attribute__((always_inline)) {
+        constexpr bool kLastStep = decltype(last_tag)::value;
+        auto phase = [&](auto t_tag) __attribute__((always_inline)) {
+            constexpr int tt = decltype(t_tag)::value;
+            if (tt == 0) issue_fetch();
+            produce(t_tag);
+            Frags gnext;
+            count(c, tt);
+            if (tt + 1 < 4)
+                expand(c, tt + 1, gnext);
+            else if (!kLastStep)
+                expand(n, 0, gnext);
+            multiply(f, t_tag);
+            // vector-ALU instructions of this phase: operands of the next one (4 per row, 8 for bit 3) and the counts
+            constexpr int kOps = 2 * WB * ((tt == 2 ? 8 : 4) + 1);
+            if (tt == 0)
+                phase_groups<kOps + 8, 2 * WB, 0, 0>(std::make_integer_sequence<int, 16>{});
+            else
+                phase_groups<kOps, 0, 0, 0>(std::make_integer_sequence<int, 16>{});
+            __builtin_amdgcn_sched_barrier(0);
+            if (!(kLastStep && tt == 3)) f = gnext;
+        };
+        phase(std::integral_constant<int, 0>{});
+        phase(std::integral_constant<int, 1>{});
+        phase(std::integral_constant<int, 2>{});
+        phase(std::integral_constant<int, 3>{});
+    };
+
+    // thresholds / flip flags of the tile being finished: n = n_wave + lane and n_wave + 64 + lane (clamped into range)
+    int32_t thr_T[2] = {0, 0};
+    uint32_t thr_F[2] = {0u, 0u};
+    auto load_thresholds = [&](const int64_t n_wave) __attribute__((always_inline)) {
+        if constexpr (kSign) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                int64_t n = n_wave + 64 * h + lane;
+                if (n > g.N - 1) n = g.N - 1;
+                thr_T[h] = g.epi.T[n];
+                thr_F[h] = g.epi.flip ? (uint32_t)g.epi.flip[n] : 0u;
+            }
+        }
+    };
+
+    // Accumulator register v of block [bi][bj] is C[m][n] with
+    //   m = m_wave + 32 bj + (lane mod 32),   n = n_wave + 32 bi + 8 (v / 4) + 4 (lane / 32) + v mod 4.
+    // kFast: the wave tile lies completely inside C and C allows 16-byte stores, so nothing needs a bounds check.
+    auto epilogue = [&](const int64_t m_wave, const int64_t n_wave, auto scale, auto fast_tag) __attribute__((always_inline)) {
+        constexpr bool kFast = decltype(fast_tag)::value;
+        // lane coordinates re-derived behind an opaque copy: index arithmetic computed before the tile loop and kept
+        // across it would be spilled, and a reload waits for every store issued before it
+        int lane_opaque = (int)(threadIdx.x & 63);
+        asm volatile("" : "+v"(lane_opaque));
+        const int lane = lane_opaque, r = lane & 31, kg = lane >> 5;
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+            ra[b] = sum_halves(ra[b]);
+            rw[b] = sum_halves(rw[b]);
+        }
+        if (mc.needRW) {
+            if (kg == 0) {
+#pragma unroll
+                for (int b = 0; b < WB; ++b) rw_table[wave][b * 32 + r] = mc.cRW * (uint32_t)rw[b];
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's own LDS writes have landed
+            __builtin_amdgcn_wave_barrier();
+        }
+        int64_t m_of[WB];
+        uint32_t mterm[WB];
+#pragma unroll
+        for (int bj = 0; bj < WB; ++bj) {
+            m_of[bj] = m_wave + bj * 32 + r;
+            mterm[bj] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
+        }
+        if constexpr (kSign) {
+            // thresholds, clamped and minus one, and flip flags at the bit position their n has in a lane's partial
+            // output word (n mod 32 = 8 q + 4 kg + i  ->  bit 8 q + i), into per-wave LDS tables
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int nl = 64 * h + lane;
+                const int32_t tv = thr_T[h];
+                const int32_t tc = tv < -(1 << 30) ? -(1 << 30) : (tv > (1 << 30) ? (1 << 30) : tv);
+                thr_table[wave][nl] = tc - 1;
+                flip_table[wave][nl] = thr_F[h] != 0 ? (1u << ((nl & 0x18) | (nl & 3))) : 0u;
+            }
+            __builtin_amdgcn_s_waitcnt(0xc07f);
+            __builtin_amdgcn_wave_barrier();
+        }
+        // kFast int32 output: lines of the block before the current one, read from LDS and not stored yet; lane
+        // (row = lane / 8, 16-byte unit = lane mod 8) of store j writes row 8 j + lane / 8 of the block
+        i32x4 pend[4];
+        int32_t *const line_base = kSign ? nullptr : g.epi.C + (m_wave + (lane >> 3)) * g.epi.ldc + n_wave + 4 * (lane & 7);
+        auto store_lines = [&](const int pbi, const int pbj) __attribute__((always_inline)) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<i32x4 *>(line_base + (int64_t)(pbj * 32 + 8 * j) * g.epi.ldc + pbi * 32) = pend[j];
+        };
+#pragma unroll
+        for (int bi = 0; bi < WB; ++bi) {
+            const int64_t n_blk = n_wave + bi * 32;
+            uint32_t nterm[16];  // the part that depends on n only
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint4 t4 = make_uint4(0u, 0u, 0u, 0u);
+                if (mc.needRW) t4 = *reinterpret_cast<const uint4 *>(&rw_table[wave][bi * 32 + 8 * q + 4 * kg]);
+                nterm[4 * q] = t4.x, nterm[4 * q + 1] = t4.y, nterm[4 * q + 2] = t4.z, nterm[4 * q + 3] = t4.w;
+            }
+            if constexpr (!kSign) {
+#pragma unroll
+                for (int bj = 0; bj < WB; ++bj) {
+                    int32_t *row = g.epi.C + m_of[bj] * g.epi.ldc + n_blk + 4 * kg;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        i32x4 val;
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            val[i] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + i])) + nterm[4 * q + i] + mterm[bj]);
+                        if constexpr (kFast) {
+                            // 16-byte unit 2 q + kg of row r, swizzled with the row: neither this write nor the read
+                            // below puts two lanes of a pass on one LDS bank
+                            *reinterpret_cast<i32x4 *>(&stage[wave][r * 32 + 4 * ((2 * q + kg) ^ ((r >> 1) & 7))]) = val;
+                        } else if (m_of[bj] < g.M) {
+                            const int64_t n0 = n_blk + 8 * q + 4 * kg;
+#pragma unroll
+                            for (int i = 0; i < 4; ++i)
+                                if (n0 + i < g.N) row[8 * q + i] = val[i];
+                        }
+                    }
+                    if constexpr (kFast) {
+                        // read the block back as 8 rows x 128 bytes per instruction (LDS operations of a wave execute
+                        // in order; only the compiler has to be kept from reordering them) and store those lines one
+                        // block later, which hides the LDS round trip behind the next block's arithmetic
+                        __builtin_amdgcn_wave_barrier();
+                        i32x4 line[4];
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) {
+                            const int R = 8 * j + (lane >> 3);
+                            line[j] = *reinterpret_cast<const i32x4 *>(&stage[wave][R * 32 + 4 * ((lane & 7) ^ ((R >> 1) & 7))]);
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                        if (bi + bj > 0) store_lines((bi * WB + bj - 1) / WB, (bi * WB + bj - 1) % WB);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j) pend[j] = line[j];
+                    }
+                }
+            } else {
+                // e[v] = T - 1 - (part of C that depends on n only): C >= T  <=>  e[v] - (rest of C) < 0.  All terms
+                // are below 2^30 in magnitude (the host checks the bound of C, thresholds are clamped to it, which
+                // does not change any comparison), so the differences cannot wrap.
+                int32_t e[16];
+                uint32_t flips = 0, live_bits = 0;  // at the bit positions 8 (v / 4) + v mod 4 of the partial word
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int col = bi * 32 + 8 * q + 4 * kg;
+                    const int4 t4 = *reinterpret_cast<const int4 *>(&thr_table[wave][col]);
+                    const uint4 f4 = *reinterpret_cast<const uint4 *>(&flip_table[wave][col]);
+                    e[4 * q + 0] = t4.x - (int32_t)nterm[4 * q + 0], e[4 * q + 1] = t4.y - (int32_t)nterm[4 * q + 1];
+                    e[4 * q + 2] = t4.z - (int32_t)nterm[4 * q + 2], e[4 * q + 3] = t4.w - (int32_t)nterm[4 * q + 3];
+                    flips |= f4.x | f4.y | f4.z | f4.w;
+                }
+                if constexpr (kFast) {
+                    live_bits = 0x0F0F0F0Fu;
+                } else {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v)
+                        if (n_blk + 8 * (v >> 2) + 4 * kg + (v & 3) < g.N) live_bits |= 1u << (8 * (v >> 2) + (v & 3));
+                }
+                const int64_t word = n_blk >> 5;
+#pragma unroll
+                for (int bj = 0; bj < WB; ++bj) {
+                    // four bits per group of consecutive n, most significant first: the sign bit of e[v] - (rest of
+                    // C) is appended with one funnel shift; flips and the n tail are applied to the whole word
+                    uint32_t bits = 0;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        uint32_t nib = 0;
+#pragma unroll
+                        for (int i = 3; i >= 0; --i) {
+                            const int v = 4 * q + i;
+                            const uint32_t rest = scale(acc_to_sum(acc[bi][bj][v])) + mterm[bj];
+                            const uint32_t x = (uint32_t)e[v] - rest;
+                            nib = __builtin_amdgcn_alignbit(nib, x, 31);  // (nib << 1) | (x >> 31)
+                        }
+                        bits |= nib << (8 * q);
+                    }
+                    bits = (bits ^ flips) & live_bits;
+                    bits <<= 4 * kg;
+                    bits = or_halves(bits);
+                    if (kg == 0 && (kFast || (m_of[bj] < g.M && word < Nw)))
+                        g.epi.out_bits[m_of[bj] * g.epi.ldo + word] = bits;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        if constexpr (kFast && !kSign) store_lines(WB - 1, WB - 1);
+    };
+    auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
+        const bool interior = m_wave + WTILE <= g.M && n_wave + WTILE <= g.N;
+        const bool wide = kSign || ((g.epi.ldc % 4 == 0) && (reinterpret_cast<uintptr_t>(g.epi.C) % 16 == 0));
+        const bool fast = interior && wide;
+        if (mc.alpha_shift >= 0) {
+            const int sh = mc.alpha_shift;
+            auto scale = [sh](uint32_t x) { return x << sh; };
+            if (fast)
+                epilogue(m_wave, n_wave, scale, std::true_type{});
+            else
+                epilogue(m_wave, n_wave, scale, std::false_type{});
+        } else {
+            const uint32_t al = mc.alpha;
+            auto scale = [al](uint32_t x) { return x * al; };
+            if (fast)
+                epilogue(m_wave, n_wave, scale, std::true_type{});
+            else
+                epilogue(m_wave, n_wave, scale, std::false_type{});
+        }
+    };
+
+    // workgroup barrier of the group buffers: this wave's loads to LDS have landed and its LDS reads have returned
+    auto panel_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+
+    // ------------------------------------------------------------------------------------------------ prologue
+    // groups 0 and 1 into the two buffers; the cursor stays at group 1
+    p_locate();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) load_quarter(q, 0u);
+    p_advance();
+#pragma unroll
+    for (int q = 0; q < 4; ++q) load_quarter(q, (uint32_t)kGroupBytes);
+    panel_barrier();
+
+    Step buf0, buf1;
+    Frags frags;
+    uint32_t rd = 0u;  // byte offset of the group buffer being consumed
+    fetch(0, rd, buf0);
+    expand(buf0, 0, frags);
+
+    auto no_produce = [](auto) __attribute__((always_inline)) {};
+    // Fourth step of a group (after the barrier, the buffer just consumed is free): phase t starts the loads of
+    // quarter t of the group after the next into it.
+    auto produce = [&](auto t_tag) __attribute__((always_inline)) {
+        constexpr int tt = decltype(t_tag)::value;
+        load_quarter(tt, rd);
+    };
+
+    uint32_t vb = blockIdx.x;
+    while (true) {
+        uint32_t tile_m, tile_n;
+        tile_of_block(vb, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
+        const int64_t m_wave = (int64_t)tile_m * BM + wm * WTILE, n_wave = (int64_t)tile_n * BN + wn * WTILE;
+        clear();
+        // one group of four steps; kLastGroup: its last step ends the tile
+        auto group = [&](auto last_tag) __attribute__((always_inline)) {
+            constexpr bool kLastGroup = decltype(last_tag)::value;
+            const uint32_t other = (uint32_t)kGroupBytes - rd;
+            // the cursor moves on to the group that this group's fourth step will load (scalar control flow: kept at
+            // the head of the group, so that the phases of a step stay one straight-line block)
+            p_advance();
+            compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(1, rd, buf1); }, no_produce, std::false_type{});
+            compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) { fetch(2, rd, buf0); }, no_produce, std::false_type{});
+            compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(3, rd, buf1); }, no_produce, std::false_type{});
+            panel_barrier();
+            // last step of the tile: the operands of the next tile's first phase are made after the epilogue, so that
+            // they do not occupy registers during it; the thresholds are loaded meanwhile
+            compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) {
+                fetch(0, other, buf0);
+                if (kLastGroup) load_thresholds(n_wave);
+            }, produce, last_tag);
+            rd = other;
+        };
+        for (uint32_t G = 0; G + 1 < ngroups; ++G) group(std::false_type{});
+        group(std::true_type{});
+        finish(m_wave, n_wave);
+        expand(buf0, 0, frags);
+        vb += gridDim.x;
+        if (vb >= total_tiles) break;
+    }
+}
+
+typedef void (*KernelFn)(const GemmArgs, const MfmaConst, uint32_t, uint32_t, uint32_t);
+KernelFn find_kernel(bool sign);
+
+}  // namespace panel
+}  // namespace qnn
