@@ -239,5 +239,50 @@ def log_quant(x: np.ndarray, emin: int, emax: int) -> np.ndarray:
     return out
 
 
+def log_code_value(code: np.ndarray) -> np.ndarray:
+    """int8 logarithmic codes -> int32 fixed-point values sign(c) * 2^(|c| - 1) (0 for code 0)."""
+    code = _c(code, np.int8)
+    out = np.empty(code.shape, dtype=np.int32)
+    _check(lib().qo_log_code_value(_p(code), C.c_int64(code.size), _p(out)), "log_code_value")
+    return out
+
+
+def ste_mask(g: np.ndarray, a: np.ndarray) -> np.ndarray:
+    """fp32 gradient g where |a| <= 1, else 0 (straight-through estimator of Alg. 1)."""
+    g = _c(g, np.float32)
+    a = _c(a, np.float32)
+    assert g.shape == a.shape
+    out = np.empty(g.shape, dtype=np.float32)
+    _check(lib().qo_ste_mask(_p(g), _p(a), C.c_int64(g.size), _p(out)), "ste_mask")
+    return out
+
+
+def bn_affine(s: np.ndarray, scale: np.ndarray, shift: np.ndarray) -> np.ndarray:
+    """int32 sums [M][N] -> fp32 fma(s, scale[n], shift[n])."""
+    s = _c(s, np.int32)
+    scale = _c(scale, np.float32)
+    shift = _c(shift, np.float32)
+    M, N = s.shape
+    assert scale.shape == (N,) and shift.shape == (N,)
+    out = np.empty((M, N), dtype=np.float32)
+    _check(lib().qo_bn_affine(_p(s), C.c_int64(M), C.c_int64(N), _p(scale), _p(shift), _p(out)), "bn_affine")
+    return out
+
+
+def backward(g: np.ndarray, w: np.ndarray, a: np.ndarray):
+    """g int32 [M][N], w int8 +-1 [N][K], a int8 +-1 [M][K] -> (g_a = g w  [M][K], g_W = g^T a  [N][K]), int32."""
+    g = _c(g, np.int32)
+    w = _c(w, np.int8)
+    a = _c(a, np.int8)
+    M, N = g.shape
+    K = w.shape[1]
+    assert w.shape == (N, K) and a.shape == (M, K)
+    ga = np.empty((M, K), dtype=np.int32)
+    gw = np.empty((N, K), dtype=np.int32)
+    rc = lib().qo_backward(_p(g), _p(w), _p(a), C.c_int64(M), C.c_int64(N), C.c_int64(K), _p(ga), _p(gw))
+    _check(rc, "backward")
+    return ga, gw
+
+
 def num_threads() -> int:
     return int(lib().qo_num_threads())

@@ -16,7 +16,8 @@
  * brute force over all sign vectors for tiny K, Eq. (FirstLayer) (planes vs integer values), a library
  * convolution in fp64, the float BatchNorm formula evaluated in double, hand-written expected bits for
  * float edge values, a library max-pooling, and the float pipeline conv -> max-pool -> BatchNorm -> sign of a library
- * in fp64 for the ConvNet.  No function here is "parity unpinned".
+ * in fp64 for the ConvNet, hand-computed values and closed forms for the quantizers, and int64 library products of
+ * transposed operands for the backward products.  No function here is "parity unpinned".
  */
 #include <stddef.h>
 #include <stdint.h>
@@ -411,6 +412,60 @@ int qo_log_quant(const float *x, int64_t n, int32_t emin, int32_t emax, int8_t *
         code[i] = (int8_t)(sg * (e - emin + 1));
     }
     return QO_OK;
+}
+
+/* Fixed-point value of a logarithmic code (Sec. 3 LogQuant; Sec. 6: with quantized gradients the backward pass can
+ * run on the bit-wise kernel): code c encodes sign(c) * 2^(emin + |c| - 1); scaled by 2^-emin that is the INTEGER
+ * sign(c) * 2^(|c| - 1), which a matrix product can consume as two's-complement bit planes.  Code 0 is 0. */
+int qo_log_code_value(const int8_t *code, int64_t n, int32_t *value) {
+    for (int64_t i = 0; i < n; ++i) {
+        int c = code[i];
+        int mag = c < 0 ? -c : c;
+        if (mag > 31) return QO_ERR_RANGE;
+        value[i] = c == 0 ? 0 : (c < 0 ? -(int32_t)(1 << (mag - 1)) : (int32_t)(1 << (mag - 1)));
+    }
+    return QO_OK;
+}
+
+/* Straight-through estimator of Alg. 1 (backward block): g_a = g_{a^b} o 1_{|a| <= 1}: the gradient passes where the
+ * pre-binarization activation lies in [-1, 1] and is cancelled elsewhere (NaN is not <= 1: cancelled). */
+int qo_ste_mask(const float *g, const float *a, int64_t n, float *out) {
+    for (int64_t i = 0; i < n; ++i) out[i] = (fabsf(a[i]) <= 1.0f) ? g[i] : 0.0f;
+    return QO_OK;
+}
+
+/* Affine form of the inference-time BatchNorm of the output layer (Alg. 4, last line): y = scale[n] * s + shift[n]
+ * on the integer sums s, evaluated as ONE fused multiply-add in single precision (one rounding). */
+int qo_bn_affine(const int32_t *s, int64_t M, int64_t N, const float *scale, const float *shift, float *y) {
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) y[m * N + n] = fmaf((float)s[m * N + n], scale[n], shift[n]);
+    return QO_OK;
+}
+
+/* Backward products of Alg. 1 with binary weights and integer (quantized) gradients:
+ *   g_a[m][k] = sum_n g[m][n] * W[n][k]        (g_{a_{k-1}^b} = g_{s_k} W_k^b)
+ *   g_W[n][k] = sum_m g[m][n] * a[m][k]        (g_{W_k^b}   = g_{s_k}^T a_{k-1}^b)
+ * g: int32 [M][N], W: int8 +-1 [N][K], a: int8 +-1 [M][K].  Plain triple loops, int64 accumulation. */
+int qo_backward(const int32_t *g, const int8_t *W, const int8_t *a, int64_t M, int64_t N, int64_t K, int32_t *g_a,
+                int32_t *g_W) {
+    int rc = QO_OK;
+#pragma omp parallel for schedule(static)
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t acc = 0;
+            for (int64_t n = 0; n < N; ++n) acc += (int64_t)g[m * N + n] * (int64_t)W[n * K + k];
+            if (!fits_i32(acc)) rc = QO_ERR_RANGE;
+            g_a[m * K + k] = (int32_t)acc;
+        }
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t k = 0; k < K; ++k) {
+            int64_t acc = 0;
+            for (int64_t m = 0; m < M; ++m) acc += (int64_t)g[m * N + n] * (int64_t)a[m * K + k];
+            if (!fits_i32(acc)) rc = QO_ERR_RANGE;
+            g_W[n * K + k] = (int32_t)acc;
+        }
+    return rc;
 }
 
 /* Number of threads the OpenMP loops above actually use (reported beside the CPU-baseline timing). */

@@ -488,3 +488,59 @@ def test_log_quant_hand_values():
     codes = oracle.log_quant(x, -3, 2).astype(np.int64)
     vals = np.sign(codes) * 2.0 ** (-3 + np.abs(codes) - 1) * (codes != 0)
     assert vals.tolist()[:7] == [1.0, -1.0, 0.125, 0.125, 0.125, 0.0, 4.0]
+
+
+# ---------------------------------------------------------------- backward pass of Alg. 1 with quantized gradients
+def test_log_code_value_and_ste_hand_values():
+    """Fixed-point value of a logarithmic code: code c is sign(c) 2^(|c| - 1) (1, 2, 4, ... and 0 for code 0); the
+    straight-through estimator of Alg. 1 passes g where |a| <= 1 (bounds included) and cancels it elsewhere."""
+    codes = np.array([0, 1, -1, 2, -2, 3, 6, -6, 7], dtype=np.int8)
+    assert oracle.log_code_value(codes).tolist() == [0, 1, -1, 2, -2, 4, 32, -32, 64]
+    g = np.array([0.5, -2.0, 3.0, 4.0, 5.0, 6.0, 7.0, 8.0], dtype=np.float32)
+    a = np.array([0.0, 1.0, -1.0, 1.0000001, -1.5, np.nan, np.inf, -0.99], dtype=np.float32)
+    assert oracle.ste_mask(g, a).tolist() == [0.5, -2.0, 3.0, 0.0, 0.0, 0.0, 0.0, 8.0]
+
+
+def test_bn_affine_exact_cases_and_double(seed):
+    """y = scale * s + shift with one rounding: exact whenever the true result is representable (integer sums, powers
+    of two as scale, small shifts), and within half an ulp of the double-precision value otherwise."""
+    s = np.array([[0, 1, -3, 1000], [7, -8, 12345, -2 ** 20]], dtype=np.int32)
+    scale = np.array([0.5, 2.0, -0.25, 1.0], dtype=np.float32)
+    shift = np.array([1.0, -3.0, 0.5, 0.25], dtype=np.float32)
+    want = [[1.0, -1.0, 1.25, 1000.25], [4.5, -19.0, -3085.75, -1048575.75]]
+    assert oracle.bn_affine(s, scale, shift).tolist() == want
+    M, N = 50, 37
+    s = qi.uniform_int(seed, 1900, (M, N), -5000, 5000)
+    scale = qi.normal_f32(seed, 1901, (N,))
+    shift = qi.normal_f32(seed, 1902, (N,)) * np.float32(10.0)
+    got = oracle.bn_affine(s, scale, shift).astype(np.float64)
+    exact = s.astype(np.float64) * scale.astype(np.float64) + shift.astype(np.float64)  # error below 2^-52 relative
+    ulp = np.spacing(np.abs(got).astype(np.float32)).astype(np.float64)
+    assert (np.abs(got - exact) <= 0.5 * ulp * (1 + 1e-6)).all()
+    # a case where rounding the product first would differ: 3 * (1 + 2^-23) + (-3) = 3 * 2^-23 exactly
+    one_eps = np.array([1.0 + 2.0 ** -23], dtype=np.float32)
+    assert oracle.bn_affine(np.array([[3]], dtype=np.int32), one_eps, np.array([-3.0], dtype=np.float32))[0, 0] == np.float32(3 * 2.0 ** -23)
+
+
+def test_backward_products_against_library(seed):
+    """g_a = g W and g_W = g^T a (Alg. 1, backward block) against int64 library products of the same matrices, a case
+    worked by hand, and the closed form for constant operands."""
+    g = np.array([[1, -2], [4, 0], [-8, 16]], dtype=np.int32)          # M = 3, N = 2
+    w = np.array([[1, -1, 1, 1], [-1, -1, 1, -1]], dtype=np.int8)      # N = 2, K = 4
+    a = np.array([[1, 1, -1, 1], [-1, 1, 1, 1], [1, -1, -1, -1]], dtype=np.int8)
+    ga, gw = oracle.backward(g, w, a)
+    assert ga.tolist() == [[3, 1, -1, 3], [4, -4, 4, 4], [-24, -8, 8, -24]]
+    assert gw.tolist() == [[-11, 13, 11, 13], [14, -18, -14, -18]]
+    M, N, K = 37, 29, 45
+    g = qi.uniform_int(seed, 1910, (M, N), -64, 64)
+    w = qi.pm1(seed, 1911, (N, K))
+    a = qi.pm1(seed, 1912, (M, K))
+    ga, gw = oracle.backward(g, w, a)
+    assert np.array_equal(ga, (g.astype(np.int64) @ w.astype(np.int64)).astype(np.int32))
+    assert np.array_equal(gw, (g.astype(np.int64).T @ a.astype(np.int64)).astype(np.int32))
+    ones_w, ones_a = np.ones((N, K), dtype=np.int8), np.ones((M, K), dtype=np.int8)
+    ga, gw = oracle.backward(g, ones_w, ones_a)
+    assert np.array_equal(ga, np.repeat(g.sum(axis=1, keepdims=True), K, axis=1))
+    assert np.array_equal(gw, np.repeat(g.sum(axis=0)[:, None], K, axis=1))
+    with pytest.raises(oracle.OracleRangeError):
+        oracle.backward(np.full((2, 2), 2 ** 30, dtype=np.int32), np.ones((2, 3), dtype=np.int8), np.ones((2, 3), dtype=np.int8))
