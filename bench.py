@@ -227,6 +227,39 @@ def main():
 
         jobs.append((2, job_c5))
 
+    if "c2" in only:
+        # backward products of Alg. 1 for a hidden layer of the MLP (10000 x 4096 -> 4096) with gradients quantized to
+        # eight-plane fixed-point values: g_a = g W and g_W = g^T a, transposes included
+        Mb, Nb, Kb = 10000, 4096, 4096
+        gb_h = qi.normal_f32(seed, 60, (Mb, Nb)) * np.float32(0.2)
+        wb_h = qi.pm1(seed, 61, (Nb, Kb))
+        ab_h = qi.pm1(seed, 62, (Mb, Kb))
+        gq_h = oracle.log_code_value(oracle.log_quant(gb_h, -6, 0))
+        idxb = np.array([0, 255, 256, 4095])
+        want_ga = oracle.gemm_int(gq_h[idxb], np.ascontiguousarray(wb_h.T).astype(np.int32))          # rows of g W
+        want_gw = oracle.gemm_int(np.ascontiguousarray(gq_h.T[idxb]), np.ascontiguousarray(ab_h.T).astype(np.int32))  # rows of g^T a
+        Gb, Wb, Ab = dev(gb_h), dev(np_pack_pm1(wb_h)), dev(np_pack_pm1(ab_h))
+        wsb = torch.empty(q.qnn_binary_backward_workspace_bytes(Mb, Nb, Kb, 8), dtype=torch.uint8, device="cuda")
+        Gp = torch.empty((8, Mb, Nb // 32), dtype=torch.int32, device="cuda")
+        coefb = [1, 2, 4, 8, 16, 32, 64, -128]
+        outb = {}
+
+        def run_bwd():
+            q.qnn_log_quant_planes(Gb, -6, 0, 8, as_value=True, out=Gp)
+            outb["ga"], outb["gw"] = q.qnn_binary_backward(Gp, coefb, q.PLANE_BIT, Nb, Wb, Ab, Kb, workspace=wsb)
+
+        def job_bwd():
+            msb = time_steps(run_bwd, sec_steps, sec_warm)
+            ok = (np.array_equal(outb["ga"][idxb].cpu().numpy(), want_ga)
+                  and np.array_equal(outb["gw"][idxb].cpu().numpy(), want_gw))
+            imac = 2.0 * Mb * Nb * Kb
+            extra["backward_hidden_layer_8bit_gradients"] = {
+                "parity_sample_ok": bool(ok), "ms": msb if ok else None,
+                "effective_integer_tmacs": imac / (msb * 1e-3) / 1e12 if ok else None,
+                "note": "LogQuant of the fp32 gradient to 8 planes, three bit transposes, two 8-plane x 1-plane products"}
+
+        jobs.append((2, job_bwd))
+
     if "c1" in only:
         xa_h, xw_h = qi.normal_f32(seed, 10, (128, 1024)), qi.normal_f32(seed, 11, (1024, 1024))
         want1 = oracle.gemm_pm1(oracle.sign(xa_h), oracle.sign(xw_h))
@@ -287,6 +320,24 @@ def main():
             msb = time_steps(lambda: q.qnn_pack_bitplanes(codes, 8, out=pl), sec_steps, sec_warm)
             gb = (n * n + n * n) / (msb * 1e-3) / 1e9
             extra["pack_bitplanes_8192x8192_8bit"] = {"ms": msb, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
+            del codes, pl
+            # quantizer front ends of Sec. 3 from fp32: 2-bit linear codes; 8-bit fixed-point log values with the
+            # straight-through gate (two fp32 arrays read); transpose of an 8192 x 8192 bit matrix
+            xq = torch.randn((n, n), dtype=torch.float32, device="cuda")
+            pl2 = torch.empty((2, n, n // 32), dtype=torch.int32, device="cuda")
+            msq = time_steps(lambda: q.qnn_linear_quant_planes(xq, 0.5, 0, 3, 2, out=pl2), sec_steps, sec_warm)
+            gb = (n * n * 4 + 2 * n * n / 8) / (msq * 1e-3) / 1e9
+            extra["linear_quant_planes_8192x8192_2bit"] = {"ms": msq, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
+            gate = torch.randn((n, n), dtype=torch.float32, device="cuda")
+            pl8 = torch.empty((8, n, n // 32), dtype=torch.int32, device="cuda")
+            msl = time_steps(lambda: q.qnn_log_quant_planes(xq, -6, 0, 8, as_value=True, gate=gate, out=pl8), sec_steps, sec_warm)
+            gb = (2 * n * n * 4 + 8 * n * n / 8) / (msl * 1e-3) / 1e9
+            extra["log_quant_planes_8192x8192_8bit_gated"] = {"ms": msl, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
+            del xq, gate, pl8
+            tb2 = torch.empty((1, n, n // 32), dtype=torch.int32, device="cuda")
+            mstr = time_steps(lambda: q.qnn_transpose_bits(pl2[:1], n, out=tb2), sec_steps, sec_warm)
+            gb = (2 * n * n / 8) / (mstr * 1e-3) / 1e9
+            extra["transpose_bits_8192x8192"] = {"ms": mstr, "GBps": gb, "frac_of_hbm_peak": gb / HBM_PEAK_GBS}
 
         jobs.append((0, job_bw))
 

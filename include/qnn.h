@@ -227,6 +227,60 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
 size_t qnn_binary_convnet_workspace_bytes(int64_t B, int64_t H, int64_t Wd, int64_t C0, int in_bits, int n_conv,
                                           const int64_t *cout, const int32_t *pool, int n_fc, const int64_t *fc_out);
 
+/* Linear quantization of Sec. 3, LinearQuant(x, step) = Clip(round(x / step) * step, minV, maxV), fused with the
+ * bit-plane split of Sec. 2.6: the integer code q = Clip(round(x / step), qmin, qmax) (value = q * step, minV =
+ * qmin * step, maxV = qmax * step) is written as nbits packed planes, plane p = bit p of q in two's complement
+ * (for qmin >= 0 that is the unsigned code; coefficients 1, 2, 4, ... and, for signed codes, -2^(nbits-1) for the top
+ * plane turn the planes back into q in qnn_bitplane_gemm).  The quotient is formed and rounded in single precision,
+ * to the nearest integer with ties to even; NaN quantizes like 0.
+ * x: DEVICE float32 [rows][ldx]; planes: DEVICE uint32, layout as in qnn_pack_bitplanes.  step > 0, finite;
+ * qmin .. qmax must fit nbits (0 .. 2^nbits - 1, or -2^(nbits-1) .. 2^(nbits-1) - 1); 1 <= nbits <= 8. */
+int qnn_linear_quant_planes(const float *x, int64_t rows, int64_t K, int64_t ldx, float step, int32_t qmin,
+                            int32_t qmax, int nbits, uint32_t *planes, int64_t ld_words, int64_t plane_stride_words,
+                            void *stream);
+
+/* Logarithmic quantization of Sec. 3, LogQuant(x) = Clip(AP2(x), minV, maxV) with AP2(x) = sign(x) 2^round(log2 |x|)
+ * (caption of Alg. 2) and magnitudes 2^emin .. 2^emax: what rounds below 2^emin (and 0, NaN) becomes 0, what rounds
+ * above 2^emax is clipped to it.  Written as nbits packed planes of a two's-complement integer:
+ *   as_value == 0: the signed code sign(x) * (e - emin + 1), e = min(round(log2 |x|), emax)   (0 = zero);
+ *   as_value != 0: the quantized value in units of 2^emin, sign(x) * 2^(e - emin), which the bit-plane products
+ *                  consume directly (coefficients 1, 2, ..., -2^(nbits-1)): this is how quantized gradients enter the
+ *                  backward products (Sec. 5: quantized gradients let the backward pass use the bit-wise kernel).
+ * gate: optional DEVICE float32 [rows][ld_gate] (NULL = none): where |gate| <= 1 does not hold the output is 0, the
+ * straight-through estimator g o 1_{|a| <= 1} of Alg. 1 applied to the gradient before it is quantized.
+ * emax - emin + 1 magnitudes must fit: < 2^(nbits-1) codes, or emax - emin + 1 <= nbits - 1 for values. */
+int qnn_log_quant_planes(const float *x, const float *gate, int64_t rows, int64_t K, int64_t ldx, int64_t ld_gate,
+                         int32_t emin, int32_t emax, int as_value, int nbits, uint32_t *planes, int64_t ld_words,
+                         int64_t plane_stride_words, void *stream);
+
+/* Inference-time BatchNorm of the output layer (Alg. 4, last line) in its affine form on the integer sums:
+ * y[m][n] = scale[n] * sums[m][n] + shift[n] as one fused multiply-add in single precision.
+ * sums: DEVICE int32 [M][ld_sums]; scale, shift: DEVICE float32 [N]; y: DEVICE float32 [M][ldy]. */
+int qnn_batchnorm_affine(const int32_t *sums, int64_t ld_sums, int64_t M, int64_t N, const float *scale,
+                         const float *shift, float *y, int64_t ldy, void *stream);
+
+/* Transpose of packed bit matrices: in is nplanes planes of [rows][ld_in_words] holding `cols` bits per row; out
+ * receives [cols][ld_out_words] holding `rows` bits per row (first ceil(rows/32) words written, tail bits zero).
+ * The backward products of Alg. 1 reduce over the axis the forward pass did not pack along. */
+int qnn_transpose_bits(const uint32_t *in, int64_t rows, int64_t cols, int64_t ld_in_words,
+                       int64_t in_plane_stride_words, int nplanes, uint32_t *out, int64_t ld_out_words,
+                       int64_t out_plane_stride_words, void *stream);
+
+/* Backward products of Alg. 1 for one layer with binary weights, binary activations and integer gradients given
+ * as bit planes (e.g. from qnn_log_quant_planes with as_value, or a linear code):
+ *   gA[m][k] = sum_n g[m][n] w[n][k]   (g_{a_{k-1}^b} = g_{s_k} W_k^b),
+ *   gW[n][k] = sum_m g[m][n] a[m][k]   (g_{W_k^b} = g_{s_k}^T a_{k-1}^b),
+ * g = sum_p coefG[p] * plane_p (read according to modeG).  G: DEVICE, Pg planes of [M][ldg_words] packed along n;
+ * W: DEVICE packed +-1 [N][ldw_words] (along k, as the forward pass holds it); A: DEVICE packed +-1 [M][lda_words].
+ * gA: DEVICE int32 [M][ld_ga]; gW: DEVICE int32 [N][ld_gw].  coefG: HOST.  workspace: DEVICE, 256-byte aligned,
+ * qnn_binary_backward_workspace_bytes(...) bytes (the transposed operands).  QNN_ERR_OVERFLOW if
+ * (sum |coefG|) * max(M, N) >= 2^31. */
+int qnn_binary_backward(const uint32_t *G, int Pg, const int32_t *coefG, int modeG, int64_t ldg_words,
+                        int64_t strideG_words, const uint32_t *W, int64_t ldw_words, const uint32_t *A,
+                        int64_t lda_words, int32_t *gA, int64_t ld_ga, int32_t *gW, int64_t ld_gw, int64_t M, int64_t N,
+                        int64_t K, void *workspace, size_t workspace_bytes, void *stream);
+size_t qnn_binary_backward_workspace_bytes(int64_t M, int64_t N, int64_t K, int Pg);
+
 /* Engine (QNN_ENGINE_VALU, QNN_ENGINE_MFMA or QNN_ENGINE_MFMA_FP4) that the calling thread's last successful multiply call used; 0 before
  * any.  For reports: results never depend on it. */
 int qnn_last_engine(void);

@@ -52,6 +52,12 @@ _SIGS = {
                                  _int, _int, _int, _vp, _vp, _vp, _int, _vp],
     "qnn_binary_convnet_forward": [_vp, _i64, _i64, _i64, _i64, _int, _int, _vp, _vp, _int, _vp, _vp, _vp, _vp, _vp, _i64,
                                    _vp, _sz, _int, _vp],
+    "qnn_linear_quant_planes": [_vp, _i64, _i64, _i64, C.c_float, C.c_int32, C.c_int32, _int, _vp, _i64, _i64, _vp],
+    "qnn_log_quant_planes": [_vp, _vp, _i64, _i64, _i64, _i64, C.c_int32, C.c_int32, _int, _int, _vp, _i64, _i64, _vp],
+    "qnn_batchnorm_affine": [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _vp],
+    "qnn_transpose_bits": [_vp, _i64, _i64, _i64, _i64, _int, _vp, _i64, _i64, _vp],
+    "qnn_binary_backward": [_vp, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64,
+                            _vp, _sz, _vp],
     "qnn_bitplane_conv2d_ex": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
                                _int, _int, _int, _vp, _int, _vp],
 }
@@ -64,6 +70,8 @@ _lib.qnn_binary_mlp_workspace_bytes.restype = _sz
 _lib.qnn_static_scratch_bytes.restype = _sz
 _lib.qnn_binary_convnet_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _int, _int, _vp, _vp, _int, _vp]
 _lib.qnn_binary_convnet_workspace_bytes.restype = _sz
+_lib.qnn_binary_backward_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
+_lib.qnn_binary_backward_workspace_bytes.restype = _sz
 _lib.qnn_last_engine.restype = C.c_int
 _lib.qnn_last_error.restype = C.c_char_p
 _lib.qnn_version.restype = C.c_char_p
@@ -71,7 +79,8 @@ _lib.qnn_version.restype = C.c_char_p
 _lib.qnn_last_engines.argtypes = [_vp, _int]
 _lib.qnn_last_engines.restype = C.c_int
 
-EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_static_scratch_bytes", "qnn_binary_convnet_workspace_bytes", "qnn_last_engine",
+EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_static_scratch_bytes", "qnn_binary_convnet_workspace_bytes",
+                               "qnn_binary_backward_workspace_bytes", "qnn_last_engine",
                                "qnn_last_engines", "qnn_last_error", "qnn_version"])
 
 
@@ -179,6 +188,84 @@ def qnn_pack_bitplanes(v: torch.Tensor, nbits: int, out: Optional[torch.Tensor] 
     _check(_lib.qnn_pack_bitplanes(_dev(v, torch.uint8, "v"), rows, K, ldv, nbits, _dev(out, torch.int32, "out"), ld,
                                    ps, _stream()))
     return out
+
+
+def qnn_linear_quant_planes(x: torch.Tensor, step: float, qmin: int, qmax: int, nbits: int,
+                            out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    rows, K, ldx = _rows_ld(x, "x")
+    if out is None:
+        out = torch.empty((nbits, rows, words_for(K)), dtype=torch.int32, device=x.device)
+    P, _, _, ld, ps = _planes_ld(out, "out")
+    if P != nbits:
+        raise ValueError("out must have nbits planes")
+    _check(_lib.qnn_linear_quant_planes(_dev(x, torch.float32, "x"), rows, K, ldx, step, qmin, qmax, nbits,
+                                        _dev(out, torch.int32, "out"), ld, ps, _stream()))
+    return out
+
+
+def qnn_log_quant_planes(x: torch.Tensor, emin: int, emax: int, nbits: int, as_value: bool = False,
+                         gate: Optional[torch.Tensor] = None, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    rows, K, ldx = _rows_ld(x, "x")
+    ldg = 0
+    if gate is not None:
+        gr, gk, ldg = _rows_ld(gate, "gate")
+        if (gr, gk) != (rows, K):
+            raise ValueError("gate must have the shape of x")
+    if out is None:
+        out = torch.empty((nbits, rows, words_for(K)), dtype=torch.int32, device=x.device)
+    P, _, _, ld, ps = _planes_ld(out, "out")
+    if P != nbits:
+        raise ValueError("out must have nbits planes")
+    _check(_lib.qnn_log_quant_planes(_dev(x, torch.float32, "x"), _dev(gate, torch.float32, "gate"), rows, K, ldx, ldg,
+                                     emin, emax, 1 if as_value else 0, nbits, _dev(out, torch.int32, "out"), ld, ps,
+                                     _stream()))
+    return out
+
+
+def qnn_batchnorm_affine(sums: torch.Tensor, scale: torch.Tensor, shift: torch.Tensor,
+                         out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    M, N, lds = _rows_ld(sums, "sums")
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.float32, device=sums.device)
+    _, _, ldy = _rows_ld(out, "out")
+    _check(_lib.qnn_batchnorm_affine(_dev(sums, torch.int32, "sums"), lds, M, N, _dev(scale, torch.float32, "scale"),
+                                     _dev(shift, torch.float32, "shift"), _dev(out, torch.float32, "out"), ldy, _stream()))
+    return out
+
+
+def qnn_transpose_bits(planes: torch.Tensor, cols: int, out: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """planes: [P][rows][words] holding `cols` bits per row -> [P][cols][ceil(rows/32)]."""
+    P, rows, _, ld, ps = _planes_ld(planes, "planes")
+    if out is None:
+        out = torch.empty((P, cols, words_for(rows)), dtype=torch.int32, device=planes.device)
+    Po, _, _, ldo, pso = _planes_ld(out, "out")
+    if Po != P:
+        raise ValueError("out must have as many planes as the input")
+    _check(_lib.qnn_transpose_bits(_dev(planes, torch.int32, "planes"), rows, cols, ld, ps, P,
+                                   _dev(out, torch.int32, "out"), ldo, pso, _stream()))
+    return out
+
+
+def qnn_binary_backward_workspace_bytes(M: int, N: int, K: int, Pg: int) -> int:
+    return int(_lib.qnn_binary_backward_workspace_bytes(M, N, K, Pg))
+
+
+def qnn_binary_backward(G: torch.Tensor, coefG: Sequence[int], modeG: int, N: int, W: torch.Tensor, A: torch.Tensor,
+                        K: int, workspace: Optional[torch.Tensor] = None):
+    """G: [Pg][M][words of N]; W: [N][words of K]; A: [M][words of K] -> (gA int32 [M][K], gW int32 [N][K])."""
+    Pg, M, _, ldg, psg = _planes_ld(G, "G")
+    _, _, ldw = _rows_ld(W, "W")
+    _, _, lda = _rows_ld(A, "A")
+    need = qnn_binary_backward_workspace_bytes(M, N, K, Pg)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=G.device)
+    gA = torch.empty((M, K), dtype=torch.int32, device=G.device)
+    gW = torch.empty((N, K), dtype=torch.int32, device=G.device)
+    _check(_lib.qnn_binary_backward(_dev(G, torch.int32, "G"), Pg, _coef(coefG), modeG, ldg, psg,
+                                    _dev(W, torch.int32, "W"), ldw, _dev(A, torch.int32, "A"), lda,
+                                    _dev(gA, torch.int32, "gA"), K, _dev(gW, torch.int32, "gW"), K, M, N, K,
+                                    workspace.data_ptr(), workspace.numel(), _stream()))
+    return gA, gW
 
 
 def qnn_binary_gemm(A: torch.Tensor, W: torch.Tensor, K: int, out: Optional[torch.Tensor] = None,

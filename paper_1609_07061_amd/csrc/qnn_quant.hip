@@ -1,0 +1,312 @@
+// Quantizer front ends of Sec. 3 (LinearQuant, LogQuant with AP2 of Alg. 2's caption) fused with the bit-plane split
+// of Sec. 2.6, the affine BatchNorm of the output layer (Alg. 4, last line), and the pieces the backward products of
+// Alg. 1 need on packed operands: a transpose of packed bit matrices and the two products themselves.
+//
+// The quantizers are bandwidth-bound elementwise kernels with the ballot packing of qnn_pack.hip: lane l of a wave
+// owns element 64 c + l of the wave's chunk, computes its integer code, and one ballot per plane and 64 elements
+// turns bit p of the codes into two finished words.  Every decision that turns a float into an integer is taken in
+// the precision the definition names: x / step correctly rounded in single precision and rounded to the nearest
+// integer with ties to even; round(log2 |x|) from the float's exponent and a comparison of its mantissa with sqrt(2)
+// (2^(e + 1/2) is irrational, so the comparison with the float below sqrt(2) decides exactly).
+#include "qnn_internal.h"
+
+namespace qnn {
+
+namespace {
+
+constexpr int kWave = 64;
+constexpr int kBlock = 256;
+constexpr int kWavesPerBlock = kBlock / kWave;
+
+unsigned grid_for_chunks(int64_t chunks) {
+    const int64_t blocks = ceil_div(chunks, kWavesPerBlock);
+    const int64_t cap = 256 * 16;  // a few workgroups per compute unit; the kernels stride over the rest
+    return (unsigned)(blocks < 1 ? 1 : (blocks > cap ? cap : blocks));
+}
+
+// LinearQuant(x, step) = Clip(round(x / step) * step, minV, maxV) as the integer code q = value / step.
+struct LinearQ {
+    float step;
+    int32_t qmin, qmax;
+    __device__ __forceinline__ int32_t operator()(float x) const {
+        float r = rintf(__fdiv_rn(x, step));  // correctly rounded quotient, nearest integer with ties to even
+        if (r != r) r = 0.0f;                 // NaN quantizes like 0
+        return r <= (float)qmin ? qmin : (r >= (float)qmax ? qmax : (int32_t)r);
+    }
+};
+
+// LogQuant(x) = Clip(AP2(x), 2^emin, 2^emax) with AP2(x) = sign(x) 2^round(log2 |x|): code 0 for 0, NaN and what
+// rounds below 2^emin, else sign * (e - emin + 1) with e clipped to emax; as_value: sign * 2^(e - emin) instead (the
+// quantized value as a fixed-point integer in units of 2^emin).
+struct LogQ {
+    int32_t emin, emax;
+    int as_value;
+    __device__ __forceinline__ int32_t operator()(float x) const {
+        const uint32_t b = __float_as_uint(x), mag = b & 0x7FFFFFFFu;
+        if (mag == 0u || mag > 0x7F800000u) return 0;
+        int32_t e;
+        if (mag == 0x7F800000u) {
+            e = emax;
+        } else {
+            int32_t E = (int32_t)(mag >> 23) - 127;
+            uint32_t man = mag & 0x7FFFFFu;
+            if ((mag >> 23) == 0u) {  // denormal: man * 2^-149, normalized by hand
+                const int sh = __clz((int)man) - 8;
+                man = (man << sh) & 0x7FFFFFu;
+                E = -126 - sh;
+            }
+            // |x| = (1 + man / 2^23) 2^E; 1.0110101000001001111 0011b is the float just below sqrt(2)
+            e = E + (man > 0x3504F3u ? 1 : 0);
+            if (e < emin) return 0;
+            if (e > emax) e = emax;
+        }
+        const int32_t c = e - emin + 1;
+        const int32_t v = as_value ? (int32_t)(1u << (c - 1)) : c;
+        return (b >> 31) ? -v : v;
+    }
+};
+
+// One wave turns kUnroll * 64 consecutive elements of one row into 2 * kUnroll words of every plane (two's complement
+// bits of the code).  gate: optional fp32 array of the layout of x; where |gate| <= 1 does not hold the code is 0 (the
+// straight-through estimator of Alg. 1: g o 1_{|a| <= 1}).
+template <int kUnroll, typename Q>
+__global__ __launch_bounds__(kBlock) void quant_planes_kernel(const float *__restrict__ x, const float *__restrict__ gate,
+                                                              int64_t rows, int64_t K, int64_t ldx, int64_t ldg, Q q,
+                                                              int nbits, uint32_t *__restrict__ planes, int64_t ld,
+                                                              int64_t plane_stride, int64_t chunks_per_row,
+                                                              int64_t total_chunks) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t Kw = (K + 31) / 32;
+    for (int64_t chunk = wave0; chunk < total_chunks; chunk += wave_stride) {
+        const int64_t r = chunk / chunks_per_row;
+        const int64_t k0 = (chunk - r * chunks_per_row) * (kUnroll * kWave);
+        const float *row = x + r * ldx;
+        float v[kUnroll], gt[kUnroll];
+#pragma unroll
+        for (int c = 0; c < kUnroll; ++c) {
+            const int64_t k = k0 + c * kWave + lane;
+            v[c] = (k < K) ? __builtin_nontemporal_load(row + k) : 0.0f;
+            gt[c] = (gate && k < K) ? __builtin_nontemporal_load(gate + r * ldg + k) : 0.0f;
+        }
+        uint32_t code[kUnroll];
+#pragma unroll
+        for (int c = 0; c < kUnroll; ++c) {
+            const int64_t k = k0 + c * kWave + lane;
+            int32_t cd = q(v[c]);
+            if (!(fabsf(gt[c]) <= 1.0f)) cd = 0;
+            code[c] = (k < K) ? (uint32_t)cd : 0u;
+        }
+        const int64_t w = k0 / 32 + lane;
+        for (int p = 0; p < nbits; ++p) {
+            uint32_t mine = 0;
+#pragma unroll
+            for (int c = 0; c < kUnroll; ++c) {
+                const unsigned long long m = __ballot((code[c] >> p) & 1u);
+                if (lane == 2 * c) mine = (uint32_t)m;
+                if (lane == 2 * c + 1) mine = (uint32_t)(m >> 32);
+            }
+            if (lane < 2 * kUnroll && w < Kw) planes[p * plane_stride + r * ld + w] = mine;
+        }
+    }
+}
+
+template <typename Q>
+int launch_quant(const char *what, const float *x, const float *gate, int64_t rows, int64_t K, int64_t ldx, int64_t ldg,
+                 const Q &q, int nbits, uint32_t *planes, int64_t ld, int64_t plane_stride, hipStream_t s) {
+    constexpr int kUnroll = 8;
+    const int64_t cpr = ceil_div(K, (int64_t)kUnroll * kWave);
+    const int64_t total = rows * cpr;
+    return QNN_LAUNCH(what, (quant_planes_kernel<kUnroll, Q>), dim3(grid_for_chunks(total)), dim3(kBlock), 0, s, x, gate, rows,
+                      K, ldx, ldg, q, nbits, planes, ld, plane_stride, cpr, total);
+}
+
+// y[m][n] = fma(float(s[m][n]), scale[n], shift[n]): one rounding.
+__global__ __launch_bounds__(kBlock) void bn_affine_kernel(const int32_t *__restrict__ sums, int64_t lds, int64_t M, int64_t N,
+                                                           const float *__restrict__ scale, const float *__restrict__ shift,
+                                                           float *__restrict__ y, int64_t ldy) {
+    const int64_t total = M * N;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
+        const int64_t m = i / N, n = i - m * N;
+        y[m * ldy + n] = __fmaf_rn((float)sums[m * lds + n], scale[n], shift[n]);
+    }
+}
+
+// Transpose of packed bit matrices.  A wave takes 64 rows x one word column: lane l holds the word of row r0 + l, and
+// ballot number c collects bit c of all 64 words, i.e. 64 consecutive bits of output row 32 j + c, which lane c
+// stores as two words.  Rows beyond the matrix read as zero words, so the output's tail bits are zero; out_words
+// (at least ceil(rows / 32)) words of every output row are written, the surplus as zeros.
+__global__ __launch_bounds__(kBlock) void transpose_bits_kernel(const uint32_t *__restrict__ in, int64_t rows, int64_t cols,
+                                                                int64_t ld_in, int64_t in_plane_stride,
+                                                                uint32_t *__restrict__ out, int64_t ld_out,
+                                                                int64_t out_plane_stride, int64_t out_words,
+                                                                int64_t row_blocks, int64_t total_units) {
+    const int lane = threadIdx.x & (kWave - 1);
+    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x / kWave);
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t Cw = (cols + 31) / 32;
+    in += (int64_t)blockIdx.y * in_plane_stride;
+    out += (int64_t)blockIdx.y * out_plane_stride;
+    for (int64_t unit = wave0; unit < total_units; unit += wave_stride) {
+        const int64_t j = unit / row_blocks, rb = unit - j * row_blocks;  // word column, block of 64 rows
+        const int64_t r = rb * 64 + lane;
+        const uint32_t w = (r < rows && j < Cw) ? in[r * ld_in + j] : 0u;
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int c = 0; c < 32; ++c) {
+            const unsigned long long m = __ballot((w >> c) & 1u);
+            if (lane == c) lo = (uint32_t)m, hi = (uint32_t)(m >> 32);
+        }
+        const int64_t orow = j * 32 + lane;
+        if (lane < 32 && orow < cols) {
+            uint32_t *dst = out + orow * ld_out + 2 * rb;
+            dst[0] = lo;
+            if (2 * rb + 1 < out_words) dst[1] = hi;
+        }
+    }
+}
+
+bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+
+int launch_transpose(const uint32_t *in, int64_t rows, int64_t cols, int64_t ld_in, int64_t in_plane_stride, int nplanes,
+                     uint32_t *out, int64_t ld_out, int64_t out_plane_stride, int64_t out_words, hipStream_t s) {
+    const int64_t row_blocks = ceil_div(out_words, 2), units = row_blocks * words_for(cols);
+    return QNN_LAUNCH("transpose_bits", transpose_bits_kernel, dim3(grid_for_chunks(units), (unsigned)nplanes), dim3(kBlock), 0, s,
+                      in, rows, cols, ld_in, in_plane_stride, out, ld_out, out_plane_stride, out_words, row_blocks, units);
+}
+
+int check_planes_out(const char *what, int64_t rows, int64_t K, int64_t ldx, int nbits, const void *x, const void *planes,
+                     int64_t ld_words, int64_t plane_stride_words) {
+    if (rows < 0 || K < 1) return fail(QNN_ERR_SHAPE, "%s: rows = %lld, K = %lld", what, (long long)rows, (long long)K);
+    if (nbits < 1 || nbits > 8) return fail(QNN_ERR_SHAPE, "%s: nbits = %d not in 1..8", what, nbits);
+    if (ldx < K || ld_words < words_for(K)) return fail(QNN_ERR_SHAPE, "%s: leading dimension too small", what);
+    if (nbits > 1 && plane_stride_words < 0) return fail(QNN_ERR_SHAPE, "%s: negative plane stride", what);
+    if (rows == 0) return QNN_OK;
+    if (!x || !planes) return fail(QNN_ERR_NULL, "%s: NULL pointer", what);
+    if (!aligned4(planes) || !aligned4(x)) return fail(QNN_ERR_ALIGN, "%s: pointer not 4-byte aligned", what);
+    return QNN_OK;
+}
+
+size_t round_up_256(size_t x) { return (x + 255u) & ~(size_t)255u; }
+
+}  // namespace
+
+}  // namespace qnn
+
+using namespace qnn;
+
+extern "C" int qnn_linear_quant_planes(const float *x, int64_t rows, int64_t K, int64_t ldx, float step, int32_t qmin,
+                                       int32_t qmax, int nbits, uint32_t *planes, int64_t ld_words,
+                                       int64_t plane_stride_words, void *stream) {
+    if (int rc = check_planes_out("linear_quant_planes", rows, K, ldx, nbits, x, planes, ld_words, plane_stride_words)) return rc;
+    if (!(step > 0.0f) || step > 3.0e38f) return fail(QNN_ERR_SHAPE, "linear_quant_planes: step must be positive and finite");
+    if (qmin > qmax) return fail(QNN_ERR_SHAPE, "linear_quant_planes: qmin > qmax");
+    // the code must fit nbits: unsigned 0 .. 2^nbits - 1, or two's complement -2^(nbits-1) .. 2^(nbits-1) - 1
+    const int64_t lim = (int64_t)1 << nbits;
+    const bool fits = qmin >= 0 ? (int64_t)qmax < lim : ((int64_t)qmin >= -(lim / 2) && (int64_t)qmax < lim / 2);
+    if (!fits) return fail(QNN_ERR_SHAPE, "linear_quant_planes: codes %d..%d do not fit %d bits", qmin, qmax, nbits);
+    if (rows == 0) return QNN_OK;
+    return launch_quant("linear_quant_planes", x, nullptr, rows, K, ldx, 0, LinearQ{step, qmin, qmax}, nbits, planes, ld_words,
+                        plane_stride_words, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int qnn_log_quant_planes(const float *x, const float *gate, int64_t rows, int64_t K, int64_t ldx, int64_t ld_gate,
+                                    int32_t emin, int32_t emax, int as_value, int nbits, uint32_t *planes,
+                                    int64_t ld_words, int64_t plane_stride_words, void *stream) {
+    if (int rc = check_planes_out("log_quant_planes", rows, K, ldx, nbits, x, planes, ld_words, plane_stride_words)) return rc;
+    if (emin > emax) return fail(QNN_ERR_SHAPE, "log_quant_planes: emin > emax");
+    if (gate && ld_gate < K) return fail(QNN_ERR_SHAPE, "log_quant_planes: leading dimension of the gate too small");
+    if (gate && !aligned4(gate)) return fail(QNN_ERR_ALIGN, "log_quant_planes: gate not 4-byte aligned");
+    // largest magnitude of the signed code (levels) or of the fixed-point value (2^(levels - 1)) in two's complement
+    const int64_t levels = (int64_t)emax - emin + 1;
+    const int64_t top = (int64_t)1 << (nbits - 1);
+    const bool fits = as_value ? (levels <= nbits - 1) : (levels < top);
+    if (!fits)
+        return fail(QNN_ERR_SHAPE, "log_quant_planes: %lld magnitudes do not fit %d-bit two's complement %s",
+                    (long long)levels, nbits, as_value ? "values" : "codes");
+    if (rows == 0) return QNN_OK;
+    return launch_quant("log_quant_planes", x, gate, rows, K, ldx, ld_gate, LogQ{emin, emax, as_value ? 1 : 0}, nbits, planes,
+                        ld_words, plane_stride_words, static_cast<hipStream_t>(stream));
+}
+
+extern "C" int qnn_batchnorm_affine(const int32_t *sums, int64_t ld_sums, int64_t M, int64_t N, const float *scale,
+                                    const float *shift, float *y, int64_t ldy, void *stream) {
+    if (M < 0 || N < 0) return fail(QNN_ERR_SHAPE, "batchnorm_affine: M = %lld, N = %lld", (long long)M, (long long)N);
+    if (ld_sums < N || ldy < N) return fail(QNN_ERR_SHAPE, "batchnorm_affine: leading dimension too small");
+    if (M == 0 || N == 0) return QNN_OK;
+    if (!sums || !scale || !shift || !y) return fail(QNN_ERR_NULL, "batchnorm_affine: NULL pointer");
+    if (!aligned4(sums) || !aligned4(scale) || !aligned4(shift) || !aligned4(y))
+        return fail(QNN_ERR_ALIGN, "batchnorm_affine: pointer not 4-byte aligned");
+    const int64_t blocks = ceil_div(M * N, kBlock);
+    return QNN_LAUNCH("batchnorm_affine", bn_affine_kernel, dim3((unsigned)(blocks > 4096 ? 4096 : blocks)), dim3(kBlock), 0,
+                      static_cast<hipStream_t>(stream), sums, ld_sums, M, N, scale, shift, y, ldy);
+}
+
+extern "C" int qnn_transpose_bits(const uint32_t *in, int64_t rows, int64_t cols, int64_t ld_in_words,
+                                  int64_t in_plane_stride_words, int nplanes, uint32_t *out, int64_t ld_out_words,
+                                  int64_t out_plane_stride_words, void *stream) {
+    if (rows < 0 || cols < 0) return fail(QNN_ERR_SHAPE, "transpose_bits: rows = %lld, cols = %lld", (long long)rows, (long long)cols);
+    if (nplanes < 1 || nplanes > QNN_MAX_PLANES) return fail(QNN_ERR_SHAPE, "transpose_bits: nplanes = %d", nplanes);
+    if (ld_in_words < words_for(cols) || ld_out_words < words_for(rows))
+        return fail(QNN_ERR_SHAPE, "transpose_bits: leading dimension too small");
+    if (nplanes > 1 && (in_plane_stride_words < 0 || out_plane_stride_words < 0))
+        return fail(QNN_ERR_SHAPE, "transpose_bits: negative plane stride");
+    if (rows == 0 || cols == 0) return QNN_OK;
+    if (!in || !out) return fail(QNN_ERR_NULL, "transpose_bits: NULL pointer");
+    if (!aligned4(in) || !aligned4(out)) return fail(QNN_ERR_ALIGN, "transpose_bits: pointer not 4-byte aligned");
+    return launch_transpose(in, rows, cols, ld_in_words, in_plane_stride_words, nplanes, out, ld_out_words,
+                            out_plane_stride_words, words_for(rows), static_cast<hipStream_t>(stream));
+}
+
+// Rows of the transposed operands are padded to multiples of 4 words (16-byte loads in the products).
+static int64_t padded_words(int64_t bits) { return (words_for(bits) + 3) / 4 * 4; }
+
+extern "C" size_t qnn_binary_backward_workspace_bytes(int64_t M, int64_t N, int64_t K, int Pg) {
+    if (M < 1 || N < 1 || K < 1 || Pg < 1 || Pg > QNN_MAX_PLANES) return 0;
+    const size_t wt = round_up_256((size_t)K * padded_words(N) * 4);        // W^T: K rows of N bits
+    const size_t at = round_up_256((size_t)K * padded_words(M) * 4);        // A^T: K rows of M bits
+    const size_t gt = round_up_256((size_t)Pg * N * padded_words(M) * 4);   // G^T: Pg planes of N rows of M bits
+    return wt + at + gt;
+}
+
+extern "C" int qnn_binary_backward(const uint32_t *G, int Pg, const int32_t *coefG, int modeG, int64_t ldg_words,
+                                   int64_t strideG_words, const uint32_t *W, int64_t ldw_words, const uint32_t *A,
+                                   int64_t lda_words, int32_t *gA, int64_t ld_ga, int32_t *gW, int64_t ld_gw, int64_t M,
+                                   int64_t N, int64_t K, void *workspace, size_t workspace_bytes, void *stream) {
+    if (M < 1 || N < 1 || K < 1) return fail(QNN_ERR_SHAPE, "binary_backward: M, N, K must be at least 1");
+    if (Pg < 1 || Pg > QNN_MAX_PLANES) return fail(QNN_ERR_SHAPE, "binary_backward: plane count %d", Pg);
+    if (!G || !coefG || !W || !A || !gA || !gW) return fail(QNN_ERR_NULL, "binary_backward: NULL pointer");
+    if (ldg_words < words_for(N) || ldw_words < words_for(K) || lda_words < words_for(K) || ld_ga < K || ld_gw < K)
+        return fail(QNN_ERR_SHAPE, "binary_backward: leading dimension too small");
+    const size_t need = qnn_binary_backward_workspace_bytes(M, N, K, Pg);
+    if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < need)
+        return fail(QNN_ERR_WORKSPACE, "binary_backward: workspace NULL, misaligned or smaller than %zu bytes", need);
+    // the products check the int32 range themselves, but only at their launch: do it here so that nothing is enqueued
+    long double sg = 0;
+    for (int p = 0; p < Pg; ++p) sg += coefG[p] < 0 ? -(long double)coefG[p] : coefG[p];
+    if (sg * (long double)((M > N ? M : N) + 127) >= 2147483648.0L)
+        return fail(QNN_ERR_OVERFLOW, "binary_backward: gradient sums may exceed int32");
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    const int64_t ldn = padded_words(N), ldm = padded_words(M);
+    uint32_t *Wt = reinterpret_cast<uint32_t *>(ws);
+    uint32_t *At = reinterpret_cast<uint32_t *>(ws + round_up_256((size_t)K * ldn * 4));
+    uint32_t *Gt = reinterpret_cast<uint32_t *>(ws + round_up_256((size_t)K * ldn * 4) + round_up_256((size_t)K * ldm * 4));
+    const int32_t one = 1;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Gradient planes in bit mode are zero beyond the matrix, so the reduction may run over whole groups of four words
+    // (the products' 16-byte load paths) whatever the other operand holds there; the transposes write that padding.
+    const bool pad = modeG == QNN_PLANE_BIT;
+    int rc;
+    // g_a = g W: the reduction runs over n, so W (N x K, packed along k) is needed packed along n
+    if ((rc = launch_transpose(W, N, K, ldw_words, 0, 1, Wt, ldn, 0, pad ? ldn : words_for(N), st))) return rc;
+    if ((rc = qnn_bitplane_gemm(G, Pg, coefG, modeG, ldg_words, strideG_words, Wt, 1, &one, QNN_PLANE_SIGN, ldn, 0, gA, ld_ga,
+                                M, K, N, stream)))
+        return rc;
+    // g_W = g^T a: the reduction runs over the samples m, so both operands are needed packed along m
+    const int64_t red_m = pad ? ldm * 32 : M;
+    if ((rc = launch_transpose(G, M, N, ldg_words, strideG_words, Pg, Gt, ldm, N * ldm, pad ? ldm : words_for(M), st))) return rc;
+    if ((rc = launch_transpose(A, M, K, lda_words, 0, 1, At, ldm, 0, pad ? ldm : words_for(M), st))) return rc;
+    return qnn_bitplane_gemm(Gt, Pg, coefG, modeG, ldm, N * ldm, At, 1, &one, QNN_PLANE_SIGN, ldm, 0, gW, ld_gw, N, K, red_m,
+                             stream);
+}
