@@ -284,5 +284,30 @@ def backward(g: np.ndarray, w: np.ndarray, a: np.ndarray):
     return ga, gw
 
 
+def filter_unique(w: np.ndarray) -> np.ndarray:
+    """w int8 +-1 [cout][kh][kw][cin] -> int32 [cin]: distinct 2-D filters per input channel, up to negation."""
+    w = _c(w, np.int8)
+    co, kh, kw, ci = w.shape
+    out = np.empty((ci,), dtype=np.int32)
+    _check(lib().qo_filter_unique(_p(w), C.c_int64(co), C.c_int64(kh), C.c_int64(kw), C.c_int64(ci), _p(out)), "filter_unique")
+    return out
+
+
+def conv2d_dedup(u: np.ndarray, w: np.ndarray, pad: int):
+    """conv2d (stride 1) evaluated through the distinct 2-D filters of every input channel; returns (out, number of
+    2-D filter applications)."""
+    u = _c(u, np.int32)
+    w = _c(w, np.int8)
+    B, H, Wd, Ci = u.shape
+    Co, KH, KW, Ci2 = w.shape
+    assert Ci == Ci2
+    out = np.empty((B, H + 2 * pad - KH + 1, Wd + 2 * pad - KW + 1, Co), dtype=np.int32)
+    applied = np.zeros(1, dtype=np.int64)
+    rc = lib().qo_conv2d_dedup(_p(u), C.c_int64(B), C.c_int64(H), C.c_int64(Wd), C.c_int64(Ci), _p(w), C.c_int64(Co),
+                               C.c_int64(KH), C.c_int64(KW), C.c_int64(pad), _p(out), _p(applied))
+    _check(rc, "conv2d_dedup")
+    return out, int(applied[0])
+
+
 def num_threads() -> int:
     return int(lib().qo_num_threads())

@@ -468,6 +468,99 @@ int qo_backward(const int32_t *g, const int8_t *W, const int8_t *a, int64_t M, i
     return rc;
 }
 
+/* Repetition of binary 2-D filters (Sec. 5): a filter bank of +-1 weights w[co][ky][kx][ci] holds, for every input
+ * channel ci, cout 2-D filters of kh x kw taps, of which many repeat; a filter and its negation count as one (the
+ * negated filter's response is minus the original's).  counts[ci] = number of distinct 2-D filters of channel ci up
+ * to negation, found by comparing every filter with every earlier one, tap by tap. */
+int qo_filter_unique(const int8_t *w, int64_t cout, int64_t kh, int64_t kw, int64_t cin, int32_t *counts) {
+    int64_t taps = kh * kw;
+    for (int64_t ci = 0; ci < cin; ++ci) {
+        int32_t n = 0;
+        for (int64_t co = 0; co < cout; ++co) {
+            int seen = 0;
+            for (int64_t prev = 0; prev < co && !seen; ++prev) {
+                int same = 1, opposite = 1;
+                for (int64_t t = 0; t < taps; ++t) {
+                    int a = w[(co * taps + t) * cin + ci], b = w[(prev * taps + t) * cin + ci];
+                    if (a != b) same = 0;
+                    if (a != -b) opposite = 0;
+                }
+                seen = same || opposite;
+            }
+            if (!seen) ++n;
+        }
+        counts[ci] = n;
+    }
+    return QO_OK;
+}
+
+/* The convolution of qo_conv2d evaluated the way Sec. 5 proposes: for every input channel only the distinct 2-D
+ * filters (up to negation) are applied to that channel's map, and every output channel adds, with the sign of its own
+ * filter relative to the representative, the response of the representative it repeats.  u: integer codes
+ * [B][H][W][cin], w: +-1 [cout][kh][kw][cin], zero padding `pad`, stride 1; out int32 [B][Ho][Wo][cout].
+ * applied[0] receives the number of 2-D filter applications (sum over channels of the distinct count). */
+int qo_conv2d_dedup(const int32_t *u, int64_t B, int64_t H, int64_t W, int64_t cin, const int8_t *w, int64_t cout,
+                    int64_t kh, int64_t kw, int64_t pad, int32_t *out, int64_t *applied) {
+    int64_t ho = H + 2 * pad - kh + 1, wo = W + 2 * pad - kw + 1, taps = kh * kw;
+    if (ho < 1 || wo < 1) return QO_ERR_ARG;
+    int64_t npix = B * ho * wo;
+    int64_t *acc = (int64_t *)calloc((size_t)(npix * cout), sizeof(int64_t));
+    int64_t *resp = (int64_t *)malloc(sizeof(int64_t) * (size_t)npix);
+    int64_t *rep = (int64_t *)malloc(sizeof(int64_t) * (size_t)cout);   /* representative filter of each output channel */
+    int *sgn = (int *)malloc(sizeof(int) * (size_t)cout);
+    if (!acc || !resp || !rep || !sgn) {
+        free(acc), free(resp), free(rep), free(sgn);
+        return QO_ERR_NOMEM;
+    }
+    int64_t count = 0;
+    for (int64_t ci = 0; ci < cin; ++ci) {
+        for (int64_t co = 0; co < cout; ++co) {
+            rep[co] = co, sgn[co] = 1;
+            for (int64_t prev = 0; prev < co; ++prev) {
+                if (rep[prev] != prev) continue;
+                int same = 1, opposite = 1;
+                for (int64_t t = 0; t < taps; ++t) {
+                    int a = w[(co * taps + t) * cin + ci], b = w[(prev * taps + t) * cin + ci];
+                    if (a != b) same = 0;
+                    if (a != -b) opposite = 0;
+                }
+                if (same || opposite) {
+                    rep[co] = prev, sgn[co] = same ? 1 : -1;
+                    break;
+                }
+            }
+        }
+        for (int64_t r = 0; r < cout; ++r) {
+            if (rep[r] != r) continue;
+            ++count;
+            /* response of representative r on channel ci */
+            for (int64_t b = 0; b < B; ++b)
+                for (int64_t y = 0; y < ho; ++y)
+                    for (int64_t x = 0; x < wo; ++x) {
+                        int64_t s = 0;
+                        for (int64_t ky = 0; ky < kh; ++ky)
+                            for (int64_t kx = 0; kx < kw; ++kx) {
+                                int64_t iy = y + ky - pad, ix = x + kx - pad;
+                                if (iy < 0 || iy >= H || ix < 0 || ix >= W) continue;
+                                s += (int64_t)u[((b * H + iy) * W + ix) * cin + ci] * w[((r * kh + ky) * kw + kx) * cin + ci];
+                            }
+                        resp[(b * ho + y) * wo + x] = s;
+                    }
+            for (int64_t co = 0; co < cout; ++co)
+                if (rep[co] == r)
+                    for (int64_t p = 0; p < npix; ++p) acc[p * cout + co] += sgn[co] * resp[p];
+        }
+    }
+    int rc = QO_OK;
+    for (int64_t i = 0; i < npix * cout; ++i) {
+        if (!fits_i32(acc[i])) rc = QO_ERR_RANGE;
+        out[i] = (int32_t)acc[i];
+    }
+    if (applied) applied[0] = count;
+    free(acc), free(resp), free(rep), free(sgn);
+    return rc;
+}
+
 /* Number of threads the OpenMP loops above actually use (reported beside the CPU-baseline timing). */
 int qo_num_threads(void) {
     int n = 1;

@@ -544,3 +544,39 @@ def test_backward_products_against_library(seed):
     assert np.array_equal(gw, np.repeat(g.sum(axis=0)[:, None], K, axis=1))
     with pytest.raises(oracle.OracleRangeError):
         oracle.backward(np.full((2, 2), 2 ** 30, dtype=np.int32), np.ones((2, 3), dtype=np.int8), np.ones((2, 3), dtype=np.int8))
+
+
+# ---------------------------------------------------------------- repetition of binary 2-D filters (Sec. 5)
+def test_filter_unique_hand_cases_and_expectation(seed):
+    """Distinct 3 x 3 filters per input channel up to negation: a bank of copies has 1, a filter and its negation count
+    once, a hand-built bank with known repeats; for random +-1 banks the expected count per channel is
+    256 (1 - (255/256)^cout) (each filter falls into one of 2^9 / 2 classes uniformly)."""
+    base = qi.pm1(seed, 3000, (1, 3, 3, 5))
+    assert oracle.filter_unique(np.repeat(base, 7, axis=0)).tolist() == [1] * 5
+    both = np.concatenate([base, -base, base], axis=0)
+    assert oracle.filter_unique(both).tolist() == [1] * 5
+    w = np.ones((4, 3, 3, 2), dtype=np.int8)
+    w[1, 0, 0, 0] = -1                      # channel 0: filters {A, B, A, -B}; channel 1: {A, A, A, C}
+    w[3, :, :, 0] = -w[1, :, :, 0]
+    w[3, 2, 2, 1] = -1
+    assert oracle.filter_unique(w).tolist() == [2, 2]
+    cout, cin = 128, 64
+    counts = oracle.filter_unique(qi.pm1(seed, 3001, (cout, 3, 3, cin)))
+    expect = 256.0 * (1.0 - (255.0 / 256.0) ** cout)   # 100.9
+    assert abs(counts.mean() - expect) < 2.0 and counts.min() >= 80 and counts.max() <= 128
+
+
+def test_conv2d_dedup_equals_direct_convolution(seed):
+    """Summing the responses of the distinct 2-D filters gives the same sums as the direct convolution (Sec. 5), for
+    +-1 and for multi-bit activations, with and without padding; the number of filter applications is the sum of the
+    per-channel distinct counts."""
+    for (B, H, W, cin, cout, pad, lo, hi) in [(2, 6, 5, 7, 40, 1, 0, 3), (1, 8, 8, 3, 600, 1, -1, 1), (3, 4, 4, 5, 9, 0, 0, 1)]:
+        u = qi.uniform_int(seed, 3010, (B, H, W, cin), lo, hi)
+        if (lo, hi) == (-1, 1):
+            u = qi.pm1(seed, 3011, (B, H, W, cin)).astype(np.int32)
+        w = qi.pm1(seed, 3012, (cout, 3, 3, cin))
+        got, applied = oracle.conv2d_dedup(u, w, pad)
+        assert np.array_equal(got, oracle.conv2d(u, w.astype(np.int32), pad))
+        assert applied == int(oracle.filter_unique(w).sum())
+        if cout == 600:
+            assert applied < 0.45 * cout * cin   # 600 filters per channel fall into at most 256 classes
