@@ -260,6 +260,37 @@ def main():
 
         jobs.append((2, job_bwd))
 
+    if "c4" in only:
+        # Sec. 5, repetition of binary 2-D filters, on a layer of the CIFAR-10 ConvNet of App. A (128 -> 128 channels,
+        # 3 x 3, 32 x 32 maps, batch 16, +-1 activations held as 2-bit codes so that zero padding is exact): the
+        # convolution through the distinct filters against the direct one, and the fraction of filter applications left
+        Bd, Hd, Cd = 16, 32, 128
+        ud = qi.uniform_int(seed, 70, (Bd, Hd, Hd, Cd), 0, 1) * 2 + 1     # codes 1 (-1) and 3 (+1) of value = code - 2
+        wd_h = qi.pm1(seed, 71, (Cd, 3, 3, Cd))
+        wantd = oracle.conv2d(ud[:1], wd_h.astype(np.int32), 1)
+        Ad = dev(np.stack([np_pack_bits((ud >> p) & 1) for p in range(2)]))
+        Wd_ = dev(np_pack_pm1(wd_h))
+        wsd = torch.empty(q._lib.qnn_conv2d_dedup_workspace_bytes(Bd, Hd, Hd, Cd, Cd, 1) * Bd, dtype=torch.uint8, device="cuda")
+        od = torch.empty((Bd, Hd, Hd, Cd), dtype=torch.int32, device="cuda")
+        resd = {}
+
+        def run_dedup():
+            resd["out"], resd["counts"] = q.qnn_conv2d_dedup(Ad, [1, 2], Cd, Wd_, 1, workspace=wsd)
+
+        def job_dedup():
+            msd = time_steps(run_dedup, 20, 5)
+            msdir = time_steps(lambda: q.qnn_bitplane_conv2d(Ad, [1, 2], q.PLANE_BIT, Cd, Wd_[None], [1], q.PLANE_SIGN, 1, 1,
+                                                             out=od, engine=engine), sec_steps, sec_warm)
+            ok = (np.array_equal(resd["out"][:1].cpu().numpy(), wantd) and np.array_equal(od[:1].cpu().numpy(), wantd))
+            uniq = int(resd["counts"].sum().item())
+            extra["filter_dedup_cifar_layer_128x128"] = {
+                "parity_sample_ok": bool(ok), "distinct_2d_filters": uniq, "of": Cd * Cd,
+                "fraction_of_filter_applications_left": uniq / (Cd * Cd),
+                "ms_through_distinct_filters": msd if ok else None, "ms_direct": msdir if ok else None,
+                "note": "random +-1 weights (the paper's 42 % is for trained ones); the direct product is the fast path"}
+
+        jobs.append((1, job_dedup))
+
     if "c1" in only:
         xa_h, xw_h = qi.normal_f32(seed, 10, (128, 1024)), qi.normal_f32(seed, 11, (1024, 1024))
         want1 = oracle.gemm_pm1(oracle.sign(xa_h), oracle.sign(xw_h))

@@ -281,6 +281,20 @@ int qnn_binary_backward(const uint32_t *G, int Pg, const int32_t *coefG, int mod
                         int64_t K, void *workspace, size_t workspace_bytes, void *stream);
 size_t qnn_binary_backward_workspace_bytes(int64_t M, int64_t N, int64_t K, int Pg);
 
+/* Convolution evaluated through the distinct 2-D filters of every input channel (Sec. 5: with binary weights the
+ * 3 x 3 slices of a filter bank repeat; apply only the distinct ones, a slice and its negation counting as one, and
+ * sum the responses into each 3-D filter's result).  Same result as qnn_bitplane_conv2d with 3 x 3 filters, stride 1,
+ * bit-mode activation planes and one +-1 weight plane.  unique_count: DEVICE uint32 [Cin] or NULL, receives the
+ * number of distinct 2-D filters of every input channel; their sum over Cout * Cin is the fraction of filter
+ * applications that remains.  It states the method and measures that fraction; the direct product is the fast path.
+ * A: Pa planes as in qnn_bitplane_conv2d; W: DEVICE packed +-1 [Cout][3][3][ceil(Cin/32)]; out: DEVICE int32
+ * [B][Ho][Wo][Cout].  workspace: DEVICE, 256-byte aligned, at least qnn_conv2d_dedup_workspace_bytes(...) bytes (more
+ * lets the call take several images at a time).  9 * sum|coefA| <= 32767; Cout <= 32767. */
+int qnn_conv2d_dedup(const uint32_t *A, int Pa, const int32_t *coefA, int64_t strideA_words, int64_t B, int64_t H,
+                     int64_t Wd, int64_t Cin, const uint32_t *W, int64_t Cout, int pad, int32_t *out,
+                     uint32_t *unique_count, void *workspace, size_t workspace_bytes, void *stream);
+size_t qnn_conv2d_dedup_workspace_bytes(int64_t B, int64_t H, int64_t Wd, int64_t Cin, int64_t Cout, int pad);
+
 /* Engine (QNN_ENGINE_VALU, QNN_ENGINE_MFMA or QNN_ENGINE_MFMA_FP4) that the calling thread's last successful multiply call used; 0 before
  * any.  For reports: results never depend on it. */
 int qnn_last_engine(void);

@@ -58,6 +58,7 @@ _SIGS = {
     "qnn_transpose_bits": [_vp, _i64, _i64, _i64, _i64, _int, _vp, _i64, _i64, _vp],
     "qnn_binary_backward": [_vp, _int, _vp, _int, _i64, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _vp, _i64, _i64, _i64, _i64,
                             _vp, _sz, _vp],
+    "qnn_conv2d_dedup": [_vp, _int, _vp, _i64, _i64, _i64, _i64, _i64, _vp, _i64, _int, _vp, _vp, _vp, _sz, _vp],
     "qnn_bitplane_conv2d_ex": [_vp, _int, _vp, _int, _i64, _i64, _i64, _i64, _i64, _vp, _int, _vp, _int, _i64, _i64, _int,
                                _int, _int, _int, _vp, _int, _vp],
 }
@@ -70,6 +71,8 @@ _lib.qnn_binary_mlp_workspace_bytes.restype = _sz
 _lib.qnn_static_scratch_bytes.restype = _sz
 _lib.qnn_binary_convnet_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _int, _int, _vp, _vp, _int, _vp]
 _lib.qnn_binary_convnet_workspace_bytes.restype = _sz
+_lib.qnn_conv2d_dedup_workspace_bytes.argtypes = [_i64, _i64, _i64, _i64, _i64, _int]
+_lib.qnn_conv2d_dedup_workspace_bytes.restype = _sz
 _lib.qnn_binary_backward_workspace_bytes.argtypes = [_i64, _i64, _i64, _int]
 _lib.qnn_binary_backward_workspace_bytes.restype = _sz
 _lib.qnn_last_engine.restype = C.c_int
@@ -80,7 +83,7 @@ _lib.qnn_last_engines.argtypes = [_vp, _int]
 _lib.qnn_last_engines.restype = C.c_int
 
 EXPORTS = sorted(list(_SIGS) + ["qnn_binary_mlp_workspace_bytes", "qnn_static_scratch_bytes", "qnn_binary_convnet_workspace_bytes",
-                               "qnn_binary_backward_workspace_bytes", "qnn_last_engine",
+                               "qnn_binary_backward_workspace_bytes", "qnn_conv2d_dedup_workspace_bytes", "qnn_last_engine",
                                "qnn_last_engines", "qnn_last_error", "qnn_version"])
 
 
@@ -244,6 +247,25 @@ def qnn_transpose_bits(planes: torch.Tensor, cols: int, out: Optional[torch.Tens
     _check(_lib.qnn_transpose_bits(_dev(planes, torch.int32, "planes"), rows, cols, ld, ps, P,
                                    _dev(out, torch.int32, "out"), ldo, pso, _stream()))
     return out
+
+
+def qnn_conv2d_dedup(A: torch.Tensor, coefA: Sequence[int], Cin: int, W: torch.Tensor, pad: int,
+                     workspace: Optional[torch.Tensor] = None):
+    """A: [Pa][B][H][W][words] bit-mode planes; W: [Cout][3][3][words] packed +-1 -> (out int32 [B][Ho][Wo][Cout],
+    distinct 2-D filters per input channel int32 [Cin])."""
+    if A.dim() != 5 or not A.is_contiguous() or W.dim() != 4 or not W.is_contiguous() or W.shape[1:3] != (3, 3):
+        raise ValueError("A must be contiguous [Pa][B][H][W][words], W contiguous [Cout][3][3][words]")
+    Pa, B, H, Wd, _ = A.shape
+    Cout = W.shape[0]
+    need = int(_lib.qnn_conv2d_dedup_workspace_bytes(B, H, Wd, Cin, Cout, pad))
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=A.device)
+    out = torch.empty((B, H + 2 * pad - 2, Wd + 2 * pad - 2, Cout), dtype=torch.int32, device=A.device)
+    counts = torch.empty((Cin,), dtype=torch.int32, device=A.device)
+    _check(_lib.qnn_conv2d_dedup(_dev(A, torch.int32, "A"), Pa, _coef(coefA), A.stride(0) if Pa > 1 else 0, B, H, Wd, Cin,
+                                 _dev(W, torch.int32, "W"), Cout, pad, _dev(out, torch.int32, "out"),
+                                 _dev(counts, torch.int32, "counts"), workspace.data_ptr(), workspace.numel(), _stream()))
+    return out, counts
 
 
 def qnn_binary_backward_workspace_bytes(M: int, N: int, K: int, Pg: int) -> int:

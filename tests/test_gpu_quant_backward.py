@@ -173,3 +173,38 @@ def test_binary_backward_workspace_errors(seed):
     with pytest.raises(q.QnnError) as e:
         q.qnn_binary_backward(G, [2 ** 30, 2 ** 30], q.PLANE_BIT, N, W, A, K)
     assert e.value.status == 4
+
+
+# ---------------------------------------------------------------- repetition of binary 2-D filters (Sec. 5)
+@pytest.mark.parametrize("B,H,W,cin,cout,pad,bits", [(2, 6, 5, 7, 40, 1, 2), (1, 8, 8, 3, 600, 1, 1), (3, 4, 4, 5, 9, 0, 1),
+                                                    (2, 9, 7, 70, 130, 1, 2), (1, 3, 3, 33, 300, 1, 4)])
+def test_conv2d_dedup(seed, B, H, W, cin, cout, pad, bits):
+    """The convolution through the distinct 2-D filters equals the oracle's direct convolution on every element, and the
+    per-channel counts of distinct filters equal the oracle's."""
+    u = qi.uniform_int(seed, 3100, (B, H, W, cin), 0, (1 << bits) - 1)
+    w = qi.pm1(seed, 3101, (cout, 3, 3, cin))
+    if cout == 600:  # plant exact repeats and negations on top of the ones chance provides
+        w[1] = w[0]
+        w[2] = -w[0]
+    A = dev(np.stack([np_pack_bits((u >> p) & 1) for p in range(bits)]))
+    got, counts = q.qnn_conv2d_dedup(A, [1 << p for p in range(bits)], cin, dev(np_pack_pm1(w)), pad)
+    assert np.array_equal(host(got), oracle.conv2d(u, w.astype(np.int32), pad))
+    assert np.array_equal(host(counts), oracle.filter_unique(w))
+
+
+def test_conv2d_dedup_in_image_chunks_and_errors(seed):
+    B, H, W, cin, cout = 5, 6, 6, 40, 64
+    u = qi.uniform_int(seed, 3110, (B, H, W, cin), 0, 3)
+    w = qi.pm1(seed, 3111, (cout, 3, 3, cin))
+    A = dev(np.stack([np_pack_bits((u >> p) & 1) for p in range(2)]))
+    Wp = dev(np_pack_pm1(w))
+    need = q._lib.qnn_conv2d_dedup_workspace_bytes(B, H, W, cin, cout, 1)  # room for one image: five chunks
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda")
+    got, _ = q.qnn_conv2d_dedup(A, [1, 2], cin, Wp, 1, workspace=ws)
+    assert np.array_equal(host(got), oracle.conv2d(u, w.astype(np.int32), 1))
+    with pytest.raises(q.QnnError) as e:
+        q.qnn_conv2d_dedup(A, [1, 2], cin, Wp, 1, workspace=ws[: need - 256])
+    assert e.value.status == 6
+    with pytest.raises(q.QnnError) as e:
+        q.qnn_conv2d_dedup(A, [4000, 2], cin, Wp, 1)
+    assert e.value.status == 4
