@@ -185,9 +185,16 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
         MfmaConst pc = mc;
         if (make_code(g.pa, pc.a, aA, bA, xA0) && make_code(g.pw, pc.w, aW, bW, xW0) &&
             fill_consts(g, aA, bA, xA0, aW, bW, xW0, ngroups * panel::kGroupWords * 32, pc)) {
-            const panel::KernelFn pf = panel::find_kernel(g.epi.T != nullptr);
-            return QNN_LAUNCH("gemm_panel", pf, dim3(grid), dim3(panel::kThreads), 0, s, g, pc, (uint32_t)tiles_m,
-                              (uint32_t)tiles_n, (uint32_t)ngroups);
+            // 256 x 128 tiles where they fill the rounds of workgroups clearly better than 256 x 256 ones (each costs
+            // a little more than half of a large tile, so a small gain does not pay)
+            auto fill = [&](int64_t tiles) { return (double)tiles / (double)(ceil_div(tiles, cus) * cus); };
+            const int64_t tiles_n2 = ceil_div(g.N, BN / 2);
+            const bool narrow = fill(tiles_m * tiles_n2) > 1.1 * fill(total);
+            const panel::KernelFn pf = panel::find_kernel(g.epi.T != nullptr, narrow);
+            const int64_t ptotal = narrow ? tiles_m * tiles_n2 : total;
+            const unsigned pgrid = (unsigned)(ptotal < cus ? ptotal : cus);
+            return QNN_LAUNCH("gemm_panel", pf, dim3(pgrid), dim3(panel::kThreads), 0, s, g, pc, (uint32_t)tiles_m,
+                              (uint32_t)(narrow ? tiles_n2 : tiles_n), (uint32_t)ngroups);
         }
     }
     const KernelFn fn = g.A.rows_are_bytes ? byte_kernels()[g.epi.T ? 1 : 0]

@@ -4,7 +4,10 @@
 namespace qnn {
 namespace panel {
 
-KernelFn find_kernel(bool sign) { return sign ? gemm_panel_kernel<true> : gemm_panel_kernel<false>; }
+KernelFn find_kernel(bool sign, bool narrow) {
+    if (narrow) return sign ? gemm_panel_kernel<true, 2> : gemm_panel_kernel<false, 2>;
+    return sign ? gemm_panel_kernel<true, 4> : gemm_panel_kernel<false, 4>;
+}
 
 }  // namespace panel
 }  // namespace qnn

@@ -62,7 +62,9 @@ __device__ __forceinline__ void phase_groups(std::integer_sequence<int, I...>) {
 }
 
 // kSign: threshold epilogue (Alg. 4: a^b = Sign(BatchNorm(a))) instead of int32 sums.
-template <bool kSign>
+// WBN: 32-column blocks per wave along n, 4 (workgroup tile 256 x 256) or 2 (256 x 128: twice the tiles, for shapes whose
+// 256 x 256 tiles would leave a large part of the last round of workgroups idle).
+template <bool kSign, int WBN>
 __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                   uint32_t tiles_n, uint32_t ngroups) {
     __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kGroupBytes];
@@ -78,7 +80,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int r = lane & 31, kg = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
-    const uint32_t Kw = (uint32_t)g.Kw;
+    constexpr int WTN = 32 * WBN, BNt = 2 * WTN;  // columns of a wave tile / of the workgroup tile
+    constexpr int kMfma = WB * WBN;               // matrix-core instructions of a phase
     const uint32_t total_tiles = tiles_m * tiles_n;
     const int64_t Nw = (g.N + 31) / 32;
 
@@ -104,7 +107,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         uint32_t tm, tn;
         tile_of_block(p_vb, total_tiles, tiles_m, tiles_n, tm, tn);
         p_m0 = tm * (uint32_t)BM;
-        p_n0 = tn * (uint32_t)BN;
+        p_n0 = tn * (uint32_t)BNt;
     };
     auto p_advance = [&]() __attribute__((always_inline)) {
         ++p_G;
@@ -131,36 +134,39 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             uint32_t m = p_m0 + (uint32_t)(64 * q + 32 * h) + pr;
             m = m > last_m ? last_m : m;
             load_to_lds(g.A.base, m * lda_bytes + jb, dst + (uint32_t)(h * 32 * kRowBytes));
-            uint32_t n = p_n0 + (uint32_t)(64 * q + 32 * h) + pr;
-            n = n > last_n ? last_n : n;
-            load_to_lds(g.W, n * ldw_bytes + jb, dst + (uint32_t)(kPanelBytes + h * 32 * kRowBytes));
+            if (64 * q + 32 * h < BNt) {
+                uint32_t n = p_n0 + (uint32_t)(64 * q + 32 * h) + pr;
+                n = n > last_n ? last_n : n;
+                load_to_lds(g.W, n * ldw_bytes + jb, dst + (uint32_t)(kPanelBytes + h * 32 * kRowBytes));
+            }
         }
     };
 
     // ------------------------------------------------------------------------------------------------ consumer
     // lane (r, kg) of block b reads piece 2 q + kg of row 32 b + r at step q of a group
     struct Step {
-        uint4 A[WB], W[WB];
+        uint4 A[WB], W[WBN];
     };
     auto fetch = [&](const int q, const uint32_t buf, Step &d) __attribute__((always_inline)) {
         const uint32_t ln = opaque(tid) & 63u;
         const uint32_t r = ln & 31u, kg = ln >> 5;
         const uint32_t piece = ((kg ^ (r & 7u)) << 4) ^ (uint32_t)(q << 5);
         const uint8_t *pa = lds + (buf + (uint32_t)(wm * WTILE * kRowBytes) + r * (uint32_t)kRowBytes + piece);
-        const uint8_t *pw = lds + (buf + (uint32_t)(kPanelBytes + wn * WTILE * kRowBytes) + r * (uint32_t)kRowBytes + piece);
+        const uint8_t *pw = lds + (buf + (uint32_t)(kPanelBytes + wn * WTN * kRowBytes) + r * (uint32_t)kRowBytes + piece);
 #pragma unroll
-        for (int b = 0; b < WB; ++b) {
-            d.A[b] = *reinterpret_cast<const uint4 *>(pa + b * (32 * kRowBytes));
-            d.W[b] = *reinterpret_cast<const uint4 *>(pw + b * (32 * kRowBytes));
-        }
+        for (int b = 0; b < WB; ++b) d.A[b] = *reinterpret_cast<const uint4 *>(pa + b * (32 * kRowBytes));
+#pragma unroll
+        for (int b = 0; b < WBN; ++b) d.W[b] = *reinterpret_cast<const uint4 *>(pw + b * (32 * kRowBytes));
     };
 
-    v16f acc[WB][WB];  // [n block][m block]
-    int32_t ra[WB], rw[WB];
+    v16f acc[WBN][WB];  // [n block][m block]
+    int32_t ra[WB], rw[WBN];
     auto clear = [&]() __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < WB; ++i) {
-            ra[i] = rw[i] = 0;
+        for (int j = 0; j < WB; ++j) ra[j] = 0;
+#pragma unroll
+        for (int i = 0; i < WBN; ++i) {
+            rw[i] = 0;
 #pragma unroll
             for (int j = 0; j < WB; ++j)
 #pragma unroll
@@ -168,7 +174,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         }
     };
     struct Frags {
-        v8i a[WB], w[WB];
+        v8i a[WB], w[WBN];
     };
     // Phase t of a step multiplies bit t of every nibble of the lane's four words (32 of its 128 elements of k; both
     // operands use the same order).  An E2M1 nibble with only bit 0 set is 0.5, with bit 1 set 1.0, with bit 2 set 2.0,
@@ -181,12 +187,21 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
-                const uint32_t a = word_of(c.A[b], j), w = word_of(c.W[b], j);
+                const uint32_t a = word_of(c.A[b], j);
                 f.a[b][j] = (int)((tt == 3 ? a >> 2 : a) & mask);
+            }
+#pragma unroll
+            for (int j = 4; j < 8; ++j) f.a[b][j] = 0;
+        }
+#pragma unroll
+        for (int b = 0; b < WBN; ++b) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint32_t w = word_of(c.W[b], j);
                 f.w[b][j] = (int)((tt == 3 ? w >> 2 : w) & mask);
             }
 #pragma unroll
-            for (int j = 4; j < 8; ++j) f.a[b][j] = f.w[b][j] = 0;
+            for (int j = 4; j < 8; ++j) f.w[b][j] = 0;
         }
     };
     // row sums of the raw bits: one word of every row per phase.  Each sum is made opaque after its addition: left
@@ -196,8 +211,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
             ra[b] += (int32_t)__builtin_popcount(word_of(c.A[b], tt));
-            rw[b] += (int32_t)__builtin_popcount(word_of(c.W[b], tt));
             asm("" : "+v"(ra[b]));
+        }
+#pragma unroll
+        for (int b = 0; b < WBN; ++b) {
+            rw[b] += (int32_t)__builtin_popcount(word_of(c.W[b], tt));
             asm("" : "+v"(rw[b]));
         }
     };
@@ -206,7 +224,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     auto multiply = [&](const Frags &f, auto t_tag) __attribute__((always_inline)) {
         constexpr int tt = decltype(t_tag)::value;
 #pragma unroll
-        for (int i = 0; i < WB; ++i)
+        for (int i = 0; i < WBN; ++i)
 #pragma unroll
             for (int j = 0; j < WB; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.w[i], f.a[j], acc[i][j], 4, 4, tt, scales, tt, scales);
@@ -230,11 +248,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
                 expand(n, 0, gnext);
             multiply(f, t_tag);
             // vector-ALU instructions of this phase: operands of the next one (4 per row, 8 for bit 3) and the counts
-            constexpr int kOps = 2 * WB * ((tt == 2 ? 8 : 4) + 1);
+            constexpr int kOps = (WB + WBN) * ((tt == 2 ? 8 : 4) + 1);
             if (tt == 0)
-                phase_groups<kOps + 8, 2 * WB, 0, 0>(std::make_integer_sequence<int, 16>{});
+                phase_groups<kOps + 8, WB + WBN, 0, 0>(std::make_integer_sequence<int, kMfma>{});
             else
-                phase_groups<kOps, 0, 0, 0>(std::make_integer_sequence<int, 16>{});
+                phase_groups<kOps, 0, 0, 0>(std::make_integer_sequence<int, kMfma>{});
             __builtin_amdgcn_sched_barrier(0);
             if (!(kLastStep && tt == 3)) f = gnext;
         };
@@ -250,7 +268,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     auto load_thresholds = [&](const int64_t n_wave) __attribute__((always_inline)) {
         if constexpr (kSign) {
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < WTN / 64; ++h) {
                 int64_t n = n_wave + 64 * h + lane;
                 if (n > g.N - 1) n = g.N - 1;
                 thr_T[h] = g.epi.T[n];
@@ -270,14 +288,13 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         asm volatile("" : "+v"(lane_opaque));
         const int lane = lane_opaque, r = lane & 31, kg = lane >> 5;
 #pragma unroll
-        for (int b = 0; b < WB; ++b) {
-            ra[b] = sum_halves(ra[b]);
-            rw[b] = sum_halves(rw[b]);
-        }
+        for (int b = 0; b < WB; ++b) ra[b] = sum_halves(ra[b]);
+#pragma unroll
+        for (int b = 0; b < WBN; ++b) rw[b] = sum_halves(rw[b]);
         if (mc.needRW) {
             if (kg == 0) {
 #pragma unroll
-                for (int b = 0; b < WB; ++b) rw_table[wave][b * 32 + r] = mc.cRW * (uint32_t)rw[b];
+                for (int b = 0; b < WBN; ++b) rw_table[wave][b * 32 + r] = mc.cRW * (uint32_t)rw[b];
             }
             __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's own LDS writes have landed
             __builtin_amdgcn_wave_barrier();
@@ -293,7 +310,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             // thresholds, clamped and minus one, and flip flags at the bit position their n has in a lane's partial
             // output word (n mod 32 = 8 q + 4 kg + i  ->  bit 8 q + i), into per-wave LDS tables
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
+            for (int h = 0; h < WTN / 64; ++h) {
                 const int nl = 64 * h + lane;
                 const int32_t tv = thr_T[h];
                 const int32_t tc = tv < -(1 << 30) ? -(1 << 30) : (tv > (1 << 30) ? (1 << 30) : tv);
@@ -313,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
                 *reinterpret_cast<i32x4 *>(line_base + (int64_t)(pbj * 32 + 8 * j) * g.epi.ldc + pbi * 32) = pend[j];
         };
 #pragma unroll
-        for (int bi = 0; bi < WB; ++bi) {
+        for (int bi = 0; bi < WBN; ++bi) {
             const int64_t n_blk = n_wave + bi * 32;
             uint32_t nterm[16];  // the part that depends on n only
 #pragma unroll
@@ -409,10 +426,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if constexpr (kFast && !kSign) store_lines(WB - 1, WB - 1);
+        if constexpr (kFast && !kSign) store_lines(WBN - 1, WB - 1);
     };
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
-        const bool interior = m_wave + WTILE <= g.M && n_wave + WTILE <= g.N;
+        const bool interior = m_wave + WTILE <= g.M && n_wave + WTN <= g.N;
         const bool wide = kSign || ((g.epi.ldc % 4 == 0) && (reinterpret_cast<uintptr_t>(g.epi.C) % 16 == 0));
         const bool fast = interior && wide;
         if (mc.alpha_shift >= 0) {
@@ -465,7 +482,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     while (true) {
         uint32_t tile_m, tile_n;
         tile_of_block(vb, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
-        const int64_t m_wave = (int64_t)tile_m * BM + wm * WTILE, n_wave = (int64_t)tile_n * BN + wn * WTILE;
+        const int64_t m_wave = (int64_t)tile_m * BM + wm * WTILE, n_wave = (int64_t)tile_n * BNt + wn * WTN;
         clear();
         // one group of four steps; kLastGroup: its last step ends the tile
         auto group = [&](auto last_tag) __attribute__((always_inline)) {
@@ -496,7 +513,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 }
 
 typedef void (*KernelFn)(const GemmArgs, const MfmaConst, uint32_t, uint32_t, uint32_t);
-KernelFn find_kernel(bool sign);
+// narrow: the 256 x 128 workgroup tile
+KernelFn find_kernel(bool sign, bool narrow);
 
 }  // namespace panel
 }  // namespace qnn

@@ -209,6 +209,43 @@ def test_many_tiles_short_k_threshold_output(seed, M, N, K, engine):
     assert_same(got[:, :ldo - 3], oracle.pack_bits(oracle.threshold(oracle.gemm_pm1(a, w), T, flip)))
 
 
+# K a multiple of 1024 and 16-byte aligned rows: the kernel that is fed from LDS panels.  (4000, 8100): 16 x 32 tiles of
+# 256 x 256, two per workgroup, ragged on both edges; (4200, 4360): 17 x 35 tiles of 256 x 128 (chosen because 17 x 18
+# large tiles would leave 40 % of the second round idle); (1000, 700): fewer tiles than workgroups, three groups of K.
+PANEL_TILES = [(4000, 8100, 1024), (4200, 4360, 2048), (1000, 700, 3072)]
+
+
+@pytest.mark.parametrize("engine", [0, FP4])
+@pytest.mark.parametrize("M,N,K", PANEL_TILES)
+def test_panel_fed_kernel_int32_output(seed, M, N, K, engine):
+    a = qi.pm1(seed, 74, (M, K))
+    w = qi.pm1(seed, 75, (N, K))
+    ldc = N + 4 * (K // 1024 - 1)
+    out = torch.full((M, ldc), -7, dtype=torch.int32, device="cuda")
+    q.qnn_binary_gemm(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, out=out[:, :N], engine=engine)
+    check_engine(engine, FP4 if M >= 4000 else 1)
+    got = host(out)
+    assert (got[:, N:] == -7).all()
+    assert_same(got[:, :N], oracle.gemm_pm1(a, w))
+
+
+@pytest.mark.parametrize("engine", [0, FP4])
+@pytest.mark.parametrize("M,N,K", PANEL_TILES)
+def test_panel_fed_kernel_threshold_output(seed, M, N, K, engine):
+    a = qi.pm1(seed, 76, (M, K))
+    w = qi.pm1(seed, 77, (N, K))
+    T = qi.uniform_int(seed, 78, (N,), -20, 20)
+    flip = qi.bernoulli_bits(seed, 79, (N,))
+    ldo = (N + 31) // 32 + 2
+    out = torch.full((M, ldo), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    q.qnn_binary_gemm_sign(dev(np_pack_pm1(a)), dev(np_pack_pm1(w)), K, dev(T), dev(flip), out=out[:, :ldo - 2],
+                           engine=engine)
+    check_engine(engine, FP4 if M >= 4000 else 1)
+    got = host_u32(out)
+    assert (got[:, ldo - 2:] == 0x5A5A5A5A).all()
+    assert_same(got[:, :ldo - 2], oracle.pack_bits(oracle.threshold(oracle.gemm_pm1(a, w), T, flip)))
+
+
 @pytest.mark.parametrize("engine", [None, MFMA])
 def test_many_tiles_first_layer_from_codes(seed, engine):
     """The byte-operand kernel of the MLP's first layer over 17 x 17 tiles, then a 10-neuron output layer."""
