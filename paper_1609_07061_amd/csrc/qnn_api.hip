@@ -331,6 +331,10 @@ size_t qnn_binary_mlp_workspace_bytes(int64_t batch, int in_bits, int n_layers, 
 namespace {
 struct MlpPlan {
     bool pack_planes;  // the input planes are materialised (otherwise the first layer reads the 8-bit codes)
+    bool expand_w;     // the first layer's weights are expanded to bytes first (into the unused plane area)
+    int8_t *w_bytes;
+    int64_t ld_w_bytes;
+    int32_t *rw_scaled;
     const uint8_t *x;
     int64_t batch, in_dim, ldx, ld0, plane_stride;
     int in_bits;
@@ -396,6 +400,7 @@ int plan_mlp(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_la
     for (int p = 0; p < in_bits; ++p) coef[p] = 1 << p;
     const Epilogue e0{nullptr, 0, T[0], flip ? flip[0] : nullptr, act[0], mlp_ldw(dims[1])};
     plan.pack_planes = true;
+    plan.expand_w = false;
     if (in_bits == 8 && engine != QNN_ENGINE_VALU) {
         GemmArgs &g = plan.g[0];
         std::memset(&g, 0, sizeof(g));
@@ -414,6 +419,17 @@ int plan_mlp(const uint8_t *x, int64_t batch, int64_t ldx, int in_bits, int n_la
             if (!aligned4(W[0]) || !aligned4(T[0])) return fail(QNN_ERR_ALIGN, "mlp: pointer not 4-byte aligned");
             plan.engine[0] = QNN_ENGINE_MFMA;
             plan.pack_planes = false;
+            // The plane area of the workspace is free then: if it holds them, the weights go there as bytes (rows of
+            // whole 128-element groups) with their row sums, which lets the kernel run without expanding bits per wave.
+            const int64_t ldb = (dims[0] + 127) / 128 * 128;
+            const size_t wb = round256((size_t)dims[1] * (size_t)ldb), rb = round256((size_t)dims[1] * 4);
+            if (wb + rb <= off) {
+                plan.expand_w = true;
+                plan.w_bytes = reinterpret_cast<int8_t *>(ws);
+                plan.ld_w_bytes = ldb;
+                plan.rw_scaled = reinterpret_cast<int32_t *>(ws + wb);
+                g.w_bytes = plan.w_bytes, g.ld_w_bytes = ldb, g.rw_scaled = plan.rw_scaled;
+            }
         }
     }
     bool none;
@@ -446,6 +462,10 @@ int run_mlp(const MlpPlan &plan, hipStream_t s) {
     if (plan.pack_planes)
         if (int rc = launch_pack_bitplanes(plan.x, plan.batch, plan.in_dim, plan.ldx, plan.in_bits, plan.planes, plan.ld0,
                                            plan.plane_stride, s))
+            return rc;
+    if (plan.expand_w)
+        if (int rc = bytes_panel::launch_expand_weights(plan.g[0].W, plan.g[0].N, plan.g[0].K, plan.g[0].ldw, plan.w_bytes,
+                                                        plan.ld_w_bytes, plan.rw_scaled, s))
             return rc;
     for (int l = 0; l < plan.n; ++l)
         if (int rc = launch_on(plan.g[l], plan.engine[l], s)) return rc;

@@ -1,8 +1,8 @@
 // Matrix-core engine of the binary / bit-plane matrix product: host side (operand codes, epilogue constants, choice of
 // the kernel instantiation, launch).  The kernel itself is in qnn_gemm_mfma_kernel.h.
-#include <cstdlib>
 
 #include "qnn_gemm_mfma_kernel.h"
+#include "qnn_gemm_bytes_panel_kernel.h"
 #include "qnn_gemm_panel_kernel.h"
 #include "qnn_gemm_stage_kernel.h"
 
@@ -175,10 +175,9 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
     const int64_t total = tiles_m * tiles_n;
     const unsigned grid = (unsigned)(total < cus ? total : cus);
     // single-plane products on the FP4 path whose rows are made of whole, aligned 16-byte groups: the panel-fed kernel
-    static const bool no_panel = std::getenv("QNN_NO_PANEL") != nullptr;
-    // (it addresses rows by 32-bit byte offsets from the operand's base)
-    const bool spans32 = 4.0L * (long double)g.M * g.A.ld < 4294967296.0L && 4.0L * (long double)g.N * g.ldw < 4294967296.0L;
-    if (fp4 && vec && spans32 && !no_panel && !g.A.rows_are_pixels && !g.A.rows_are_bytes && v->WPL == 4 &&
+    // (row offsets are 32-bit and formed for up to one tile beyond the last row before they are clamped)
+    const bool spans32 = 4.0L * (long double)(g.M + 256) * g.A.ld < 4294967296.0L && 4.0L * (long double)(g.N + 256) * g.ldw < 4294967296.0L;
+    if (fp4 && vec && spans32 && !g.A.rows_are_pixels && !g.A.rows_are_bytes && v->WPL == 4 &&
         g.Kw % panel::kGroupWords == 0) {
         const int64_t ngroups = ceil_div(g.Kw, panel::kGroupWords);
         int64_t aA, bA, xA0, aW, bW, xW0;
@@ -195,6 +194,23 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
             const unsigned pgrid = (unsigned)(ptotal < cus ? ptotal : cus);
             return QNN_LAUNCH("gemm_panel", pf, dim3(pgrid), dim3(panel::kThreads), 0, s, g, pc, (uint32_t)tiles_m,
                               (uint32_t)(narrow ? tiles_n2 : tiles_n), (uint32_t)ngroups);
+        }
+    }
+    // uint8 left operand with the weights expanded to bytes beforehand: the panel-fed kernel (threshold epilogue)
+    if (g.A.rows_are_bytes && g.w_bytes && g.rw_scaled && g.epi.T && (long double)g.M * g.A.ld < 4294967296.0L &&
+        (long double)g.N * g.ld_w_bytes < 4294967296.0L && g.ld_w_bytes % bytes_panel::kGroupK == 0 && g.ld_w_bytes >= g.K) {
+        MfmaConst pc = mc;
+        pc.alpha = 1, pc.alpha_shift = 0, pc.cRA = 0, pc.cRW = 1, pc.c0 = 0, pc.needRW = 1;
+        const int64_t ngroups = ceil_div(g.K, bytes_panel::kGroupK);
+        // 256 x 128 tiles where they fill the rounds of workgroups clearly better than 256 x 256 ones
+        auto fill = [&](int64_t tiles) { return (double)tiles / (double)(ceil_div(tiles, cus) * cus); };
+        const int64_t wide_n = ceil_div(g.N, 256), narrow_n = ceil_div(g.N, 128);
+        const bool narrow = fill(tiles_m * narrow_n) > 1.1 * fill(tiles_m * wide_n);
+        const int64_t tiles_nb = narrow ? narrow_n : wide_n, ptotal = tiles_m * tiles_nb;
+        if (ptotal <= 0x7FFFFFFFLL) {
+            const unsigned pgrid = (unsigned)(ptotal < cus ? ptotal : cus);
+            return QNN_LAUNCH("gemm_bytes_panel", bytes_panel::kernel(narrow), dim3(pgrid), dim3(bytes_panel::kThreads), 0, s, g, pc,
+                              (uint32_t)tiles_m, (uint32_t)tiles_nb, (uint32_t)ngroups);
         }
     }
     const KernelFn fn = g.A.rows_are_bytes ? byte_kernels()[g.epi.T ? 1 : 0]

@@ -25,16 +25,11 @@
 // starting on 16-byte boundaries, operands that span less than 4 GiB each.
 #pragma once
 #include "qnn_gemm_mfma_kernel.h"
+#include "qnn_gemm_panel_epilogue.h"
 
 namespace qnn {
 namespace panel {
 
-using mfma::acc_to_sum;
-using mfma::expand_fp4;
-using mfma::i32x4;
-using mfma::MfmaConst;
-using mfma::or_halves;
-using mfma::sum_halves;
 using mfma::v16f;
 using mfma::v8i;
 
@@ -42,7 +37,6 @@ constexpr int kThreads = 256;
 constexpr int WB = 4, WTILE = 128, BM = 256, BN = 256;
 constexpr int kRowBytes = 128;                 // bytes of a row per group: four steps of two 16-byte k-groups
 constexpr int kPanelBytes = BM * kRowBytes;    // one operand's 256 rows
-constexpr int kGroupBytes = 2 * kPanelBytes;   // activation panel, then weight panel
 constexpr int kGroupWords = kRowBytes / 4;
 
 __device__ __forceinline__ uint32_t word_of(const uint4 &v, int t) { return t == 0 ? v.x : (t == 1 ? v.y : (t == 2 ? v.z : v.w)); }
@@ -67,7 +61,12 @@ __device__ __forceinline__ void phase_groups(std::integer_sequence<int, I...>) {
 template <bool kSign, int WBN>
 __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                   uint32_t tiles_n, uint32_t ngroups) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds[2 * kGroupBytes];
+    // Group buffers: activation panel (256 rows) + weight panel (BN rows).  Two take turns; the narrow tile with the
+    // threshold epilogue has room for three, which its steps (half as long) need to keep the loads three steps, in
+    // time, ahead.
+    constexpr int kGroupBytesT = kPanelBytes + 2 * 32 * WBN * kRowBytes;
+    constexpr int kBuffers = (kSign && WBN == 2) ? 3 : 2;
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kBuffers * kGroupBytesT];
     __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
     __shared__ __attribute__((aligned(16))) int32_t thr_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
     __shared__ __attribute__((aligned(16))) uint32_t flip_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
@@ -82,8 +81,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     const int wm = wave >> 1, wn = wave & 1;
     constexpr int WTN = 32 * WBN, BNt = 2 * WTN;  // columns of a wave tile / of the workgroup tile
     constexpr int kMfma = WB * WBN;               // matrix-core instructions of a phase
+    constexpr int kLoadsPerGroup = 8 + BNt / 32;  // loads to LDS that a wave issues per group (8 activation, BN / 32 weight)
     const uint32_t total_tiles = tiles_m * tiles_n;
-    const int64_t Nw = (g.N + 31) / 32;
 
     // ------------------------------------------------------------------------------------------------ producer
     // A load instruction of a wave covers 8 consecutive rows x 128 bytes and fills 1 KiB of LDS: lane i lands at
@@ -97,47 +96,93 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         return x;
     };
     const uint32_t tid = (uint32_t)t;
+    if constexpr (kSign) {  // flip flags default to "none" (complete long before the first epilogue reads them)
+        flip_table[wave][lane] = 0u;
+        flip_table[wave][lane + 64] = 0u;
+    }
     const uint32_t lds_base = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t *)lds);
-    // the group being loaded: tile p_vb (origin p_m0, p_n0), group p_G of its row
+    // The producer's cursor: tile p_vb, group p_G of its rows.  Everything that depends on the tile only (the byte
+    // offsets of the rows this lane loads, with its piece of the line) is worked out when the cursor enters a tile,
+    // under a branch of its own; per group only the scalar base pointers move on.  The one wave a SIMD holds issues
+    // every instruction of the loop itself, so each instruction kept out of the groups is time won.
     uint32_t p_vb = blockIdx.x, p_G = 0;
-    uint32_t p_m0 = 0, p_n0 = 0;
+    // kRowRegs (the narrow tile, whose accumulators leave registers free): one offset register per load, and a copy is
+    // all a load needs.  Otherwise one register per panel holds the offset of the lane's row in the first 32-row
+    // block, a second one the offset in the operand's last row, and a load adds its block's distance and clamps.
+    constexpr bool kRowRegs = WBN == 2;
+    uint32_t a_off[kRowRegs ? 8 : 1], w_off[kRowRegs ? BNt / 32 : 1], a_max = 0, w_max = 0;
     const uint32_t lda_bytes = (uint32_t)g.A.ld * 4u, ldw_bytes = (uint32_t)g.ldw * 4u;
     const uint32_t last_m = (uint32_t)(g.M - 1), last_n = (uint32_t)(g.N - 1);
     auto p_locate = [&]() __attribute__((always_inline)) {
         uint32_t tm, tn;
         tile_of_block(p_vb, total_tiles, tiles_m, tiles_n, tm, tn);
-        p_m0 = tm * (uint32_t)BM;
-        p_n0 = tn * (uint32_t)BNt;
+        const uint32_t tt = opaque(tid);
+        const uint32_t pr = tt >> 3;                                  // row within a load's 32-row block
+        const uint32_t piece16 = ((tt & 7u) ^ ((tt >> 3) & 7u)) << 4;  // (slot xor (row mod 8)) * 16 bytes
+        if constexpr (kRowRegs) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                uint32_t m = tm * (uint32_t)BM + (uint32_t)(32 * i) + pr;
+                m = m > last_m ? last_m : m;
+                a_off[i] = m * lda_bytes + piece16;
+            }
+#pragma unroll
+            for (int i = 0; i < BNt / 32; ++i) {
+                uint32_t n = tn * (uint32_t)BNt + (uint32_t)(32 * i) + pr;
+                n = n > last_n ? last_n : n;
+                w_off[i] = n * ldw_bytes + piece16;
+            }
+        } else {
+            // (the host checks that offsets up to one tile beyond the last row still fit 32 bits)
+            a_off[0] = (tm * (uint32_t)BM + pr) * lda_bytes + piece16;
+            w_off[0] = (tn * (uint32_t)BNt + pr) * ldw_bytes + piece16;
+            a_max = last_m * lda_bytes + piece16;
+            w_max = last_n * ldw_bytes + piece16;
+        }
     };
     auto p_advance = [&]() __attribute__((always_inline)) {
         ++p_G;
-        const bool wrap = p_G == ngroups;
-        const uint32_t nb = p_vb + gridDim.x;
-        // after the last tile the loads are repeated and never used
-        p_vb = (wrap && nb < total_tiles) ? nb : p_vb;
-        p_G = wrap ? 0u : p_G;
-        p_locate();
+        if (p_G == ngroups) {
+            asm volatile("" ::: "memory");  // keeps the branch a branch
+            p_G = 0;
+            const uint32_t nb = p_vb + gridDim.x;
+            p_vb = nb < total_tiles ? nb : p_vb;  // after the last tile the loads are repeated and never used
+            p_locate();
+        }
     };
-    // 16 bytes per lane from base + voff to LDS address lds_addr + 16 * lane (the address travels in M0)
+    // 16 bytes per lane from base + voff (or base + min(voff + sadd, vmax)) to LDS address lds_addr + 16 * lane.  The
+    // address travels in M0; between the write of M0 and the load there has to be an instruction, here the one that
+    // makes the offset.
     auto load_to_lds = [](const void *base, uint32_t voff, uint32_t lds_addr) __attribute__((always_inline)) {
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(lds_addr), "v"(voff), "s"(base) : "memory");
+        uint32_t tmp;
+        asm volatile("s_mov_b32 m0, %1\n\tv_mov_b32 %0, %2\n\tglobal_load_lds_dwordx4 %0, %3"
+                     : "=&v"(tmp)
+                     : "s"(lds_addr), "v"(voff), "s"(base)
+                     : "memory");
     };
-    // quarter q of the group at the cursor into the group buffer at byte offset buf
+    auto load_clamped_to_lds = [](const void *base, uint32_t voff, uint32_t sadd, uint32_t vmax, uint32_t lds_addr) __attribute__((always_inline)) {
+        uint32_t tmp;
+        asm volatile("s_mov_b32 m0, %1\n\tv_add_u32 %0, %3, %2\n\tv_min_u32 %0, %0, %4\n\tglobal_load_lds_dwordx4 %0, %5"
+                     : "=&v"(tmp)
+                     : "s"(lds_addr), "v"(voff), "s"(sadd), "v"(vmax), "s"(base)
+                     : "memory");
+    };
+    // quarter q (rows 64 q .. 64 q + 63 of both panels) of the group at the cursor into the group buffer at byte offset buf
     auto load_quarter = [&](const int q, const uint32_t buf) __attribute__((always_inline)) {
-        const uint32_t tt = opaque(tid);
-        const uint32_t pr = tt >> 3;                           // row of the quarter's first half (0..31)
-        const uint32_t piece = (tt & 7u) ^ ((tt >> 3) & 7u);   // slot xor (row mod 8)
-        const uint32_t jb = (p_G * kGroupWords + piece * 4u) * 4u;
+        const uint8_t *a_base = reinterpret_cast<const uint8_t *>(g.A.base) + p_G * (uint32_t)kRowBytes;
+        const uint8_t *w_base = reinterpret_cast<const uint8_t *>(g.W) + p_G * (uint32_t)kRowBytes;
         const uint32_t dst = lds_base + buf + (uint32_t)(q * (64 * kRowBytes)) + (uint32_t)wave * (8u * kRowBytes);
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
-            uint32_t m = p_m0 + (uint32_t)(64 * q + 32 * h) + pr;
-            m = m > last_m ? last_m : m;
-            load_to_lds(g.A.base, m * lda_bytes + jb, dst + (uint32_t)(h * 32 * kRowBytes));
-            if (64 * q + 32 * h < BNt) {
-                uint32_t n = p_n0 + (uint32_t)(64 * q + 32 * h) + pr;
-                n = n > last_n ? last_n : n;
-                load_to_lds(g.W, n * ldw_bytes + jb, dst + (uint32_t)(kPanelBytes + h * 32 * kRowBytes));
+            const int i = 2 * q + h;
+            const bool has_w = 32 * i < BNt;
+            if constexpr (kRowRegs) {
+                load_to_lds(a_base, a_off[i], dst + (uint32_t)(h * 32 * kRowBytes));
+                if (has_w) load_to_lds(w_base, w_off[i % (BNt / 32)], dst + (uint32_t)(kPanelBytes + h * 32 * kRowBytes));
+            } else {
+                load_clamped_to_lds(a_base, a_off[0], (uint32_t)(32 * i) * lda_bytes, a_max, dst + (uint32_t)(h * 32 * kRowBytes));
+                if (has_w)
+                    load_clamped_to_lds(w_base, w_off[0], (uint32_t)(32 * i) * ldw_bytes, w_max, dst + (uint32_t)(kPanelBytes + h * 32 * kRowBytes));
             }
         }
     };
@@ -262,207 +307,39 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         phase(std::integral_constant<int, 3>{});
     };
 
-    // thresholds / flip flags of the tile being finished: n = n_wave + lane and n_wave + 64 + lane (clamped into range)
-    int32_t thr_T[2] = {0, 0};
-    uint32_t thr_F[2] = {0u, 0u};
+    // thresholds / flip flags of the tile being finished, straight into this wave's LDS tables
     auto load_thresholds = [&](const int64_t n_wave) __attribute__((always_inline)) {
-        if constexpr (kSign) {
-#pragma unroll
-            for (int h = 0; h < WTN / 64; ++h) {
-                int64_t n = n_wave + 64 * h + lane;
-                if (n > g.N - 1) n = g.N - 1;
-                thr_T[h] = g.epi.T[n];
-                thr_F[h] = g.epi.flip ? (uint32_t)g.epi.flip[n] : 0u;
-            }
-        }
+        if constexpr (kSign) load_thresholds_to_lds<WBN>(g, n_wave, thr_table[wave], flip_table[wave]);
     };
 
-    // Accumulator register v of block [bi][bj] is C[m][n] with
-    //   m = m_wave + 32 bj + (lane mod 32),   n = n_wave + 32 bi + 8 (v / 4) + 4 (lane / 32) + v mod 4.
-    // kFast: the wave tile lies completely inside C and C allows 16-byte stores, so nothing needs a bounds check.
-    auto epilogue = [&](const int64_t m_wave, const int64_t n_wave, auto scale, auto fast_tag) __attribute__((always_inline)) {
-        constexpr bool kFast = decltype(fast_tag)::value;
-        // lane coordinates re-derived behind an opaque copy: index arithmetic computed before the tile loop and kept
-        // across it would be spilled, and a reload waits for every store issued before it
-        int lane_opaque = (int)(threadIdx.x & 63);
-        asm volatile("" : "+v"(lane_opaque));
-        const int lane = lane_opaque, r = lane & 31, kg = lane >> 5;
-#pragma unroll
-        for (int b = 0; b < WB; ++b) ra[b] = sum_halves(ra[b]);
-#pragma unroll
-        for (int b = 0; b < WBN; ++b) rw[b] = sum_halves(rw[b]);
-        if (mc.needRW) {
-            if (kg == 0) {
-#pragma unroll
-                for (int b = 0; b < WBN; ++b) rw_table[wave][b * 32 + r] = mc.cRW * (uint32_t)rw[b];
-            }
-            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the wave's own LDS writes have landed
-            __builtin_amdgcn_wave_barrier();
-        }
-        int64_t m_of[WB];
-        uint32_t mterm[WB];
-#pragma unroll
-        for (int bj = 0; bj < WB; ++bj) {
-            m_of[bj] = m_wave + bj * 32 + r;
-            mterm[bj] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
-        }
-        if constexpr (kSign) {
-            // thresholds, clamped and minus one, and flip flags at the bit position their n has in a lane's partial
-            // output word (n mod 32 = 8 q + 4 kg + i  ->  bit 8 q + i), into per-wave LDS tables
-#pragma unroll
-            for (int h = 0; h < WTN / 64; ++h) {
-                const int nl = 64 * h + lane;
-                const int32_t tv = thr_T[h];
-                const int32_t tc = tv < -(1 << 30) ? -(1 << 30) : (tv > (1 << 30) ? (1 << 30) : tv);
-                thr_table[wave][nl] = tc - 1;
-                flip_table[wave][nl] = thr_F[h] != 0 ? (1u << ((nl & 0x18) | (nl & 3))) : 0u;
-            }
-            __builtin_amdgcn_s_waitcnt(0xc07f);
-            __builtin_amdgcn_wave_barrier();
-        }
-        // kFast int32 output: lines of the block before the current one, read from LDS and not stored yet; lane
-        // (row = lane / 8, 16-byte unit = lane mod 8) of store j writes row 8 j + lane / 8 of the block
-        i32x4 pend[4];
-        int32_t *const line_base = kSign ? nullptr : g.epi.C + (m_wave + (lane >> 3)) * g.epi.ldc + n_wave + 4 * (lane & 7);
-        auto store_lines = [&](const int pbi, const int pbj) __attribute__((always_inline)) {
-#pragma unroll
-            for (int j = 0; j < 4; ++j)
-                *reinterpret_cast<i32x4 *>(line_base + (int64_t)(pbj * 32 + 8 * j) * g.epi.ldc + pbi * 32) = pend[j];
-        };
-#pragma unroll
-        for (int bi = 0; bi < WBN; ++bi) {
-            const int64_t n_blk = n_wave + bi * 32;
-            uint32_t nterm[16];  // the part that depends on n only
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                uint4 t4 = make_uint4(0u, 0u, 0u, 0u);
-                if (mc.needRW) t4 = *reinterpret_cast<const uint4 *>(&rw_table[wave][bi * 32 + 8 * q + 4 * kg]);
-                nterm[4 * q] = t4.x, nterm[4 * q + 1] = t4.y, nterm[4 * q + 2] = t4.z, nterm[4 * q + 3] = t4.w;
-            }
-            if constexpr (!kSign) {
-#pragma unroll
-                for (int bj = 0; bj < WB; ++bj) {
-                    int32_t *row = g.epi.C + m_of[bj] * g.epi.ldc + n_blk + 4 * kg;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        i32x4 val;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            val[i] = (int32_t)(scale(acc_to_sum(acc[bi][bj][4 * q + i])) + nterm[4 * q + i] + mterm[bj]);
-                        if constexpr (kFast) {
-                            // 16-byte unit 2 q + kg of row r, swizzled with the row: neither this write nor the read
-                            // below puts two lanes of a pass on one LDS bank
-                            *reinterpret_cast<i32x4 *>(&stage[wave][r * 32 + 4 * ((2 * q + kg) ^ ((r >> 1) & 7))]) = val;
-                        } else if (m_of[bj] < g.M) {
-                            const int64_t n0 = n_blk + 8 * q + 4 * kg;
-#pragma unroll
-                            for (int i = 0; i < 4; ++i)
-                                if (n0 + i < g.N) row[8 * q + i] = val[i];
-                        }
-                    }
-                    if constexpr (kFast) {
-                        // read the block back as 8 rows x 128 bytes per instruction (LDS operations of a wave execute
-                        // in order; only the compiler has to be kept from reordering them) and store those lines one
-                        // block later, which hides the LDS round trip behind the next block's arithmetic
-                        __builtin_amdgcn_wave_barrier();
-                        i32x4 line[4];
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) {
-                            const int R = 8 * j + (lane >> 3);
-                            line[j] = *reinterpret_cast<const i32x4 *>(&stage[wave][R * 32 + 4 * ((lane & 7) ^ ((R >> 1) & 7))]);
-                        }
-                        __builtin_amdgcn_wave_barrier();
-                        if (bi + bj > 0) store_lines((bi * WB + bj - 1) / WB, (bi * WB + bj - 1) % WB);
-#pragma unroll
-                        for (int j = 0; j < 4; ++j) pend[j] = line[j];
-                    }
-                }
-            } else {
-                // e[v] = T - 1 - (part of C that depends on n only): C >= T  <=>  e[v] - (rest of C) < 0.  All terms
-                // are below 2^30 in magnitude (the host checks the bound of C, thresholds are clamped to it, which
-                // does not change any comparison), so the differences cannot wrap.
-                int32_t e[16];
-                uint32_t flips = 0, live_bits = 0;  // at the bit positions 8 (v / 4) + v mod 4 of the partial word
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int col = bi * 32 + 8 * q + 4 * kg;
-                    const int4 t4 = *reinterpret_cast<const int4 *>(&thr_table[wave][col]);
-                    const uint4 f4 = *reinterpret_cast<const uint4 *>(&flip_table[wave][col]);
-                    e[4 * q + 0] = t4.x - (int32_t)nterm[4 * q + 0], e[4 * q + 1] = t4.y - (int32_t)nterm[4 * q + 1];
-                    e[4 * q + 2] = t4.z - (int32_t)nterm[4 * q + 2], e[4 * q + 3] = t4.w - (int32_t)nterm[4 * q + 3];
-                    flips |= f4.x | f4.y | f4.z | f4.w;
-                }
-                if constexpr (kFast) {
-                    live_bits = 0x0F0F0F0Fu;
-                } else {
-#pragma unroll
-                    for (int v = 0; v < 16; ++v)
-                        if (n_blk + 8 * (v >> 2) + 4 * kg + (v & 3) < g.N) live_bits |= 1u << (8 * (v >> 2) + (v & 3));
-                }
-                const int64_t word = n_blk >> 5;
-#pragma unroll
-                for (int bj = 0; bj < WB; ++bj) {
-                    // four bits per group of consecutive n, most significant first: the sign bit of e[v] - (rest of
-                    // C) is appended with one funnel shift; flips and the n tail are applied to the whole word
-                    uint32_t bits = 0;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        uint32_t nib = 0;
-#pragma unroll
-                        for (int i = 3; i >= 0; --i) {
-                            const int v = 4 * q + i;
-                            const uint32_t rest = scale(acc_to_sum(acc[bi][bj][v])) + mterm[bj];
-                            const uint32_t x = (uint32_t)e[v] - rest;
-                            nib = __builtin_amdgcn_alignbit(nib, x, 31);  // (nib << 1) | (x >> 31)
-                        }
-                        bits |= nib << (8 * q);
-                    }
-                    bits = (bits ^ flips) & live_bits;
-                    bits <<= 4 * kg;
-                    bits = or_halves(bits);
-                    if (kg == 0 && (kFast || (m_of[bj] < g.M && word < Nw)))
-                        g.epi.out_bits[m_of[bj] * g.epi.ldo + word] = bits;
-                }
-            }
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        if constexpr (kFast && !kSign) store_lines(WBN - 1, WB - 1);
-    };
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
-        const bool interior = m_wave + WTILE <= g.M && n_wave + WTN <= g.N;
-        const bool wide = kSign || ((g.epi.ldc % 4 == 0) && (reinterpret_cast<uintptr_t>(g.epi.C) % 16 == 0));
-        const bool fast = interior && wide;
-        if (mc.alpha_shift >= 0) {
-            const int sh = mc.alpha_shift;
-            auto scale = [sh](uint32_t x) { return x << sh; };
-            if (fast)
-                epilogue(m_wave, n_wave, scale, std::true_type{});
-            else
-                epilogue(m_wave, n_wave, scale, std::false_type{});
-        } else {
-            const uint32_t al = mc.alpha;
-            auto scale = [al](uint32_t x) { return x * al; };
-            if (fast)
-                epilogue(m_wave, n_wave, scale, std::true_type{});
-            else
-                epilogue(m_wave, n_wave, scale, std::false_type{});
-        }
+        wave_finish<kSign, WBN, kLoadsPerGroup>(g, mc, acc, ra, rw, rw_table[wave], thr_table[wave], flip_table[wave],
+                                                stage[wave], m_wave, n_wave);
     };
 
     // workgroup barrier of the group buffers: this wave's loads to LDS have landed and its LDS reads have returned
+    // The group needed next was loaded kBuffers - 1 groups ago; the loads of the kBuffers - 2 groups after it may stay
+    // in flight (loads complete in order, so waiting until at most that many are outstanding means the older ones have
+    // landed).
+    constexpr int kPending = kLoadsPerGroup * (kBuffers - 2);
+    static_assert(kPending < 64, "vmcnt is a 6-bit counter");
     auto panel_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(kPending) : "memory");
+    };
+    auto first_barrier = [&]() __attribute__((always_inline)) {
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
     };
 
     // ------------------------------------------------------------------------------------------------ prologue
-    // groups 0 and 1 into the two buffers; the cursor stays at group 1
+    // the first groups into the buffers; the cursor stays at the last of them
     p_locate();
+#pragma unroll 1
+    for (int b = 0; b < kBuffers; ++b) {
+        if (b > 0) p_advance();
 #pragma unroll
-    for (int q = 0; q < 4; ++q) load_quarter(q, 0u);
-    p_advance();
-#pragma unroll
-    for (int q = 0; q < 4; ++q) load_quarter(q, (uint32_t)kGroupBytes);
-    panel_barrier();
+        for (int q = 0; q < 4; ++q) load_quarter(q, (uint32_t)(b * kGroupBytesT));
+    }
+    first_barrier();
 
     Step buf0, buf1;
     Frags frags;
@@ -472,7 +349,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 
     auto no_produce = [](auto) __attribute__((always_inline)) {};
     // Fourth step of a group (after the barrier, the buffer just consumed is free): phase t starts the loads of
-    // quarter t of the group after the next into it.
+    // quarter t of the group kBuffers groups ahead into it.
     auto produce = [&](auto t_tag) __attribute__((always_inline)) {
         constexpr int tt = decltype(t_tag)::value;
         load_quarter(tt, rd);
@@ -487,7 +364,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         // one group of four steps; kLastGroup: its last step ends the tile
         auto group = [&](auto last_tag) __attribute__((always_inline)) {
             constexpr bool kLastGroup = decltype(last_tag)::value;
-            const uint32_t other = (uint32_t)kGroupBytes - rd;
+            const uint32_t other = rd + kGroupBytesT == kBuffers * kGroupBytesT ? 0u : rd + (uint32_t)kGroupBytesT;
             // the cursor moves on to the group that this group's fourth step will load (scalar control flow: kept at
             // the head of the group, so that the phases of a step stay one straight-line block)
             p_advance();

@@ -68,6 +68,12 @@ struct GemmArgs {
     Epilogue epi;
     int64_t M, N, K;  // K = true number of elements per row (not words)
     int64_t Kw;       // words per row = ceil(K/32) (for pixels: KH*KW*Cw)
+    // Optional, with a left operand of uint8 codes only: the +-1 weights expanded to one int8 per element (row pitch
+    // ld_w_bytes, a multiple of 128, zeros beyond K) and 128 * (sum of the weights of row n), both written by
+    // bytes_panel::launch_expand_weights earlier on the same stream.  Null: the kernels expand the packed bits.
+    const int8_t *w_bytes;
+    int64_t ld_w_bytes;
+    const int32_t *rw_scaled;
 };
 
 // Tile index with consecutive ids of one XCD (ids congruent mod 8 share an L2) laid on neighbouring tiles, and tiles
@@ -100,6 +106,12 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4 = false);
 bool stage_supports(const GemmArgs &g);
 int launch_gemm_stage(const GemmArgs &g, hipStream_t s);
 
+// Expansion of packed +-1 weights (N rows of K elements) to one int8 per element (row pitch ld_out, a multiple of 128,
+// zeros beyond K) and rw_scaled[n] = 128 * (sum of the weights of row n): operands of the uint8-input kernel.
+namespace bytes_panel {
+int launch_expand_weights(const uint32_t *W, int64_t N, int64_t K, int64_t ldw, int8_t *out, int64_t ld_out, int32_t *rw_scaled,
+                          hipStream_t s);
+}
 int launch_pack_sign(const float *x, int64_t rows, int64_t K, int64_t ldx, uint32_t *out, int64_t ldo, hipStream_t s);
 int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv, int nbits, uint32_t *planes,
                           int64_t ld, int64_t plane_stride, hipStream_t s);
