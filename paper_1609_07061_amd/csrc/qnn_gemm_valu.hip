@@ -233,38 +233,67 @@ __global__ __launch_bounds__(kThreads) void gemm_valu_kernel(const GemmArgs g, u
 // reads.  Sign x sign single planes, int32 output.
 constexpr int kSkinnyMaxN = 16;
 constexpr int kSkinnyRows = 64;
+constexpr int kSkinnyThreads = 4 * kSkinnyRows;
 constexpr int kSkinnyChunk = 128;  // words per staged chunk
-__global__ __launch_bounds__(kThreads) void gemm_skinny_kernel(const GemmArgs g) {
+__global__ __launch_bounds__(kSkinnyThreads) void gemm_skinny_kernel(const GemmArgs g) {
     constexpr int kPitchA = kSkinnyChunk + 4;  // keeps 16-byte alignment, spreads rows over the banks
     __shared__ __attribute__((aligned(16))) uint32_t sA[kSkinnyRows][kPitchA];
-    __shared__ __attribute__((aligned(16))) uint32_t sWt[kSkinnyChunk][kSkinnyMaxN];  // [word][neuron]
+    __shared__ __attribute__((aligned(16))) uint32_t sW[kSkinnyMaxN][kPitchA];
     const int t = threadIdx.x, row = t >> 2, grp = t & 3;
     const int64_t m0 = (int64_t)blockIdx.x * kSkinnyRows;
     const int Kw = (int)g.Kw;
     uint32_t cnt[4] = {0u, 0u, 0u, 0u};
+    // rows made of whole, aligned 16-byte pieces are staged with 16-byte loads
+    const bool wide = Kw % 4 == 0 && g.A.ld % 4 == 0 && g.ldw % 4 == 0 && reinterpret_cast<uintptr_t>(g.A.base) % 16 == 0 &&
+                      reinterpret_cast<uintptr_t>(g.W) % 16 == 0;
     for (int k0 = 0; k0 < Kw; k0 += kSkinnyChunk) {
-        // stage: consecutive threads take consecutive words of a row (rows and words past the ends read as zero)
-        for (int i = t; i < kSkinnyRows * kSkinnyChunk; i += kThreads) {
-            const int rr = i / kSkinnyChunk, j = i - rr * kSkinnyChunk;
-            const int64_t m = m0 + rr;
-            sA[rr][j] = (m < g.M && k0 + j < Kw) ? g.A.base[m * g.A.ld + k0 + j] : 0u;
-        }
-        for (int i = t; i < kSkinnyMaxN * kSkinnyChunk; i += kThreads) {
-            const int n = i / kSkinnyChunk, j = i - n * kSkinnyChunk;
-            sWt[j][n] = (n < g.N && k0 + j < Kw) ? g.W[(int64_t)n * g.ldw + k0 + j] : 0u;
+        // stage: consecutive threads take consecutive words of a row (rows and words past the ends read as zero).  All
+        // loads of a thread are issued before the first LDS store, so that their latencies overlap.
+        if (wide) {
+            uint4 va[kSkinnyRows * kSkinnyChunk / 4 / kSkinnyThreads], vw[kSkinnyMaxN * kSkinnyChunk / 4 / kSkinnyThreads];
+#pragma unroll
+            for (int u = 0; u < kSkinnyRows * kSkinnyChunk / 4 / kSkinnyThreads; ++u) {
+                const int i = t + u * kSkinnyThreads, rr = i / (kSkinnyChunk / 4), j = 4 * (i % (kSkinnyChunk / 4));
+                const int64_t m = m0 + rr;
+                va[u] = (m < g.M && k0 + j < Kw) ? *reinterpret_cast<const uint4 *>(&g.A.base[m * g.A.ld + k0 + j]) : make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int u = 0; u < kSkinnyMaxN * kSkinnyChunk / 4 / kSkinnyThreads; ++u) {
+                const int i = t + u * kSkinnyThreads, n = i / (kSkinnyChunk / 4), j = 4 * (i % (kSkinnyChunk / 4));
+                vw[u] = (n < g.N && k0 + j < Kw) ? *reinterpret_cast<const uint4 *>(&g.W[(int64_t)n * g.ldw + k0 + j]) : make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (int u = 0; u < kSkinnyRows * kSkinnyChunk / 4 / kSkinnyThreads; ++u) {
+                const int i = t + u * kSkinnyThreads, rr = i / (kSkinnyChunk / 4), j = 4 * (i % (kSkinnyChunk / 4));
+                *reinterpret_cast<uint4 *>(&sA[rr][j]) = va[u];
+            }
+#pragma unroll
+            for (int u = 0; u < kSkinnyMaxN * kSkinnyChunk / 4 / kSkinnyThreads; ++u) {
+                const int i = t + u * kSkinnyThreads, n = i / (kSkinnyChunk / 4), j = 4 * (i % (kSkinnyChunk / 4));
+                *reinterpret_cast<uint4 *>(&sW[n][j]) = vw[u];
+            }
+        } else {
+            for (int i = t; i < kSkinnyRows * kSkinnyChunk; i += kSkinnyThreads) {
+                const int rr = i / kSkinnyChunk, j = i - rr * kSkinnyChunk;
+                const int64_t m = m0 + rr;
+                sA[rr][j] = (m < g.M && k0 + j < Kw) ? g.A.base[m * g.A.ld + k0 + j] : 0u;
+            }
+            for (int i = t; i < kSkinnyMaxN * kSkinnyChunk; i += kSkinnyThreads) {
+                const int n = i / kSkinnyChunk, j = i - n * kSkinnyChunk;
+                sW[n][j] = (n < g.N && k0 + j < Kw) ? g.W[(int64_t)n * g.ldw + k0 + j] : 0u;
+            }
         }
         __syncthreads();
 #pragma unroll 2
         for (int j = 0; j < kSkinnyChunk; j += 4) {
             const uint4 a = *reinterpret_cast<const uint4 *>(&sA[row][j]);
-            const uint32_t aw[4] = {a.x, a.y, a.z, a.w};
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) {
-                const uint4 w = *reinterpret_cast<const uint4 *>(&sWt[j + jj][grp * 4]);
-                cnt[0] += __builtin_popcount(aw[jj] ^ w.x);
-                cnt[1] += __builtin_popcount(aw[jj] ^ w.y);
-                cnt[2] += __builtin_popcount(aw[jj] ^ w.z);
-                cnt[3] += __builtin_popcount(aw[jj] ^ w.w);
+            for (int c = 0; c < 4; ++c) {
+                // (the threads of a wave that share a neuron group read the same address; the four groups fall on
+                // different banks)
+                const uint4 w = *reinterpret_cast<const uint4 *>(&sW[grp * 4 + c][j]);
+                cnt[c] += __builtin_popcount(a.x ^ w.x) + __builtin_popcount(a.y ^ w.y) + __builtin_popcount(a.z ^ w.z) +
+                          __builtin_popcount(a.w ^ w.w);
             }
         }
         __syncthreads();
@@ -317,7 +346,7 @@ int launch_gemm_valu(const GemmArgs &g, hipStream_t s) {
     const bool big = ceil_div(g.M, 128) * ceil_div(g.N, 128) >= 512;
     if (!pixels && !sign && g.N <= kSkinnyMaxN && g.M >= 256 && g.pa.count == 1 && g.pw.count == 1 &&
         g.pa.mode == QNN_PLANE_SIGN && g.pw.mode == QNN_PLANE_SIGN && ceil_div(g.M, kSkinnyRows) <= 0x7FFFFFFFLL) {
-        return QNN_LAUNCH("gemm_skinny", gemm_skinny_kernel, dim3((unsigned)ceil_div(g.M, kSkinnyRows)), dim3(kThreads), 0, s, g);
+        return QNN_LAUNCH("gemm_skinny", gemm_skinny_kernel, dim3((unsigned)ceil_div(g.M, kSkinnyRows)), dim3(kSkinnyThreads), 0, s, g);
     }
     if (pixels) {
         if (sign) return big ? launch_modes<8, 8, true, true>(g, s) : launch_modes<4, 4, true, true>(g, s);
