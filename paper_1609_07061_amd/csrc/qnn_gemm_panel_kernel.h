@@ -231,20 +231,49 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t a = word_of(c.A[b], j);
-                f.a[b][j] = (int)((tt == 3 ? a >> 2 : a) & mask);
-            }
+            for (int j = 0; j < 4; ++j) f.a[b][j] = (int)(word_of(c.A[b], j) & mask);
 #pragma unroll
             for (int j = 4; j < 8; ++j) f.a[b][j] = 0;
         }
 #pragma unroll
         for (int b = 0; b < WBN; ++b) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t w = word_of(c.W[b], j);
-                f.w[b][j] = (int)((tt == 3 ? w >> 2 : w) & mask);
-            }
+            for (int j = 0; j < 4; ++j) f.w[b][j] = (int)(word_of(c.W[b], j) & mask);
+#pragma unroll
+            for (int j = 4; j < 8; ++j) f.w[b][j] = 0;
+        }
+    };
+    // Bit 3 of a nibble takes two instructions per word (shift, mask).  The shifts are spread over the three phases
+    // before the one that needs them (word number idx of the step in phase idx mod 3), so that every phase carries about
+    // the same number of vector-ALU instructions: a phase that carries more than its matrix-core instructions cover
+    // stalls the one wave of the SIMD.
+    struct Shifted {
+        uint32_t a[WB][4], w[WBN][4];
+    };
+    auto shift_part = [&](const Step &c, const int part, Shifted &sh) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < WB; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((b * 4 + j) % 3 == part) sh.a[b][j] = word_of(c.A[b], j) >> 2;
+#pragma unroll
+        for (int b = 0; b < WBN; ++b)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                if ((WB * 4 + b * 4 + j) % 3 == part) sh.w[b][j] = word_of(c.W[b], j) >> 2;
+    };
+    auto expand_shifted = [&](const Shifted &sh, Frags &f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int b = 0; b < WB; ++b) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f.a[b][j] = (int)(sh.a[b][j] & 0x22222222u);
+#pragma unroll
+            for (int j = 4; j < 8; ++j) f.a[b][j] = 0;
+        }
+#pragma unroll
+        for (int b = 0; b < WBN; ++b) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) f.w[b][j] = (int)(sh.w[b][j] & 0x22222222u);
 #pragma unroll
             for (int j = 4; j < 8; ++j) f.w[b][j] = 0;
         }
@@ -281,19 +310,27 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     auto compute = [&](const Step &c, const Step &n, Frags &f, auto issue_fetch, auto produce,
                        auto last_tag) __attribute__((always_inline)) {
         constexpr bool kLastStep = decltype(last_tag)::value;
+        Shifted sh;
         auto phase = [&](auto t_tag) __attribute__((always_inline)) {
             constexpr int tt = decltype(t_tag)::value;
             if (tt == 0) issue_fetch();
             produce(t_tag);
             Frags gnext;
-            count(c, tt);
-            if (tt + 1 < 4)
+            // counts: word t in phases 0, 1 and 3; word 2 in phase 3 as well (phase 2 carries shifts instead)
+            if (tt != 2) count(c, tt);
+            if (tt == 3) count(c, 2);
+            if (tt < 3) shift_part(c, tt, sh);
+            if (tt + 1 < 3)
                 expand(c, tt + 1, gnext);
+            else if (tt == 2)
+                expand_shifted(sh, gnext);
             else if (!kLastStep)
                 expand(n, 0, gnext);
             multiply(f, t_tag);
-            // vector-ALU instructions of this phase: operands of the next one (4 per row, 8 for bit 3) and the counts
-            constexpr int kOps = (WB + WBN) * ((tt == 2 ? 8 : 4) + 1);
+            // vector-ALU instructions of this phase: 4 masks per row, its share of the shifts and of the counts
+            constexpr int kRows = WB + WBN;
+            constexpr int kShifts = tt < 3 ? (4 * kRows + 2 - tt) / 3 : 0;
+            constexpr int kOps = kRows * 4 + kShifts + (tt == 2 ? 0 : (tt == 3 ? 2 * kRows : kRows));
             if (tt == 0)
                 phase_groups<kOps + 8, WB + WBN, 0, 0>(std::make_integer_sequence<int, kMfma>{});
             else
