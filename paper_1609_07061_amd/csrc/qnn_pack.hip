@@ -4,6 +4,7 @@
 // 64-wide wave owns element 64*c + l of the wave's chunk, so one ballot yields two finished 32-bit words.  Long aligned
 // float rows have a second sign+pack kernel that loads 16 bytes per lane and combines nibbles across lanes instead.
 #include "qnn_internal.h"
+#include "qnn_bitsplit.h"
 
 namespace qnn {
 
@@ -181,22 +182,6 @@ __global__ __launch_bounds__(kBlock) void pack_bitplanes_vec4_kernel(const uint8
 // 4 x 4 blocks between the two dwords; 21 instructions), after which byte p holds bit p of the eight codes; byte
 // permutes then collect byte p of the four groups into the word of plane p (two per word).  About 100 instructions
 // per 32 codes and eight planes (extracting plane by plane with masks and shifts takes 320 and was the bound).
-__device__ __forceinline__ void transpose_8x8_bits(uint32_t &lo, uint32_t &hi) {
-    uint32_t t;
-    t = (lo ^ (lo >> 7)) & 0x00AA00AAu, lo = lo ^ t ^ (t << 7);
-    t = (hi ^ (hi >> 7)) & 0x00AA00AAu, hi = hi ^ t ^ (t << 7);
-    t = (lo ^ (lo >> 14)) & 0x0000CCCCu, lo = lo ^ t ^ (t << 14);
-    t = (hi ^ (hi >> 14)) & 0x0000CCCCu, hi = hi ^ t ^ (t << 14);
-    t = (lo ^ __builtin_amdgcn_alignbit(hi, lo, 28)) & 0xF0F0F0F0u;  // (hi:lo) >> 28
-    lo ^= t, hi ^= t >> 4;
-}
-// r[g] byte p = plane byte p of group g  ->  w[p] byte g
-__device__ __forceinline__ void transpose_4x4_bytes(const uint32_t (&r)[4], uint32_t (&w)[4]) {
-    const uint32_t t01 = __builtin_amdgcn_perm(r[1], r[0], 0x05010400u), u01 = __builtin_amdgcn_perm(r[1], r[0], 0x07030602u);
-    const uint32_t t23 = __builtin_amdgcn_perm(r[3], r[2], 0x05010400u), u23 = __builtin_amdgcn_perm(r[3], r[2], 0x07030602u);
-    w[0] = __builtin_amdgcn_perm(t23, t01, 0x05040100u), w[1] = __builtin_amdgcn_perm(t23, t01, 0x07060302u);
-    w[2] = __builtin_amdgcn_perm(u23, u01, 0x05040100u), w[3] = __builtin_amdgcn_perm(u23, u01, 0x07060302u);
-}
 __global__ __launch_bounds__(kBlock) void pack_bitplanes_word_kernel(const uint8_t *__restrict__ v, int64_t rows,
                                                                      int64_t K, int64_t ldv, int nbits,
                                                                      uint32_t *__restrict__ planes, int64_t ld,

@@ -8,6 +8,9 @@
 // the precision the definition names: x / step correctly rounded in single precision and rounded to the nearest
 // integer with ties to even; round(log2 |x|) from the float's exponent and a comparison of its mantissa with sqrt(2)
 // (2^(e + 1/2) is irrational, so the comparison with the float below sqrt(2) decides exactly).
+#include <cmath>
+
+#include "qnn_bitsplit.h"
 #include "qnn_internal.h"
 
 namespace qnn {
@@ -25,11 +28,14 @@ unsigned grid_for_chunks(int64_t chunks) {
 }
 
 // LinearQuant(x, step) = Clip(round(x / step) * step, minV, maxV) as the integer code q = value / step.
+// inv: 1 / step where the step is a power of two (the product x * inv is then the same correctly rounded value as the
+// quotient: both round the exact real x / step once), else 0.
 struct LinearQ {
-    float step;
+    float step, inv;
     int32_t qmin, qmax;
     __device__ __forceinline__ int32_t operator()(float x) const {
-        float r = rintf(__fdiv_rn(x, step));  // correctly rounded quotient, nearest integer with ties to even
+        // correctly rounded quotient, then the nearest integer with ties to even
+        float r = rintf(inv != 0.0f ? __fmul_rn(x, inv) : __fdiv_rn(x, step));
         if (r != r) r = 0.0f;                 // NaN quantizes like 0
         return r <= (float)qmin ? qmin : (r >= (float)qmax ? qmax : (int32_t)r);
     }
@@ -112,9 +118,80 @@ __global__ __launch_bounds__(kBlock) void quant_planes_kernel(const float *__res
     }
 }
 
+// Rows made of whole, 16-byte aligned groups of four floats: a wave takes 2048 consecutive elements of a row.  Lane l
+// loads four consecutive floats of each of eight 1 KiB pieces (whole lines per load), quantizes them and leaves the
+// four codes as one dword in a wave-private LDS area; then it reads back the 32 consecutive codes of "its" output
+// word and splits them into planes by bit-matrix transposition (about 3 instructions per element and eight planes,
+// where one ballot per plane and 64 elements costs four per element and plane).  LDS operations of a wave execute in
+// order, so only the compiler has to be kept from reordering the two passes.
+template <typename Q>
+__global__ __launch_bounds__(kBlock) void quant_planes_vec_kernel(const float *__restrict__ x, const float *__restrict__ gate,
+                                                                  int64_t rows, int64_t K, int64_t ldx, int64_t ldg, Q q,
+                                                                  int nbits, uint32_t *__restrict__ planes, int64_t ld,
+                                                                  int64_t plane_stride, int64_t chunks_per_row,
+                                                                  int64_t total_chunks) {
+    constexpr int kChunk = 2048;
+    __shared__ __attribute__((aligned(16))) uint32_t codes[kWavesPerBlock][kChunk / 4];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int64_t wave0 = (int64_t)blockIdx.x * kWavesPerBlock + wave;
+    const int64_t wave_stride = (int64_t)gridDim.x * kWavesPerBlock;
+    const int64_t Kw = (K + 31) / 32;
+    typedef float f32x4 __attribute__((ext_vector_type(4)));
+    for (int64_t chunk = wave0; chunk < total_chunks; chunk += wave_stride) {
+        const int64_t r = chunk / chunks_per_row;
+        const int64_t k0 = (chunk - r * chunks_per_row) * kChunk;
+        f32x4 v[8], gt[8];
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const int64_t k = k0 + c * 256 + 4 * lane;  // K is a multiple of 4: a group is all inside or outside
+            v[c] = f32x4{0.0f, 0.0f, 0.0f, 0.0f}, gt[c] = f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+            if (k < K) v[c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(x + r * ldx + k));
+            if (gate && k < K) gt[c] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(gate + r * ldg + k));
+        }
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+            const int64_t k = k0 + c * 256 + 4 * lane;
+            uint32_t four = 0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                int32_t cd = q(v[c][i]);
+                if (!(fabsf(gt[c][i]) <= 1.0f)) cd = 0;
+                four |= ((uint32_t)cd & 0xFFu) << (8 * i);
+            }
+            codes[wave][c * 64 + lane] = (k < K) ? four : 0u;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint4 c0 = *reinterpret_cast<const uint4 *>(&codes[wave][8 * lane]);
+        const uint4 c1 = *reinterpret_cast<const uint4 *>(&codes[wave][8 * lane + 4]);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t mine[8] = {c0.x, c0.y, c0.z, c0.w, c1.x, c1.y, c1.z, c1.w};
+        uint32_t word[8];
+        split_32_codes(mine, nbits, word);
+        const int64_t w = k0 / 32 + lane;
+        if (w < Kw) {
+            uint32_t *dst = planes + r * ld + w;
+#pragma unroll
+            for (int p = 0; p < 8; ++p)
+                if (p < nbits) dst[p * plane_stride] = word[p];
+        }
+    }
+}
+
 template <typename Q>
 int launch_quant(const char *what, const float *x, const float *gate, int64_t rows, int64_t K, int64_t ldx, int64_t ldg,
                  const Q &q, int nbits, uint32_t *planes, int64_t ld, int64_t plane_stride, hipStream_t s) {
+    const bool vec = K >= 1024 && K % 4 == 0 && ldx % 4 == 0 && reinterpret_cast<uintptr_t>(x) % 16 == 0 &&
+                     (!gate || (ldg % 4 == 0 && reinterpret_cast<uintptr_t>(gate) % 16 == 0));
+    if (vec) {
+        const int64_t cpr = ceil_div(K, (int64_t)2048);
+        const int64_t total = rows * cpr;
+        return QNN_LAUNCH(what, (quant_planes_vec_kernel<Q>), dim3(grid_for_chunks(total)), dim3(kBlock), 0, s, x, gate, rows, K, ldx,
+                          ldg, q, nbits, planes, ld, plane_stride, cpr, total);
+    }
     constexpr int kUnroll = 8;
     const int64_t cpr = ceil_div(K, (int64_t)kUnroll * kWave);
     const int64_t total = rows * cpr;
@@ -167,6 +244,14 @@ __global__ __launch_bounds__(kBlock) void transpose_bits_kernel(const uint32_t *
     }
 }
 
+// 1 / step if step is a normal power of two whose inverse is normal too, else 0
+float pow2_inverse(float step) {
+    int e = 0;
+    const float m = std::frexp(step, &e);  // step = m 2^e, 0.5 <= |m| < 1
+    if (!(m == 0.5f || m == -0.5f) || e < -120 || e > 120) return 0.0f;
+    return 1.0f / step;
+}
+
 bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
 
 int launch_transpose(const uint32_t *in, int64_t rows, int64_t cols, int64_t ld_in, int64_t in_plane_stride, int nplanes,
@@ -207,7 +292,7 @@ extern "C" int qnn_linear_quant_planes(const float *x, int64_t rows, int64_t K, 
     const bool fits = qmin >= 0 ? (int64_t)qmax < lim : ((int64_t)qmin >= -(lim / 2) && (int64_t)qmax < lim / 2);
     if (!fits) return fail(QNN_ERR_SHAPE, "linear_quant_planes: codes %d..%d do not fit %d bits", qmin, qmax, nbits);
     if (rows == 0) return QNN_OK;
-    return launch_quant("linear_quant_planes", x, nullptr, rows, K, ldx, 0, LinearQ{step, qmin, qmax}, nbits, planes, ld_words,
+    return launch_quant("linear_quant_planes", x, nullptr, rows, K, ldx, 0, LinearQ{step, pow2_inverse(step), qmin, qmax}, nbits, planes, ld_words,
                         plane_stride_words, static_cast<hipStream_t>(stream));
 }
 

@@ -44,7 +44,8 @@ def edge_floats(seed, stream, shape, scale):
     return x
 
 
-@pytest.mark.parametrize("rows,K", [(1, 1), (3, 31), (5, 64), (7, 65), (4, 300), (9, 1000), (33, 4099)])
+@pytest.mark.parametrize("rows,K", [(1, 1), (3, 31), (5, 64), (7, 65), (4, 300), (9, 1000), (33, 4099), (5, 1024), (3, 2048),
+                                     (33, 4100), (2, 6148)])
 @pytest.mark.parametrize("step,qmin,qmax,nbits", [(0.25, -8, 7, 4), (1.0, 0, 3, 2), (0.1, 0, 15, 4), (1.0 / 3.0, -2, 1, 2),
                                                  (0.05, -128, 127, 8), (0.5, 0, 255, 8), (2.0, 0, 1, 1)])
 def test_linear_quant_planes(seed, rows, K, step, qmin, qmax, nbits):
@@ -76,7 +77,7 @@ def test_linear_quant_planes_strided_and_padding(seed):
     assert (got[:, :, 3:] == 0x5A5A5A5A).all()
 
 
-@pytest.mark.parametrize("rows,K", [(1, 1), (3, 33), (5, 64), (4, 300), (17, 2051)])
+@pytest.mark.parametrize("rows,K", [(1, 1), (3, 33), (5, 64), (4, 300), (17, 2051), (5, 1024), (9, 2052), (3, 6144)])
 @pytest.mark.parametrize("emin,emax,nbits", [(-3, 2, 4), (-6, 0, 4), (-10, 4, 5), (0, 0, 2), (-126, -120, 4), (-20, 10, 6)])
 def test_log_quant_planes_codes(seed, rows, K, emin, emax, nbits):
     x = edge_floats(seed, 2100, (rows, K), 2.0 ** ((emin + emax) // 2))
@@ -85,9 +86,9 @@ def test_log_quant_planes_codes(seed, rows, K, emin, emax, nbits):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("rows,K", [(9, 333), (7, 2060)])  # the second shape takes the 16-byte-load kernel
 @pytest.mark.parametrize("emin,emax,nbits", [(-3, 2, 8), (-6, 0, 8), (-2, 0, 4), (0, 0, 2)])
-def test_log_quant_planes_values_and_gate(seed, emin, emax, nbits):
-    rows, K = 9, 333
+def test_log_quant_planes_values_and_gate(seed, emin, emax, nbits, rows, K):
     g = edge_floats(seed, 2200, (rows, K), 2.0 ** emax / 4)
     a = qi.with_special_floats(qi.normal_f32(seed, 2210, (rows, K)), seed, 2211)
     a.reshape(-1)[:6] = [1.0, -1.0, 1.0000001, -1.0000001, 0.0, 0.99999994]
