@@ -381,6 +381,19 @@ def main():
 
         jobs.append((4, job_bw))
 
+    def job_valu_probe():
+        # the vector-ALU rate that the 1258 TOP/s peak of the xor + popcount engine assumes, measured: sixteen
+        # register-resident {xor, popcount-accumulate} pairs per lane and iteration on every SIMD of the chip
+        blocks, iters = 256 * 32, 4096
+        sink = torch.empty((blocks * 256,), dtype=torch.int32, device="cuda")
+        ms = time_secondary(lambda: q.qnn_probe_valu_peak(sink, blocks, iters), 10, 3)
+        tops = 2.0 * blocks * 256 * iters * 16 * 32 / (ms * 1e-3) / 1e12
+        extra["valu_xor_popcount_probe"] = {"ms": ms, "TOPS": tops, "assumed_peak_TOPS": VALU_PEAK_TOPS,
+                                            "frac_of_assumed_peak": tops / VALU_PEAK_TOPS}
+
+    if "c1" in only:
+        jobs.append((0, job_valu_probe))
+
     # ================================================================ GPU work, back to back
     primary = {}
 

@@ -313,6 +313,12 @@ int qnn_probe_shader_clock(unsigned long long *out3, void *stream);
  * one stream, taken on the same die, give the average shader clock over that stretch. */
 int qnn_stamp_clocks(unsigned long long *out3, void *stream);
 
+/* Measurement helper: the rate of the vector ALU on the inner product of the vector-ALU engine (Sec. 6, Eq. (popc):
+ * one xor and one popcount-accumulate per 32 connections) with all operands in registers.  `blocks` workgroups of 256
+ * lanes run `iterations` times sixteen such pairs per lane, i.e. blocks * 256 * iterations * 16 * 32 MACs; sink
+ * (DEVICE, blocks * 256 uint32) receives one checksum per lane.  The caller times the launch.  blocks in 1 .. 65536. */
+int qnn_probe_valu_peak(uint32_t *sink, int64_t blocks, uint32_t iterations, void *stream);
+
 const char *qnn_last_error(void);
 const char *qnn_version(void);
 

@@ -42,6 +42,7 @@ _SIGS = {
     "qnn_threshold_sign": [_vp, _i64, _i64, _i64, _vp, _vp, _vp, _i64, _vp],
     "qnn_probe_shader_clock": [_vp, _vp],
     "qnn_stamp_clocks": [_vp, _vp],
+    "qnn_probe_valu_peak": [_vp, C.c_int64, C.c_uint32, _vp],
     "qnn_fold_batchnorm": [_vp, _vp, _vp, _vp, C.c_double, _i64, _vp, _vp],
     "qnn_binary_mlp_forward": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp],
     "qnn_binary_mlp_forward_ex": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _int, _vp],
@@ -158,6 +159,13 @@ def qnn_probe_shader_clock() -> float:
 def qnn_stamp_clocks(out: torch.Tensor) -> None:
     """Enqueues a stamp {shader-clock counter, 100 MHz counter, die id} into out (int64[3] on the GPU)."""
     _check(_lib.qnn_stamp_clocks(_dev(out, torch.int64, "out"), _stream()))
+
+
+def qnn_probe_valu_peak(sink: torch.Tensor, blocks: int, iterations: int) -> None:
+    """Enqueues the register-resident xor + popcount kernel: blocks * 256 * iterations * 16 * 32 MACs."""
+    if sink.numel() < blocks * 256:
+        raise ValueError("sink needs blocks * 256 elements")
+    _check(_lib.qnn_probe_valu_peak(_dev(sink, torch.int32, "sink"), int(blocks), int(iterations), _stream()))
 
 
 def average_shader_clock_mhz(stamp0: torch.Tensor, stamp1: torch.Tensor) -> Optional[float]:

@@ -37,6 +37,26 @@ __global__ __launch_bounds__(64) void clock_stamp_kernel(unsigned long long *out
     }
 }
 
+// Every lane keeps sixteen packed words in registers and, per iteration, counts their disagreements with one more
+// word: sixteen independent {xor, popcount-accumulate} pairs, the inner product of the vector-ALU engine (Sec. 6,
+// Eq. (popc)) without any memory traffic.  The word is made opaque once per iteration so that the pairs are not hoisted
+// out of the loop.  One dword per lane leaves the kernel (the sum of the counts).
+__global__ __launch_bounds__(256) void valu_peak_kernel(uint32_t *sink, uint32_t iterations) {
+    uint32_t a[16], cnt[16];
+    uint32_t w = threadIdx.x * 2654435761u + blockIdx.x;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) a[j] = w * (2u * j + 3u), cnt[j] = 0u;
+    for (uint32_t i = 0; i < iterations; ++i) {
+        asm volatile("" : "+v"(w));
+#pragma unroll
+        for (int j = 0; j < 16; ++j) cnt[j] += __builtin_popcount(a[j] ^ w);
+    }
+    uint32_t total = 0;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) total += cnt[j];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = total;
+}
+
 }  // namespace
 }  // namespace qnn
 
@@ -53,4 +73,12 @@ extern "C" int qnn_stamp_clocks(unsigned long long *out3, void *stream) {
     if (!out3) return fail(QNN_ERR_NULL, "stamp_clocks: NULL pointer");
     if (reinterpret_cast<uintptr_t>(out3) & 7u) return fail(QNN_ERR_ALIGN, "stamp_clocks: pointer not 8-byte aligned");
     return QNN_LAUNCH("clock_stamp", clock_stamp_kernel, dim3(1), dim3(64), 0, static_cast<hipStream_t>(stream), out3);
+}
+
+extern "C" int qnn_probe_valu_peak(uint32_t *sink, int64_t blocks, uint32_t iterations, void *stream) {
+    using namespace qnn;
+    if (!sink) return fail(QNN_ERR_NULL, "probe_valu_peak: NULL pointer");
+    if (blocks <= 0 || blocks > 65536) return fail(QNN_ERR_SHAPE, "probe_valu_peak: blocks must lie in 1 .. 65536");
+    return QNN_LAUNCH("valu_peak", valu_peak_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), sink,
+                      iterations);
 }
