@@ -31,6 +31,7 @@ namespace qnn {
 namespace panel {
 
 using mfma::v16f;
+using mfma::v4i;
 using mfma::v8i;
 
 constexpr int kThreads = 256;
@@ -218,9 +219,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
                 for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
         }
     };
+    // An E2M1 operand of the instruction is four registers; the builtin's operand type has eight, of which the upper
+    // four are left undefined (the instruction does not read them in this format), so that they occupy nothing.
     struct Frags {
-        v8i a[WB], w[WBN];
+        v4i a[WB], w[WBN];
     };
+    auto widen = [](const v4i &x) __attribute__((always_inline)) { return __builtin_shufflevector(x, x, 0, 1, 2, 3, -1, -1, -1, -1); };
     // Phase t of a step multiplies bit t of every nibble of the lane's four words (32 of its 128 elements of k; both
     // operands use the same order).  An E2M1 nibble with only bit 0 set is 0.5, with bit 1 set 1.0, with bit 2 set 2.0,
     // so for t = 0, 1, 2 one AND per word makes the operand and the block scale of the instruction (2, 1, 1/2 on
@@ -232,15 +236,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) f.a[b][j] = (int)(word_of(c.A[b], j) & mask);
-#pragma unroll
-            for (int j = 4; j < 8; ++j) f.a[b][j] = 0;
         }
 #pragma unroll
         for (int b = 0; b < WBN; ++b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) f.w[b][j] = (int)(word_of(c.W[b], j) & mask);
-#pragma unroll
-            for (int j = 4; j < 8; ++j) f.w[b][j] = 0;
         }
     };
     // Bit 3 of a nibble takes two instructions per word (shift, mask).  The shifts are spread over the three phases
@@ -267,15 +267,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) f.a[b][j] = (int)(sh.a[b][j] & 0x22222222u);
-#pragma unroll
-            for (int j = 4; j < 8; ++j) f.a[b][j] = 0;
         }
 #pragma unroll
         for (int b = 0; b < WBN; ++b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) f.w[b][j] = (int)(sh.w[b][j] & 0x22222222u);
-#pragma unroll
-            for (int j = 4; j < 8; ++j) f.w[b][j] = 0;
         }
     };
     // row sums of the raw bits: one word of every row per phase.  Each sum is made opaque after its addition: left
@@ -301,7 +297,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         for (int i = 0; i < WBN; ++i)
 #pragma unroll
             for (int j = 0; j < WB; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(f.w[i], f.a[j], acc[i][j], 4, 4, tt, scales, tt, scales);
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(f.w[i]), widen(f.a[j]), acc[i][j], 4, 4, tt, scales, tt, scales);
     };
     // One step = four phases; each phase multiplies the operands made during the previous one and meanwhile counts
     // one word per row and makes the next phase's operands.  `issue_fetch` (the LDS reads of the following step) runs
