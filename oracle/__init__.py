@@ -14,13 +14,18 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qnn_oracle.c")
-_SO = os.path.join(_HERE, "libqnn_oracle.so")
+# QNN_ORACLE_SANITIZE=1: a second build with the undefined-behaviour sanitizer (signed overflow, shifts, bounds of
+# arrays with known size, alignment), every finding fatal; `QNN_ORACLE_SANITIZE=1 pytest tests -m "not gpu"` runs the
+# pins on it.  (The address sanitizer would have to be preloaded into the interpreter and is not used.)
+_SANITIZE = os.environ.get("QNN_ORACLE_SANITIZE", "") not in ("", "0")
+_SO = os.path.join(_HERE, "libqnn_oracle_ubsan.so" if _SANITIZE else "libqnn_oracle.so")
 
 
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc (plain C, OpenMP over output rows)."""
     if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        cmd = ["gcc", "-std=c11", "-O3", "-march=native", "-fopenmp", "-fno-fast-math", "-shared", "-fPIC",
+        opt = ["-O1", "-g", "-fsanitize=undefined", "-fno-sanitize-recover=all"] if _SANITIZE else ["-O3", "-march=native"]
+        cmd = ["gcc", "-std=c11", *opt, "-fopenmp", "-fno-fast-math", "-shared", "-fPIC",
                "-Wall", "-Wextra", "-o", _SO, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _SO
