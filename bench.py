@@ -391,8 +391,33 @@ def main():
         extra["valu_xor_popcount_probe"] = {"ms": ms, "TOPS": tops, "assumed_peak_TOPS": VALU_PEAK_TOPS,
                                             "frac_of_assumed_peak": tops / VALU_PEAK_TOPS}
 
+    def job_mfma_probe():
+        # the rate the matrix cores sustain on the FP4 instruction alone (operands in registers, one wave per SIMD on
+        # every CU, about 0.1 s per pattern): what the 10.1 POP/s peak becomes under this card's power management
+        blocks, iters = 256, 200000
+        sink = torch.empty((blocks * 256,), dtype=torch.float32, device="cuda")
+        res = {}
+        for name, bits, vary in (("zero_operands", 0, False), ("all_ones", 0x22222222, False),
+                                 ("zeros_and_ones_at_random", 0x22222222, True), ("random_nibbles", 0xFFFFFFFF, True)):
+            s0 = torch.zeros(3, dtype=torch.int64, device="cuda")
+            s1 = torch.zeros(3, dtype=torch.int64, device="cuda")
+
+            def run(bits=bits, vary=vary):
+                q.qnn_probe_mfma_fp4_peak(sink, blocks, iters, bits, vary)
+
+            run()
+            q.qnn_stamp_clocks(s0)
+            ms = time_steps(run, 2, 0)
+            q.qnn_stamp_clocks(s1)
+            torch.cuda.synchronize()
+            tops = 2.0 * blocks * 4 * iters * 16 * 65536 / (ms * 1e-3) / 1e12
+            res[name] = {"ms": ms, "TOPS": tops, "frac_of_fp4_peak": tops / MFMA_FP4_PEAK_TOPS,
+                         "avg_sclk_mhz": q.average_shader_clock_mhz(s0, s1)}
+        extra["mfma_fp4_probe"] = res
+
     if "c1" in only:
         jobs.append((0, job_valu_probe))
+        jobs.append((0, job_mfma_probe))
 
     # ================================================================ GPU work, back to back
     primary = {}

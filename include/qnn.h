@@ -319,6 +319,14 @@ int qnn_stamp_clocks(unsigned long long *out3, void *stream);
  * (DEVICE, blocks * 256 uint32) receives one checksum per lane.  The caller times the launch.  blocks in 1 .. 65536. */
 int qnn_probe_valu_peak(uint32_t *sink, int64_t blocks, uint32_t iterations, void *stream);
 
+/* Measurement helper: the rate the matrix cores sustain on the instruction of the FP4 path with all operands in
+ * registers.  `blocks` workgroups of four waves (one per SIMD) run `iterations` times sixteen
+ * v_mfma_scale_f32_32x32x64_f8f6f4 per wave, i.e. blocks * 4 * iterations * 16 * 65536 MACs.  Every operand register
+ * holds operand_bits, and-ed with a per-lane hash if vary is non-zero (E2M1 nibbles: 0 all zeros, 0x22222222 all ones,
+ * 0x22222222 with vary zeros and ones at random, 0xFFFFFFFF with vary random values).  sink (DEVICE, blocks * 256 float) receives one checksum per lane.  The caller times the
+ * launch.  blocks in 1 .. 65536. */
+int qnn_probe_mfma_fp4_peak(float *sink, int64_t blocks, uint32_t iterations, uint32_t operand_bits, int vary, void *stream);
+
 const char *qnn_last_error(void);
 const char *qnn_version(void);
 

@@ -43,6 +43,7 @@ _SIGS = {
     "qnn_probe_shader_clock": [_vp, _vp],
     "qnn_stamp_clocks": [_vp, _vp],
     "qnn_probe_valu_peak": [_vp, C.c_int64, C.c_uint32, _vp],
+    "qnn_probe_mfma_fp4_peak": [_vp, C.c_int64, C.c_uint32, C.c_uint32, C.c_int, _vp],
     "qnn_fold_batchnorm": [_vp, _vp, _vp, _vp, C.c_double, _i64, _vp, _vp],
     "qnn_binary_mlp_forward": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _vp],
     "qnn_binary_mlp_forward_ex": [_vp, _i64, _i64, _int, _int, _vp, _vp, _vp, _vp, _vp, _i64, _vp, _sz, _int, _vp],
@@ -166,6 +167,14 @@ def qnn_probe_valu_peak(sink: torch.Tensor, blocks: int, iterations: int) -> Non
     if sink.numel() < blocks * 256:
         raise ValueError("sink needs blocks * 256 elements")
     _check(_lib.qnn_probe_valu_peak(_dev(sink, torch.int32, "sink"), int(blocks), int(iterations), _stream()))
+
+
+def qnn_probe_mfma_fp4_peak(sink: torch.Tensor, blocks: int, iterations: int, operand_bits: int, vary: bool) -> None:
+    """Enqueues the register-resident FP4 matrix-core kernel: blocks * 4 * iterations * 16 * 65536 MACs."""
+    if sink.numel() < blocks * 256:
+        raise ValueError("sink needs blocks * 256 elements")
+    _check(_lib.qnn_probe_mfma_fp4_peak(_dev(sink, torch.float32, "sink"), int(blocks), int(iterations),
+                                        int(operand_bits) & 0xFFFFFFFF, 1 if vary else 0, _stream()))
 
 
 def average_shader_clock_mhz(stamp0: torch.Tensor, stamp1: torch.Tensor) -> Optional[float]:

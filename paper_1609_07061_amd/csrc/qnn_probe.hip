@@ -57,6 +57,47 @@ __global__ __launch_bounds__(256) void valu_peak_kernel(uint32_t *sink, uint32_t
     sink[(size_t)blockIdx.x * 256 + threadIdx.x] = total;
 }
 
+// One wave per SIMD runs nothing but the matrix-core instruction of the FP4 path, v_mfma_scale_f32_32x32x64_f8f6f4 on
+// E2M1 operands, on sixteen independent accumulator blocks with operands that stay in registers: the rate the matrix
+// cores sustain on this card, power management included.  operand_bits: the 32-bit pattern every operand register is
+// filled with, and-ed with a per-lane hash if `vary` is set (0: all-zero operands; 0x22222222: all ones; 0x22222222
+// with vary: zeros and ones at random, the operands the product kernels make; 0xFFFFFFFF with vary: random nibbles).
+// One float per lane leaves the kernel.
+typedef int probe_v8i __attribute__((ext_vector_type(8)));
+typedef float probe_v16f __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256, 1) void mfma_fp4_peak_kernel(float *sink, uint32_t iterations, uint32_t operand_bits, uint32_t vary) {
+    probe_v16f acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[i][v] = 0.0f;
+    probe_v8i a[4], w[4];
+    uint32_t h = (threadIdx.x + 256u * blockIdx.x) * 2654435761u;
+#pragma unroll
+    for (int b = 0; b < 4; ++b)
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            h = h * 1664525u + 1013904223u;
+            a[b][j] = (int)(vary ? (operand_bits & h) : operand_bits);
+            h = h * 1664525u + 1013904223u;
+            w[b][j] = (int)(vary ? (operand_bits & h) : operand_bits);
+        }
+    const int one = 0x7F7F7F7F;  // block scales 2^0
+    for (uint32_t it = 0; it < iterations; ++it) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                acc[i * 4 + j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(w[i], a[j], acc[i * 4 + j], 4, 4, 0, one, 0, one);
+    }
+    float s = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) s += acc[i][v];
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = s;
+}
+
 }  // namespace
 }  // namespace qnn
 
@@ -81,4 +122,12 @@ extern "C" int qnn_probe_valu_peak(uint32_t *sink, int64_t blocks, uint32_t iter
     if (blocks <= 0 || blocks > 65536) return fail(QNN_ERR_SHAPE, "probe_valu_peak: blocks must lie in 1 .. 65536");
     return QNN_LAUNCH("valu_peak", valu_peak_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream), sink,
                       iterations);
+}
+
+extern "C" int qnn_probe_mfma_fp4_peak(float *sink, int64_t blocks, uint32_t iterations, uint32_t operand_bits, int vary, void *stream) {
+    using namespace qnn;
+    if (!sink) return fail(QNN_ERR_NULL, "probe_mfma_fp4_peak: NULL pointer");
+    if (blocks <= 0 || blocks > 65536) return fail(QNN_ERR_SHAPE, "probe_mfma_fp4_peak: blocks must lie in 1 .. 65536");
+    return QNN_LAUNCH("mfma_fp4_peak", mfma_fp4_peak_kernel, dim3((unsigned)blocks), dim3(256), 0, static_cast<hipStream_t>(stream),
+                      sink, iterations, operand_bits, (uint32_t)(vary != 0));
 }
