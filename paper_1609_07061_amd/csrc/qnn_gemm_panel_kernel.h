@@ -357,13 +357,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     constexpr int kPending = kLoadsPerGroup * (kBuffers - 2);
     static_assert(kPending < 64, "vmcnt is a 6-bit counter");
     auto panel_barrier = [&]() __attribute__((always_inline)) {
-#ifdef QNN_EXP_NOBARRIER
-        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-#elif defined(QNN_EXP_NOVMWAIT)
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-#else
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(kPending) : "memory");
-#endif
     };
     auto first_barrier = [&]() __attribute__((always_inline)) {
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
@@ -391,9 +385,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     // quarter t of the group kBuffers groups ahead into it.
     auto produce = [&](auto t_tag) __attribute__((always_inline)) {
         constexpr int tt = decltype(t_tag)::value;
-#ifndef QNN_EXP_NOLOADS
         load_quarter(tt, rd);
-#endif
     };
 
     uint32_t vb = blockIdx.x;
