@@ -405,7 +405,9 @@ def test_mlp_forward_small(seed, batch, dims, engine):
 
 @pytest.mark.parametrize("engine", [0, 2])
 @pytest.mark.parametrize("batch,dims,ldx", [(1100, [784, 2048, 64, 10], 800), (520, [1008, 4096, 10], 1008),
-                                            (1030, [16, 2048, 10], 16), (1100, [784, 2048, 64, 10], 788)])
+                                            (1030, [16, 2048, 10], 16), (1100, [784, 2048, 64, 10], 788),
+                                            (700, [144, 2000, 10], 160), (300, [2064, 1100, 10], 2064),
+                                            (2600, [272, 4096, 10], 272), (257, [48, 129, 10], 64)])
 def test_mlp_forward_first_layer_from_codes(seed, batch, dims, ldx, engine):
     """Large enough for the matrix-core engine: the first layer reads the 8-bit codes directly when rows are 16-byte
     aligned (ldx a multiple of 16) and falls back to bit planes otherwise; both must give the oracle's logits."""
