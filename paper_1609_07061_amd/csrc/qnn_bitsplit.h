@@ -39,4 +39,31 @@ __device__ __forceinline__ void split_32_codes(const uint32_t (&codes)[8], int n
     for (int p = 0; p < 4; ++p) word[p] = lo4[p], word[p + 4] = hi4[p];
 }
 
+// 32 x 32 bit matrix held as 32 words (x[k] bit c = element (k, c)), transposed in place: five rounds of exchanges
+// of 16-, 8-, 4-, 2- and 1-bit blocks between words 16, 8, 4, 2 and 1 apart; the first two rounds move whole bytes
+// and are byte permutes.
+__device__ __forceinline__ void transpose_32x32_bits(uint32_t (&x)[32]) {
+#pragma unroll
+    for (int k = 0; k < 16; ++k) {
+        const uint32_t a = x[k], b = x[k + 16];
+        x[k] = __builtin_amdgcn_perm(b, a, 0x05040100u), x[k + 16] = __builtin_amdgcn_perm(b, a, 0x07060302u);
+    }
+#pragma unroll
+    for (int k = 0; k < 32; ++k)
+        if (!(k & 8)) {
+            const uint32_t a = x[k], b = x[k + 8];
+            x[k] = __builtin_amdgcn_perm(b, a, 0x06020400u), x[k + 8] = __builtin_amdgcn_perm(b, a, 0x07030501u);
+        }
+#pragma unroll
+    for (int j = 4; j >= 1; j >>= 1) {
+        const uint32_t m = j == 4 ? 0x0F0F0F0Fu : (j == 2 ? 0x33333333u : 0x55555555u);
+#pragma unroll
+        for (int k = 0; k < 32; ++k)
+            if (!(k & j)) {
+                const uint32_t t = ((x[k] >> j) ^ x[k + j]) & m;
+                x[k] ^= t << j, x[k + j] ^= t;
+            }
+    }
+}
+
 }  // namespace qnn

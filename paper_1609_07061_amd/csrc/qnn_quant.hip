@@ -252,10 +252,97 @@ float pow2_inverse(float step) {
     return 1.0f / step;
 }
 
+// The same transposition for matrices whose rows (input and output) are made of whole, 16-byte aligned groups of four
+// words: a workgroup takes a tile of 512 input rows x 16 word columns (512 x 512 bits), loads it with 16-byte loads
+// (four lanes share 64 contiguous bytes of a row) into LDS, every thread transposes one 32 x 32 bit block in its
+// registers (about 300 instructions for 32 words, where the ballot scheme above spends 170 on 64 words per wave, i.e.
+// per instruction issued, a thirteenth of the work), and the 512 output rows leave as 64-byte pieces with 16-byte
+// stores.  LDS layouts: input row r at word 16 (r + r / 32), output row o at word 16 o + 4 (o / 32): with these
+// skews the word reads and writes of the 64 lanes of a wave (four row blocks x sixteen word columns) hit 64 banks.
+constexpr int kTrRows = 512, kTrWords = 16;
+__global__ __launch_bounds__(kBlock) void transpose_bits_tile_kernel(const uint32_t *__restrict__ in, int64_t rows, int64_t cols,
+                                                                     int64_t ld_in, int64_t in_plane_stride,
+                                                                     uint32_t *__restrict__ out, int64_t ld_out,
+                                                                     int64_t out_plane_stride, int64_t out_words,
+                                                                     int64_t tiles_r, int64_t tiles_c) {
+    __shared__ __attribute__((aligned(16))) uint32_t s_in[(kTrRows + kTrRows / 32) * kTrWords];
+    __shared__ __attribute__((aligned(16))) uint32_t s_out[kTrWords * 32 * kTrWords + 4 * kTrWords];
+    const int t = threadIdx.x;
+    const int64_t Cw = (cols + 31) / 32;
+    in += (int64_t)blockIdx.y * in_plane_stride;
+    out += (int64_t)blockIdx.y * out_plane_stride;
+    for (int64_t tile = blockIdx.x; tile < tiles_r * tiles_c; tile += gridDim.x) {
+        const int64_t tr = tile / tiles_c, tc = tile - tr * tiles_c;
+        const int64_t r0 = tr * kTrRows, j0 = tc * kTrWords;
+        // load: 2048 pieces of 16 bytes, eight per thread, all issued before the first LDS store
+        uint4 v[kTrRows * kTrWords / 4 / kBlock];
+#pragma unroll
+        for (int u = 0; u < kTrRows * kTrWords / 4 / kBlock; ++u) {
+            const int idx = t + u * kBlock, rr = idx >> 2, pc = idx & 3;
+            const int64_t r = r0 + rr, j = j0 + 4 * pc;
+            v[u] = make_uint4(0u, 0u, 0u, 0u);
+            if (r < rows && j < Cw) {
+                v[u] = *reinterpret_cast<const uint4 *>(in + r * ld_in + j);
+                // words beyond the row's last one lie inside the padded row but are not part of the matrix
+                if (j + 1 >= Cw) v[u].y = 0u;
+                if (j + 2 >= Cw) v[u].z = 0u;
+                if (j + 3 >= Cw) v[u].w = 0u;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kTrRows * kTrWords / 4 / kBlock; ++u) {
+            const int idx = t + u * kBlock, rr = idx >> 2, pc = idx & 3;
+            *reinterpret_cast<uint4 *>(&s_in[(rr + (rr >> 5)) * kTrWords + 4 * pc]) = v[u];
+        }
+        __syncthreads();
+        // turn: thread (rb, j) takes rows 32 rb .. + 31 of word column j
+        {
+            const int rb = t >> 4, j = t & 15;
+            uint32_t x[32];
+#pragma unroll
+            for (int k = 0; k < 32; ++k) x[k] = s_in[(rb * 33 + k) * kTrWords + j];
+            transpose_32x32_bits(x);
+            // x[c] = bits (rows 32 rb .. + 31, column 32 j + c) = word rb of output row 32 j + c
+#pragma unroll
+            for (int c = 0; c < 32; ++c) s_out[(j * 32 + c) * kTrWords + 4 * j + rb] = x[c];
+        }
+        __syncthreads();
+        // store: output row 32 j0 + o, words r0 / 32 .. + 15
+#pragma unroll
+        for (int u = 0; u < kTrRows * kTrWords / 4 / kBlock; ++u) {
+            const int idx = t + u * kBlock, o = idx >> 2, pc = idx & 3;
+            const int64_t orow = j0 * 32 + o, wj = r0 / 32 + 4 * pc;
+            if (orow < cols && wj < out_words) {
+                const uint4 x = *reinterpret_cast<const uint4 *>(&s_out[o * kTrWords + 4 * (o >> 5) + 4 * pc]);
+                uint32_t *dst = out + orow * ld_out + wj;
+                if (wj + 3 < out_words) {
+                    *reinterpret_cast<uint4 *>(dst) = x;
+                } else {
+                    dst[0] = x.x;
+                    if (wj + 1 < out_words) dst[1] = x.y;
+                    if (wj + 2 < out_words) dst[2] = x.z;
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
 bool aligned4(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 3u) == 0; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 int launch_transpose(const uint32_t *in, int64_t rows, int64_t cols, int64_t ld_in, int64_t in_plane_stride, int nplanes,
                      uint32_t *out, int64_t ld_out, int64_t out_plane_stride, int64_t out_words, hipStream_t s) {
+    // large matrices whose rows are made of whole, aligned 16-byte groups: the tiled kernel
+    if (rows >= 256 && cols >= 256 && ld_in % 4 == 0 && ld_out % 4 == 0 && in_plane_stride % 4 == 0 && out_plane_stride % 4 == 0 &&
+        aligned16(in) && aligned16(out)) {
+        // (the tiles cover out_words words of every output row: what lies beyond the input's rows is written as zeros)
+        const int64_t tiles_r = ceil_div(out_words * 32, (int64_t)kTrRows), tiles_c = ceil_div(words_for(cols), (int64_t)kTrWords);
+        const int64_t tiles = tiles_r * tiles_c;
+        return QNN_LAUNCH("transpose_bits", transpose_bits_tile_kernel, dim3((unsigned)(tiles > 65536 ? 65536 : tiles), (unsigned)nplanes),
+                          dim3(kBlock), 0, s, in, rows, cols, ld_in, in_plane_stride, out, ld_out, out_plane_stride, out_words, tiles_r,
+                          tiles_c);
+    }
     const int64_t row_blocks = ceil_div(out_words, 2), units = row_blocks * words_for(cols);
     return QNN_LAUNCH("transpose_bits", transpose_bits_kernel, dim3(grid_for_chunks(units), (unsigned)nplanes), dim3(kBlock), 0, s,
                       in, rows, cols, ld_in, in_plane_stride, out, ld_out, out_plane_stride, out_words, row_blocks, units);

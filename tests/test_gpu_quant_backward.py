@@ -131,6 +131,24 @@ def test_transpose_bits(seed, rows, cols, P):
     assert np.array_equal(got, want)
 
 
+@pytest.mark.parametrize("rows,cols,ld_in,ld_out", [(1024, 1024, 32, 32), (1000, 1000, 32, 32), (600, 4000, 128, 20),
+                                                    (4100, 300, 12, 132), (513, 257, 12, 20), (2050, 2050, 68, 68)])
+@pytest.mark.parametrize("P", [1, 2])
+def test_transpose_bits_large_padded_rows(seed, rows, cols, ld_in, ld_out, P):
+    """Rows of whole 16-byte groups on both sides: the tiled kernel.  The padding words of the input hold garbage; the
+    padding words of the output (beyond ceil(rows / 32)) must be left alone."""
+    bits = qi.bernoulli_bits(seed, 2420, (P, rows, cols))
+    cw, rw = (cols + 31) // 32, (rows + 31) // 32
+    src = torch.full((P, rows, ld_in), 0x3C3C3C3C, dtype=torch.int32, device="cuda")
+    src[:, :, :cw] = dev(np_pack_bits(bits))
+    out = torch.full((P, cols, ld_out), 0x5A5A5A5A, dtype=torch.int32, device="cuda")
+    q.qnn_transpose_bits(src[:, :, :cw], cols, out=out[:, :, :rw])
+    got = host_u32(out)
+    want = np.stack([oracle.pack_bits(np.ascontiguousarray(bits[p].T).astype(np.int8)) for p in range(P)])
+    assert np.array_equal(got[:, :, :rw], want)
+    assert (got[:, :, rw:] == 0x5A5A5A5A).all()
+
+
 def test_transpose_bits_strided_and_padding(seed):
     rows, cols = 70, 45
     bits = qi.bernoulli_bits(seed, 2410, (2, rows, cols))
