@@ -11,7 +11,8 @@
 //     row: 256 activation rows + 256 weight rows = 64 KiB) at a time, with loads that write straight to LDS
 //     (global_load_lds_dwordx4: no registers are held while the data is on its way), each wave 16 of them per group,
 //     issued right after the barrier that frees a group buffer, i.e. at least three steps (about 6000 cycles)
-//     before the data is needed; two group buffers take turns;
+//     before the data is needed; two group buffers take turns (three for the 256 x 128 tile, whose steps are half as
+//     long), and the barrier lets the loads of the later groups stay in flight;
 //   * a 16-byte piece c of row r sits at piece c xor (r mod 8) of its LDS row (the lanes of a load pick their global
 //     piece accordingly; the order of pieces inside a line does not change the cost of the load), so that the reads
 //     (lanes = consecutive rows, same piece) use all banks;
@@ -20,7 +21,10 @@
 //     every nibble of the lane's four words, and a nibble with only bit 0 / 1 / 2 set is 0.5 / 1.0 / 2.0, which the
 //     block scale of the instruction (exact powers of two) turns into 1;
 //   * one workgroup barrier per group (between its third and fourth step: by then every wave holds the fourth step's
-//     words in registers and the next group is complete in the other buffer).
+//     words in registers and the next group is complete in the other buffer);
+//   * the one wave a SIMD holds issues every instruction itself, so whatever depends on the tile only (row offsets of
+//     the loads) is worked out when the producer's cursor enters a tile, and thresholds and flip flags reach their
+//     LDS tables by the same kind of load, not through registers.
 // Requirements (otherwise gemm_mfma_kernel takes the product): one plane per operand, rows of whole 128-byte groups
 // starting on 16-byte boundaries, operands that span less than 4 GiB each.
 #pragma once
