@@ -211,8 +211,9 @@ def test_many_tiles_short_k_threshold_output(seed, M, N, K, engine):
 
 # K a multiple of 1024 and 16-byte aligned rows: the kernel that is fed from LDS panels.  (4000, 8100): 16 x 32 tiles of
 # 256 x 256, two per workgroup, ragged on both edges; (4200, 4360): 17 x 35 tiles of 256 x 128 (chosen because 17 x 18
-# large tiles would leave 40 % of the second round idle); (1000, 700): fewer tiles than workgroups, three groups of K.
-PANEL_TILES = [(4000, 8100, 1024), (4200, 4360, 2048), (1000, 700, 3072)]
+# large tiles would leave 40 % of the second round idle); (1000, 700): fewer tiles than workgroups, three groups of K;
+# (6000, 8500): 24 x 34 tiles, three or four per workgroup.
+PANEL_TILES = [(4000, 8100, 1024), (4200, 4360, 2048), (1000, 700, 3072), (6000, 8500, 1024)]
 
 
 @pytest.mark.parametrize("engine", [0, FP4])
