@@ -13,7 +13,11 @@
 // lines straight to LDS (global_load_lds), a group of 128 elements of k (two steps) at a time into a ring of three group
 // buffers; 16-byte piece c of row r sits at piece c xor (r mod 8).  Activation pieces beyond K are read from the row's
 // start instead (valid memory, any value): they meet weights that are zero.
-// Workgroup tile 256 x 128, threshold epilogue (the layer is always followed by Sign(BatchNorm(.)) in Alg. 4).
+// Workgroup tile 256 x 128 or 256 x 256, threshold epilogue (the layer is always followed by Sign(BatchNorm(.)) in
+// Alg. 4).
+// The same kernel, with kCodes = false, multiplies two operands that are int8 values already (bit planes merged to one
+// byte per element by merge_planes_kernel, Sec. 2.6 / Sec. 3: the weighted sum of the plane products is the product of
+// the values the planes stand for), with int32 sums as output and no correction terms.
 #pragma once
 #include "qnn_gemm_mfma_kernel.h"
 #include "qnn_gemm_panel_epilogue.h"
@@ -43,27 +47,37 @@ __device__ __forceinline__ void phase_groups(std::integer_sequence<int, I...>) {
 }
 
 // WBN: 32-column blocks per wave along n (2: workgroup tile 256 x 128).
-template <bool kSign, int WBN>
+// kCodes: the left operand holds uint8 codes (the kernel subtracts 128 and adds the weight rows' term g.rw_scaled);
+// otherwise int8 values.
+template <bool kSign, int WBN, bool kCodes = true>
 __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                         uint32_t tiles_n, uint32_t ngroups) {
-    static_assert(kSign, "the layer this kernel serves is always thresholded");
+    static_assert(kSign == kCodes, "uint8 codes with threshold output (first layer), or int8 values with int32 output");
     constexpr int WTN = 32 * WBN, BNt = 2 * WTN;
     constexpr int kMfma = WB * WBN;  // matrix-core instructions of a phase (16 elements of k per lane)
     constexpr int kWPanelBytes = BNt * kRowBytes;
     constexpr int kGroupBytesT = kPanelBytes + kWPanelBytes;
     constexpr int kBuffers = WBN == 2 ? 3 : 2;
-    __shared__ __attribute__((aligned(16))) uint8_t lds[kBuffers * kGroupBytesT];
-    __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
-    __shared__ __attribute__((aligned(16))) int32_t thr_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
-    __shared__ __attribute__((aligned(16))) uint32_t flip_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
-    __shared__ __attribute__((aligned(16))) int32_t stage[kSign ? 1 : kThreads / 64][kSign ? 4 : 32 * 32];
-
+    // One LDS array: the ring of group buffers, then either the per-wave tables of the threshold epilogue (thresholds,
+    // flip flags, weight rows' terms: 128 entries each) or the per-wave 32 x 32 staging blocks of the int32 epilogue.
+    // The narrow tile with int32 output takes all 160 KiB.
+    constexpr int kRingBytes = kBuffers * kGroupBytesT;
+    constexpr int kTableBytes = WTILE * 4;
+    constexpr int kTailBytes = kSign ? 3 * (kThreads / 64) * kTableBytes : (kThreads / 64) * 32 * 32 * 4;
+    static_assert(kRingBytes + kTailBytes <= 160 * 1024, "LDS of a compute unit");
+    __shared__ __attribute__((aligned(16))) uint8_t lds[kRingBytes + kTailBytes];
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
     const int wm = wave >> 1, wn = wave & 1;
     const uint32_t total_tiles = tiles_m * tiles_n;
     const uint32_t K = (uint32_t)g.K;
+    // this wave's tables / staging block
+    uint8_t *const tail = lds + kRingBytes;
+    uint32_t *const rw_tab = kSign ? reinterpret_cast<uint32_t *>(tail + (3 * wave) * kTableBytes) : nullptr;
+    int32_t *const thr_tab = kSign ? reinterpret_cast<int32_t *>(tail + (3 * wave + 1) * kTableBytes) : nullptr;
+    uint32_t *const flip_tab = kSign ? reinterpret_cast<uint32_t *>(tail + (3 * wave + 2) * kTableBytes) : nullptr;
+    int32_t *const stage_w = kSign ? nullptr : reinterpret_cast<int32_t *>(tail + wave * (32 * 32 * 4));
 
     // lane-dependent values are re-derived behind an opaque copy wherever they are used (address arithmetic that the
     // compiler computes once before the loops ends up spilled, and a reload in the main loop stalls the wave)
@@ -73,8 +87,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
     };
     const uint32_t tid = (uint32_t)t;
     if constexpr (kSign) {  // flip flags default to "none"
-        flip_table[wave][lane] = 0u;
-        flip_table[wave][lane + 64] = 0u;
+        flip_tab[lane] = 0u;
+        flip_tab[lane + 64] = 0u;
     }
     const uint32_t lds_base = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint8_t *)lds);
 
@@ -193,13 +207,14 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
     struct Frags {
         v4i a[WB], w[WBN];
     };
-    // operands of half h: the codes minus 128; the weights as they lie
+    // operands of half h: the codes minus 128 (int8 values: as they lie); the weights as they lie
     auto expand = [&](const Step &c, const int h, Frags &f) __attribute__((always_inline)) {
+        constexpr uint32_t flip = kCodes ? 0x80808080u : 0u;
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
             const uint4 a = c.A[b][h];
-            f.a[b][0] = (int)(a.x ^ 0x80808080u), f.a[b][1] = (int)(a.y ^ 0x80808080u);
-            f.a[b][2] = (int)(a.z ^ 0x80808080u), f.a[b][3] = (int)(a.w ^ 0x80808080u);
+            f.a[b][0] = (int)(a.x ^ flip), f.a[b][1] = (int)(a.y ^ flip);
+            f.a[b][2] = (int)(a.z ^ flip), f.a[b][3] = (int)(a.w ^ flip);
         }
 #pragma unroll
         for (int b = 0; b < WBN; ++b) {
@@ -218,13 +233,14 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
     // of the following step) runs inside phase 0, `produce(h)` in both.
     auto compute = [&](const Step &c, const Step &n, Frags &f, auto issue_fetch, auto produce, auto last_tag) __attribute__((always_inline)) {
         constexpr bool kLastStep = decltype(last_tag)::value;
+        constexpr int kXors = kCodes ? 4 * WB : 0;  // vector-ALU instructions of a phase
         {
             issue_fetch();
             produce(std::integral_constant<int, 0>{});
             Frags gnext;
             expand(c, 1, gnext);
             multiply(f);
-            phase_groups<4 * WB + 8, 2 * WB + 2 * WBN>(std::make_integer_sequence<int, kMfma>{});
+            phase_groups<kXors + 8, 2 * WB + 2 * WBN>(std::make_integer_sequence<int, kMfma>{});
             __builtin_amdgcn_sched_barrier(0);
             f = gnext;
         }
@@ -233,7 +249,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
             Frags gnext;
             if (!kLastStep) expand(n, 0, gnext);
             multiply(f);
-            phase_groups<4 * WB, 0>(std::make_integer_sequence<int, kMfma>{});
+            phase_groups<kXors, 0>(std::make_integer_sequence<int, kMfma>{});
             __builtin_amdgcn_sched_barrier(0);
             if (!kLastStep) f = gnext;
         }
@@ -241,10 +257,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
 
     // thresholds / flip flags of the tile being finished, straight into this wave's LDS tables
     auto load_thresholds = [&](const int64_t n_wave) __attribute__((always_inline)) {
-        panel::load_thresholds_to_lds<WBN>(g, n_wave, thr_table[wave], flip_table[wave]);
+        if constexpr (!kSign) return;
+        panel::load_thresholds_to_lds<WBN>(g, n_wave, thr_tab, flip_tab);
         // the weight rows' terms 128 sum_k w[n][k], straight into the table the epilogue reads them from
         const uint32_t ln = threadIdx.x & 63u;
-        const uint32_t rw_lds = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint32_t *)rw_table[wave]);
+        const uint32_t rw_lds = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint32_t *)rw_tab);
 #pragma unroll
         for (int h = 0; h < WBN / 2; ++h) {
             int64_t n = n_wave + 64 * h + ln;
@@ -317,8 +334,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
         };
         for (uint32_t G = 0; G + 1 < ngroups; ++G) group(std::false_type{});
         group(std::true_type{});
-        panel::wave_finish<kSign, WBN, kLoadsPerGroup, true>(g, mc, acc, ra, rw, rw_table[wave], thr_table[wave], flip_table[wave],
-                                                             stage[wave], m_wave, n_wave);
+        panel::wave_finish<kSign, WBN, kLoadsPerGroup, kCodes>(g, mc, acc, ra, rw, rw_tab, thr_tab, flip_tab, stage_w,
+                                                               m_wave, n_wave);
         expand(buf0, 0, frags);
         vb += gridDim.x;
         if (vb >= total_tiles) break;
@@ -326,7 +343,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
 }
 
 typedef void (*KernelFn)(const GemmArgs, const MfmaConst, uint32_t, uint32_t, uint32_t);
-KernelFn kernel(bool narrow);  // workgroup tile 256 x 128 (narrow) or 256 x 256
+KernelFn kernel(bool narrow);         // uint8 codes, threshold output; workgroup tile 256 x 128 (narrow) or 256 x 256
+KernelFn kernel_values(bool narrow);  // int8 values, int32 output
 
 
 }  // namespace bytes_panel

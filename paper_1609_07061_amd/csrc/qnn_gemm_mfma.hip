@@ -188,8 +188,20 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
             // a little more than half of a large tile, so a small gain does not pay)
             auto fill = [&](int64_t tiles) { return (double)tiles / (double)(ceil_div(tiles, cus) * cus); };
             const int64_t tiles_n2 = ceil_div(g.N, BN / 2);
-            const bool narrow = fill(tiles_m * tiles_n2) > 1.1 * fill(total);
-            const panel::KernelFn pf = panel::find_kernel(g.epi.T != nullptr, narrow);
+            bool narrow = fill(tiles_m * tiles_n2) > 1.1 * fill(total);
+            // Wide tiles with the last round's tiles halved (each half to a workgroup of its own): possible when that
+            // round has tiles for at most half of the workgroups, and worth it only for long rows, where a wide tile
+            // costs less than two narrow ones.  Costs in units of a round of narrow tiles, as measured at K = 4096:
+            // a round of wide tiles 1.86, the round of halves 1.17.
+            bool tail = false;
+            if (cus % 16 == 0 && total > cus && total % cus != 0 && 2 * (total % cus) <= cus && ngroups >= 4) {
+                const double wide_round = 1.86, half_round = 1.17;
+                const double cost_tail = (double)(total / cus) * wide_round + half_round;
+                const double cost_else = narrow ? (double)ceil_div(tiles_m * tiles_n2, cus) : (double)ceil_div(total, cus) * wide_round;
+                tail = cost_tail < cost_else;
+            }
+            narrow = narrow && !tail;
+            const panel::KernelFn pf = panel::find_kernel(g.epi.T != nullptr, narrow, tail);
             const int64_t ptotal = narrow ? tiles_m * tiles_n2 : total;
             const unsigned pgrid = (unsigned)(ptotal < cus ? ptotal : cus);
             return QNN_LAUNCH("gemm_panel", pf, dim3(pgrid), dim3(panel::kThreads), 0, s, g, pc, (uint32_t)tiles_m,
@@ -272,9 +284,76 @@ bool prepare_stage(const GemmArgs &g, MfmaConst &mc, StageConst &sc, StageFn &fn
     return fn != nullptr;
 }
 
+// Large products of multi-plane operands with int32 output: the planes of both operands are merged to int8 values once
+// per call, into memory borrowed from the stream's pool, and the panel-fed byte kernel multiplies them.  (Merging in
+// every workgroup repeats the work for every tile of a row of tiles and holds the multiplication up behind loads of
+// one row per lane.)
+// Row pitch of the merged operands: whole groups of k.
+int64_t values_pitch(int64_t K) {
+    const int64_t p = ceil_div(K, bytes_panel::kGroupK) * bytes_panel::kGroupK;
+    return p;
+}
+bool values_path(const GemmArgs &g) {
+    if (g.A.rows_are_pixels || g.A.rows_are_bytes || g.epi.T) return false;
+    if (g.pa.count == 1 && g.pw.count == 1) return false;
+    if (g.K < 512 || g.K >= 131072 || g.M < 256 || g.N < 256) return false;  // |S| <= K 2^14 stays below 2^31
+    if ((long double)g.M * (long double)g.N * (long double)g.K < 2147483648.0L) return false;  // small: not worth three launches
+    const int64_t pitch = values_pitch(g.K);
+    if ((long double)(g.M + 256) * pitch >= 4294967296.0L || (long double)(g.N + 256) * pitch >= 4294967296.0L) return false;
+    if (ceil_div(g.M, 256) * ceil_div(g.N, 128) > 0x7FFFFFFFLL) return false;
+    return bytes_panel::merge_supports(g.pa, g.pw);
+}
+
+int launch_values(const GemmArgs &g, hipStream_t s) {
+    const int64_t pitch = values_pitch(g.K);
+    const size_t bytes_a = (size_t)g.M * (size_t)pitch, bytes_w = (size_t)g.N * (size_t)pitch;
+    void *mem = nullptr;
+    if (hipMallocAsync(&mem, bytes_a + bytes_w, s) != hipSuccess || !mem) {
+        (void)hipGetLastError();
+        return fail(QNN_ERR_HIP, "gemm: no memory for the merged operands (%zu bytes)", bytes_a + bytes_w);
+    }
+    int8_t *a8 = static_cast<int8_t *>(mem), *w8 = a8 + bytes_a;  // (bytes_a is a multiple of 128)
+    int64_t scale = 0;
+    int rc = bytes_panel::launch_merge_planes(g, a8, w8, pitch, scale, s);
+    if (rc == QNN_OK) {
+        GemmArgs v = g;
+        v.A.base = reinterpret_cast<const uint32_t *>(a8);
+        v.A.ld = pitch;
+        v.A.plane_stride = 0;
+        v.A.rows_are_bytes = 1;
+        v.w_bytes = w8;
+        v.ld_w_bytes = pitch;
+        v.rw_scaled = nullptr;
+        MfmaConst mc;
+        std::memset(&mc, 0, sizeof(mc));
+        mc.alpha = (uint32_t)scale;
+        mc.alpha_shift = -1;
+        for (int sh = 0; sh < 31; ++sh)
+            if (scale == ((int64_t)1 << sh)) mc.alpha_shift = sh;
+        const int cus = compute_units();
+        const int64_t tiles_m = ceil_div(g.M, 256);
+        auto fill = [&](int64_t tiles) { return (double)tiles / (double)(ceil_div(tiles, cus) * cus); };
+        const int64_t wide_n = ceil_div(g.N, 256), narrow_n = ceil_div(g.N, 128);
+        // The narrow tile has room for three group buffers and keeps more bytes on their way from memory, which is what
+        // bounds this kernel (a byte per element, eight times the traffic of packed bits): the wide tile only where its
+        // tiles fill the compute units at least as well as the narrow ones would.
+        const bool narrow = tiles_m * wide_n < cus || fill(tiles_m * narrow_n) > fill(tiles_m * wide_n);
+        const int64_t tiles_n = narrow ? narrow_n : wide_n, total = tiles_m * tiles_n;
+        const unsigned grid = (unsigned)(total < cus ? total : cus);
+        rc = QNN_LAUNCH("gemm_values", bytes_panel::kernel_values(narrow), dim3(grid), dim3(bytes_panel::kThreads), 0, s, v, mc,
+                        (uint32_t)tiles_m, (uint32_t)tiles_n, (uint32_t)ceil_div(g.K, bytes_panel::kGroupK));
+    }
+    if (hipFreeAsync(mem, s) != hipSuccess) {
+        (void)hipGetLastError();
+        if (rc == QNN_OK) rc = fail(QNN_ERR_HIP, "gemm: returning the merged operands' memory failed");
+    }
+    return rc;
+}
+
 }  // namespace
 
 bool stage_supports(const GemmArgs &g) {
+    if (values_path(g)) return true;
     MfmaConst mc;
     StageConst sc;
     StageFn fn;
@@ -282,6 +361,7 @@ bool stage_supports(const GemmArgs &g) {
 }
 
 int launch_gemm_stage(const GemmArgs &g, hipStream_t s) {
+    if (values_path(g)) return launch_values(g, s);
     MfmaConst mc;
     StageConst sc;
     StageFn fn;

@@ -63,7 +63,9 @@ __device__ __forceinline__ void phase_groups(std::integer_sequence<int, I...>) {
 // kSign: threshold epilogue (Alg. 4: a^b = Sign(BatchNorm(a))) instead of int32 sums.
 // WBN: 32-column blocks per wave along n, 4 (workgroup tile 256 x 256) or 2 (256 x 128: twice the tiles, for shapes whose
 // 256 x 256 tiles would leave a large part of the last round of workgroups idle).
-template <bool kSign, int WBN>
+// kTail (WBN = 4; grid = a multiple of 16 workgroups, fewer than there are tiles, and at most half a grid of tiles in the
+// last round): that round's tiles are taken as halves of 128 columns by two workgroups each.
+template <bool kSign, int WBN, bool kTail = false>
 __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                   uint32_t tiles_n, uint32_t ngroups) {
     // Group buffers: activation panel (256 rows) + weight panel (BN rows).  Two take turns; the narrow tile with the
@@ -82,10 +84,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     const int t = threadIdx.x;
     const int lane = t & 63;
     const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
-    const int r = lane & 31, kg = lane >> 5;
     const int wm = wave >> 1, wn = wave & 1;
     constexpr int WTN = 32 * WBN, BNt = 2 * WTN;  // columns of a wave tile / of the workgroup tile
-    constexpr int kMfma = WB * WBN;               // matrix-core instructions of a phase
     constexpr int kLoadsPerGroup = 8 + BNt / 32;  // loads to LDS that a wave issues per group (8 activation, BN / 32 weight)
     const uint32_t total_tiles = tiles_m * tiles_n;
 
@@ -110,7 +110,20 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     // offsets of the rows this lane loads, with its piece of the line) is worked out when the cursor enters a tile,
     // under a branch of its own; per group only the scalar base pointers move on.  The one wave a SIMD holds issues
     // every instruction of the loop itself, so each instruction kept out of the groups is time won.
-    uint32_t p_vb = blockIdx.x, p_G = 0;
+    // This workgroup's tiles: vb0, vb0 + gridDim.x, ... (n_mine of them).
+    // kTail (the host launches it when the tiles left for the last round are at most half as many as the workgroups):
+    // the tiles of the whole rounds as above; every tile of the last round goes, as two halves of 128 columns, to
+    // two workgroups of one XCD (workgroups w and w + 8), so that the last round takes about half the time of a whole
+    // one instead of leaving half of the chip idle.  The loads do not change: a half consumes the same panels as a
+    // whole tile and skips half of the weight rows.
+    const uint32_t vb0 = blockIdx.x;
+    const uint32_t whole_rounds = total_tiles / gridDim.x;
+    const uint32_t n_mine = kTail ? whole_rounds : (total_tiles - vb0 + gridDim.x - 1u) / gridDim.x;
+    const uint32_t tail_vb = whole_rounds * gridDim.x + ((vb0 >> 4) << 3) + (vb0 & 7u);
+    const bool has_half = kTail && tail_vb < total_tiles;
+    const uint32_t half_col = ((vb0 >> 3) & 1u) * (uint32_t)(32 * WBN);
+    static_assert(!kTail || WBN == 4, "halved tiles in the last round: the wide tile only");
+    uint32_t p_vb = vb0, p_G = 0, p_item = 0;
     // kRowRegs (the narrow tile, whose accumulators leave registers free): one offset register per load, and a copy is
     // all a load needs.  Otherwise one register per panel holds the offset of the lane's row in the first 32-row
     // block, a second one the offset in the operand's last row, and a load adds its block's distance and clamps.
@@ -150,8 +163,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         if (p_G == ngroups) {
             asm volatile("" ::: "memory");  // keeps the branch a branch
             p_G = 0;
-            const uint32_t nb = p_vb + gridDim.x;
-            p_vb = nb < total_tiles ? nb : p_vb;  // after the last tile the loads are repeated and never used
+            ++p_item;
+            if (p_item < n_mine)
+                p_vb = vb0 + p_item * gridDim.x;
+            else if (has_half && p_item == n_mine)
+                p_vb = tail_vb;
+            // (after the last tile the loads are repeated and never used)
             p_locate();
         }
     };
@@ -192,30 +209,70 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         }
     };
 
+    // workgroup barrier of the group buffers: this wave's loads to LDS have landed and its LDS reads have returned
+    // The group needed next was loaded kBuffers - 1 groups ago; the loads of the kBuffers - 2 groups after it may stay
+    // in flight (loads complete in order, so waiting until at most that many are outstanding means the older ones have
+    // landed).
+    constexpr int kPending = kLoadsPerGroup * (kBuffers - 2);
+    static_assert(kPending < 64, "vmcnt is a 6-bit counter");
+    auto panel_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(kPending) : "memory");
+    };
+    auto first_barrier = [&]() __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    };
+
+    // ------------------------------------------------------------------------------------------------ prologue
+    // the first groups into the buffers; the cursor stays at the last of them
+    p_locate();
+#pragma unroll 1
+    for (int b = 0; b < kBuffers; ++b) {
+        if (b > 0) p_advance();
+#pragma unroll
+        for (int q = 0; q < 4; ++q) load_quarter(q, (uint32_t)(b * kGroupBytesT));
+    }
+    first_barrier();
+
+    uint32_t rd = 0u;  // byte offset of the group buffer being consumed
+    auto no_produce = [](auto) __attribute__((always_inline)) {};
+    // Fourth step of a group (after the barrier, the buffer just consumed is free): phase t starts the loads of
+    // quarter t of the group kBuffers groups ahead into it.
+    auto produce = [&](auto t_tag) __attribute__((always_inline)) {
+        constexpr int tt = decltype(t_tag)::value;
+        load_quarter(tt, rd);
+    };
+
     // ------------------------------------------------------------------------------------------------ consumer
+    // n_tiles tiles first_vb, first_vb + gridDim.x, ..., each wave multiplying WI blocks of 32 weight rows: WBN of them
+    // (the whole tile), or fewer, starting at weight row first_col of the panel.  The group buffer at rd holds the first
+    // group of the first tile when this is entered.
+    auto run_tiles = [&](auto wi_tag, const uint32_t first_vb, const uint32_t n_tiles, const uint32_t first_col) __attribute__((always_inline)) {
+    constexpr int WI = decltype(wi_tag)::value;
+    constexpr int kMfma = WB * WI;  // matrix-core instructions of a phase
     // lane (r, kg) of block b reads piece 2 q + kg of row 32 b + r at step q of a group
     struct Step {
-        uint4 A[WB], W[WBN];
+        uint4 A[WB], W[WI];
     };
     auto fetch = [&](const int q, const uint32_t buf, Step &d) __attribute__((always_inline)) {
         const uint32_t ln = opaque(tid) & 63u;
         const uint32_t r = ln & 31u, kg = ln >> 5;
         const uint32_t piece = ((kg ^ (r & 7u)) << 4) ^ (uint32_t)(q << 5);
         const uint8_t *pa = lds + (buf + (uint32_t)(wm * WTILE * kRowBytes) + r * (uint32_t)kRowBytes + piece);
-        const uint8_t *pw = lds + (buf + (uint32_t)(kPanelBytes + wn * WTN * kRowBytes) + r * (uint32_t)kRowBytes + piece);
+        const uint8_t *pw = lds + (buf + (uint32_t)kPanelBytes + (first_col + (uint32_t)(wn * 32 * WI)) * (uint32_t)kRowBytes +
+                                   r * (uint32_t)kRowBytes + piece);
 #pragma unroll
         for (int b = 0; b < WB; ++b) d.A[b] = *reinterpret_cast<const uint4 *>(pa + b * (32 * kRowBytes));
 #pragma unroll
-        for (int b = 0; b < WBN; ++b) d.W[b] = *reinterpret_cast<const uint4 *>(pw + b * (32 * kRowBytes));
+        for (int b = 0; b < WI; ++b) d.W[b] = *reinterpret_cast<const uint4 *>(pw + b * (32 * kRowBytes));
     };
 
-    v16f acc[WBN][WB];  // [n block][m block]
-    int32_t ra[WB], rw[WBN];
+    v16f acc[WI][WB];  // [n block][m block]
+    int32_t ra[WB], rw[WI];
     auto clear = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int j = 0; j < WB; ++j) ra[j] = 0;
 #pragma unroll
-        for (int i = 0; i < WBN; ++i) {
+        for (int i = 0; i < WI; ++i) {
             rw[i] = 0;
 #pragma unroll
             for (int j = 0; j < WB; ++j)
@@ -226,7 +283,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     // An E2M1 operand of the instruction is four registers; the builtin's operand type has eight, of which the upper
     // four are left undefined (the instruction does not read them in this format), so that they occupy nothing.
     struct Frags {
-        v4i a[WB], w[WBN];
+        v4i a[WB], w[WI];
     };
     auto widen = [](const v4i &x) __attribute__((always_inline)) { return __builtin_shufflevector(x, x, 0, 1, 2, 3, -1, -1, -1, -1); };
     // Phase t of a step multiplies bit t of every nibble of the lane's four words (32 of its 128 elements of k; both
@@ -242,7 +299,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             for (int j = 0; j < 4; ++j) f.a[b][j] = (int)(word_of(c.A[b], j) & mask);
         }
 #pragma unroll
-        for (int b = 0; b < WBN; ++b) {
+        for (int b = 0; b < WI; ++b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) f.w[b][j] = (int)(word_of(c.W[b], j) & mask);
         }
@@ -252,7 +309,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     // the same number of vector-ALU instructions: a phase that carries more than its matrix-core instructions cover
     // stalls the one wave of the SIMD.
     struct Shifted {
-        uint32_t a[WB][4], w[WBN][4];
+        uint32_t a[WB][4], w[WI][4];
     };
     auto shift_part = [&](const Step &c, const int part, Shifted &sh) __attribute__((always_inline)) {
 #pragma unroll
@@ -261,7 +318,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             for (int j = 0; j < 4; ++j)
                 if ((b * 4 + j) % 3 == part) sh.a[b][j] = word_of(c.A[b], j) >> 2;
 #pragma unroll
-        for (int b = 0; b < WBN; ++b)
+        for (int b = 0; b < WI; ++b)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 if ((WB * 4 + b * 4 + j) % 3 == part) sh.w[b][j] = word_of(c.W[b], j) >> 2;
@@ -273,7 +330,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             for (int j = 0; j < 4; ++j) f.a[b][j] = (int)(sh.a[b][j] & 0x22222222u);
         }
 #pragma unroll
-        for (int b = 0; b < WBN; ++b) {
+        for (int b = 0; b < WI; ++b) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) f.w[b][j] = (int)(sh.w[b][j] & 0x22222222u);
         }
@@ -288,7 +345,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             asm("" : "+v"(ra[b]));
         }
 #pragma unroll
-        for (int b = 0; b < WBN; ++b) {
+        for (int b = 0; b < WI; ++b) {
             rw[b] += (int32_t)__builtin_popcount(word_of(c.W[b], tt));
             asm("" : "+v"(rw[b]));
         }
@@ -298,7 +355,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     auto multiply = [&](const Frags &f, auto t_tag) __attribute__((always_inline)) {
         constexpr int tt = decltype(t_tag)::value;
 #pragma unroll
-        for (int i = 0; i < WBN; ++i)
+        for (int i = 0; i < WI; ++i)
 #pragma unroll
             for (int j = 0; j < WB; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(f.w[i]), widen(f.a[j]), acc[i][j], 4, 4, tt, scales, tt, scales);
@@ -328,11 +385,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
                 expand(n, 0, gnext);
             multiply(f, t_tag);
             // vector-ALU instructions of this phase: 4 masks per row, its share of the shifts and of the counts
-            constexpr int kRows = WB + WBN;
+            constexpr int kRows = WB + WI;
             constexpr int kShifts = tt < 3 ? (4 * kRows + 2 - tt) / 3 : 0;
             constexpr int kOps = kRows * 4 + kShifts + (tt == 2 ? 0 : (tt == 3 ? 2 * kRows : kRows));
             if (tt == 0)
-                phase_groups<kOps + 8, WB + WBN, 0, 0>(std::make_integer_sequence<int, kMfma>{});
+                phase_groups<kOps + 8, WB + WI, 0, 0>(std::make_integer_sequence<int, kMfma>{});
             else
                 phase_groups<kOps, 0, 0, 0>(std::make_integer_sequence<int, kMfma>{});
             __builtin_amdgcn_sched_barrier(0);
@@ -346,57 +403,25 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 
     // thresholds / flip flags of the tile being finished, straight into this wave's LDS tables
     auto load_thresholds = [&](const int64_t n_wave) __attribute__((always_inline)) {
-        if constexpr (kSign) load_thresholds_to_lds<WBN>(g, n_wave, thr_table[wave], flip_table[wave]);
+        if constexpr (kSign) load_thresholds_to_lds<WI>(g, n_wave, thr_table[wave], flip_table[wave]);
     };
 
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
-        wave_finish<kSign, WBN, kLoadsPerGroup>(g, mc, acc, ra, rw, rw_table[wave], thr_table[wave], flip_table[wave],
+        wave_finish<kSign, WI, kLoadsPerGroup>(g, mc, acc, ra, rw, rw_table[wave], thr_table[wave], flip_table[wave],
                                                 stage[wave], m_wave, n_wave);
     };
 
-    // workgroup barrier of the group buffers: this wave's loads to LDS have landed and its LDS reads have returned
-    // The group needed next was loaded kBuffers - 1 groups ago; the loads of the kBuffers - 2 groups after it may stay
-    // in flight (loads complete in order, so waiting until at most that many are outstanding means the older ones have
-    // landed).
-    constexpr int kPending = kLoadsPerGroup * (kBuffers - 2);
-    static_assert(kPending < 64, "vmcnt is a 6-bit counter");
-    auto panel_barrier = [&]() __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(kPending) : "memory");
-    };
-    auto first_barrier = [&]() __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
-    };
-
-    // ------------------------------------------------------------------------------------------------ prologue
-    // the first groups into the buffers; the cursor stays at the last of them
-    p_locate();
-#pragma unroll 1
-    for (int b = 0; b < kBuffers; ++b) {
-        if (b > 0) p_advance();
-#pragma unroll
-        for (int q = 0; q < 4; ++q) load_quarter(q, (uint32_t)(b * kGroupBytesT));
-    }
-    first_barrier();
-
     Step buf0, buf1;
     Frags frags;
-    uint32_t rd = 0u;  // byte offset of the group buffer being consumed
     fetch(0, rd, buf0);
     expand(buf0, 0, frags);
 
-    auto no_produce = [](auto) __attribute__((always_inline)) {};
-    // Fourth step of a group (after the barrier, the buffer just consumed is free): phase t starts the loads of
-    // quarter t of the group kBuffers groups ahead into it.
-    auto produce = [&](auto t_tag) __attribute__((always_inline)) {
-        constexpr int tt = decltype(t_tag)::value;
-        load_quarter(tt, rd);
-    };
-
-    uint32_t vb = blockIdx.x;
-    while (true) {
+    uint32_t vb = first_vb;
+    for (uint32_t done = 0; done < n_tiles; ++done, vb += gridDim.x) {
         uint32_t tile_m, tile_n;
         tile_of_block(vb, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
-        const int64_t m_wave = (int64_t)tile_m * BM + wm * WTILE, n_wave = (int64_t)tile_n * BNt + wn * WTN;
+        const int64_t m_wave = (int64_t)tile_m * BM + wm * WTILE;
+        const int64_t n_wave = (int64_t)tile_n * BNt + (int64_t)first_col + wn * 32 * WI;
         clear();
         // one group of four steps; kLastGroup: its last step ends the tile
         auto group = [&](auto last_tag) __attribute__((always_inline)) {
@@ -421,14 +446,18 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         group(std::true_type{});
         finish(m_wave, n_wave);
         expand(buf0, 0, frags);
-        vb += gridDim.x;
-        if (vb >= total_tiles) break;
+    }
+    };
+
+    run_tiles(std::integral_constant<int, WBN>{}, vb0, n_mine, 0u);
+    if constexpr (kTail) {
+        if (has_half) run_tiles(std::integral_constant<int, WBN / 2>{}, tail_vb, 1u, half_col);
     }
 }
 
 typedef void (*KernelFn)(const GemmArgs, const MfmaConst, uint32_t, uint32_t, uint32_t);
-// narrow: the 256 x 128 workgroup tile
-KernelFn find_kernel(bool sign, bool narrow);
+// narrow: the 256 x 128 workgroup tile; tail: the wide tile with the last round's tiles taken as halves by two workgroups each
+KernelFn find_kernel(bool sign, bool narrow, bool tail);
 
 }  // namespace panel
 }  // namespace qnn

@@ -109,6 +109,11 @@ int launch_gemm_stage(const GemmArgs &g, hipStream_t s);
 // Expansion of packed +-1 weights (N rows of K elements) to one int8 per element (row pitch ld_out, a multiple of 128,
 // zeros beyond K) and rw_scaled[n] = 128 * (sum of the weights of row n): operands of the uint8-input kernel.
 namespace bytes_panel {
+// Bit planes of both operands of `g` merged to one int8 per element (rows of ld_out bytes, a multiple of 128, zeros
+// beyond K): value = scale_of_operand * int8, and `scale` returns the product of the two operands' factors.
+// merge_supports: whether the values of both operands fit int8.
+bool merge_supports(const Planes &pa, const Planes &pw);
+int launch_merge_planes(const GemmArgs &g, int8_t *outA, int8_t *outW, int64_t ld_out, int64_t &scale, hipStream_t s);
 int launch_expand_weights(const uint32_t *W, int64_t N, int64_t K, int64_t ldw, int8_t *out, int64_t ld_out, int32_t *rw_scaled,
                           hipStream_t s);
 }

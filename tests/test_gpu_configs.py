@@ -212,8 +212,9 @@ def test_many_tiles_short_k_threshold_output(seed, M, N, K, engine):
 # K a multiple of 1024 and 16-byte aligned rows: the kernel that is fed from LDS panels.  (4000, 8100): 16 x 32 tiles of
 # 256 x 256, two per workgroup, ragged on both edges; (4200, 4360): 17 x 35 tiles of 256 x 128 (chosen because 17 x 18
 # large tiles would leave 40 % of the second round idle); (1000, 700): fewer tiles than workgroups, three groups of K;
-# (6000, 8500): 24 x 34 tiles, three or four per workgroup.
-PANEL_TILES = [(4000, 8100, 1024), (4200, 4360, 2048), (1000, 700, 3072), (6000, 8500, 1024)]
+# (6000, 8500): 24 x 34 tiles, three or four per workgroup; (5000, 7000) with K = 4096: 20 x 28 = 560 tiles of
+# 256 x 256, two whole rounds of 256 workgroups and 48 tiles that are halved and shared out among 96 workgroups.
+PANEL_TILES = [(4000, 8100, 1024), (4200, 4360, 2048), (1000, 700, 3072), (6000, 8500, 1024), (5000, 7000, 4096)]
 
 
 @pytest.mark.parametrize("engine", [0, FP4])
@@ -286,6 +287,41 @@ def test_many_tiles_int4_times_int4(seed, engine):
                               dev(np_pack_bits(oracle.split_planes(w, 4))), coef, q.PLANE_BIT, K, engine=engine)
     check_engine(engine or 0, MFMA_LDS)
     assert_same(host(got), oracle.gemm_int(a, w))
+
+
+# Large products of multi-plane operands with int32 output: the library merges the planes of both operands to int8
+# values once per call and multiplies bytes.  Coefficients with a common factor that is not a power of two, both plane
+# modes, eight planes, K that is not a multiple of 32, ragged tiles on both edges.
+MERGED = [(1100, 1000, 2000, [3, -6, 15], 1, [5, 10], 0),
+          (1300, 1400, 1237, [1, 2, 4, 8, 16, 32, 64, -128], 0, [1], 1),
+          (2100, 1300, 800, [1, 2, 4, -8], 0, [-7, 2, 1], 1),
+          (1024, 1024, 2048, [64, 32, 16], 1, [1, 2], 0)]
+
+
+@pytest.mark.parametrize("engine", [None, MFMA_LDS])
+@pytest.mark.parametrize("M,N,K,ca,modeA,cw,modeW", MERGED)
+def test_large_multi_plane_products_merged_to_bytes(seed, M, N, K, ca, modeA, cw, modeW, engine):
+    pa = qi.bernoulli_bits(seed, 86, (len(ca), M, K))
+    pw = qi.bernoulli_bits(seed, 87, (len(cw), N, K))
+    want = oracle.gemm_planes(pa, ca, modeA, pw, cw, modeW)
+    got = q.qnn_bitplane_gemm(dev(np_pack_bits(pa)), ca, modeA, dev(np_pack_bits(pw)), cw, modeW, K, engine=engine)
+    if engine is not None:
+        check_engine(engine, MFMA_LDS)
+    assert_same(host(got), want)
+
+
+def test_large_multi_plane_product_whose_values_exceed_a_byte(seed):
+    """127 b0 + 2 b1 reaches 129: no int8 value and no power-of-two code, so the library's choice falls on another
+    engine, with the same result."""
+    M, N, K = 1100, 1000, 2000
+    pa = qi.bernoulli_bits(seed, 88, (2, M, K))
+    pw = qi.bernoulli_bits(seed, 89, (2, N, K))
+    ca, cw = [127, 2], [1, -1]
+    want = oracle.gemm_planes(pa, ca, 0, pw, cw, 1)
+    got = q.qnn_bitplane_gemm(dev(np_pack_bits(pa)), ca, 0, dev(np_pack_bits(pw)), cw, 1, K)
+    assert_same(host(got), want)
+    with pytest.raises(q.QnnError):
+        q.qnn_bitplane_gemm(dev(np_pack_bits(pa)), ca, 0, dev(np_pack_bits(pw)), cw, 1, K, engine=MFMA_LDS)
 
 
 @pytest.mark.parametrize("Cin,auto", [(64, MFMA), (128, MFMA_LDS)])
