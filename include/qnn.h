@@ -60,9 +60,10 @@ typedef enum {
     QNN_ENGINE_MFMA = 2, /* bits expanded on chip to int8 and contracted on the matrix cores */
     QNN_ENGINE_MFMA_FP4 = 3, /* single-plane operands expanded to FP4 zeros and ones, contracted on the matrix cores
                                 with fp32 accumulation (exact: the sums are integers far below 2^24) */
-    QNN_ENGINE_MFMA_LDS = 4 /* as QNN_ENGINE_MFMA for operands of several bit planes: a workgroup merges the planes
-                               into int8 once, in LDS (16-byte aligned operands with rows of whole groups of four
-                               words, plane counts 1, 2, 4 or 8, coefficients a common factor times 1, 2, 4, ...) */
+    QNN_ENGINE_MFMA_LDS = 4 /* as QNN_ENGINE_MFMA for operands of several bit planes, merged into int8 once: per
+                               workgroup in LDS (16-byte aligned operands with rows of whole groups of four words,
+                               plane counts 1, 2, 4 or 8, coefficients a common factor times 1, 2, 4, ...), or, for
+                               large products with int32 output, per call in memory (see qnn_bitplane_gemm) */
 } qnn_engine;
 
 #define QNN_MAX_PLANES 8
@@ -105,7 +106,12 @@ int qnn_binary_gemm_sign(const uint32_t *A, int64_t lda_words, const uint32_t *W
  * C = sum_{i<Pa} sum_{j<Pb} coefA[i] * coefW[j] * (A_i . W_j^T), plane entries read according to modeA / modeW.
  * A_i = A + i * strideA_words is [M][lda_words]; W_j = W + j * strideW_words is [N][ldw_words].
  * coefA, coefW: HOST int32 arrays (e.g. 1,2,4,...,128 for 8-bit unsigned inputs; 1,2,4,-8 for 4-bit two's
- * complement).  1 <= Pa, Pb <= QNN_MAX_PLANES.  QNN_ERR_OVERFLOW if (sum|coefA|)(sum|coefW|) K >= 2^31. */
+ * complement).  1 <= Pa, Pb <= QNN_MAX_PLANES.  QNN_ERR_OVERFLOW if (sum|coefA|)(sum|coefW|) K >= 2^31.
+ * Large products (M, N >= 256, K >= 512, M N K >= 2^31) of multi-plane operands whose values fit int8 are computed
+ * from the values: both operands' planes are merged to one byte per element in temporary device memory of
+ * (M + N) * roundup(K, 128) bytes that the call takes from, and returns to, the memory pool of `stream`
+ * (hipMallocAsync / hipFreeAsync: stream-ordered, no synchronization); QNN_ERR_HIP if the pool cannot supply it.
+ * qnn_binary_backward's two products are of this kind. */
 int qnn_bitplane_gemm(const uint32_t *A, int Pa, const int32_t *coefA, int modeA, int64_t lda_words,
                       int64_t strideA_words, const uint32_t *W, int Pb, const int32_t *coefW, int modeW,
                       int64_t ldw_words, int64_t strideW_words, int32_t *C, int64_t ldc, int64_t M, int64_t N,
