@@ -304,10 +304,17 @@ def test_large_multi_plane_products_merged_to_bytes(seed, M, N, K, ca, modeA, cw
     pa = qi.bernoulli_bits(seed, 86, (len(ca), M, K))
     pw = qi.bernoulli_bits(seed, 87, (len(cw), N, K))
     want = oracle.gemm_planes(pa, ca, modeA, pw, cw, modeW)
-    got = q.qnn_bitplane_gemm(dev(np_pack_bits(pa)), ca, modeA, dev(np_pack_bits(pw)), cw, modeW, K, engine=engine)
+    # padded row pitches, plane strides beyond the rows used, padded output pitch
+    Kw = (K + 31) // 32
+    A = dev(np_pack_bits(np.concatenate([pa, pa[:, :3]], axis=1), Kw + 3))[:, :M, :Kw]
+    W = dev(np_pack_bits(np.concatenate([pw, pw[:, :2]], axis=1), Kw + 1))[:, :N, :Kw]
+    out = torch.full((M, N + 5), -7, dtype=torch.int32, device="cuda")
+    q.qnn_bitplane_gemm(A, ca, modeA, W, cw, modeW, K, out=out[:, :N], engine=engine)
     if engine is not None:
         check_engine(engine, MFMA_LDS)
-    assert_same(host(got), want)
+    got = host(out)
+    assert (got[:, N:] == -7).all()
+    assert_same(got[:, :N], want)
 
 
 def test_large_multi_plane_product_whose_values_exceed_a_byte(seed):
