@@ -270,6 +270,55 @@ def main():
         jobs.append((2, job_bwd))
 
     if "c4" in only:
+        # Binarized ConvNet forward (Alg. 4) on the CIFAR-10 architecture of App. A: 2 x 128C3 - MP2 - 2 x 256C3 - MP2 -
+        # 2 x 512C3 - MP2 - 1024FC - 1024FC - 10, 32 x 32 RGB images (8-bit), batch 256; logits of sampled images
+        # against the oracle (images of a batch are independent)
+        Bn, Hn = 256, 32
+        couts, pools, fcs = [128, 128, 256, 256, 512, 512], [0, 1, 0, 1, 0, 1], [1024, 1024, 10]
+        xn = qi.uniform_int(seed, 80, (Bn, Hn, Hn, 3), 0, 255, dtype=np.uint8)
+        conv_w, cin = [], 3
+        for l, co in enumerate(couts):
+            conv_w.append(qi.pm1(seed, 81 + l, (co, 3, 3, cin)))
+            cin = co
+        fc_w, fin = [], (Hn // 8) * (Hn // 8) * cin
+        for j, fo in enumerate(fcs):
+            fc_w.append(qi.pm1(seed, 90 + j, (fo, fin)))
+            fin = fo
+        widths = couts + fcs[:-1]
+        Tn = [qi.uniform_int(seed, 100 + l, (wd,), -(3000 if l == 0 else 40), 3000 if l == 0 else 40) for l, wd in enumerate(widths)]
+        Fn = [qi.bernoulli_bits(seed, 110 + l, (wd,)) for l, wd in enumerate(widths)]
+        idxn = np.array([0, 100, Bn - 1])
+        wantn = oracle.convnet(xn[idxn], conv_w, pools, fc_w, Tn, Fn)
+        Xn = dev(xn)
+        Wn = [dev(np_pack_pm1(w)) for w in conv_w] + [dev(np_pack_pm1(w)) for w in fc_w]
+        Tnd, Fnd = [dev(t) for t in Tn], [dev(f) for f in Fn]
+        wsn = torch.empty(q.qnn_binary_convnet_workspace_bytes(Bn, Hn, Hn, 3, 8, couts, pools, fcs), dtype=torch.uint8, device="cuda")
+        lgn = torch.empty((Bn, 10), dtype=torch.int32, device="cuda")
+        # multiply-accumulates of the network per image
+        macs, hh, cc = 0, Hn, 3
+        for co, pl in zip(couts, pools):
+            macs += hh * hh * 9 * cc * co
+            cc = co
+            hh = hh // 2 if pl else hh
+        fin = hh * hh * cc
+        for fo in fcs:
+            macs += fin * fo
+            fin = fo
+
+        def job_convnet():
+            msn = time_secondary(lambda: q.qnn_binary_convnet_forward(Xn, 8, couts, pools, fcs, Wn, Tnd, Fnd, logits=lgn, workspace=wsn,
+                                                                      engine=engine or 0), 20, 5)
+            engs = q.qnn_last_engines()
+            ok = np.array_equal(lgn[idxn].cpu().numpy(), wantn)
+            extra["convnet_cifar10_forward_batch256"] = {
+                "parity_sample_ok": bool(ok), "ms": msn if ok else None, "images_per_s": Bn / (msn * 1e-3) if ok else None,
+                "engines_per_layer": [ENGINE_NAMES.get(e, str(e)) for e in engs],
+                "effective_integer_tmacs": Bn * macs / (msn * 1e-3) / 1e12 if ok else None,
+                "macs_per_image": macs}
+
+        jobs.append((2, job_convnet))
+
+    if "c4" in only:
         # Sec. 5, repetition of binary 2-D filters, on a layer of the CIFAR-10 ConvNet of App. A (128 -> 128 channels,
         # 3 x 3, 32 x 32 maps, batch 16, +-1 activations held as 2-bit codes so that zero padding is exact): the
         # convolution through the distinct filters against the direct one, and the fraction of filter applications left

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(PKG, "_build")
 LIB = os.path.join(PKG, "libqnn.so")
-SOURCES = ["qnn_api.hip", "qnn_probe.hip", "qnn_pack.hip", "qnn_quant.hip", "qnn_dedup.hip", "qnn_gemm_valu.hip", "qnn_gemm_mfma.hip", "qnn_gemm_mfma_k0.hip",
+SOURCES = ["qnn_api.hip", "qnn_probe.hip", "qnn_pack.hip", "qnn_quant.hip", "qnn_dedup.hip", "qnn_conv_first.hip", "qnn_gemm_valu.hip", "qnn_gemm_mfma.hip", "qnn_gemm_mfma_k0.hip",
            "qnn_gemm_mfma_k1.hip", "qnn_gemm_mfma_k2.hip", "qnn_gemm_mfma_k3.hip", "qnn_gemm_mfma_k4.hip", "qnn_gemm_stage_k0.hip",
            "qnn_gemm_stage_k1.hip", "qnn_gemm_stage_k2.hip", "qnn_gemm_panel_k0.hip", "qnn_gemm_bytes_panel_k0.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")

@@ -643,7 +643,7 @@ int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int mod
 namespace {
 constexpr int kMaxNetLayers = 2 * QNN_MAX_LAYERS;
 struct NetStep {
-    enum Kind { kPack, kFlags, kOnes, kGemm, kPool } kind;
+    enum Kind { kPack, kFlags, kOnes, kGemm, kPool, kFirstConv } kind;
     GemmArgs g;      // kGemm (convolution or fully connected)
     int engine;      // kGemm
     // kPack / kFlags / kOnes / kPool operands
@@ -656,6 +656,7 @@ struct NetStep {
 };
 struct NetPlan {
     int n;
+    FlagJobs flags;  // kFlags: every layer's flip flags, one launch
     NetStep step[6 * kMaxNetLayers + 4];
 };
 
@@ -723,8 +724,7 @@ int run_net(const NetPlan &plan, hipStream_t s) {
                                            static_cast<uint32_t *>(st.dst), st.b, st.rows * st.b, s);
                 break;
             case NetStep::kFlags:
-                rc = launch_flags(static_cast<const uint8_t *>(st.src), st.n, static_cast<uint32_t *>(st.dst),
-                                  static_cast<uint8_t *>(st.dst2), s);
+                rc = launch_flags(plan.flags, s);
                 break;
             case NetStep::kOnes:
                 rc = launch_ones_plane(static_cast<uint32_t *>(st.dst), st.rows, st.a, st.b, s);
@@ -732,9 +732,19 @@ int run_net(const NetPlan &plan, hipStream_t s) {
             case NetStep::kGemm:
                 rc = launch_on(st.g, st.engine, s);
                 break;
+            case NetStep::kFirstConv:
+                // src = image, mask = weights, dst = output bits; rows = B, a / b / c = H / W / C0, n = filters;
+                // the thresholds and flips travel in g.epi
+                rc = launch_conv_first(static_cast<const uint8_t *>(st.src), st.rows, st.a, st.b, st.c, st.mask, st.n, st.g.epi.T,
+                                       st.g.epi.flip, static_cast<uint32_t *>(st.dst), static_cast<uint32_t *>(st.dst2), st.g.epi.ldo, s);
+                if (rc == QNN_OK) {
+                    g_last_engine = QNN_ENGINE_MFMA;
+                    if (g_engine_count < 2 * QNN_MAX_LAYERS) g_engines[g_engine_count++] = QNN_ENGINE_MFMA;
+                }
+                break;
             case NetStep::kPool:
                 rc = launch_pool_bits(static_cast<const uint32_t *>(st.src), st.rows, st.a, st.b, st.c, st.mask, st.invert,
-                                      static_cast<uint32_t *>(st.dst), s);
+                                      static_cast<uint32_t *>(st.dst), static_cast<uint32_t *>(st.dst2), (int)st.n, s);
                 break;
         }
         if (rc) return rc;
@@ -786,17 +796,20 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
         return rc;
     };
     // per-layer flags: packed flip bits (for the pooling) and inverted flip bytes (for layers that emit plane 1)
+    plan.flags.count = n_layers - 1;
     for (int l = 0; l < n_layers - 1; ++l) {
-        NetStep &st = push();
-        st.kind = NetStep::kFlags;
-        st.src = flip ? flip[l] : nullptr;
-        st.n = l < n_conv ? cout[l] : fc_out[l - n_conv];
-        st.dst = ws + L.flag_bits[l];
-        st.dst2 = ws + L.flag_inv[l];
+        plan.flags.flip[l] = flip ? flip[l] : nullptr;
+        plan.flags.n[l] = l < n_conv ? cout[l] : fc_out[l - n_conv];
+        plan.flags.bits[l] = words(L.flag_bits[l]);
+        plan.flags.inv[l] = ws + L.flag_inv[l];
     }
-    // the input's bit planes (Sec. 2.6): [in_bits][pixels][words per pixel]
+    if (n_layers > 1) push().kind = NetStep::kFlags;
+    // The first convolution multiplies the 8-bit codes themselves when a pixel's patch fits one matrix-core operand
+    // row (three channels or fewer); otherwise, and when another engine is asked for, it goes through the input's
+    // bit planes (Sec. 2.6): [in_bits][pixels][words per pixel]
+    const bool first_direct = (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA) && conv_first_supports(C0, cout[0], 3, 3, 1, 1);
     const int64_t Cw0 = words_for(C0);
-    {
+    if (!first_direct) {
         NetStep &st = push();
         st.kind = NetStep::kPack;
         st.src = x, st.dst = ws + L.planes0;
@@ -824,10 +837,18 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
         NetStep &st = push();
         st.kind = NetStep::kGemm;
         const Epilogue e{nullptr, 0, T[l], fl, conv_dst, Cwo};
+        if (l == 0 && first_direct) {
+            st.kind = NetStep::kFirstConv;
+            st.src = x, st.mask = W[0], st.dst = conv_dst;
+            st.dst2 = (inverted && !pool[l]) ? kept : nullptr;  // the ones plane of an unpooled output, written alongside
+            st.rows = B, st.a = (int)H, st.b = (int)Wd, st.c = (int)C0, st.n = co;
+            st.g.epi = e;
+        } else {
         if (int rc = conv_args(a_planes, a_count, a_coef, QNN_PLANE_BIT, a_stride, B, h, w, cin, W[l], 1, kOne, QNN_PLANE_SIGN, 0,
                                co, 3, 3, 1, 1, e, engine, st.g, empty))
             return rc;
         if (int rc = choose(st.g, st.engine)) return rc;
+        }
         if (pool[l]) {
             NetStep &pl = push();
             pl.kind = NetStep::kPool;
@@ -835,8 +856,10 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
             pl.rows = B, pl.a = (int)h, pl.b = (int)w, pl.c = (int)Cwo;
             pl.mask = words(L.flag_bits[l]);
             pl.invert = inverted;
+            pl.dst2 = inverted ? kept : nullptr;  // the ones plane of the pooled output, written alongside
+            pl.n = co;
         }
-        if (inverted) {
+        if (inverted && !pool[l] && !(l == 0 && first_direct)) {
             NetStep &on = push();
             on.kind = NetStep::kOnes;
             on.dst = kept, on.rows = B * ho * wo, on.a = (int)Cwo, on.b = (int)co;

@@ -123,9 +123,25 @@ int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv
 int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
                           uint32_t *out, int64_t ldo, hipStream_t s);
 
+// First convolution of a ConvNet straight from a uint8 image with at most three channels (3 x 3, pad 1, stride 1,
+// threshold output packed along the filters): whether the kernel takes the shape, and its launch.
+bool conv_first_supports(int64_t C0, int64_t N, int KH, int KW, int pad, int stride);
+// ones (may be null): also writes the "inside the image" plane of the output map, [pixels][ldo] like `out`.
+int launch_conv_first(const uint8_t *x, int64_t B, int H, int Wd, int C0, const uint32_t *W, int64_t N, const int32_t *T,
+                      const uint8_t *flip, uint32_t *out, uint32_t *ones, int64_t ldo, hipStream_t s);
+
+// ones (may be null) receives the "inside the image" plane of the pooled map (first C bits of every pixel set)
 int launch_pool_bits(const uint32_t *in, int64_t B, int H, int Wd, int Cw, const uint32_t *use_and, bool invert_all,
-                     uint32_t *out, hipStream_t s);
-int launch_flags(const uint8_t *flip, int64_t n, uint32_t *out_bits, uint8_t *out_inv, hipStream_t s);
+                     uint32_t *out, uint32_t *ones, int C, hipStream_t s);
+// Flip flags of the layers of a network, turned into packed words and inverted bytes by one launch
+struct FlagJobs {
+    int count;
+    const uint8_t *flip[2 * QNN_MAX_LAYERS];  // may be null: no channel flipped
+    int64_t n[2 * QNN_MAX_LAYERS];
+    uint32_t *bits[2 * QNN_MAX_LAYERS];
+    uint8_t *inv[2 * QNN_MAX_LAYERS];
+};
+int launch_flags(const FlagJobs &jobs, hipStream_t s);
 int launch_ones_plane(uint32_t *out, int64_t rows, int Cw, int C, hipStream_t s);
 
 }  // namespace qnn

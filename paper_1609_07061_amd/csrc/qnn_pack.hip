@@ -310,9 +310,12 @@ __global__ __launch_bounds__(kBlock) void threshold_sign_vec4_kernel(const int32
 // AND where it is (there the maximum sum gives the smallest BatchNorm output).  `use_and` holds one bit per channel
 // (packed like the data) saying which; `invert_all` swaps the roles for maps stored with inverted bits.
 // One thread per output word; in [B][H][W][Cw], out [B][H/2][W/2][Cw].
+// `ones` (may be null): a second output of the same shape that receives the "inside the image" plane of the pooled map,
+// the first C bits of every pixel set (see ones_plane_kernel).
 __global__ __launch_bounds__(kBlock) void pool_bits_kernel(const uint32_t *__restrict__ in, int64_t B, int H, int Wd, int Cw,
                                                            const uint32_t *__restrict__ use_and, uint32_t invert_all,
-                                                           uint32_t *__restrict__ out) {
+                                                           uint32_t *__restrict__ out, uint32_t *__restrict__ ones, int C) {
+    const uint32_t tail = (C % 32) ? ((1u << (C % 32)) - 1u) : 0xFFFFFFFFu;
     const int Ho = H / 2, Wo = Wd / 2;
     const int64_t total = B * Ho * Wo * Cw;
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
@@ -326,15 +329,22 @@ __global__ __launch_bounds__(kBlock) void pool_bits_kernel(const uint32_t *__res
         const uint32_t v00 = src[0], v01 = src[Cw], v10 = src[(int64_t)Wd * Cw], v11 = src[(int64_t)Wd * Cw + Cw];
         const uint32_t m = use_and[c] ^ invert_all;
         out[i] = ((v00 | v01 | v10 | v11) & ~m) | ((v00 & v01 & v10 & v11) & m);
+        if (ones) ones[i] = c == Cw - 1 ? tail : 0xFFFFFFFFu;
     }
 }
 
-// Per-channel flags -> packed words and inverted byte flags (helpers of the ConvNet forward): out_bits[w] bit t =
-// (flip[32 w + t] != 0) for channels below n (flip == nullptr reads as all zero); out_inv[c] = !flip[c].
-__global__ __launch_bounds__(kBlock) void flags_kernel(const uint8_t *__restrict__ flip, int64_t n, uint32_t *__restrict__ out_bits,
-                                                       uint8_t *__restrict__ out_inv) {
+// Per-channel flags -> packed words and inverted byte flags (helpers of the ConvNet forward), for all layers of a
+// network in one launch (blockIdx.y = layer): bits[w] bit t = (flip[32 w + t] != 0) for channels below n (flip ==
+// nullptr reads as all zero); inv[c] = !flip[c].
+__global__ __launch_bounds__(kBlock) void flags_kernel(const FlagJobs jobs) {
+    const int j = blockIdx.y;
+    const uint8_t *flip = jobs.flip[j];
+    const int64_t n = jobs.n[j];
+    uint32_t *out_bits = jobs.bits[j];
+    uint8_t *out_inv = jobs.inv[j];
     const int lane = threadIdx.x & (kWave - 1);
     const int64_t c = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (c - lane >= n) return;  // (whole waves leave: the ballot below sees complete waves only)
     const bool f = (c < n && flip) ? (flip[c] != 0) : false;
     const unsigned long long m = __ballot(f);
     if (c < n) out_inv[c] = f ? 0 : 1;
@@ -415,17 +425,19 @@ int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, c
 }
 
 int launch_pool_bits(const uint32_t *in, int64_t B, int H, int Wd, int Cw, const uint32_t *use_and, bool invert_all,
-                     uint32_t *out, hipStream_t s) {
+                     uint32_t *out, uint32_t *ones, int C, hipStream_t s) {
     const int64_t total = B * (H / 2) * (Wd / 2) * Cw;
     if (total == 0) return QNN_OK;
     return QNN_LAUNCH("pool_bits", pool_bits_kernel, dim3(grid_for(ceil_div(total, (int64_t)kWave))), dim3(kBlock), 0, s, in, B,
-                      H, Wd, Cw, use_and, invert_all ? 0xFFFFFFFFu : 0u, out);
+                      H, Wd, Cw, use_and, invert_all ? 0xFFFFFFFFu : 0u, out, ones, C);
 }
 
-int launch_flags(const uint8_t *flip, int64_t n, uint32_t *out_bits, uint8_t *out_inv, hipStream_t s) {
-    if (n == 0) return QNN_OK;
-    return QNN_LAUNCH("flags", flags_kernel, dim3((unsigned)ceil_div(n, (int64_t)kBlock)), dim3(kBlock), 0, s, flip, n, out_bits,
-                      out_inv);
+int launch_flags(const FlagJobs &jobs, hipStream_t s) {
+    int64_t most = 0;
+    for (int j = 0; j < jobs.count; ++j) most = jobs.n[j] > most ? jobs.n[j] : most;
+    if (jobs.count == 0 || most == 0) return QNN_OK;
+    return QNN_LAUNCH("flags", flags_kernel, dim3((unsigned)ceil_div(most, (int64_t)kBlock), (unsigned)jobs.count), dim3(kBlock), 0, s,
+                      jobs);
 }
 
 int launch_ones_plane(uint32_t *out, int64_t rows, int Cw, int C, hipStream_t s) {

@@ -49,6 +49,8 @@ def _run(q, case, couts, fcs, engine=0, with_flip=True):
     (3, 6, 10, 3, [40, 64], [1, 0], [9, 6, 4]),                    # channel tails inside the network, odd map sizes
     (2, 5, 7, 2, [6], [1], [3]),                                   # odd sizes dropped by the pooling; tiny
     (5, 12, 12, 3, [128, 128, 256], [0, 1, 1], [100, 10]),         # wide enough for the matrix-core kernels
+    (3, 9, 11, 1, [70, 32], [1, 1], [10]),                         # grey images; 99 pixels per image, 70 filters
+    (2, 7, 7, 4, [32, 32], [0, 1], [5]),                           # four input channels: the first layer goes through planes
 ])
 def test_convnet_small(seed, B, H, Wd, C0, couts, pools, fcs, engine):
     import paper_1609_07061_amd as q
@@ -84,4 +86,5 @@ def test_convnet_cifar10_architecture(seed):
     got = _run(q, case, couts, fcs)
     assert np.array_equal(got, want)
     engines = q.qnn_last_engines()
-    assert len(engines) == 9 and engines[0] == 1 and all(e == 4 for e in engines[1:6]), engines
+    # first layer: the byte kernel for images of up to three channels, reported as the matrix-core engine
+    assert len(engines) == 9 and engines[0] == 2 and all(e == 4 for e in engines[1:6]), engines
