@@ -38,41 +38,62 @@ struct FirstConvArgs {
 
 __global__ __launch_bounds__(kFirstThreads) void conv_first_kernel(const FirstConvArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t sW[kFirstMaxN * 32];
-    __shared__ __attribute__((aligned(16))) int32_t sT[kFirstMaxN];
-    __shared__ __attribute__((aligned(16))) int32_t sRw[kFirstMaxN];
+    // per filter: threshold - 1 - 128 sum_k w (the matrix-core sum S meets the threshold iff S > that), and the filter's
+    // flip flag and "exists" flag at the bit its n has in a lane's partial output word (n mod 32 = 8 q + 4 kg + i ->
+    // bit 8 q + i)
+    __shared__ __attribute__((aligned(16))) int32_t sE[kFirstMaxN];
     __shared__ __attribute__((aligned(16))) uint32_t sFlip[kFirstMaxN];
+    __shared__ __attribute__((aligned(16))) uint32_t sLive[kFirstMaxN];
     const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
     const int r = lane & 31, kg = lane >> 5;
     const int C0 = a.C0, ktot = 9 * C0;
     const int Npad = (a.N + 31) / 32 * 32;
-    // the filters as bytes (+1 / -1, 0 beyond the patch and beyond the last filter), their sums times 128, thresholds, flips
-    for (int n = t; n < Npad; n += kFirstThreads) {
-        uint32_t bytes[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
-        int32_t sum = 0;
+    // k / C0 for k < 32 and C0 in 1 .. 3 without a division
+    auto tap_of = [C0](int k) { return C0 == 1 ? k : (C0 == 2 ? k >> 1 : (k * 11) >> 5); };
+    // the filters as bytes (+1 / -1, 0 beyond the patch and beyond the last filter): one 4-byte piece per thread and turn
+    for (int item = t; item < Npad * 8; item += kFirstThreads) {
+        const int n = item >> 3, j = item & 7;
+        uint32_t piece = 0;
         if (n < a.N) {
-            for (int k = 0; k < ktot; ++k) {
-                const int tap = k / C0, c = k - tap * C0;
-                const bool plus = (a.W[(int64_t)n * 9 + tap] >> c) & 1u;
-                bytes[k >> 2] |= (plus ? 0x01u : 0xFFu) << (8 * (k & 3));
-                sum += plus ? 1 : -1;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int k = 4 * j + i;
+                if (k < ktot) {
+                    const int tap = tap_of(k), c = k - tap * C0;
+                    piece |= (((a.W[(int64_t)n * 9 + tap] >> c) & 1u) ? 0x01u : 0xFFu) << (8 * i);
+                }
             }
         }
-        uint4 *dst = reinterpret_cast<uint4 *>(&sW[n * 32]);
-        dst[0] = make_uint4(bytes[0], bytes[1], bytes[2], bytes[3]);
-        dst[1] = make_uint4(bytes[4], bytes[5], bytes[6], bytes[7]);
-        sRw[n] = 128 * sum;
-        sT[n] = n < a.N ? a.T[n] : 0;
-        sFlip[n] = (n < a.N && a.flip && a.flip[n]) ? 1u : 0u;
+        *reinterpret_cast<uint32_t *>(&sW[n * 32 + 4 * j]) = piece;
+    }
+    // per filter: the sum of its weights (2 x set bits - patch size) folded into the threshold, the flags
+    for (int n = t; n < Npad; n += kFirstThreads) {
+        int32_t sum = 0;
+        if (n < a.N) {
+            int32_t set = 0;
+#pragma unroll
+            for (int i = 0; i < 9; ++i) set += __builtin_popcount(a.W[(int64_t)n * 9 + i] & ((1u << C0) - 1u));
+            sum = 2 * set - ktot;
+        }
+        // |S + 128 sum| < 2^16: thresholds beyond +-2^30 decide the same way as +-2^30, and the difference cannot wrap
+        const int32_t tv = n < a.N ? a.T[n] : 0;
+        const int32_t tc = tv < -(1 << 30) ? -(1 << 30) : (tv > (1 << 30) ? (1 << 30) : tv);
+        const uint32_t pos = 1u << ((n & 0x18) | (n & 3));
+        sE[n] = tc - 1 - 128 * sum;
+        sFlip[n] = (n < a.N && a.flip && a.flip[n]) ? pos : 0u;
+        sLive[n] = n < a.N ? pos : 0u;
     }
     __syncthreads();
-    // this lane's 16 elements of k: tap offsets and channel, once
-    int dy[16], dx[16], ch[16];
+    // this lane's 16 elements of k, once:
+    // (dy + 1) | (dx + 1) << 2, or -1 for an element beyond the patch; byte offset from the centre pixel's first channel
+    int tapc[16], off[16];
 #pragma unroll
     for (int j = 0; j < 16; ++j) {
         const int k = 16 * kg + j;
-        const int tap = k / C0;
-        ch[j] = k < ktot ? k - tap * C0 : -1;
-        dy[j] = tap / 3 - 1, dx[j] = tap % 3 - 1;
+        const int tap = tap_of(k), c = k - tap * C0;
+        const int ty = (tap * 11) >> 5, tx = tap - 3 * ty;  // tap / 3 for tap < 32
+        tapc[j] = k < ktot ? (ty | (tx << 2)) : -1;
+        off[j] = ((ty - 1) * a.Wd + (tx - 1)) * C0 + c;
     }
     const int64_t tiles = (a.pixels + 31) / 32;
     const int Nw = Npad / 32;
@@ -83,46 +104,82 @@ __global__ __launch_bounds__(kFirstThreads) void conv_first_kernel(const FirstCo
         const uint32_t rowi = pc / (uint32_t)a.Wd;                // b H + y
         const int x0 = (int)(pc - rowi * (uint32_t)a.Wd);
         const int y0 = (int)(rowi % (uint32_t)a.H);
-        const uint8_t *img = a.x + (int64_t)(rowi - (uint32_t)y0) * a.Wd * C0;  // start of the pixel's image
-        uint32_t av[4] = {0u, 0u, 0u, 0u};
+        const uint8_t *centre = a.x + (int64_t)pc * C0;  // first channel of the pixel itself
+        // which of the three patch rows / columns lie inside the image, as bit masks indexed like tapc
+        const uint32_t rows_in = (y0 > 0 ? 1u : 0u) | 2u | (y0 + 1 < a.H ? 4u : 0u);
+        const uint32_t cols_in = (x0 > 0 ? 1u : 0u) | 2u | (x0 + 1 < a.Wd ? 4u : 0u);
+        // branch-free: an element outside the image (or beyond the patch) reads the pixel's own first byte and is
+        // dropped afterwards, so that the sixteen loads are issued back to back
+        uint32_t got[16];
+        bool in[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int yy = y0 + dy[j], xx = x0 + dx[j];
-            const bool in = ch[j] >= 0 && (unsigned)yy < (unsigned)a.H && (unsigned)xx < (unsigned)a.Wd;
-            const uint32_t v = in ? img[((int64_t)yy * a.Wd + xx) * C0 + ch[j]] : 0u;
-            av[j >> 2] |= v << (8 * (j & 3));
+            in[j] = tapc[j] >= 0 && ((rows_in >> (tapc[j] & 3)) & (cols_in >> (tapc[j] >> 2)) & 1u);
+            got[j] = centre[in[j] ? off[j] : 0];
         }
+        uint32_t av[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int j = 0; j < 16; ++j) av[j >> 2] |= (in[j] ? got[j] : 0u) << (8 * (j & 3));
         v4i af;
 #pragma unroll
         for (int i = 0; i < 4; ++i) af[i] = (int)(av[i] ^ 0x80808080u);
-        for (int nb = 0; nb < Nw; ++nb) {
-            const uint4 wq = *reinterpret_cast<const uint4 *>(&sW[(nb * 32 + r) * 32 + 16 * kg]);
-            v4i wf;
-            wf[0] = (int)wq.x, wf[1] = (int)wq.y, wf[2] = (int)wq.z, wf[3] = (int)wq.w;
-            v16i acc;
+        // four output words (128 filters) at a time, so that a pixel's words leave as one 16-byte store: lanes of the
+        // lower half write the bits, lanes of the upper half the ones plane
+        const bool vec = a.ldo % 4 == 0 && ((reinterpret_cast<uintptr_t>(a.out) | reinterpret_cast<uintptr_t>(a.ones)) & 15u) == 0;
+        for (int nb0 = 0; nb0 < Nw; nb0 += 4) {
+            uint32_t word[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[v] = 0;
-            // acc[v] = sum for pixel r and filter 32 nb + 8 (v / 4) + 4 kg + v mod 4
-            acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, af, acc, 0, 0, 0);
-            uint32_t bits = 0;
+            for (int u = 0; u < 4; ++u) {
+                const int nb = nb0 + u;
+                if (nb >= Nw) break;
+                const uint4 wq = *reinterpret_cast<const uint4 *>(&sW[(nb * 32 + r) * 32 + 16 * kg]);
+                v4i wf;
+                wf[0] = (int)wq.x, wf[1] = (int)wq.y, wf[2] = (int)wq.z, wf[3] = (int)wq.w;
+                v16i acc;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n0 = nb * 32 + 8 * q + 4 * kg;
-                const int4 t4 = *reinterpret_cast<const int4 *>(&sT[n0]);
-                const int4 r4 = *reinterpret_cast<const int4 *>(&sRw[n0]);
-                const uint4 f4 = *reinterpret_cast<const uint4 *>(&sFlip[n0]);
-                const int32_t tv[4] = {t4.x, t4.y, t4.z, t4.w}, rv[4] = {r4.x, r4.y, r4.z, r4.w};
-                const uint32_t fv[4] = {f4.x, f4.y, f4.z, f4.w};
+                for (int v = 0; v < 16; ++v) acc[v] = 0;
+                // acc[v] = sum for pixel r and filter 32 nb + 8 (v / 4) + 4 kg + v mod 4
+                acc = __builtin_amdgcn_mfma_i32_32x32x32_i8(wf, af, acc, 0, 0, 0);
+                uint32_t bits = 0, flips = 0, lives = 0;
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
-                    const uint32_t b = ((acc[4 * q + i] + rv[i] >= tv[i]) ? 1u : 0u) ^ fv[i];
-                    bits |= (n0 + i < a.N ? b : 0u) << (8 * q + 4 * kg + i);
+                for (int q = 0; q < 4; ++q) {
+                    const int n0 = nb * 32 + 8 * q + 4 * kg;
+                    const int4 e4 = *reinterpret_cast<const int4 *>(&sE[n0]);
+                    const uint4 f4 = *reinterpret_cast<const uint4 *>(&sFlip[n0]);
+                    const uint4 l4 = *reinterpret_cast<const uint4 *>(&sLive[n0]);
+                    const int32_t ev[4] = {e4.x, e4.y, e4.z, e4.w};
+                    flips |= f4.x | f4.y | f4.z | f4.w;
+                    lives |= l4.x | l4.y | l4.z | l4.w;
+                    // four bits, most significant first: the sign of e - S (set iff S > e) appended with one funnel shift
+                    uint32_t nib = 0;
+#pragma unroll
+                    for (int i = 3; i >= 0; --i) nib = __builtin_amdgcn_alignbit(nib, (uint32_t)(ev[i] - acc[4 * q + i]), 31);
+                    bits |= nib << (8 * q);
+                }
+                bits = ((bits ^ flips) & lives) << (4 * kg);
+                bits = or_halves(bits);
+                word[u] = bits;
+            }
+            if (!live) continue;
+            uint32_t *dst = nullptr;
+            if (kg == 0) {
+                dst = a.out + p * a.ldo + nb0;
+            } else if (a.ones) {
+                dst = a.ones + p * a.ldo + nb0;
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int nb = nb0 + u;
+                    word[u] = (nb == Nw - 1 && (a.N % 32)) ? ((1u << (a.N % 32)) - 1u) : 0xFFFFFFFFu;
                 }
             }
-            bits = or_halves(bits);
-            if (kg == 0 && live) {
-                a.out[p * a.ldo + nb] = bits;
-                if (a.ones) a.ones[p * a.ldo + nb] = (nb == Nw - 1 && (a.N % 32)) ? ((1u << (a.N % 32)) - 1u) : 0xFFFFFFFFu;
+            if (dst) {
+                if (vec && nb0 + 4 <= Nw) {
+                    *reinterpret_cast<uint4 *>(dst) = make_uint4(word[0], word[1], word[2], word[3]);
+                } else {
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (nb0 + u < Nw) dst[u] = word[u];
+                }
             }
         }
     }
@@ -143,7 +200,7 @@ int launch_conv_first(const uint8_t *x, int64_t B, int H, int Wd, int C0, const 
     const int64_t tiles = ceil_div(a.pixels, 32);
     // a workgroup prepares the filter bytes once and then walks over pixel tiles: a few workgroups per compute unit
     const int64_t blocks = ceil_div(tiles, 4);
-    const unsigned grid = (unsigned)(blocks < 1024 ? blocks : 1024);
+    const unsigned grid = (unsigned)(blocks < 768 ? blocks : 768);  // three workgroups fit a compute unit (LDS, registers)
     return QNN_LAUNCH("conv_first", conv_first_kernel, dim3(grid), dim3(kFirstThreads), 0, s, a);
 }
 
