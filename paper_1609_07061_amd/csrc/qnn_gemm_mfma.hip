@@ -148,7 +148,11 @@ bool mfma_supports(const GemmArgs &g, bool fp4) {
 bool mfma_preferred(const GemmArgs &g) {
     // small or skinny products (a 10-neuron output layer fills 10 of a tile's 256 columns) are better served by the
     // finer tiles of the vector-ALU engine
-    return ceil_div(g.M, BM) * ceil_div(g.N, BN) >= 32 && g.K >= 256 && g.M >= 128 && g.N >= 128;
+    if (ceil_div(g.M, BM) * ceil_div(g.N, BN) >= 32 && g.K >= 256 && g.M >= 128 && g.N >= 128) return true;
+    // single planes with long rows: a few matrix-core tiles beat many vector-ALU tiles (a fully connected layer of 8192
+    // inputs on a batch of 256: 27 us on eight 256 x 128 tiles against 41 us on sixty-four 64 x 64 tiles)
+    return g.pa.count == 1 && g.pw.count == 1 && !g.A.rows_are_pixels && !g.A.rows_are_bytes && g.K >= 4096 && g.M >= 256 &&
+           g.N >= 256;
 }
 
 static int compute_units() {
