@@ -643,7 +643,7 @@ int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int mod
 namespace {
 constexpr int kMaxNetLayers = 2 * QNN_MAX_LAYERS;
 struct NetStep {
-    enum Kind { kPack, kFlags, kOnes, kGemm, kPool, kFirstConv } kind;
+    enum Kind { kPack, kFlags, kOnes, kGemm, kPool, kFirstConv, kConvPanel } kind;
     GemmArgs g;      // kGemm (convolution or fully connected)
     int engine;      // kGemm
     // kPack / kFlags / kOnes / kPool operands
@@ -663,6 +663,7 @@ struct NetPlan {
 struct NetLayout {
     size_t planes0, flags, act[2], tmp, fc[2], total;
     size_t flag_bits[kMaxNetLayers], flag_inv[kMaxNetLayers];
+    size_t class_thr[kMaxNetLayers], zero_line;  // scratch of the convolutions on the panel-fed kernel
 };
 
 // Sizes of the workspace regions; false if the shapes are not valid.
@@ -708,7 +709,9 @@ bool net_layout(int64_t B, int64_t H, int64_t Wd, int64_t C0, int in_bits, int n
         const int64_t n = l < n_conv ? cout[l] : fc_out[l - n_conv];
         L.flag_bits[l] = take((size_t)words_for(n) * 4);
         L.flag_inv[l] = take((size_t)n);
+        L.class_thr[l] = l < n_conv ? take((size_t)16 * (size_t)conv_panel_class_ld(n) * 4) : 0;
     }
+    L.zero_line = take(256);
     L.total = off + 256;
     return true;
 }
@@ -740,6 +743,18 @@ int run_net(const NetPlan &plan, hipStream_t s) {
                 if (rc == QNN_OK) {
                     g_last_engine = QNN_ENGINE_MFMA;
                     if (g_engine_count < 2 * QNN_MAX_LAYERS) g_engines[g_engine_count++] = QNN_ENGINE_MFMA;
+                }
+                break;
+            case NetStep::kConvPanel:
+                // src = plane "value is -1" of the input map, mask = weights, dst = output bits, dst2 = class thresholds;
+                // rows = B, a / b / c = H / W / C, n = filters; thresholds, complemented flips and the output pitch in
+                // g.epi; g.W = the line of zeros
+                rc = launch_conv_panel(static_cast<const uint32_t *>(st.src), st.rows, st.a, st.b, st.c, st.mask, st.n, st.g.epi.T,
+                                       st.g.epi.flip, static_cast<uint32_t *>(st.dst), st.g.epi.ldo, static_cast<int32_t *>(st.dst2),
+                                       const_cast<uint32_t *>(st.g.W), s);
+                if (rc == QNN_OK) {
+                    g_last_engine = QNN_ENGINE_MFMA_FP4;
+                    if (g_engine_count < 2 * QNN_MAX_LAYERS) g_engines[g_engine_count++] = QNN_ENGINE_MFMA_FP4;
                 }
                 break;
             case NetStep::kPool:
@@ -837,7 +852,18 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
         NetStep &st = push();
         st.kind = NetStep::kGemm;
         const Epilogue e{nullptr, 0, T[l], fl, conv_dst, Cwo};
-        if (l == 0 && first_direct) {
+        const bool on_panel = l > 0 && (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA_FP4) &&
+                              conv_panel_supports(B, h, w, cin, co);
+        if (on_panel) {
+            // the map's plane "value is -1" alone; out = (conv >= T) xor fl, and the kernel takes the complement of fl:
+            // the caller's flags where fl is their inversion, the inverted ones where fl is the caller's
+            st.kind = NetStep::kConvPanel;
+            st.src = a_planes + a_stride, st.mask = W[l], st.dst = conv_dst, st.dst2 = ws + L.class_thr[l];
+            st.rows = B, st.a = (int)h, st.b = (int)w, st.c = (int)cin, st.n = co;
+            st.g.epi = e;
+            st.g.epi.flip = inverted ? (flip ? flip[l] : nullptr) : reinterpret_cast<const uint8_t *>(ws + L.flag_inv[l]);
+            st.g.W = words(L.zero_line);
+        } else if (l == 0 && first_direct) {
             st.kind = NetStep::kFirstConv;
             st.src = x, st.mask = W[0], st.dst = conv_dst;
             st.dst2 = (inverted && !pool[l]) ? kept : nullptr;  // the ones plane of an unpooled output, written alongside

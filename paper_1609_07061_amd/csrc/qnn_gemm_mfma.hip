@@ -236,6 +236,57 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
                        (uint32_t)tiles_n);
 }
 
+// ------------------------------------------------------------------------------------------------ convolution on the panel-fed kernel
+bool conv_panel_supports(int64_t B, int64_t H, int64_t Wd, int64_t C, int64_t N) {
+    if (B < 1 || H < 1 || Wd < 1 || H > 32767 || Wd > 32767 || C < 128 || C % 128 || N < 1) return false;
+    const int64_t cpt = C / 128;
+    if (cpt & (cpt - 1)) return false;
+    const int64_t M = B * H * Wd, Cw = C / 32;
+    if (M < 256 || M > 0x7FFFFFFFLL) return false;
+    // 32-bit byte offsets: the plane (plus the distance to the line of zeros, checked at the launch) and the weights
+    if ((long double)(M + 256) * Cw * 4 >= 2147483648.0L || (long double)(N + 256) * 9 * Cw * 4 >= 4294967296.0L) return false;
+    return ceil_div(M, 256) * ceil_div(N, 128) <= 0x7FFFFFFFLL;
+}
+
+int64_t conv_panel_class_ld(int64_t N) { return ceil_div(N, 128) * 128; }
+
+int launch_conv_panel(const uint32_t *plane, int64_t B, int H, int Wd, int C, const uint32_t *W, int64_t N, const int32_t *T,
+                      const uint8_t *flip_complement, uint32_t *out, int64_t ldo, int32_t *class_thr, uint32_t *zero_line,
+                      hipStream_t s) {
+    if (!conv_panel_supports(B, H, Wd, C, N)) return fail(QNN_ERR_UNSUPPORTED, "convolution on the panel-fed kernel: shape not supported");
+    const int Cw = C / 32;
+    const int64_t M = B * H * Wd, ld = conv_panel_class_ld(N);
+    const uint8_t *pa = reinterpret_cast<const uint8_t *>(plane), *pz = reinterpret_cast<const uint8_t *>(zero_line);
+    const uint8_t *base = pa < pz ? pa : pz;
+    const uint64_t a_delta = (uint64_t)(pa - base), z_off = (uint64_t)(pz - base);
+    if (a_delta + (uint64_t)(M + 256) * Cw * 4 >= 4294967296ULL || z_off + 256 >= 4294967296ULL)
+        return fail(QNN_ERR_UNSUPPORTED, "convolution on the panel-fed kernel: scratch too far from the feature map");
+    if (int rc = panel::launch_conv_class_thr(W, N, Cw, C, T, class_thr, ld, zero_line, s)) return rc;
+    GemmArgs g;
+    std::memset(&g, 0, sizeof(g));
+    g.A.base = reinterpret_cast<const uint32_t *>(base);
+    g.A.ld = Cw, g.A.rows_are_pixels = 1;
+    g.A.H = H, g.A.Wd = Wd, g.A.Ho = H, g.A.Wo = Wd, g.A.Cw = Cw, g.A.KH = 3, g.A.KW = 3, g.A.pad = 1, g.A.stride = 1;
+    g.pa.count = 1, g.pa.mode = QNN_PLANE_BIT, g.pa.coef[0] = 1;
+    g.W = W, g.ldw = 9 * Cw, g.pw.count = 1, g.pw.mode = QNN_PLANE_BIT, g.pw.coef[0] = 1;
+    g.epi.T = T, g.epi.flip = flip_complement, g.epi.out_bits = out, g.epi.ldo = ldo;
+    g.M = M, g.N = N, g.K = 9 * (int64_t)C, g.Kw = 9 * Cw;
+    g.class_thr = class_thr, g.class_ld = ld;
+    g.a_delta = (uint32_t)a_delta, g.zero_off = (uint32_t)z_off;
+    g.inv_w = 1.0 / (double)Wd, g.inv_hw = 1.0 / ((double)H * (double)Wd);
+    int sh = 0;
+    while ((1 << sh) < C / 128) ++sh;
+    g.cpt_shift = sh;
+    MfmaConst mc;
+    std::memset(&mc, 0, sizeof(mc));
+    mc.alpha = 4u, mc.alpha_shift = 2, mc.cRA = (uint32_t)-2;  // 4 S - 2 RA (see the kernel)
+    const int64_t tiles_m = ceil_div(M, 256), tiles_n = ceil_div(N, 128), total = tiles_m * tiles_n;
+    const int cus = compute_units();
+    const unsigned grid = (unsigned)(total < cus ? total : cus);
+    return QNN_LAUNCH("conv_panel", panel::conv_kernel(), dim3(grid), dim3(panel::kThreads), 0, s, g, mc, (uint32_t)tiles_m,
+                      (uint32_t)tiles_n, (uint32_t)ceil_div(g.Kw, panel::kGroupWords));
+}
+
 // ------------------------------------------------------------------------------------------------ staged kernels
 namespace {
 

@@ -205,6 +205,88 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs &g, const MfmaConst
     if constexpr (kFast && !kSign) store_lines(WBN - 1, WB - 1);
 }
 
+// Threshold epilogue of the convolution on the panel-fed kernel: the comparison value depends on the pixel's border
+// class (which of the nine taps lie inside the image) as well as on the filter, so it is read per (row block, filter
+// block) from class_thr[class][n] in memory (a table of 16 x N entries, made once per layer) instead of a per-wave
+// LDS table:  bit = (alpha S + cRA RA[m] > class_thr[class(m)][n]) xor flip[n].  flip_tab arrives as in wave_epilogue
+// (flip flags by a load to LDS, followed by kLoadsAfter further loads of that kind); thr_tab is not used.
+template <int WBN, int kLoadsAfter, typename Acc, typename PixelOf>
+__device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, const MfmaConst &mc, Acc (&acc)[WBN][4], int32_t (&ra)[4],
+                                                   int32_t *thr_tab, uint32_t *flip_tab, const int64_t m_wave,
+                                                   const int64_t n_wave, PixelOf pixel_of) {
+    constexpr int WB = 4, WTN = 32 * WBN;
+    (void)thr_tab;
+    const int64_t Nw = (g.N + 31) / 32;
+    int lane_opaque = (int)(threadIdx.x & 63);
+    asm volatile("" : "+v"(lane_opaque));
+    const int lane = lane_opaque, r = lane & 31, kg = lane >> 5;
+#pragma unroll
+    for (int b = 0; b < WB; ++b) ra[b] = sum_halves(ra[b]);
+    int64_t m_of[WB];
+    uint32_t mterm[WB];
+    const int32_t *thr_row[WB];  // class_thr row of the pixel's class, at the wave's first filter
+#pragma unroll
+    for (int bj = 0; bj < WB; ++bj) {
+        m_of[bj] = m_wave + bj * 32 + r;
+        mterm[bj] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
+        const uint32_t m = (uint32_t)(m_of[bj] < g.M ? m_of[bj] : g.M - 1);
+        uint32_t y, x;
+        pixel_of(m, y, x);
+        const uint32_t cls = (y == 0u ? 1u : 0u) | (y == (uint32_t)g.A.H - 1u ? 2u : 0u) | (x == 0u ? 4u : 0u) |
+                             (x == (uint32_t)g.A.Wd - 1u ? 8u : 0u);
+        thr_row[bj] = g.class_thr + (int64_t)cls * g.class_ld + n_wave;
+    }
+    // flip flags at the bit position their n has in a lane's partial output word (as in wave_epilogue)
+    asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kLoadsAfter) : "memory");
+#pragma unroll
+    for (int h = 0; h < WTN / 64; ++h) {
+        const int nl = 64 * h + lane;
+        const uint32_t fv = flip_tab[nl];
+        flip_tab[nl] = fv != 0 ? (1u << ((nl & 0x18) | (nl & 3))) : 0u;
+    }
+    __builtin_amdgcn_s_waitcnt(0xc07f);
+    __builtin_amdgcn_wave_barrier();
+    const int sh = mc.alpha_shift;  // (alpha is a power of two here: 4)
+#pragma unroll
+    for (int bi = 0; bi < WBN; ++bi) {
+        const int64_t n_blk = n_wave + bi * 32;
+        uint32_t flips = 0, live_bits = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint4 f4 = *reinterpret_cast<const uint4 *>(&flip_tab[bi * 32 + 8 * q + 4 * kg]);
+            flips |= f4.x | f4.y | f4.z | f4.w;
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (n_blk + 8 * (v >> 2) + 4 * kg + (v & 3) < g.N) live_bits |= 1u << (8 * (v >> 2) + (v & 3));
+        const int64_t word = n_blk >> 5;
+#pragma unroll
+        for (int bj = 0; bj < WB; ++bj) {
+            uint32_t bits = 0;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                // (the table's rows are padded to whole tiles of filters, so the 16-byte read stays inside)
+                const int4 e4 = *reinterpret_cast<const int4 *>(thr_row[bj] + bi * 32 + 8 * q + 4 * kg);
+                const int32_t e[4] = {e4.x, e4.y, e4.z, e4.w};
+                uint32_t nib = 0;
+#pragma unroll
+                for (int i = 3; i >= 0; --i) {
+                    const uint32_t s32 = acc_to_sum(acc[bi][bj][4 * q + i]);
+                    const uint32_t rest = (s32 << sh) + mterm[bj];
+                    const uint32_t x = (uint32_t)e[i] - rest;  // sign bit set  <=>  rest > e
+                    nib = __builtin_amdgcn_alignbit(nib, x, 31);
+                }
+                bits |= nib << (8 * q);
+            }
+            bits = (bits ^ flips) & live_bits;
+            bits <<= 4 * kg;
+            bits = or_halves(bits);
+            if (kg == 0 && m_of[bj] < g.M && word < Nw) g.epi.out_bits[m_of[bj] * g.epi.ldo + word] = bits;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
+
 // Chooses the epilogue variant for a finished wave tile (interior or edge, scale by shift or by multiplication).
 template <bool kSign, int WBN, int kLoadsAfter, bool kRwInLds = false, typename Acc>
 __device__ __forceinline__ void wave_finish(const GemmArgs &g, const MfmaConst &mc, Acc (&acc)[WBN][4], int32_t (&ra)[4],

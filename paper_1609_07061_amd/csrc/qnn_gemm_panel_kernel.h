@@ -65,7 +65,14 @@ __device__ __forceinline__ void phase_groups(std::integer_sequence<int, I...>) {
 // 256 x 256 tiles would leave a large part of the last round of workgroups idle).
 // kTail (WBN = 4; grid = a multiple of 16 workgroups, fewer than there are tiles, and at most half a grid of tiles in the
 // last round): that round's tiles are taken as halves of 128 columns by two workgroups each.
-template <bool kSign, int WBN, bool kTail = false>
+// kConv (kSign, WBN = 2): the activation rows are the patch rows of a 3 x 3 "same" convolution (pad 1, stride 1) over
+// the plane "value is -1" of a +-1 feature map, channels-last, whole 16-byte pieces of channels per tap (App. A's
+// ConvNet under Alg. 4).  With a = 1 - 2 p inside the image (0 outside) and w = 2 b - 1,
+//   conv = 2 sum_{taps inside} sum_c b  -  (taps inside) C  -  4 sum p b  +  2 sum p,
+// so the kernel multiplies the bits p and b as they are (taps outside the image read a line of zeros), and the part that
+// depends on which taps lie inside, a function of the pixel's border class and the filter, sits in the threshold: the
+// epilogue compares 4 S - 2 RA with class_thr[class][n] (see wave_epilogue_conv).
+template <bool kSign, int WBN, bool kTail = false, bool kConv = false>
 __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                   uint32_t tiles_n, uint32_t ngroups) {
     // Group buffers: activation panel (256 rows) + weight panel (BN rows).  Two take turns; the narrow tile with the
@@ -123,21 +130,74 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     const bool has_half = kTail && tail_vb < total_tiles;
     const uint32_t half_col = ((vb0 >> 3) & 1u) * (uint32_t)(32 * WBN);
     static_assert(!kTail || WBN == 4, "halved tiles in the last round: the wide tile only");
+    static_assert(!kConv || (kSign && WBN == 2 && !kTail), "convolution: threshold output, 256 x 128 tiles");
     uint32_t p_vb = vb0, p_G = 0, p_item = 0;
     // kRowRegs (the narrow tile, whose accumulators leave registers free): one offset register per load, and a copy is
     // all a load needs.  Otherwise one register per panel holds the offset of the lane's row in the first 32-row
     // block, a second one the offset in the operand's last row, and a load adds its block's distance and clamps.
     constexpr bool kRowRegs = WBN == 2;
     uint32_t a_off[kRowRegs ? 8 : 1], w_off[kRowRegs ? BNt / 32 : 1], a_max = 0, w_max = 0;
+    // kConv: a_off = byte offset of the pixel's channels, a_yx = its coordinates (y | x << 16); per group: the byte
+    // offset from the pixel to this lane's piece of the group (tap, part of the tap), the tap's ky | kx << 2 (-1 beyond
+    // the ninth tap), and what to add to w_off (the group's offset; for pieces beyond the end of a weight row, minus
+    // the lane's piece offset: the row's first bytes, which meet zeros on the other side)
+    uint32_t a_yx[kConv ? 8 : 1];
+    uint32_t p_tap_off = 0, p_w_add = 0;
+    int p_tap = -1;
     const uint32_t lda_bytes = (uint32_t)g.A.ld * 4u, ldw_bytes = (uint32_t)g.ldw * 4u;
     const uint32_t last_m = (uint32_t)(g.M - 1), last_n = (uint32_t)(g.N - 1);
+    // (y, x) of output pixel m = (b H + y) Wd + x: quotients through double-precision reciprocals (exact to within one,
+    // then corrected), a dozen instructions instead of two integer divisions
+    auto pixel_of = [&](uint32_t m, uint32_t &y, uint32_t &x) __attribute__((always_inline)) {
+        auto div = [](uint32_t a, uint32_t d, double inv, uint32_t &q, uint32_t &r) __attribute__((always_inline)) {
+            q = (uint32_t)((double)a * inv);
+            int32_t rem = (int32_t)(a - q * d);
+            if (rem < 0) --q, rem += (int32_t)d;
+            if (rem >= (int32_t)d) ++q, rem -= (int32_t)d;
+            r = (uint32_t)rem;
+        };
+        const uint32_t hw = (uint32_t)(g.A.H * g.A.Wd);
+        uint32_t b, rem;
+        div(m, hw, g.inv_hw, b, rem);
+        div(rem, (uint32_t)g.A.Wd, g.inv_w, y, x);
+    };
+    // kConv, per group: this lane's piece of the group at the cursor
+    auto p_piece = [&]() __attribute__((always_inline)) {
+        if constexpr (kConv) {
+            const uint32_t tt = opaque(tid);
+            const uint32_t piece = (tt & 7u) ^ ((tt >> 3) & 7u);
+            const uint32_t q = p_G * 8u + piece;               // piece of the row
+            const uint32_t tap = q >> g.cpt_shift, sub = q - (tap << g.cpt_shift);
+            const uint32_t ky = (tap * 11u) >> 5, kx = tap - 3u * ky;  // tap / 3, tap mod 3 (tap < 32)
+            p_tap = tap < 9u ? (int)(ky | (kx << 2)) : -1;
+            p_tap_off = (uint32_t)(((int)ky - 1) * g.A.Wd + ((int)kx - 1)) * lda_bytes + sub * 16u;
+            const bool in_row = q * 16u < (uint32_t)g.Kw * 4u;
+            p_w_add = in_row ? p_G * (uint32_t)kRowBytes : 0u - piece * 16u;
+        }
+    };
     auto p_locate = [&]() __attribute__((always_inline)) {
         uint32_t tm, tn;
         tile_of_block(p_vb, total_tiles, tiles_m, tiles_n, tm, tn);
         const uint32_t tt = opaque(tid);
         const uint32_t pr = tt >> 3;                                  // row within a load's 32-row block
         const uint32_t piece16 = ((tt & 7u) ^ ((tt >> 3) & 7u)) << 4;  // (slot xor (row mod 8)) * 16 bytes
-        if constexpr (kRowRegs) {
+        if constexpr (kConv) {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                uint32_t m = tm * (uint32_t)BM + (uint32_t)(32 * i) + pr;
+                m = m > last_m ? last_m : m;
+                uint32_t y, x;
+                pixel_of(m, y, x);
+                a_off[i] = m * lda_bytes + g.a_delta;
+                a_yx[i] = y | (x << 16);
+            }
+#pragma unroll
+            for (int i = 0; i < BNt / 32; ++i) {
+                uint32_t n = tn * (uint32_t)BNt + (uint32_t)(32 * i) + pr;
+                n = n > last_n ? last_n : n;
+                w_off[i] = n * ldw_bytes + piece16;
+            }
+        } else if constexpr (kRowRegs) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 uint32_t m = tm * (uint32_t)BM + (uint32_t)(32 * i) + pr;
@@ -171,6 +231,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             // (after the last tile the loads are repeated and never used)
             p_locate();
         }
+        p_piece();
     };
     // 16 bytes per lane from base + voff (or base + min(voff + sadd, vmax)) to LDS address lds_addr + 16 * lane.  The
     // address travels in M0; between the write of M0 and the load there has to be an instruction, here the one that
@@ -198,7 +259,16 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         for (int h = 0; h < 2; ++h) {
             const int i = 2 * q + h;
             const bool has_w = 32 * i < BNt;
-            if constexpr (kRowRegs) {
+            if constexpr (kConv) {
+                // the tap's pixel lies inside the image: its channels; otherwise the line of zeros
+                const uint32_t y = a_yx[i] & 0xFFFFu, x = a_yx[i] >> 16;
+                const uint32_t yy = y + ((uint32_t)p_tap & 3u) - 1u, xx = x + (((uint32_t)p_tap >> 2) & 3u) - 1u;
+                // (bitwise: a short-circuit here becomes branches, which cut the phase into pieces)
+                const uint32_t in = (uint32_t)(p_tap >= 0) & (uint32_t)(yy < (uint32_t)g.A.H) & (uint32_t)(xx < (uint32_t)g.A.Wd);
+                const uint32_t there = a_off[i] + p_tap_off;
+                load_to_lds(g.A.base, g.zero_off ^ ((g.zero_off ^ there) & (0u - in)), dst + (uint32_t)(h * 32 * kRowBytes));
+                if (has_w) load_to_lds(g.W, w_off[i % (BNt / 32)] + p_w_add, dst + (uint32_t)(kPanelBytes + h * 32 * kRowBytes));
+            } else if constexpr (kRowRegs) {
                 load_to_lds(a_base, a_off[i], dst + (uint32_t)(h * 32 * kRowBytes));
                 if (has_w) load_to_lds(w_base, w_off[i % (BNt / 32)], dst + (uint32_t)(kPanelBytes + h * 32 * kRowBytes));
             } else {
@@ -225,6 +295,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     // ------------------------------------------------------------------------------------------------ prologue
     // the first groups into the buffers; the cursor stays at the last of them
     p_locate();
+    p_piece();
 #pragma unroll 1
     for (int b = 0; b < kBuffers; ++b) {
         if (b > 0) p_advance();
@@ -407,8 +478,11 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     };
 
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
-        wave_finish<kSign, WI, kLoadsPerGroup>(g, mc, acc, ra, rw, rw_table[wave], thr_table[wave], flip_table[wave],
-                                                stage[wave], m_wave, n_wave);
+        if constexpr (kConv)
+            wave_epilogue_conv<WI, kLoadsPerGroup>(g, mc, acc, ra, thr_table[wave], flip_table[wave], m_wave, n_wave, pixel_of);
+        else
+            wave_finish<kSign, WI, kLoadsPerGroup>(g, mc, acc, ra, rw, rw_table[wave], thr_table[wave], flip_table[wave],
+                                                   stage[wave], m_wave, n_wave);
     };
 
     Step buf0, buf1;
@@ -458,6 +532,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 typedef void (*KernelFn)(const GemmArgs, const MfmaConst, uint32_t, uint32_t, uint32_t);
 // narrow: the 256 x 128 workgroup tile; tail: the wide tile with the last round's tiles taken as halves by two workgroups each
 KernelFn find_kernel(bool sign, bool narrow, bool tail);
+KernelFn conv_kernel();  // the convolution variant (threshold output, 256 x 128 tiles)
 
 }  // namespace panel
 }  // namespace qnn

@@ -74,6 +74,16 @@ struct GemmArgs {
     const int8_t *w_bytes;
     int64_t ld_w_bytes;
     const int32_t *rw_scaled;
+    // Only for the convolution on the panel-fed FP4 kernel (panel::gemm_panel_kernel<true, 2, false, true>): A.base is
+    // the lower of {the plane "value is -1" of a +-1 map, a 16-byte line of zeros}; a_delta / zero_off are the byte
+    // offsets of the two from it; class_thr[cls * class_ld + n] is the threshold of filter n for a pixel of border class
+    // cls (bit 0: first row, 1: last row, 2: first column, 3: last column); inv_w = 1 / Wd and inv_hw = 1 / (H Wd) for
+    // the pixel coordinates; cpt_shift = log2(16-byte pieces per tap).
+    const int32_t *class_thr;
+    int64_t class_ld;
+    uint32_t a_delta, zero_off;
+    double inv_w, inv_hw;
+    int cpt_shift;
 };
 
 // Tile index with consecutive ids of one XCD (ids congruent mod 8 share an L2) laid on neighbouring tiles, and tiles
@@ -122,6 +132,21 @@ int launch_pack_bitplanes(const uint8_t *v, int64_t rows, int64_t K, int64_t ldv
                           int64_t ld, int64_t plane_stride, hipStream_t s);
 int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, const int32_t *T, const uint8_t *flip,
                           uint32_t *out, int64_t ldo, hipStream_t s);
+
+// 3 x 3 "same" convolution of a +-1 feature map (held as its plane "value is -1", [B][H][Wd][C / 32] words, C a
+// multiple of 128 with C / 128 a power of two) with +-1 filters and threshold output, on the panel-fed FP4 kernel.
+// bit = (conv >= T[n]) xor !flip_complement[n]: the caller passes the COMPLEMENT of its flip flags.  class_thr
+// (16 x conv_panel_class_ld(N) int32) and zero_line (256 bytes) are scratch of the call; zero_line and the plane must
+// lie within 4 GiB of each other.
+bool conv_panel_supports(int64_t B, int64_t H, int64_t Wd, int64_t C, int64_t N);
+int64_t conv_panel_class_ld(int64_t N);
+int launch_conv_panel(const uint32_t *plane, int64_t B, int H, int Wd, int C, const uint32_t *W, int64_t N, const int32_t *T,
+                      const uint8_t *flip_complement, uint32_t *out, int64_t ldo, int32_t *class_thr, uint32_t *zero_line,
+                      hipStream_t s);
+namespace panel {
+int launch_conv_class_thr(const uint32_t *W, int64_t N, int Cw, int C, const int32_t *T, int32_t *out, int64_t ld,
+                          uint32_t *zero_line, hipStream_t s);
+}
 
 // First convolution of a ConvNet straight from a uint8 image with at most three channels (3 x 3, pad 1, stride 1,
 // threshold output packed along the filters): whether the kernel takes the shape, and its launch.

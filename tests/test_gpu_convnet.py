@@ -86,5 +86,6 @@ def test_convnet_cifar10_architecture(seed):
     got = _run(q, case, couts, fcs)
     assert np.array_equal(got, want)
     engines = q.qnn_last_engines()
-    # first layer: the byte kernel for images of up to three channels, reported as the matrix-core engine
-    assert len(engines) == 9 and engines[0] == 2 and all(e == 4 for e in engines[1:6]), engines
+    # first layer: the byte kernel for images of up to three channels, reported as the matrix-core engine; the other
+    # convolutions (128, 256, 512 channels in): the panel-fed FP4 kernel on the maps' sign planes
+    assert len(engines) == 9 and engines[0] == 2 and all(e == 3 for e in engines[1:6]), engines
