@@ -643,7 +643,7 @@ int qnn_bitplane_conv2d(const uint32_t *A, int Pa, const int32_t *coefA, int mod
 namespace {
 constexpr int kMaxNetLayers = 2 * QNN_MAX_LAYERS;
 struct NetStep {
-    enum Kind { kPack, kFlags, kOnes, kGemm, kPool, kFirstConv, kConvPanel } kind;
+    enum Kind { kPack, kFlags, kOnes, kGemm, kPool, kFirstConv, kConvPrep, kConvPanel } kind;
     GemmArgs g;      // kGemm (convolution or fully connected)
     int engine;      // kGemm
     // kPack / kFlags / kOnes / kPool operands
@@ -656,7 +656,8 @@ struct NetStep {
 };
 struct NetPlan {
     int n;
-    FlagJobs flags;  // kFlags: every layer's flip flags, one launch
+    FlagJobs flags;     // kFlags: every layer's flip flags, one launch
+    ConvPrepJobs prep;  // kConvPrep: border-class thresholds of every convolution on the panel-fed kernel, one launch
     NetStep step[6 * kMaxNetLayers + 4];
 };
 
@@ -745,13 +746,18 @@ int run_net(const NetPlan &plan, hipStream_t s) {
                     if (g_engine_count < 2 * QNN_MAX_LAYERS) g_engines[g_engine_count++] = QNN_ENGINE_MFMA;
                 }
                 break;
+            case NetStep::kConvPrep: {
+                ConvPrepJobs jobs = plan.prep;
+                rc = panel::launch_conv_class_thr(jobs, s);
+                break;
+            }
             case NetStep::kConvPanel:
                 // src = plane "value is -1" of the input map, mask = weights, dst = output bits, dst2 = class thresholds;
                 // rows = B, a / b / c = H / W / C, n = filters; thresholds, complemented flips and the output pitch in
                 // g.epi; g.W = the line of zeros
                 rc = launch_conv_panel(static_cast<const uint32_t *>(st.src), st.rows, st.a, st.b, st.c, st.mask, st.n, st.g.epi.T,
-                                       st.g.epi.flip, static_cast<uint32_t *>(st.dst), st.g.epi.ldo, static_cast<int32_t *>(st.dst2),
-                                       const_cast<uint32_t *>(st.g.W), s);
+                                       st.g.epi.flip, static_cast<uint32_t *>(st.dst), st.g.epi.ldo, static_cast<const int32_t *>(st.dst2),
+                                       st.g.W, s);
                 if (rc == QNN_OK) {
                     g_last_engine = QNN_ENGINE_MFMA_FP4;
                     if (g_engine_count < 2 * QNN_MAX_LAYERS) g_engines[g_engine_count++] = QNN_ENGINE_MFMA_FP4;
@@ -819,6 +825,25 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
         plan.flags.inv[l] = ws + L.flag_inv[l];
     }
     if (n_layers > 1) push().kind = NetStep::kFlags;
+    // convolutions that take the panel-fed FP4 kernel (every one but the first, if the shapes allow): their thresholds
+    // per border class, all in one launch
+    plan.prep.count = 0;
+    plan.prep.zero_line = words(L.zero_line);
+    {
+        int64_t hh = H, ww = Wd, cc = C0;
+        for (int l = 0; l < n_conv; ++l) {
+            if (l > 0 && (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA_FP4) && conv_panel_supports(B, hh, ww, cc, cout[l])) {
+                const int j = plan.prep.count++;
+                plan.prep.W[j] = W[l], plan.prep.T[j] = T[l];
+                plan.prep.out[j] = reinterpret_cast<int32_t *>(ws + L.class_thr[l]);
+                plan.prep.N[j] = cout[l], plan.prep.ld[j] = conv_panel_class_ld(cout[l]);
+                plan.prep.Cw[j] = (int)words_for(cc);
+            }
+            if (pool[l]) hh /= 2, ww /= 2;
+            cc = cout[l];
+        }
+    }
+    if (plan.prep.count > 0) push().kind = NetStep::kConvPrep;
     // The first convolution multiplies the 8-bit codes themselves when a pixel's patch fits one matrix-core operand
     // row (three channels or fewer); otherwise, and when another engine is asked for, it goes through the input's
     // bit planes (Sec. 2.6): [in_bits][pixels][words per pixel]

@@ -251,8 +251,8 @@ bool conv_panel_supports(int64_t B, int64_t H, int64_t Wd, int64_t C, int64_t N)
 int64_t conv_panel_class_ld(int64_t N) { return ceil_div(N, 128) * 128; }
 
 int launch_conv_panel(const uint32_t *plane, int64_t B, int H, int Wd, int C, const uint32_t *W, int64_t N, const int32_t *T,
-                      const uint8_t *flip_complement, uint32_t *out, int64_t ldo, int32_t *class_thr, uint32_t *zero_line,
-                      hipStream_t s) {
+                      const uint8_t *flip_complement, uint32_t *out, int64_t ldo, const int32_t *class_thr,
+                      const uint32_t *zero_line, hipStream_t s) {
     if (!conv_panel_supports(B, H, Wd, C, N)) return fail(QNN_ERR_UNSUPPORTED, "convolution on the panel-fed kernel: shape not supported");
     const int Cw = C / 32;
     const int64_t M = B * H * Wd, ld = conv_panel_class_ld(N);
@@ -261,7 +261,6 @@ int launch_conv_panel(const uint32_t *plane, int64_t B, int H, int Wd, int C, co
     const uint64_t a_delta = (uint64_t)(pa - base), z_off = (uint64_t)(pz - base);
     if (a_delta + (uint64_t)(M + 256) * Cw * 4 >= 4294967296ULL || z_off + 256 >= 4294967296ULL)
         return fail(QNN_ERR_UNSUPPORTED, "convolution on the panel-fed kernel: scratch too far from the feature map");
-    if (int rc = panel::launch_conv_class_thr(W, N, Cw, C, T, class_thr, ld, zero_line, s)) return rc;
     GemmArgs g;
     std::memset(&g, 0, sizeof(g));
     g.A.base = reinterpret_cast<const uint32_t *>(base);

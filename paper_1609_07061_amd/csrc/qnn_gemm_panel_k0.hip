@@ -15,41 +15,48 @@ KernelFn conv_kernel() { return gemm_panel_kernel<true, 2, false, true>; }
 namespace {
 // class_thr[cls][n] = 2 sum_{taps inside for cls} sum_c b[n][tap][c] - (taps inside) C - T[n], clamped to +-2^30 (the sums
 // it is compared with are far smaller); cls bit 0: the pixel is in the first row (the upper taps lie outside), 1: last
-// row, 2: first column, 3: last column.  Entries of filters beyond N are zero.  Also clears the line of zeros that the
-// convolution reads for taps outside the image.
-__global__ __launch_bounds__(256) void conv_class_thr_kernel(const uint32_t *__restrict__ W, int64_t N, int Cw, int C,
-                                                             const int32_t *__restrict__ T, int32_t *__restrict__ out, int64_t ld,
-                                                             uint32_t *__restrict__ zero_line) {
-    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (blockIdx.x == 0 && threadIdx.x < 64) zero_line[threadIdx.x] = 0u;
-    if (n >= ld) return;
-    int32_t pc[9];
+// row, 2: first column, 3: last column.  Entries of filters beyond N are zero.  All layers of a network in one launch:
+// sixteen lanes per filter, lane t < 9 counts the set bits of tap t, then lane c sums the taps that class c keeps.
+// Also clears the line of zeros that the convolutions read for taps outside the image.
+__global__ __launch_bounds__(256) void conv_class_thr_kernel(const ConvPrepJobs jobs) {
+    if (blockIdx.x == 0 && threadIdx.x < 64) jobs.zero_line[threadIdx.x] = 0u;
+    int j = 0;
+    while (j + 1 < jobs.count && (int64_t)blockIdx.x >= jobs.first_block[j + 1]) ++j;
+    const int64_t n = ((int64_t)blockIdx.x - jobs.first_block[j]) * 16 + (threadIdx.x >> 4);
+    const int sub = threadIdx.x & 15;
+    const int64_t N = jobs.N[j], ld = jobs.ld[j];
+    const int Cw = jobs.Cw[j];
+    int32_t count = 0;
+    if (n < N && sub < 9) {
+        const uint32_t *w = jobs.W[j] + (n * 9 + sub) * Cw;
+        for (int c = 0; c < Cw; ++c) count += __builtin_popcount(w[c]);
+    }
+    int64_t sum = 0, taps = 0;
 #pragma unroll
     for (int tap = 0; tap < 9; ++tap) {
-        int32_t c = 0;
-        if (n < N)
-            for (int j = 0; j < Cw; ++j) c += __builtin_popcount(W[(n * 9 + tap) * Cw + j]);
-        pc[tap] = c;
+        const int32_t pc = __shfl(count, (threadIdx.x & 48) + tap, 64);  // (every lane takes part in the exchange)
+        const int ky = tap / 3, kx = tap % 3;
+        const bool outside = (ky == 0 && (sub & 1)) || (ky == 2 && (sub & 2)) || (kx == 0 && (sub & 4)) || (kx == 2 && (sub & 8));
+        if (!outside) sum += pc, ++taps;
     }
-    for (int cls = 0; cls < 16; ++cls) {
-        int64_t sum = 0, taps = 0;
-#pragma unroll
-        for (int tap = 0; tap < 9; ++tap) {
-            const int ky = tap / 3, kx = tap % 3;
-            const bool outside = (ky == 0 && (cls & 1)) || (ky == 2 && (cls & 2)) || (kx == 0 && (cls & 4)) || (kx == 2 && (cls & 8));
-            if (!outside) sum += pc[tap], ++taps;
-        }
-        int64_t e = n < N ? 2 * sum - taps * C - (int64_t)T[n] : 0;
+    if (n < ld) {
+        int64_t e = n < N ? 2 * sum - taps * (int64_t)Cw * 32 - (int64_t)jobs.T[j][n] : 0;
         e = e < -(1 << 30) ? -(1 << 30) : (e > (1 << 30) ? (1 << 30) : e);
-        out[cls * ld + n] = (int32_t)e;
+        jobs.out[j][sub * ld + n] = (int32_t)e;
     }
 }
 }  // namespace
 
-int launch_conv_class_thr(const uint32_t *W, int64_t N, int Cw, int C, const int32_t *T, int32_t *out, int64_t ld,
-                          uint32_t *zero_line, hipStream_t s) {
-    return QNN_LAUNCH("conv_class_thr", conv_class_thr_kernel, dim3((unsigned)ceil_div(ld, 256)), dim3(256), 0, s, W, N, Cw, C, T, out,
-                      ld, zero_line);
+int launch_conv_class_thr(ConvPrepJobs &jobs, hipStream_t s) {
+    if (jobs.count == 0) return QNN_OK;
+    int64_t blocks = 0;
+    for (int j = 0; j < jobs.count; ++j) {
+        jobs.first_block[j] = blocks;
+        blocks += ceil_div(jobs.ld[j], 16);
+    }
+    jobs.first_block[jobs.count] = blocks;
+    if (blocks > 0x7FFFFFFFLL) return fail(QNN_ERR_SHAPE, "convolution thresholds: too many filters");
+    return QNN_LAUNCH("conv_class_thr", conv_class_thr_kernel, dim3((unsigned)blocks), dim3(256), 0, s, jobs);
 }
 
 }  // namespace panel

@@ -136,16 +136,26 @@ int launch_threshold_sign(const int32_t *C, int64_t ldc, int64_t M, int64_t N, c
 // 3 x 3 "same" convolution of a +-1 feature map (held as its plane "value is -1", [B][H][Wd][C / 32] words, C a
 // multiple of 128 with C / 128 a power of two) with +-1 filters and threshold output, on the panel-fed FP4 kernel.
 // bit = (conv >= T[n]) xor !flip_complement[n]: the caller passes the COMPLEMENT of its flip flags.  class_thr
-// (16 x conv_panel_class_ld(N) int32) and zero_line (256 bytes) are scratch of the call; zero_line and the plane must
-// lie within 4 GiB of each other.
+// (16 x conv_panel_class_ld(N) int32) and zero_line (256 bytes) are written beforehand, on the same stream, by
+// panel::launch_conv_class_thr (one launch for all convolutions of a network); zero_line and the plane must lie within
+// 4 GiB of each other.
 bool conv_panel_supports(int64_t B, int64_t H, int64_t Wd, int64_t C, int64_t N);
 int64_t conv_panel_class_ld(int64_t N);
 int launch_conv_panel(const uint32_t *plane, int64_t B, int H, int Wd, int C, const uint32_t *W, int64_t N, const int32_t *T,
-                      const uint8_t *flip_complement, uint32_t *out, int64_t ldo, int32_t *class_thr, uint32_t *zero_line,
-                      hipStream_t s);
+                      const uint8_t *flip_complement, uint32_t *out, int64_t ldo, const int32_t *class_thr,
+                      const uint32_t *zero_line, hipStream_t s);
+struct ConvPrepJobs {
+    int count;
+    const uint32_t *W[2 * QNN_MAX_LAYERS];  // [N][9][Cw] filter bits
+    const int32_t *T[2 * QNN_MAX_LAYERS];
+    int32_t *out[2 * QNN_MAX_LAYERS];       // [16][ld]
+    int64_t N[2 * QNN_MAX_LAYERS], ld[2 * QNN_MAX_LAYERS];
+    int Cw[2 * QNN_MAX_LAYERS];
+    int64_t first_block[2 * QNN_MAX_LAYERS + 1];  // filled by the launch
+    uint32_t *zero_line;
+};
 namespace panel {
-int launch_conv_class_thr(const uint32_t *W, int64_t N, int Cw, int C, const int32_t *T, int32_t *out, int64_t ld,
-                          uint32_t *zero_line, hipStream_t s);
+int launch_conv_class_thr(ConvPrepJobs &jobs, hipStream_t s);
 }
 
 // First convolution of a ConvNet straight from a uint8 image with at most three channels (3 x 3, pad 1, stride 1,
