@@ -238,7 +238,9 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
 
 // ------------------------------------------------------------------------------------------------ convolution on the panel-fed kernel
 bool conv_panel_supports(int64_t B, int64_t H, int64_t Wd, int64_t C, int64_t N) {
-    if (B < 1 || H < 1 || Wd < 1 || H > 32767 || Wd > 32767 || C < 128 || C % 128 || N < 1) return false;
+    // (at least two rows and columns: a pixel is then in one of three row classes and one of three column classes)
+    if (B < 1 || H < 2 || Wd < 2 || H > 32767 || Wd > 32767 || C < 128 || C % 128 || N < 1) return false;
+    if (16 * conv_panel_class_ld(N) >= (1 << 28)) return false;  // 32-bit byte offsets into the class table
     const int64_t cpt = C / 128;
     if (cpt & (cpt - 1)) return false;
     const int64_t M = B * H * Wd, Cw = C / 32;

@@ -205,17 +205,42 @@ __device__ __forceinline__ void wave_epilogue(const GemmArgs &g, const MfmaConst
     if constexpr (kFast && !kSign) store_lines(WBN - 1, WB - 1);
 }
 
+// Convolution: the thresholds of nine border classes (row class 0 = interior, 1 = first row, 2 = last row; column class
+// likewise; class9 = 3 row + column) for the wave's 64 filters n_wave .. + 63 into thr_tab[class9][64], and the flip
+// flags as in load_thresholds_to_lds.  The table in memory is indexed by four bits (first row, last row, first column,
+// last column).  Three loads of 64 lanes x 16 bytes: lane i of load j lands at 16 (64 j + i), i.e. class 4 j + i / 16,
+// filters 4 (i mod 16) .. + 3 (loads beyond the ninth class repeat it and land behind the table's used part).
+__device__ __forceinline__ void load_class_thresholds_to_lds(const GemmArgs &g, const int64_t n_wave, int32_t *thr_tab,
+                                                             uint32_t *flip_tab) {
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t thr_lds = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) int32_t *)thr_tab);
+    const uint32_t flip_lds = (uint32_t)reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) uint32_t *)flip_tab);
+#pragma unroll
+    for (int j = 0; j < 3; ++j) {
+        uint32_t c9 = 4u * j + (lane >> 4);
+        c9 = c9 > 8u ? 8u : c9;
+        const uint32_t rc = c9 / 3u, cc = c9 - 3u * rc;
+        const uint32_t c16 = (rc == 1u ? 1u : 0u) | (rc == 2u ? 2u : 0u) | (cc == 1u ? 4u : 0u) | (cc == 2u ? 8u : 0u);
+        const uint32_t off = (c16 * (uint32_t)g.class_ld + (uint32_t)n_wave + 4u * (lane & 15u)) * 4u;  // (16 class_ld < 2^30)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" : : "s"(thr_lds + 1024u * j), "v"(off), "s"(g.class_thr) : "memory");
+    }
+    int64_t n = n_wave + lane;
+    if (n > g.N - 1) n = g.N - 1;
+    if (g.epi.flip)
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_ubyte %1, %2" : : "s"(flip_lds), "v"((uint32_t)n), "s"(g.epi.flip) : "memory");
+}
+
 // Threshold epilogue of the convolution on the panel-fed kernel: the comparison value depends on the pixel's border
-// class (which of the nine taps lie inside the image) as well as on the filter, so it is read per (row block, filter
-// block) from class_thr[class][n] in memory (a table of 16 x N entries, made once per layer) instead of a per-wave
-// LDS table:  bit = (alpha S + cRA RA[m] > class_thr[class(m)][n]) xor flip[n].  flip_tab arrives as in wave_epilogue
-// (flip flags by a load to LDS, followed by kLoadsAfter further loads of that kind); thr_tab is not used.
+// class (which of the nine taps lie inside the image) as well as on the filter, so thr_tab holds the thresholds of nine
+// classes for the wave's 64 filters (see load_class_thresholds_to_lds) and a lane reads the row of its pixel's class:
+//   bit = (alpha S + cRA RA[m] > thr_tab[class9(m)][n]) xor flip[n].
+// The loads that fill thr_tab and flip_tab were followed by kLoadsAfter further loads to LDS.
 template <int WBN, int kLoadsAfter, typename Acc, typename PixelOf>
 __device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, const MfmaConst &mc, Acc (&acc)[WBN][4], int32_t (&ra)[4],
                                                    int32_t *thr_tab, uint32_t *flip_tab, const int64_t m_wave,
                                                    const int64_t n_wave, PixelOf pixel_of) {
     constexpr int WB = 4, WTN = 32 * WBN;
-    (void)thr_tab;
+    static_assert(WBN == 2, "the class table holds 64 filters per wave");
     const int64_t Nw = (g.N + 31) / 32;
     int lane_opaque = (int)(threadIdx.x & 63);
     asm volatile("" : "+v"(lane_opaque));
@@ -224,7 +249,7 @@ __device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, const Mfma
     for (int b = 0; b < WB; ++b) ra[b] = sum_halves(ra[b]);
     int64_t m_of[WB];
     uint32_t mterm[WB];
-    const int32_t *thr_row[WB];  // class_thr row of the pixel's class, at the wave's first filter
+    const int32_t *thr_row[WB];  // thr_tab row of the pixel's class
 #pragma unroll
     for (int bj = 0; bj < WB; ++bj) {
         m_of[bj] = m_wave + bj * 32 + r;
@@ -232,9 +257,10 @@ __device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, const Mfma
         const uint32_t m = (uint32_t)(m_of[bj] < g.M ? m_of[bj] : g.M - 1);
         uint32_t y, x;
         pixel_of(m, y, x);
-        const uint32_t cls = (y == 0u ? 1u : 0u) | (y == (uint32_t)g.A.H - 1u ? 2u : 0u) | (x == 0u ? 4u : 0u) |
-                             (x == (uint32_t)g.A.Wd - 1u ? 8u : 0u);
-        thr_row[bj] = g.class_thr + (int64_t)cls * g.class_ld + n_wave;
+        // (maps of at least two rows and two columns: a pixel is in one row class and one column class)
+        const uint32_t c9 = 3u * (y == 0u ? 1u : (y == (uint32_t)g.A.H - 1u ? 2u : 0u)) +
+                            (x == 0u ? 1u : (x == (uint32_t)g.A.Wd - 1u ? 2u : 0u));
+        thr_row[bj] = thr_tab + c9 * 64u;
     }
     // flip flags at the bit position their n has in a lane's partial output word (as in wave_epilogue)
     asm volatile("s_waitcnt vmcnt(%0)" : : "n"(kLoadsAfter) : "memory");
@@ -265,7 +291,6 @@ __device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, const Mfma
             uint32_t bits = 0;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                // (the table's rows are padded to whole tiles of filters, so the 16-byte read stays inside)
                 const int4 e4 = *reinterpret_cast<const int4 *>(thr_row[bj] + bi * 32 + 8 * q + 4 * kg);
                 const int32_t e[4] = {e4.x, e4.y, e4.z, e4.w};
                 uint32_t nib = 0;

@@ -81,8 +81,9 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     constexpr int kGroupBytesT = kPanelBytes + 2 * 32 * WBN * kRowBytes;
     constexpr int kBuffers = (kSign && WBN == 2) ? 3 : 2;
     __shared__ __attribute__((aligned(16))) uint8_t lds[kBuffers * kGroupBytesT];
-    __shared__ __attribute__((aligned(16))) uint32_t rw_table[kThreads / 64][WTILE];
-    __shared__ __attribute__((aligned(16))) int32_t thr_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
+    __shared__ __attribute__((aligned(16))) uint32_t rw_table[kConv ? 1 : kThreads / 64][kConv ? 4 : WTILE];
+    // (kConv: per wave the thresholds of nine border classes x the wave's 64 filters, three 1 KiB loads' worth)
+    __shared__ __attribute__((aligned(16))) int32_t thr_table[kSign ? kThreads / 64 : 1][kSign ? (kConv ? 12 * 64 : WTILE) : 4];
     __shared__ __attribute__((aligned(16))) uint32_t flip_table[kSign ? kThreads / 64 : 1][kSign ? WTILE : 4];
     // int32 epilogue: per wave one 32 x 32 staging block, through which a block is turned from the accumulator layout
     // (a lane = one row) into whole 128-byte lines per row
@@ -474,14 +475,17 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 
     // thresholds / flip flags of the tile being finished, straight into this wave's LDS tables
     auto load_thresholds = [&](const int64_t n_wave) __attribute__((always_inline)) {
-        if constexpr (kSign) load_thresholds_to_lds<WI>(g, n_wave, thr_table[wave], flip_table[wave]);
+        if constexpr (kConv)
+            load_class_thresholds_to_lds(g, n_wave, thr_table[wave], flip_table[wave]);
+        else if constexpr (kSign)
+            load_thresholds_to_lds<WI>(g, n_wave, thr_table[wave], flip_table[wave]);
     };
 
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
         if constexpr (kConv)
             wave_epilogue_conv<WI, kLoadsPerGroup>(g, mc, acc, ra, thr_table[wave], flip_table[wave], m_wave, n_wave, pixel_of);
         else
-            wave_finish<kSign, WI, kLoadsPerGroup>(g, mc, acc, ra, rw, rw_table[wave], thr_table[wave], flip_table[wave],
+            wave_finish<kSign, WI, kLoadsPerGroup>(g, mc, acc, ra, rw, rw_table[kConv ? 0 : wave], thr_table[wave], flip_table[wave],
                                                    stage[wave], m_wave, n_wave);
     };
 
