@@ -66,6 +66,21 @@ def test_convnet_small(seed, B, H, Wd, C0, couts, pools, fcs, engine):
     assert np.array_equal(_run(q, case, couts, fcs, engine), want)
 
 
+@pytest.mark.parametrize("with_flip", [True, False])
+def test_convnet_ragged_shapes_on_the_panel_fed_convolution(seed, with_flip):
+    """Non-square maps of 10 x 14 pixels, 420 pixels per batch (one whole tile of 256 rows and a ragged one), 256 channels
+    into 200 filters (a ragged tile of filters) and 200 channels into 64 (not a multiple of 128: another kernel)."""
+    import paper_1609_07061_amd as q
+
+    couts, pools, fcs = [256, 200, 64], [0, 0, 1], [10]
+    x, conv_w, pools, fc_w, T, flip = _case(seed, 3, 10, 14, 3, couts, pools, fcs, 1800)
+    want = oracle.convnet(x, conv_w, pools, fc_w, T, flip if with_flip else None)
+    got = _run(q, (x, conv_w, pools, fc_w, T, flip), couts, fcs, with_flip=with_flip)
+    assert np.array_equal(got, want)
+    engines = q.qnn_last_engines()
+    assert engines[0] == 2 and engines[1] == 3 and engines[2] != 3, engines
+
+
 def test_convnet_without_flips(seed):
     import paper_1609_07061_amd as q
 
