@@ -877,8 +877,11 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
         NetStep &st = push();
         st.kind = NetStep::kGemm;
         const Epilogue e{nullptr, 0, T[l], fl, conv_dst, Cwo};
-        const bool on_panel = l > 0 && (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA_FP4) &&
-                              conv_panel_supports(B, h, w, cin, co);
+        const bool panel_engine = engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA_FP4;
+        const bool on_panel = l > 0 && panel_engine && conv_panel_supports(B, h, w, cin, co);
+        // the next convolution reads this layer's output: on the panel-fed kernel it takes the plane "value is -1" alone,
+        // otherwise the 2-bit code, whose plane "inside the image" is then written too
+        const bool ones_needed = inverted && !(panel_engine && conv_panel_supports(B, ho, wo, co, cout[l + 1]));
         if (on_panel) {
             // the map's plane "value is -1" alone; out = (conv >= T) xor fl, and the kernel takes the complement of fl:
             // the caller's flags where fl is their inversion, the inverted ones where fl is the caller's
@@ -891,7 +894,7 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
         } else if (l == 0 && first_direct) {
             st.kind = NetStep::kFirstConv;
             st.src = x, st.mask = W[0], st.dst = conv_dst;
-            st.dst2 = (inverted && !pool[l]) ? kept : nullptr;  // the ones plane of an unpooled output, written alongside
+            st.dst2 = (ones_needed && !pool[l]) ? kept : nullptr;  // the ones plane of an unpooled output, written alongside
             st.rows = B, st.a = (int)H, st.b = (int)Wd, st.c = (int)C0, st.n = co;
             st.g.epi = e;
         } else {
@@ -907,10 +910,10 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
             pl.rows = B, pl.a = (int)h, pl.b = (int)w, pl.c = (int)Cwo;
             pl.mask = words(L.flag_bits[l]);
             pl.invert = inverted;
-            pl.dst2 = inverted ? kept : nullptr;  // the ones plane of the pooled output, written alongside
+            pl.dst2 = ones_needed ? kept : nullptr;  // the ones plane of the pooled output, written alongside
             pl.n = co;
         }
-        if (inverted && !pool[l] && !(l == 0 && first_direct)) {
+        if (ones_needed && !pool[l] && !(l == 0 && first_direct)) {
             NetStep &on = push();
             on.kind = NetStep::kOnes;
             on.dst = kept, on.rows = B * ho * wo, on.a = (int)Cwo, on.b = (int)co;
