@@ -832,7 +832,8 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
     {
         int64_t hh = H, ww = Wd, cc = C0;
         for (int l = 0; l < n_conv; ++l) {
-            if (l > 0 && (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA_FP4) && conv_panel_supports(B, hh, ww, cc, cout[l])) {
+            if (l > 0 && (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA_FP4) && L.total < 0xFFFF0000ull &&
+                conv_panel_supports(B, hh, ww, cc, cout[l])) {
                 const int j = plan.prep.count++;
                 plan.prep.W[j] = W[l], plan.prep.T[j] = T[l];
                 plan.prep.out[j] = reinterpret_cast<int32_t *>(ws + L.class_thr[l]);
@@ -877,7 +878,8 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
         NetStep &st = push();
         st.kind = NetStep::kGemm;
         const Epilogue e{nullptr, 0, T[l], fl, conv_dst, Cwo};
-        const bool panel_engine = engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA_FP4;
+        // (the panel-fed convolution addresses its input and the line of zeros, both in the workspace, with 32-bit offsets)
+        const bool panel_engine = (engine == QNN_ENGINE_AUTO || engine == QNN_ENGINE_MFMA_FP4) && L.total < 0xFFFF0000ull;
         const bool on_panel = l > 0 && panel_engine && conv_panel_supports(B, h, w, cin, co);
         // the next convolution reads this layer's output: on the panel-fed kernel it takes the plane "value is -1" alone,
         // otherwise the 2-bit code, whose plane "inside the image" is then written too
