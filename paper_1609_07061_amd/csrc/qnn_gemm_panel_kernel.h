@@ -501,9 +501,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         const int64_t m_wave = (int64_t)tile_m * BM + wm * WTILE;
         const int64_t n_wave = (int64_t)tile_n * BNt + (int64_t)first_col + wn * 32 * WI;
         clear();
-        // one group of four steps; kLastGroup: its last step ends the tile
+        // Thresholds and flip flags of this tile on their way to the wave's LDS tables (free since the previous tile's
+        // epilogue) before its first group: issued in the tile's last step they arrive a microsecond or two after the
+        // epilogue wants them, which a tile of one or two groups cannot afford.  At least a group's loads follow them.
+        load_thresholds(n_wave);
+        // one group of four steps; last_tag: its last step ends the tile
         auto group = [&](auto last_tag) __attribute__((always_inline)) {
-            constexpr bool kLastGroup = decltype(last_tag)::value;
             const uint32_t other = rd + kGroupBytesT == kBuffers * kGroupBytesT ? 0u : rd + (uint32_t)kGroupBytesT;
             // the cursor moves on to the group that this group's fourth step will load (scalar control flow: kept at
             // the head of the group, so that the phases of a step stay one straight-line block)
@@ -513,11 +516,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(3, rd, buf1); }, no_produce, std::false_type{});
             panel_barrier();
             // last step of the tile: the operands of the next tile's first phase are made after the epilogue, so that
-            // they do not occupy registers during it; the thresholds are loaded meanwhile
-            compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) {
-                fetch(0, other, buf0);
-                if (kLastGroup) load_thresholds(n_wave);
-            }, produce, last_tag);
+            // they do not occupy registers during it
+            compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) { fetch(0, other, buf0); }, produce, last_tag);
             rd = other;
         };
         for (uint32_t G = 0; G + 1 < ngroups; ++G) group(std::false_type{});
