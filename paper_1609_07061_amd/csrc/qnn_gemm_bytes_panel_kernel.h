@@ -319,17 +319,16 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
         tile_of_block(vb, total_tiles, tiles_m, tiles_n, tile_m, tile_n);
         const int64_t m_wave = (int64_t)tile_m * BM + wm * WTILE, n_wave = (int64_t)tile_n * BNt + wn * WTN;
         clear();
-        // one group of two steps; kLastGroup: its second step ends the tile
+        // thresholds, flip flags and the weight rows' terms of this tile on their way to the wave's LDS tables before its
+        // first group (issued in the last step they would arrive after the epilogue wants them); a group's loads follow
+        load_thresholds(n_wave);
+        // one group of two steps; last_tag: its second step ends the tile
         auto group = [&](auto last_tag) __attribute__((always_inline)) {
-            constexpr bool kLastGroup = decltype(last_tag)::value;
             const uint32_t next = rd + kGroupBytesT == kBuffers * kGroupBytesT ? 0u : rd + (uint32_t)kGroupBytesT;
             p_advance();  // scalar control flow: kept at the head of the group
             compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(1, rd, buf1); }, no_produce, std::false_type{});
             panel_barrier();
-            compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) {
-                fetch(0, next, buf0);
-                if (kLastGroup) load_thresholds(n_wave);
-            }, produce, last_tag);
+            compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) { fetch(0, next, buf0); }, produce, last_tag);
             rd = next;
         };
         for (uint32_t G = 0; G + 1 < ngroups; ++G) group(std::false_type{});
