@@ -507,7 +507,7 @@ def main():
     peak = ENGINE_PEAK[used]
     roof = {"bound": "alu" if used == 1 else "mfma", "achieved": tops3, "peak": peak, "unit": "TOP/s", "frac": tops3 / peak,
             "traffic": None,
-            "kernel": {1: "gemm_valu_kernel", 2: "gemm_mfma_kernel", 3: "gemm_panel_kernel<false, 4, false>"}[used],
+            "kernel": {1: "gemm_valu_kernel", 2: "gemm_mfma_kernel", 3: "gemm_panel_kernel<false, 4, false, false>"}[used],
             "peak_dtype": {1: "integer vector ALU: one xor and one popcount-accumulate per 32 MACs",
                            2: "int8 dense MFMA, int32 accumulate",
                            3: "fp4 (E2M1) dense MFMA, fp32 accumulate"}[used],
