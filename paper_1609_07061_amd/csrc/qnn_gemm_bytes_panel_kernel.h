@@ -279,8 +279,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
     auto panel_barrier = [&]() __attribute__((always_inline)) {
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(kPending) : "memory");
     };
+    // after the prologue: the first group has landed (the other kBuffers - 1 may still be on their way: every workgroup
+    // asks for its first groups at the same moment, and waiting for all of them costs microseconds per launch)
+    constexpr int kPendingFirst = kLoadsPerGroup * (kBuffers - 1);
+    static_assert(kPendingFirst < 64, "vmcnt is a 6-bit counter");
     auto first_barrier = [&]() __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" : : "n"(kPendingFirst) : "memory");
     };
 
     // ------------------------------------------------------------------------------------------------ prologue
