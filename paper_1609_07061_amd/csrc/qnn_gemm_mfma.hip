@@ -188,21 +188,21 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
         MfmaConst pc = mc;
         if (make_code(g.pa, pc.a, aA, bA, xA0) && make_code(g.pw, pc.w, aW, bW, xW0) &&
             fill_consts(g, aA, bA, xA0, aW, bW, xW0, ngroups * panel::kGroupWords * 32, pc)) {
-            // 256 x 128 tiles where they fill the rounds of workgroups clearly better than 256 x 256 ones (each costs
-            // a little more than half of a large tile, so a small gain does not pay)
-            auto fill = [&](int64_t tiles) { return (double)tiles / (double)(ceil_div(tiles, cus) * cus); };
+            // Tile schedule by cost, in units of a round of 256 x 128 tiles: a round of 256 x 256 tiles costs 1.86 with
+            // long rows (measured at K = 4096) and two with short ones, where the epilogue dominates.  The rounds count
+            // whole tiles, so the padding of a ragged edge (128 columns under 256-column tiles: half of every tile) and
+            // a thinly filled last round both show.  Third schedule: wide tiles with the last round's tiles halved
+            // (each half to a workgroup of its own, 1.17 for that round), possible when that round has tiles for at most
+            // half of the workgroups and worth it only for long rows.
             const int64_t tiles_n2 = ceil_div(g.N, BN / 2);
-            bool narrow = fill(tiles_m * tiles_n2) > 1.1 * fill(total);
-            // Wide tiles with the last round's tiles halved (each half to a workgroup of its own): possible when that
-            // round has tiles for at most half of the workgroups, and worth it only for long rows, where a wide tile
-            // costs less than two narrow ones.  Costs in units of a round of narrow tiles, as measured at K = 4096:
-            // a round of wide tiles 1.86, the round of halves 1.17.
+            const double wide_round = ngroups >= 4 ? 1.86 : 2.0, half_round = 1.17;
+            const double cost_wide = (double)ceil_div(total, cus) * wide_round;
+            const double cost_narrow = (double)ceil_div(tiles_m * tiles_n2, cus);
+            bool narrow = cost_narrow < cost_wide;
             bool tail = false;
             if (cus % 16 == 0 && total > cus && total % cus != 0 && 2 * (total % cus) <= cus && ngroups >= 4) {
-                const double wide_round = 1.86, half_round = 1.17;
                 const double cost_tail = (double)(total / cus) * wide_round + half_round;
-                const double cost_else = narrow ? (double)ceil_div(tiles_m * tiles_n2, cus) : (double)ceil_div(total, cus) * wide_round;
-                tail = cost_tail < cost_else;
+                tail = cost_tail < (narrow ? cost_narrow : cost_wide);
             }
             narrow = narrow && !tail;
             const panel::KernelFn pf = panel::find_kernel(g.epi.T != nullptr, narrow, tail);
