@@ -388,12 +388,13 @@ int launch_values(const GemmArgs &g, hipStream_t s) {
             if (scale == ((int64_t)1 << sh)) mc.alpha_shift = sh;
         const int cus = compute_units();
         const int64_t tiles_m = ceil_div(g.M, 256);
-        auto fill = [&](int64_t tiles) { return (double)tiles / (double)(ceil_div(tiles, cus) * cus); };
         const int64_t wide_n = ceil_div(g.N, 256), narrow_n = ceil_div(g.N, 128);
         // The narrow tile has room for three group buffers and keeps more bytes on their way from memory, which is what
         // bounds this kernel (a byte per element, eight times the traffic of packed bits): the wide tile only where its
-        // tiles fill the compute units at least as well as the narrow ones would.
-        const bool narrow = tiles_m * wide_n < cus || fill(tiles_m * narrow_n) > fill(tiles_m * wide_n);
+        // tiles come out cheaper by a count of rounds of whole tiles (a round of wide tiles = 1.9 rounds of narrow ones),
+        // which sees padded columns as well as thin last rounds.
+        const bool narrow = tiles_m * wide_n < cus ||
+                            (double)ceil_div(tiles_m * narrow_n, cus) <= 1.9 * (double)ceil_div(tiles_m * wide_n, cus);
         const int64_t tiles_n = narrow ? narrow_n : wide_n, total = tiles_m * tiles_n;
         const unsigned grid = (unsigned)(total < cus ? total : cus);
         rc = QNN_LAUNCH("gemm_values", bytes_panel::kernel_values(narrow), dim3(grid), dim3(bytes_panel::kThreads), 0, s, v, mc,
