@@ -214,7 +214,9 @@ def test_many_tiles_short_k_threshold_output(seed, M, N, K, engine):
 # large tiles would leave 40 % of the second round idle); (1000, 700): fewer tiles than workgroups, three groups of K;
 # (6000, 8500): 24 x 34 tiles, three or four per workgroup; (5000, 7000) with K = 4096: 20 x 28 = 560 tiles of
 # 256 x 256, two whole rounds of 256 workgroups and 48 tiles that are halved and shared out among 96 workgroups.
-PANEL_TILES = [(4000, 8100, 1024), (4200, 4360, 2048), (1000, 700, 3072), (6000, 8500, 1024), (5000, 7000, 4096)]
+# (9000, 128, 2048): 128 columns, which 256-column tiles would pad to twice the work: 36 tiles of 256 x 128.
+PANEL_TILES = [(4000, 8100, 1024), (4200, 4360, 2048), (1000, 700, 3072), (6000, 8500, 1024), (5000, 7000, 4096),
+               (9000, 128, 2048)]
 
 
 @pytest.mark.parametrize("engine", [0, FP4])
