@@ -746,9 +746,9 @@ int run_net(const NetPlan &plan, hipStream_t s) {
                     if (g_engine_count < 2 * QNN_MAX_LAYERS) g_engines[g_engine_count++] = QNN_ENGINE_MFMA;
                 }
                 break;
-            case NetStep::kConvPrep: {
+            case NetStep::kConvPrep: {  // with the layers' flip flags
                 ConvPrepJobs jobs = plan.prep;
-                rc = panel::launch_conv_class_thr(jobs, s);
+                rc = panel::launch_conv_class_thr(jobs, plan.flags, s);
                 break;
             }
             case NetStep::kConvPanel:
@@ -824,6 +824,7 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
         plan.flags.bits[l] = words(L.flag_bits[l]);
         plan.flags.inv[l] = ws + L.flag_inv[l];
     }
+    const int flags_step = plan.n;
     if (n_layers > 1) push().kind = NetStep::kFlags;
     // convolutions that take the panel-fed FP4 kernel (every one but the first, if the shapes allow): their thresholds
     // per border class, all in one launch
@@ -844,7 +845,13 @@ int qnn_binary_convnet_forward(const uint8_t *x, int64_t B, int64_t H, int64_t W
             cc = cout[l];
         }
     }
-    if (plan.prep.count > 0) push().kind = NetStep::kConvPrep;
+    // (one launch prepares both the thresholds and the flags)
+    if (plan.prep.count > 0) {
+        if (n_layers > 1)
+            plan.step[flags_step].kind = NetStep::kConvPrep;
+        else
+            push().kind = NetStep::kConvPrep;
+    }
     // The first convolution multiplies the 8-bit codes themselves when a pixel's patch fits one matrix-core operand
     // row (three channels or fewer); otherwise, and when another engine is asked for, it goes through the input's
     // bit planes (Sec. 2.6): [in_bits][pixels][words per pixel]

@@ -154,8 +154,10 @@ struct ConvPrepJobs {
     int64_t first_block[2 * QNN_MAX_LAYERS + 1];  // filled by the launch
     uint32_t *zero_line;
 };
+struct FlagJobs;
 namespace panel {
-int launch_conv_class_thr(ConvPrepJobs &jobs, hipStream_t s);
+// (also prepares the layers' flip flags, see launch_flags, in the same launch; flags.count may be 0)
+int launch_conv_class_thr(ConvPrepJobs &jobs, const FlagJobs &flags, hipStream_t s);
 }
 
 // First convolution of a ConvNet straight from a uint8 image with at most three channels (3 x 3, pad 1, stride 1,
