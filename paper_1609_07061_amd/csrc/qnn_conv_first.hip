@@ -10,6 +10,8 @@
 // A wave takes 32 consecutive pixels at a time: lane (r, kg) gathers the 16 patch bytes k = 16 kg .. 16 kg + 15 of pixel
 // r (the image is small and stays in cache), and for every block of 32 filters reads its 16 filter bytes from LDS,
 // multiplies, thresholds its 16 sums and the two lane halves are OR-ed into the pixel's output word.
+#include <type_traits>
+
 #include "qnn_gemm_mfma_kernel.h"
 #include "qnn_internal.h"
 
@@ -50,40 +52,6 @@ __global__ __launch_bounds__(kFirstThreads) void conv_first_kernel(const FirstCo
     const int Npad = (a.N + 31) / 32 * 32;
     // k / C0 for k < 32 and C0 in 1 .. 3 without a division
     auto tap_of = [C0](int k) { return C0 == 1 ? k : (C0 == 2 ? k >> 1 : (k * 11) >> 5); };
-    // the filters as bytes (+1 / -1, 0 beyond the patch and beyond the last filter): one 4-byte piece per thread and turn
-    for (int item = t; item < Npad * 8; item += kFirstThreads) {
-        const int n = item >> 3, j = item & 7;
-        uint32_t piece = 0;
-        if (n < a.N) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int k = 4 * j + i;
-                if (k < ktot) {
-                    const int tap = tap_of(k), c = k - tap * C0;
-                    piece |= (((a.W[(int64_t)n * 9 + tap] >> c) & 1u) ? 0x01u : 0xFFu) << (8 * i);
-                }
-            }
-        }
-        *reinterpret_cast<uint32_t *>(&sW[n * 32 + 4 * j]) = piece;
-    }
-    // per filter: the sum of its weights (2 x set bits - patch size) folded into the threshold, the flags
-    for (int n = t; n < Npad; n += kFirstThreads) {
-        int32_t sum = 0;
-        if (n < a.N) {
-            int32_t set = 0;
-#pragma unroll
-            for (int i = 0; i < 9; ++i) set += __builtin_popcount(a.W[(int64_t)n * 9 + i] & ((1u << C0) - 1u));
-            sum = 2 * set - ktot;
-        }
-        // |S + 128 sum| < 2^16: thresholds beyond +-2^30 decide the same way as +-2^30, and the difference cannot wrap
-        const int32_t tv = n < a.N ? a.T[n] : 0;
-        const int32_t tc = tv < -(1 << 30) ? -(1 << 30) : (tv > (1 << 30) ? (1 << 30) : tv);
-        const uint32_t pos = 1u << ((n & 0x18) | (n & 3));
-        sE[n] = tc - 1 - 128 * sum;
-        sFlip[n] = (n < a.N && a.flip && a.flip[n]) ? pos : 0u;
-        sLive[n] = n < a.N ? pos : 0u;
-    }
-    __syncthreads();
     // this lane's 16 elements of k, once:
     // (dy + 1) | (dx + 1) << 2, or -1 for an element beyond the patch; byte offset from the centre pixel's first channel
     int tapc[16], off[16];
@@ -96,33 +64,83 @@ __global__ __launch_bounds__(kFirstThreads) void conv_first_kernel(const FirstCo
         off[j] = ((ty - 1) * a.Wd + (tx - 1)) * C0 + c;
     }
     const int64_t tiles = (a.pixels + 31) / 32;
-    const int Nw = Npad / 32;
-    for (int64_t tile = (int64_t)blockIdx.x * (kFirstThreads / 64) + wave; tile < tiles; tile += (int64_t)gridDim.x * (kFirstThreads / 64)) {
+    const int64_t tile_step = (int64_t)gridDim.x * (kFirstThreads / 64);
+    // The patch bytes of a tile of 32 pixels: lane (r, kg) asks for its 16 bytes of pixel r, branch-free (an element
+    // outside the image or beyond the patch reads the pixel's own first byte and is dropped when the operand is put
+    // together), so that the sixteen loads are issued back to back.  The loads of a wave's next tile are issued before
+    // it works on the current one, and those of its first tile before the filter tables below are built.
+    auto gather = [&](int64_t tile, uint32_t(&got)[16], uint32_t &in_mask) {
         const int64_t p = tile * 32 + r;
-        const bool live = p < a.pixels;
-        const uint32_t pc = (uint32_t)(live ? p : a.pixels - 1);  // (the host checks that the pixel count fits 31 bits)
-        const uint32_t rowi = pc / (uint32_t)a.Wd;                // b H + y
+        const uint32_t pc = (uint32_t)(p < a.pixels ? p : a.pixels - 1);  // (the host checks that the pixel count fits 31 bits)
+        const uint32_t rowi = pc / (uint32_t)a.Wd;                        // b H + y
         const int x0 = (int)(pc - rowi * (uint32_t)a.Wd);
         const int y0 = (int)(rowi % (uint32_t)a.H);
         const uint8_t *centre = a.x + (int64_t)pc * C0;  // first channel of the pixel itself
         // which of the three patch rows / columns lie inside the image, as bit masks indexed like tapc
         const uint32_t rows_in = (y0 > 0 ? 1u : 0u) | 2u | (y0 + 1 < a.H ? 4u : 0u);
         const uint32_t cols_in = (x0 > 0 ? 1u : 0u) | 2u | (x0 + 1 < a.Wd ? 4u : 0u);
-        // branch-free: an element outside the image (or beyond the patch) reads the pixel's own first byte and is
-        // dropped afterwards, so that the sixteen loads are issued back to back
-        uint32_t got[16];
-        bool in[16];
+        in_mask = 0;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            in[j] = tapc[j] >= 0 && ((rows_in >> (tapc[j] & 3)) & (cols_in >> (tapc[j] >> 2)) & 1u);
-            got[j] = centre[in[j] ? off[j] : 0];
+            const bool in = tapc[j] >= 0 && ((rows_in >> (tapc[j] & 3)) & (cols_in >> (tapc[j] >> 2)) & 1u);
+            got[j] = centre[in ? off[j] : 0];
+            in_mask |= (in ? 1u : 0u) << j;
         }
+    };
+    const int64_t first_tile = (int64_t)blockIdx.x * (kFirstThreads / 64) + wave;
+    uint32_t got[16], in_mask = 0;
+    if (first_tile < tiles) gather(first_tile, got, in_mask);
+    // Per filter, by one thread: its nine words, threshold and flip flag are asked for together; then the filter as
+    // bytes (+1 / -1, 0 beyond the patch and beyond the last filter), the sum of its weights (2 x set bits - patch
+    // size) folded into the threshold, and the flags.
+    auto build_tables = [&](auto c0_tag) {
+        constexpr int kC0 = decltype(c0_tag)::value;
+        for (int n = t; n < Npad; n += kFirstThreads) {
+            const bool there = n < a.N;
+            uint32_t w9[9];
+#pragma unroll
+            for (int i = 0; i < 9; ++i) w9[i] = there ? a.W[(int64_t)n * 9 + i] & ((1u << kC0) - 1u) : 0u;
+            const int32_t tv = there ? a.T[n] : 0;
+            const bool flipped = there && a.flip && a.flip[n];
+            uint32_t piece[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+            int32_t set = 0;
+#pragma unroll
+            for (int k = 0; k < 9 * kC0; ++k) {
+                const uint32_t bit = (w9[k / kC0] >> (k % kC0)) & 1u;
+                piece[k >> 2] |= (bit ? 0x01u : 0xFFu) << (8 * (k & 3));
+                set += (int32_t)bit;
+            }
+            uint4 *row = reinterpret_cast<uint4 *>(&sW[n * 32]);
+            row[0] = there ? make_uint4(piece[0], piece[1], piece[2], piece[3]) : make_uint4(0u, 0u, 0u, 0u);
+            row[1] = there ? make_uint4(piece[4], piece[5], piece[6], piece[7]) : make_uint4(0u, 0u, 0u, 0u);
+            const int32_t sum = there ? 2 * set - 9 * kC0 : 0;
+            // |S + 128 sum| < 2^16: thresholds beyond +-2^30 decide the same way as +-2^30, and the difference cannot wrap
+            const int32_t tc = tv < -(1 << 30) ? -(1 << 30) : (tv > (1 << 30) ? (1 << 30) : tv);
+            const uint32_t pos = 1u << ((n & 0x18) | (n & 3));
+            sE[n] = tc - 1 - 128 * sum;
+            sFlip[n] = flipped ? pos : 0u;
+            sLive[n] = there ? pos : 0u;
+        }
+    };
+    if (C0 == 3) {
+        build_tables(std::integral_constant<int, 3>{});
+    } else if (C0 == 2) {
+        build_tables(std::integral_constant<int, 2>{});
+    } else {
+        build_tables(std::integral_constant<int, 1>{});
+    }
+    __syncthreads();
+    const int Nw = Npad / 32;
+    for (int64_t tile = first_tile; tile < tiles; tile += tile_step) {
+        const int64_t p = tile * 32 + r;
+        const bool live = p < a.pixels;
         uint32_t av[4] = {0u, 0u, 0u, 0u};
 #pragma unroll
-        for (int j = 0; j < 16; ++j) av[j >> 2] |= (in[j] ? got[j] : 0u) << (8 * (j & 3));
+        for (int j = 0; j < 16; ++j) av[j >> 2] |= ((in_mask >> j) & 1u ? got[j] : 0u) << (8 * (j & 3));
         v4i af;
 #pragma unroll
         for (int i = 0; i < 4; ++i) af[i] = (int)(av[i] ^ 0x80808080u);
+        if (tile + tile_step < tiles) gather(tile + tile_step, got, in_mask);
         // four output words (128 filters) at a time, so that a pixel's words leave as one 16-byte store: lanes of the
         // lower half write the bits, lanes of the upper half the ones plane
         const bool vec = a.ldo % 4 == 0 && ((reinterpret_cast<uintptr_t>(a.out) | reinterpret_cast<uintptr_t>(a.ones)) & 15u) == 0;

@@ -51,6 +51,7 @@ def _run(q, case, couts, fcs, engine=0, with_flip=True):
     (5, 12, 12, 3, [128, 128, 256], [0, 1, 1], [100, 10]),         # wide enough for the matrix-core kernels
     (3, 9, 11, 1, [70, 32], [1, 1], [10]),                         # grey images; 99 pixels per image, 70 filters
     (2, 7, 7, 4, [32, 32], [0, 1], [5]),                           # four input channels: the first layer goes through planes
+    (2, 6, 6, 3, [100, 32], [0, 1], [7]),                          # first layer: four words of filters, the last ragged
 ])
 def test_convnet_small(seed, B, H, Wd, C0, couts, pools, fcs, engine):
     import paper_1609_07061_amd as q
