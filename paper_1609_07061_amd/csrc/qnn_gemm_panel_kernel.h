@@ -526,6 +526,15 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
         };
         for (uint32_t G = 0; G + 1 < ngroups; ++G) group(std::false_type{});
         group(std::true_type{});
+        // The sums are pinned here: otherwise the compiler moves the last group's matrix-core instructions down into the
+        // epilogue's blocks (their only users), one dependent chain per accumulator block behind that block's store,
+        // and keeps the whole group's operands in registers until then.
+        if constexpr (kConv) {
+#pragma unroll
+            for (int i = 0; i < WI; ++i)
+#pragma unroll
+                for (int j = 0; j < WB; ++j) asm volatile("" : "+a"(acc[i][j]));
+        }
         finish(m_wave, n_wave);
         expand(buf0, 0, frags);
     }
