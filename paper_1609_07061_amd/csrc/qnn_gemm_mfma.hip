@@ -278,6 +278,7 @@ int launch_conv_panel(const uint32_t *plane, int64_t B, int H, int Wd, int C, co
     int sh = 0;
     while ((1 << sh) < C / 128) ++sh;
     g.cpt_shift = sh;
+    g.last_steps = (int)ceil_div(g.Kw - (ceil_div(g.Kw, panel::kGroupWords) - 1) * panel::kGroupWords, 8);
     MfmaConst mc;
     std::memset(&mc, 0, sizeof(mc));
     mc.alpha = 4u, mc.alpha_shift = 2, mc.cRA = (uint32_t)-2;  // 4 S - 2 RA (see the kernel)

@@ -524,8 +524,43 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) { fetch(0, other, buf0); }, produce, last_tag);
             rd = other;
         };
+        // kConv: the patch's 9 C bits end inside the tile's last group; its steps that hold padding alone are left
+        // out (the loads stay as they are).  A step consumes buf0 and fetches into buf1 or the other way round, and
+        // the next tile expects its first step in buf0.
+        auto short_group = [&](auto steps_tag) __attribute__((always_inline)) {
+            constexpr int kSteps = decltype(steps_tag)::value;
+            const uint32_t other = rd + kGroupBytesT == kBuffers * kGroupBytesT ? 0u : rd + (uint32_t)kGroupBytesT;
+            p_advance();
+            if constexpr (kSteps == 1) {
+                panel_barrier();
+                compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(0, other, buf1); }, produce, std::true_type{});
+                buf0 = buf1;
+            } else if constexpr (kSteps == 2) {
+                compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(1, rd, buf1); }, no_produce, std::false_type{});
+                panel_barrier();
+                compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) { fetch(0, other, buf0); }, produce, std::true_type{});
+            } else {
+                compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(1, rd, buf1); }, no_produce, std::false_type{});
+                compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) { fetch(2, rd, buf0); }, no_produce, std::false_type{});
+                panel_barrier();
+                compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(0, other, buf1); }, produce, std::true_type{});
+                buf0 = buf1;
+            }
+            rd = other;
+        };
         for (uint32_t G = 0; G + 1 < ngroups; ++G) group(std::false_type{});
-        group(std::true_type{});
+        if constexpr (kConv) {
+            if (g.last_steps == 1)
+                short_group(std::integral_constant<int, 1>{});
+            else if (g.last_steps == 2)
+                short_group(std::integral_constant<int, 2>{});
+            else if (g.last_steps == 3)
+                short_group(std::integral_constant<int, 3>{});
+            else
+                group(std::true_type{});
+        } else {
+            group(std::true_type{});
+        }
         // The sums are pinned here: otherwise the compiler moves the last group's matrix-core instructions down into the
         // epilogue's blocks (their only users), one dependent chain per accumulator block behind that block's store,
         // and keeps the whole group's operands in registers until then.

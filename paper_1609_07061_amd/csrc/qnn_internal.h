@@ -78,12 +78,14 @@ struct GemmArgs {
     // the lower of {the plane "value is -1" of a +-1 map, a 16-byte line of zeros}; a_delta / zero_off are the byte
     // offsets of the two from it; class_thr[cls * class_ld + n] is the threshold of filter n for a pixel of border class
     // cls (bit 0: first row, 1: last row, 2: first column, 3: last column); inv_w = 1 / Wd and inv_hw = 1 / (H Wd) for
-    // the pixel coordinates; cpt_shift = log2(16-byte pieces per tap).
+    // the pixel coordinates; cpt_shift = log2(16-byte pieces per tap); last_steps = how many of the four 256-bit steps of
+    // a tile's last group of k hold bits of the patch (the others are padding and are not multiplied).
     const int32_t *class_thr;
     int64_t class_ld;
     uint32_t a_delta, zero_off;
     double inv_w, inv_hw;
     int cpt_shift;
+    int last_steps;
 };
 
 // Tile index with consecutive ids of one XCD (ids congruent mod 8 share an L2) laid on neighbouring tiles, and tiles
