@@ -281,7 +281,7 @@ int launch_conv_panel(const uint32_t *plane, int64_t B, int H, int Wd, int C, co
     g.last_steps = (int)ceil_div(g.Kw - (ceil_div(g.Kw, panel::kGroupWords) - 1) * panel::kGroupWords, 8);
     MfmaConst mc;
     std::memset(&mc, 0, sizeof(mc));
-    mc.alpha = 4u, mc.alpha_shift = 2, mc.cRA = (uint32_t)-2;  // 4 S - 2 RA (see the kernel)
+    mc.alpha = 1u;  // (the convolution's epilogue compares the sums as they are)
     const int64_t tiles_m = ceil_div(M, 256), tiles_n = ceil_div(N, 128), total = tiles_m * tiles_n;
     const int cus = compute_units();
     const unsigned grid = (unsigned)(total < cus ? total : cus);

@@ -233,27 +233,23 @@ __device__ __forceinline__ void load_class_thresholds_to_lds(const GemmArgs &g, 
 // Threshold epilogue of the convolution on the panel-fed kernel: the comparison value depends on the pixel's border
 // class (which of the nine taps lie inside the image) as well as on the filter, so thr_tab holds the thresholds of nine
 // classes for the wave's 64 filters (see load_class_thresholds_to_lds) and a lane reads the row of its pixel's class:
-//   bit = (alpha S + cRA RA[m] > thr_tab[class9(m)][n]) xor flip[n].
+//   bit = (S > thr_tab[class9(m)][n]) xor flip[n],  S = sum_k p[m][k] w[n][k] (w = +-1),
+// compared as floats (both sides are whole numbers below 2^24, so the difference is exact and its sign bit the answer).
 // The loads that fill thr_tab and flip_tab were followed by kLoadsAfter further loads to LDS.
 template <int WBN, int kLoadsAfter, typename Acc, typename PixelOf>
-__device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, const MfmaConst &mc, Acc (&acc)[WBN][4], int32_t (&ra)[4],
-                                                   int32_t *thr_tab, uint32_t *flip_tab, const int64_t m_wave,
-                                                   const int64_t n_wave, PixelOf pixel_of) {
+__device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, Acc (&acc)[WBN][4], int32_t *thr_tab, uint32_t *flip_tab,
+                                                   const int64_t m_wave, const int64_t n_wave, PixelOf pixel_of) {
     constexpr int WB = 4, WTN = 32 * WBN;
     static_assert(WBN == 2, "the class table holds 64 filters per wave");
     const int64_t Nw = (g.N + 31) / 32;
     int lane_opaque = (int)(threadIdx.x & 63);
     asm volatile("" : "+v"(lane_opaque));
     const int lane = lane_opaque, r = lane & 31, kg = lane >> 5;
-#pragma unroll
-    for (int b = 0; b < WB; ++b) ra[b] = sum_halves(ra[b]);
     int64_t m_of[WB];
-    uint32_t mterm[WB];
     const int32_t *thr_row[WB];  // thr_tab row of the pixel's class
 #pragma unroll
     for (int bj = 0; bj < WB; ++bj) {
         m_of[bj] = m_wave + bj * 32 + r;
-        mterm[bj] = mc.cRA * (uint32_t)ra[bj] + mc.c0;
         const uint32_t m = (uint32_t)(m_of[bj] < g.M ? m_of[bj] : g.M - 1);
         uint32_t y, x;
         pixel_of(m, y, x);
@@ -272,7 +268,6 @@ __device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, const Mfma
     }
     __builtin_amdgcn_s_waitcnt(0xc07f);
     __builtin_amdgcn_wave_barrier();
-    const int sh = mc.alpha_shift;  // (alpha is a power of two here: 4)
 #pragma unroll
     for (int bi = 0; bi < WBN; ++bi) {
         const int64_t n_blk = n_wave + bi * 32;
@@ -291,15 +286,13 @@ __device__ __forceinline__ void wave_epilogue_conv(const GemmArgs &g, const Mfma
             uint32_t bits = 0;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int4 e4 = *reinterpret_cast<const int4 *>(thr_row[bj] + bi * 32 + 8 * q + 4 * kg);
-                const int32_t e[4] = {e4.x, e4.y, e4.z, e4.w};
+                const float4 e4 = *reinterpret_cast<const float4 *>(thr_row[bj] + bi * 32 + 8 * q + 4 * kg);
+                const float e[4] = {e4.x, e4.y, e4.z, e4.w};
                 uint32_t nib = 0;
 #pragma unroll
                 for (int i = 3; i >= 0; --i) {
-                    const uint32_t s32 = acc_to_sum(acc[bi][bj][4 * q + i]);
-                    const uint32_t rest = (s32 << sh) + mterm[bj];
-                    const uint32_t x = (uint32_t)e[i] - rest;  // sign bit set  <=>  rest > e
-                    nib = __builtin_amdgcn_alignbit(nib, x, 31);
+                    const float d = e[i] - acc[bi][bj][4 * q + i];  // sign bit set  <=>  S > e
+                    nib = __builtin_amdgcn_alignbit(nib, __float_as_uint(d), 31);
                 }
                 bits |= nib << (8 * q);
             }

@@ -13,8 +13,9 @@ KernelFn find_kernel(bool sign, bool narrow, bool tail) {
 KernelFn conv_kernel() { return gemm_panel_kernel<true, 2, false, true>; }
 
 namespace {
-// class_thr[cls][n] = 2 sum_{taps inside for cls} sum_c b[n][tap][c] - (taps inside) C - T[n], clamped to +-2^30 (the sums
-// it is compared with are far smaller); cls bit 0: the pixel is in the first row (the upper taps lie outside), 1: last
+// class_thr[cls][n] = floor(e / 2) as a float, clamped to +-2^23 (the sums it is compared with are far smaller), where
+// e = 2 sum_{taps inside for cls} sum_c b[n][tap][c] - (taps inside) C - T[n] = (sum of the filter's weights on the taps
+// inside) - T[n]: the convolution is that sum minus 2 S, S = sum_k p w, so it reaches T[n] iff S <= e / 2; cls bit 0: the pixel is in the first row (the upper taps lie outside), 1: last
 // row, 2: first column, 3: last column.  Entries of filters beyond N are zero.  All layers of a network in one launch:
 // sixteen lanes per filter, lane t < 9 counts the set bits of tap t, then lane c sums the taps that class c keeps.
 // Also clears the line of zeros that the convolutions read for taps outside the image.
@@ -62,8 +63,9 @@ __global__ __launch_bounds__(256) void conv_class_thr_kernel(const ConvPrepJobs 
     }
     if (n < ld) {
         int64_t e = n < N ? 2 * sum - taps * (int64_t)Cw * 32 - (int64_t)jobs.T[j][n] : 0;
-        e = e < -(1 << 30) ? -(1 << 30) : (e > (1 << 30) ? (1 << 30) : e);
-        jobs.out[j][sub * ld + n] = (int32_t)e;
+        e >>= 1;  // floor
+        e = e < -(1 << 23) ? -(1 << 23) : (e > (1 << 23) ? (1 << 23) : e);
+        jobs.out[j][sub * ld + n] = (int32_t)__float_as_uint((float)(int32_t)e);
     }
 }
 }  // namespace

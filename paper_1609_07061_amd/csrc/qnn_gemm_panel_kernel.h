@@ -68,10 +68,11 @@ __device__ __forceinline__ void phase_groups(std::integer_sequence<int, I...>) {
 // kConv (kSign, WBN = 2): the activation rows are the patch rows of a 3 x 3 "same" convolution (pad 1, stride 1) over
 // the plane "value is -1" of a +-1 feature map, channels-last, whole 16-byte pieces of channels per tap (App. A's
 // ConvNet under Alg. 4).  With a = 1 - 2 p inside the image (0 outside) and w = 2 b - 1,
-//   conv = 2 sum_{taps inside} sum_c b  -  (taps inside) C  -  4 sum p b  +  2 sum p,
-// so the kernel multiplies the bits p and b as they are (taps outside the image read a line of zeros), and the part that
-// depends on which taps lie inside, a function of the pixel's border class and the filter, sits in the threshold: the
-// epilogue compares 4 S - 2 RA with class_thr[class][n] (see wave_epilogue_conv).
+//   conv = sum_{taps inside} sum_c w  -  2 S,   S = sum_k p w,
+// so the kernel multiplies the bits p as they are (taps outside the image read a line of zeros) with the filters as +-1,
+// and the part that depends on which taps lie inside, a function of the pixel's border class and the filter, sits in
+// the threshold: the epilogue compares S with class_thr[class][n] (see wave_epilogue_conv).  The steps of a tile's
+// last group of k that lie wholly beyond the patch's 9 C bits are not multiplied (g.last_steps).
 template <bool kSign, int WBN, bool kTail = false, bool kConv = false>
 __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs g, const MfmaConst mc, uint32_t tiles_m,
                                                                   uint32_t tiles_n, uint32_t ngroups) {
@@ -367,6 +368,10 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     // so for t = 0, 1, 2 one AND per word makes the operand and the block scale of the instruction (2, 1, 1/2 on
     // both sides: exact powers of two) turns every product of two set bits into 1; bit 3 is the sign and is moved to
     // bit 1 first.  20 vector-ALU instructions per 128 elements instead of 28 with shift-and-mask throughout.
+    // kConv: the filters enter as +-1 instead of 0 / 1 (a set bit is +1), so that the sum over k of p w is the whole
+    // data-dependent part of the convolution and no row sums are needed: with bit t of a nibble moved to bit 3, every
+    // nibble becomes 0b0010 (1.0) with the sign bit set where the filter bit is clear; block scale 1 in all phases.
+    auto plus_minus_one = [](uint32_t x) __attribute__((always_inline)) { return (x & 0x22222222u) | (~x & 0xAAAAAAAAu); };
     auto expand = [&](const Step &c, const int tt, Frags &f) __attribute__((always_inline)) {
         const uint32_t mask = tt == 0 ? 0x11111111u : (tt == 2 ? 0x44444444u : 0x22222222u);
 #pragma unroll
@@ -377,7 +382,12 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 #pragma unroll
         for (int b = 0; b < WI; ++b) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) f.w[b][j] = (int)(word_of(c.W[b], j) & mask);
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (kConv)
+                    f.w[b][j] = (int)plus_minus_one(word_of(c.W[b], j) << (3 - tt));
+                else
+                    f.w[b][j] = (int)(word_of(c.W[b], j) & mask);
+            }
         }
     };
     // Bit 3 of a nibble takes two instructions per word (shift, mask).  The shifts are spread over the three phases
@@ -393,13 +403,15 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 #pragma unroll
             for (int j = 0; j < 4; ++j)
                 if ((b * 4 + j) % 3 == part) sh.a[b][j] = word_of(c.A[b], j) >> 2;
+        if constexpr (!kConv) {
 #pragma unroll
-        for (int b = 0; b < WI; ++b)
+            for (int b = 0; b < WI; ++b)
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
-                if ((WB * 4 + b * 4 + j) % 3 == part) sh.w[b][j] = word_of(c.W[b], j) >> 2;
+                for (int j = 0; j < 4; ++j)
+                    if ((WB * 4 + b * 4 + j) % 3 == part) sh.w[b][j] = word_of(c.W[b], j) >> 2;
+        }
     };
-    auto expand_shifted = [&](const Shifted &sh, Frags &f) __attribute__((always_inline)) {
+    auto expand_shifted = [&](const Step &c, const Shifted &sh, Frags &f) __attribute__((always_inline)) {
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
 #pragma unroll
@@ -408,13 +420,19 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 #pragma unroll
         for (int b = 0; b < WI; ++b) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) f.w[b][j] = (int)(sh.w[b][j] & 0x22222222u);
+            for (int j = 0; j < 4; ++j) {
+                if constexpr (kConv)
+                    f.w[b][j] = (int)plus_minus_one(word_of(c.W[b], j));
+                else
+                    f.w[b][j] = (int)(sh.w[b][j] & 0x22222222u);
+            }
         }
     };
     // row sums of the raw bits: one word of every row per phase.  Each sum is made opaque after its addition: left
     // alone, the compiler keeps the counts of a whole loop trip in registers of their own and adds them up at the end
     // (three-operand adds), which costs over a hundred registers and spills the sums themselves.
     auto count = [&](const Step &c, const int tt) __attribute__((always_inline)) {
+        if constexpr (kConv) return;  // (the convolution's epilogue needs no row sums)
 #pragma unroll
         for (int b = 0; b < WB; ++b) {
             ra[b] += (int32_t)__builtin_popcount(word_of(c.A[b], tt));
@@ -428,13 +446,14 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
     };
     // block scales of the four phases as E8M0 bytes (2^(e - 127)): 2, 1, 1/2, 1
     const int scales = 0x7F7E7F80;
+    const int scales_w = kConv ? 0x7F7F7F7F : scales;
     auto multiply = [&](const Frags &f, auto t_tag) __attribute__((always_inline)) {
         constexpr int tt = decltype(t_tag)::value;
 #pragma unroll
         for (int i = 0; i < WI; ++i)
 #pragma unroll
             for (int j = 0; j < WB; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(f.w[i]), widen(f.a[j]), acc[i][j], 4, 4, tt, scales, tt, scales);
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(widen(f.w[i]), widen(f.a[j]), acc[i][j], 4, 4, tt, scales_w, tt, scales);
     };
     // One step = four phases; each phase multiplies the operands made during the previous one and meanwhile counts
     // one word per row and makes the next phase's operands.  `issue_fetch` (the LDS reads of the following step) runs
@@ -456,7 +475,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
             if (tt + 1 < 3)
                 expand(c, tt + 1, gnext);
             else if (tt == 2)
-                expand_shifted(sh, gnext);
+                expand_shifted(c, sh, gnext);
             else if (!kLastStep)
                 expand(n, 0, gnext);
             multiply(f, t_tag);
@@ -487,7 +506,7 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_panel_kernel(const GemmArgs 
 
     auto finish = [&](const int64_t m_wave, const int64_t n_wave) __attribute__((always_inline)) {
         if constexpr (kConv)
-            wave_epilogue_conv<WI, kLoadsPerGroup>(g, mc, acc, ra, thr_table[wave], flip_table[wave], m_wave, n_wave, pixel_of);
+            wave_epilogue_conv<WI, kLoadsPerGroup>(g, acc, thr_table[wave], flip_table[wave], m_wave, n_wave, pixel_of);
         else
             wave_finish<kSign, WI, kLoadsPerGroup>(g, mc, acc, ra, rw, rw_table[kConv ? 0 : wave], thr_table[wave], flip_table[wave],
                                                    stage[wave], m_wave, n_wave);
