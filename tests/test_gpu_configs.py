@@ -297,7 +297,8 @@ def test_many_tiles_int4_times_int4(seed, engine):
 MERGED = [(1100, 1000, 2000, [3, -6, 15], 1, [5, 10], 0),
           (1300, 1400, 1237, [1, 2, 4, 8, 16, 32, 64, -128], 0, [1], 1),
           (2100, 1300, 800, [1, 2, 4, -8], 0, [-7, 2, 1], 1),
-          (1024, 1024, 2048, [64, 32, 16], 1, [1, 2], 0)]
+          (1024, 1024, 2048, [64, 32, 16], 1, [1, 2], 0),
+          (2100, 1100, 1050, [1, 2, -4], 0, [1, -2], 0)]   # K ends in the first half of its last group of 128
 
 
 @pytest.mark.parametrize("engine", [None, MFMA_LDS])
