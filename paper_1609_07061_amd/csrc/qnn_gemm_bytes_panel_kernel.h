@@ -335,27 +335,8 @@ __global__ __launch_bounds__(kThreads, 1) void gemm_bytes_panel_kernel(const Gem
             compute(buf1, buf0, frags, [&]() __attribute__((always_inline)) { fetch(0, next, buf0); }, produce, last_tag);
             rd = next;
         };
-        // g.last_steps == 1: the rows' elements end within the first step of the tile's last group (zeros follow on
-        // the weights' side), so its second step is not multiplied; the step consumes buf0 and fetches into buf1,
-        // and the next tile expects its first step in buf0
-        auto short_group = [&]() __attribute__((always_inline)) {
-            const uint32_t next = rd + kGroupBytesT == kBuffers * kGroupBytesT ? 0u : rd + (uint32_t)kGroupBytesT;
-            p_advance();
-            panel_barrier();
-            compute(buf0, buf1, frags, [&]() __attribute__((always_inline)) { fetch(0, next, buf1); }, produce, std::true_type{});
-            buf0 = buf1;
-            rd = next;
-        };
         for (uint32_t G = 0; G + 1 < ngroups; ++G) group(std::false_type{});
-        // (the narrow tile only: the wide tile has no registers to spare for a second way into the epilogue)
-        if constexpr (WBN == 2) {
-            if (g.last_steps == 1)
-                short_group();
-            else
-                group(std::true_type{});
-        } else {
-            group(std::true_type{});
-        }
+        group(std::true_type{});
         panel::wave_finish<kSign, WBN, kLoadsPerGroup, kCodes>(g, mc, acc, ra, rw, rw_tab, thr_tab, flip_tab, stage_w,
                                                                m_wave, n_wave);
         expand(buf0, 0, frags);

@@ -225,9 +225,7 @@ int launch_gemm_mfma(const GemmArgs &g, hipStream_t s, bool fp4) {
         const int64_t tiles_nb = narrow ? narrow_n : wide_n, ptotal = tiles_m * tiles_nb;
         if (ptotal <= 0x7FFFFFFFLL) {
             const unsigned pgrid = (unsigned)(ptotal < cus ? ptotal : cus);
-            GemmArgs gb = g;
-            gb.last_steps = g.K - (ngroups - 1) * bytes_panel::kGroupK <= bytes_panel::kGroupK / 2 ? 1 : 2;
-            return QNN_LAUNCH("gemm_bytes_panel", bytes_panel::kernel(narrow), dim3(pgrid), dim3(bytes_panel::kThreads), 0, s, gb, pc,
+            return QNN_LAUNCH("gemm_bytes_panel", bytes_panel::kernel(narrow), dim3(pgrid), dim3(bytes_panel::kThreads), 0, s, g, pc,
                               (uint32_t)tiles_m, (uint32_t)tiles_nb, (uint32_t)ngroups);
         }
     }
@@ -382,7 +380,6 @@ int launch_values(const GemmArgs &g, hipStream_t s) {
         v.A.rows_are_bytes = 1;
         v.w_bytes = w8;
         v.ld_w_bytes = pitch;
-        v.last_steps = g.K - (ceil_div(g.K, bytes_panel::kGroupK) - 1) * bytes_panel::kGroupK <= bytes_panel::kGroupK / 2 ? 1 : 2;
         v.rw_scaled = nullptr;
         MfmaConst mc;
         std::memset(&mc, 0, sizeof(mc));
