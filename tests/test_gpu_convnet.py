@@ -82,6 +82,19 @@ def test_convnet_ragged_shapes_on_the_panel_fed_convolution(seed, with_flip):
     assert engines[0] == 2 and engines[1] == 3 and engines[2] != 3, engines
 
 
+def test_convnet_panel_fed_convolution_with_1024_channels(seed):
+    """1024 channels into 40 filters: the patch's 9216 bits are nine whole groups of 1024, so every step of a tile's last
+    group is multiplied (with 128, 256 or 512 channels some are padding and are left out)."""
+    import paper_1609_07061_amd as q
+
+    couts, pools, fcs = [1024, 40, 32], [0, 0, 1], [6]
+    case = _case(seed, 2, 8, 16, 3, couts, pools, fcs, 1900)
+    want = oracle.convnet(*case)
+    assert np.array_equal(_run(q, case, couts, fcs), want)
+    engines = q.qnn_last_engines()
+    assert engines[0] == 2 and engines[1] == 3, engines
+
+
 def test_convnet_without_flips(seed):
     import paper_1609_07061_amd as q
 
