@@ -95,6 +95,19 @@ def test_convnet_panel_fed_convolution_with_1024_channels(seed):
     assert engines[0] == 2 and engines[1] == 3, engines
 
 
+def test_convnet_first_convolution_over_several_turns_per_wave(seed):
+    """110 images of 30 x 31 pixels: 102 300 pixels are 3197 tiles of 32 (the last one ragged), more than the 3072 waves
+    the first-layer kernel launches at most, so some waves take a second tile, whose patch bytes they asked for while
+    working on the first."""
+    import paper_1609_07061_amd as q
+
+    couts, pools, fcs = [32], [1], [4]
+    case = _case(seed, 110, 30, 31, 3, couts, pools, fcs, 2000)
+    want = oracle.convnet(*case)
+    assert np.array_equal(_run(q, case, couts, fcs), want)
+    assert q.qnn_last_engines()[0] == 2
+
+
 def test_convnet_without_flips(seed):
     import paper_1609_07061_amd as q
 
