@@ -108,6 +108,18 @@ def test_convnet_first_convolution_over_several_turns_per_wave(seed):
     assert q.qnn_last_engines()[0] == 2
 
 
+def test_convnet_panel_fed_convolution_over_several_tiles_per_workgroup(seed):
+    """75 images of 31 x 31 pixels and 128 channels: 72 075 pixels are 282 tiles of 256 rows (the last one ragged) for the
+    256 persistent workgroups, so some of them take a second tile."""
+    import paper_1609_07061_amd as q
+
+    couts, pools, fcs = [128, 128], [0, 1], [10]
+    case = _case(seed, 75, 31, 31, 3, couts, pools, fcs, 2100)
+    want = oracle.convnet(*case)
+    assert np.array_equal(_run(q, case, couts, fcs), want)
+    assert q.qnn_last_engines()[:2] == [2, 3]
+
+
 def test_convnet_without_flips(seed):
     import paper_1609_07061_amd as q
 
